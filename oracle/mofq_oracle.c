@@ -1,0 +1,346 @@
+/*
+ * mofq_oracle.c -- CPU oracle for the MoFQ quantize-and-score path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * HIP library is checked against; it shares no code with that library and is
+ * never called from the product path.  Only the tests, the smoke check and the
+ * cpu_baseline leg of the benchmark may load it.
+ *
+ * What it follows (arXiv 2305.12356):
+ *   - Algorithm 1: per layer, try each candidate format, keep the one with the
+ *     strictly smallest error, then quantize again with it.
+ *   - Section 3.2 / Section 5: per-channel weight scales, per-tensor activation
+ *     scales; FP4 is E2M1, FP8 is E4M3; error = MSE between the quantized and
+ *     the original tensor (returned here as the sum of squared errors).
+ *   - Section 4.2 and Table 1: the sixteen E2M1 codes with NaN/Inf reassigned
+ *     to +-4 and +-6 ("w/o NaN&Inf" row), and the IEEE-aligned row.
+ *   - Section 1 / Section 5.1: naive linear quantization, round to nearest.
+ *
+ * The paper fixes no scale formula, tie rule or clip search; the readings used
+ * here are (each also stated where it is applied):
+ *   scale   s = fl32(fl32(r*a)/qmax), a = max|x| of the unit, r = clip ratio,
+ *           qmax = 7 (INT4), 6 (E2M1), 3 (E2M1 IEEE row), 127 (INT8), 448 (E4M3);
+ *           optional rounding of s to fp16; s below 2^-126 (or zero) becomes 1.
+ *   scaled  t = fl32(x * fl32(1/s)).
+ *   INT     q = clamp(round-half-to-even(t), qmin, qmax).
+ *   FP      nearest grid value; a midpoint goes to the neighbour with the even
+ *           code; magnitudes beyond the largest grid value saturate; the code's
+ *           sign bit is the sign bit of t (so a negative t that rounds to zero
+ *           gives the "-0" code).
+ *   error   sum over the unit of ((double)x - (double)g*(double)s)^2 in fp64,
+ *           element order.
+ *   search  first clip candidate with the smallest error (strict '<').
+ *
+ * "fl32" is one IEEE binary32 operation; build with -ffp-contract=off and
+ * without fast-math so the compiler keeps them separate.
+ *
+ * Parity pins are in tests/test_oracle_*.py.  The clip search, group-wise
+ * scales and fp16 scales are not in the paper: for those the pins are the
+ * brute-force, closed-form and invariance checks only ("parity unpinned" by
+ * the paper itself).
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_INT4 = 0, ORC_FP4_E2M1 = 1, ORC_INT8 = 2, ORC_FP8_E4M3 = 3, ORC_FP4_E2M1_IEEE = 4 };
+enum { ORC_PER_TENSOR = 0, ORC_PER_CHANNEL = 1, ORC_PER_GROUP = 2 };
+
+#define ORC_NFMT 5
+
+/* ---- formats -------------------------------------------------------------- */
+
+/* Table 1, row "FP4 w/o NaN&Inf": magnitudes of codes 0..7; codes 8..15 are the
+ * same values negated (code 8 is -0). */
+static const double E2M1_MAG[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+
+int orc_is_int(int fmt) { return fmt == ORC_INT4 || fmt == ORC_INT8; }
+int orc_bits(int fmt) { return (fmt == ORC_INT8 || fmt == ORC_FP8_E4M3) ? 8 : 4; }
+
+/* Largest magnitude the scale maps the (clipped) absmax onto. */
+double orc_qmax(int fmt) {
+  switch (fmt) {
+    case ORC_INT4: return 7.0;
+    case ORC_FP4_E2M1: return 6.0;
+    case ORC_INT8: return 127.0;
+    case ORC_FP8_E4M3: return 448.0;
+    case ORC_FP4_E2M1_IEEE: return 3.0;
+  }
+  return NAN;
+}
+
+/* Number of non-negative finite magnitudes of an FP format. */
+static int fp_num_mag(int fmt) {
+  switch (fmt) {
+    case ORC_FP4_E2M1: return 8;
+    case ORC_FP4_E2M1_IEEE: return 6;   /* Table 1, row "w/ NaN&Inf": 0 .. 3 */
+    case ORC_FP8_E4M3: return 127;      /* 0x00 .. 0x7E; 0x7F is NaN */
+  }
+  return 0;
+}
+
+/* Value of a code.  INT codes are two's complement in 4 or 8 bits.  E4M3 is
+ * sign / 4 exponent bits (bias 7) / 3 mantissa bits: exponent field 0 is
+ * subnormal m*2^-9, otherwise (1+m/8)*2^(e-7); there is no infinity, and the
+ * single pattern with all exponent and mantissa bits set is NaN. */
+double orc_decode(int fmt, int code) {
+  switch (fmt) {
+    case ORC_INT4: {
+      int v = code & 0xF;
+      return (double)(v >= 8 ? v - 16 : v);
+    }
+    case ORC_INT8: {
+      int v = code & 0xFF;
+      return (double)(v >= 128 ? v - 256 : v);
+    }
+    case ORC_FP4_E2M1: {
+      double m = E2M1_MAG[code & 7];
+      return (code & 8) ? -m : m;
+    }
+    case ORC_FP4_E2M1_IEEE: {
+      int c = code & 7;
+      double m = (c == 6) ? INFINITY : (c == 7) ? NAN : E2M1_MAG[c];
+      return (code & 8) ? -m : m;
+    }
+    case ORC_FP8_E4M3: {
+      int e = (code >> 3) & 0xF, m = code & 7;
+      double mag;
+      if (e == 15 && m == 7) return NAN;
+      if (e == 0) mag = ldexp((double)m, -9);
+      else mag = ldexp(1.0 + (double)m / 8.0, e - 7);
+      return (code & 0x80) ? -mag : mag;
+    }
+  }
+  return NAN;
+}
+
+/* Round half to even to an integer, written out: floor, exact remainder, and
+ * the even neighbour at exactly one half. */
+static double round_half_even(double t) {
+  double f = floor(t);
+  double r = t - f; /* exact for every fp32 t */
+  if (r > 0.5) return f + 1.0;
+  if (r < 0.5) return f;
+  return (floor(f * 0.5) == f * 0.5) ? f : f + 1.0; /* f even ? */
+}
+
+/* Non-negative finite magnitudes of each FP format in code order, filled once
+ * from orc_decode so that the nearest-value search below reads a plain table. */
+static double g_mag[ORC_NFMT][128];
+static int g_mag_ready = 0;
+
+void orc_init(void) {
+  if (g_mag_ready) return;
+  for (int fmt = 0; fmt < ORC_NFMT; ++fmt)
+    for (int c = 0; c < fp_num_mag(fmt); ++c) g_mag[fmt][c] = orc_decode(fmt, c);
+  g_mag_ready = 1;
+}
+
+/* Code of the scaled value t. */
+int orc_encode(int fmt, float t) {
+  if (orc_is_int(fmt)) {
+    int bits = orc_bits(fmt);
+    double qmin = (bits == 4) ? -8.0 : -128.0;
+    double qmax = (bits == 4) ? 7.0 : 127.0;
+    double q = round_half_even((double)t);
+    if (q < qmin) q = qmin;
+    if (q > qmax) q = qmax;
+    return ((int)q) & ((1 << bits) - 1);
+  }
+  if (!g_mag_ready) orc_init();
+  const double* mag = g_mag[fmt];
+  int n = fp_num_mag(fmt);
+  int signbit_mask = (orc_bits(fmt) == 4) ? 0x8 : 0x80;
+  double a = fabs((double)t);
+  /* largest i with mag(i) <= a */
+  int i = 0;
+  for (int c = 0; c < n; ++c)
+    if (mag[c] <= a) i = c;
+  int mag_code;
+  if (i == n - 1) {
+    mag_code = i; /* at or beyond the largest value: saturate */
+  } else {
+    double lo = mag[i], hi = mag[i + 1];
+    double mid = 0.5 * (lo + hi); /* exact */
+    if (a < mid) mag_code = i;
+    else if (a > mid) mag_code = i + 1;
+    else mag_code = (i % 2 == 0) ? i : i + 1;
+  }
+  return mag_code | (signbit((double)t) ? signbit_mask : 0);
+}
+
+/* Dequantised grid value of the scaled value t. */
+double orc_quantize_value(int fmt, float t) { return orc_decode(fmt, orc_encode(fmt, t)); }
+
+/* Nearest fp16 value (ties to even, fp16 subnormals kept), clamped to the
+ * largest finite fp16, returned as fp32. */
+float orc_round_fp16(float v) {
+  if (v == 0.0f || isnan(v)) return v;
+  double a = fabs((double)v);
+  int e;
+  (void)frexp(a, &e);          /* a = f*2^e, f in [0.5,1): floor(log2 a) = e-1 */
+  int ex = e - 1;
+  if (ex < -14) ex = -14;      /* subnormal range shares the quantum of 2^-14 */
+  double q = ldexp(1.0, ex - 10);
+  double n = round_half_even(a / q); /* a/q exact: q is a power of two */
+  double r = n * q;
+  if (r > 65504.0) r = 65504.0;
+  return (float)(v < 0 ? -r : r);
+}
+
+/* Scale of a unit with absolute maximum `absmax` at clip ratio `ratio`. */
+float orc_scale(float absmax, float ratio, int fmt, int scale_f16) {
+  float ra = ratio * absmax;
+  float s = ra / (float)orc_qmax(fmt);
+  if (scale_f16) s = orc_round_fp16(s);
+  if (!(s >= 0x1p-126f)) s = 1.0f; /* zero or degenerate unit */
+  return s;
+}
+
+/* ---- units ---------------------------------------------------------------- */
+
+int64_t orc_num_units(int64_t rows, int64_t cols, int gran, int64_t group) {
+  switch (gran) {
+    case ORC_PER_TENSOR: return 1;
+    case ORC_PER_CHANNEL: return rows;
+    case ORC_PER_GROUP: return (group > 0 && cols % group == 0) ? rows * (cols / group) : -1;
+  }
+  return -1;
+}
+
+typedef struct { int64_t r0, nr, c0, nc; } unit_t;
+
+static unit_t unit_of(int64_t u, int64_t rows, int64_t cols, int gran, int64_t group) {
+  unit_t t;
+  if (gran == ORC_PER_TENSOR) { t.r0 = 0; t.nr = rows; t.c0 = 0; t.nc = cols; }
+  else if (gran == ORC_PER_CHANNEL) { t.r0 = u; t.nr = 1; t.c0 = 0; t.nc = cols; }
+  else { int64_t g = cols / group; t.r0 = u / g; t.nr = 1; t.c0 = (u % g) * group; t.nc = group; }
+  return t;
+}
+
+static float unit_absmax(const float* w, int64_t cols, unit_t un) {
+  float a = 0.0f;
+  for (int64_t r = un.r0; r < un.r0 + un.nr; ++r)
+    for (int64_t c = un.c0; c < un.c0 + un.nc; ++c) {
+      float v = fabsf(w[r * cols + c]);
+      if (v > a) a = v;
+    }
+  return a;
+}
+
+/* Sum of squared errors of a unit quantized at scale s. */
+static double unit_sse(const float* w, int64_t cols, unit_t un, int fmt, float s) {
+  float inv_s = 1.0f / s;
+  double sse = 0.0;
+  for (int64_t r = un.r0; r < un.r0 + un.nr; ++r)
+    for (int64_t c = un.c0; c < un.c0 + un.nc; ++c) {
+      float x = w[r * cols + c];
+      float t = x * inv_s;
+      double g = orc_quantize_value(fmt, t);
+      double d = (double)x - g * (double)s;
+      double d2 = d * d;
+      sse = sse + d2;
+    }
+  return sse;
+}
+
+/* ---- scale search --------------------------------------------------------- */
+
+/*
+ * For every unit of w [rows x cols] (row-major, contiguous) and one format:
+ * search the clip ratios, keep the first with the smallest error.
+ *   unit_scale[u], unit_clip[u], unit_err[u] : winner per unit (any may be NULL)
+ *   err_table[u*n_clip + k]                  : error of every candidate (may be NULL)
+ *   unit_first, unit_count                   : range of units to process (results
+ *                                              are still indexed by absolute unit)
+ * Returns 0, or -1 on bad arguments.
+ */
+int orc_sweep(const float* w, int64_t rows, int64_t cols, int gran, int64_t group, int fmt,
+              int scale_f16, const float* clip, int n_clip, int64_t unit_first, int64_t unit_count,
+              float* unit_scale, int32_t* unit_clip, double* unit_err, double* err_table,
+              int n_threads) {
+  int64_t nu = orc_num_units(rows, cols, gran, group);
+  if (!w || !clip || n_clip < 1 || nu < 0 || fmt < 0 || fmt >= ORC_NFMT) return -1;
+  if (unit_first < 0 || unit_count < 0 || unit_first + unit_count > nu) return -1;
+  orc_init();
+#ifdef _OPENMP
+  if (n_threads > 0) omp_set_num_threads(n_threads);
+#else
+  (void)n_threads;
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t u = unit_first; u < unit_first + unit_count; ++u) {
+    unit_t un = unit_of(u, rows, cols, gran, group);
+    float a = unit_absmax(w, cols, un);
+    double best = INFINITY;
+    int best_k = 0;
+    float best_s = 0.0f;
+    for (int k = 0; k < n_clip; ++k) {
+      float s = orc_scale(a, clip[k], fmt, scale_f16);
+      double e = unit_sse(w, cols, un, fmt, s);
+      if (err_table) err_table[u * n_clip + k] = e;
+      if (e < best) { best = e; best_k = k; best_s = s; }
+    }
+    if (unit_scale) unit_scale[u] = best_s;
+    if (unit_clip) unit_clip[u] = best_k;
+    if (unit_err) unit_err[u] = best;
+  }
+  return 0;
+}
+
+/* Codes (one byte per element, low bits) of w quantized with the given
+ * per-unit scales. */
+int orc_emit(const float* w, int64_t rows, int64_t cols, int gran, int64_t group, int fmt,
+             const float* unit_scale, uint8_t* codes) {
+  int64_t nu = orc_num_units(rows, cols, gran, group);
+  if (!w || !unit_scale || !codes || nu < 0) return -1;
+  orc_init();
+  for (int64_t u = 0; u < nu; ++u) {
+    unit_t un = unit_of(u, rows, cols, gran, group);
+    float inv_s = 1.0f / unit_scale[u];
+    for (int64_t r = un.r0; r < un.r0 + un.nr; ++r)
+      for (int64_t c = un.c0; c < un.c0 + un.nc; ++c) {
+        float t = w[r * cols + c] * inv_s;
+        codes[r * cols + c] = (uint8_t)orc_encode(fmt, t);
+      }
+  }
+  return 0;
+}
+
+/* Two 4-bit codes per byte: element 2j in the low nibble, 2j+1 in the high. */
+int orc_pack4(const uint8_t* codes, int64_t n, uint8_t* packed) {
+  if (n % 2) return -1;
+  for (int64_t j = 0; j < n / 2; ++j)
+    packed[j] = (uint8_t)((codes[2 * j] & 0xF) | ((codes[2 * j + 1] & 0xF) << 4));
+  return 0;
+}
+
+/* Tensor error of one format: unit errors added in unit order. */
+double orc_tensor_err(const double* unit_err, int64_t n_units) {
+  double e = 0.0;
+  for (int64_t u = 0; u < n_units; ++u) e = e + unit_err[u];
+  return e;
+}
+
+/* Algorithm 1's inner loop on already computed errors: candidates visited in
+ * list order, a candidate replaces the incumbent only if strictly smaller. */
+int orc_select(const double* err, int n_candidates) {
+  double min_err = INFINITY;
+  int best = -1;
+  for (int f = 0; f < n_candidates; ++f)
+    if (err[f] < min_err) { min_err = err[f]; best = f; }
+  return best;
+}
+
+int orc_max_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}

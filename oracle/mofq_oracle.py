@@ -1,0 +1,297 @@
+"""Python face of the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Loads ``libmofq_oracle.so`` (built from ``mofq_oracle.c`` with gcc) through
+ctypes and adds the two pieces that are plain library calls on top of it: the
+per-layer select of Algorithm 1 and the layer-output error of Section 3.2
+(``A_out = W * A_in``) written as fp64 numpy matrix products.
+
+Nothing here is imported by the product package.  Only tests, the smoke check
+and the benchmark's cpu_baseline leg use it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+INT4, FP4_E2M1, INT8, FP8_E4M3, FP4_E2M1_IEEE = 0, 1, 2, 3, 4
+PER_TENSOR, PER_CHANNEL, PER_GROUP = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mofq_oracle.c")
+_LIB = os.path.join(_HERE, "libmofq_oracle.so")
+
+GCC_FLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+             "-fPIC", "-shared", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (seconds)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.run(["gcc", *GCC_FLAGS, _SRC, "-o", tmp, "-lm"], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        f32p, i32p, f64p, u8p = (C.POINTER(C.c_float), C.POINTER(C.c_int32),
+                                 C.POINTER(C.c_double), C.POINTER(C.c_uint8))
+        L.orc_decode.restype = C.c_double
+        L.orc_decode.argtypes = [C.c_int, C.c_int]
+        L.orc_encode.restype = C.c_int
+        L.orc_encode.argtypes = [C.c_int, C.c_float]
+        L.orc_qmax.restype = C.c_double
+        L.orc_qmax.argtypes = [C.c_int]
+        L.orc_round_fp16.restype = C.c_float
+        L.orc_round_fp16.argtypes = [C.c_float]
+        L.orc_scale.restype = C.c_float
+        L.orc_scale.argtypes = [C.c_float, C.c_float, C.c_int, C.c_int]
+        L.orc_num_units.restype = C.c_int64
+        L.orc_num_units.argtypes = [C.c_int64, C.c_int64, C.c_int, C.c_int64]
+        L.orc_sweep.restype = C.c_int
+        L.orc_sweep.argtypes = [f32p, C.c_int64, C.c_int64, C.c_int, C.c_int64, C.c_int, C.c_int,
+                                f32p, C.c_int, C.c_int64, C.c_int64, f32p, i32p, f64p, f64p, C.c_int]
+        L.orc_emit.restype = C.c_int
+        L.orc_emit.argtypes = [f32p, C.c_int64, C.c_int64, C.c_int, C.c_int64, C.c_int, f32p, u8p]
+        L.orc_pack4.restype = C.c_int
+        L.orc_pack4.argtypes = [u8p, C.c_int64, u8p]
+        L.orc_tensor_err.restype = C.c_double
+        L.orc_tensor_err.argtypes = [f64p, C.c_int64]
+        L.orc_select.restype = C.c_int
+        L.orc_select.argtypes = [f64p, C.c_int]
+        L.orc_max_threads.restype = C.c_int
+        L.orc_init()
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray, ct):
+    return a.ctypes.data_as(C.POINTER(ct))
+
+
+def _f32c(w) -> np.ndarray:
+    a = np.ascontiguousarray(w, dtype=np.float32)
+    if a.ndim != 2:
+        raise ValueError("expected a 2-D array")
+    return a
+
+
+# ---- scalars -----------------------------------------------------------------
+
+def decode(fmt: int, code: int) -> float:
+    return float(lib().orc_decode(fmt, int(code)))
+
+
+def encode(fmt: int, t) -> int:
+    return int(lib().orc_encode(fmt, C.c_float(float(np.float32(t)))))
+
+
+def encode_array(fmt: int, t: np.ndarray) -> np.ndarray:
+    """Codes of an fp32 array of already scaled values (scale 1 per element)."""
+    t = np.ascontiguousarray(t, dtype=np.float32).reshape(1, -1)
+    out = np.empty(t.shape, dtype=np.uint8)
+    one = np.ones(1, dtype=np.float32)
+    rc = lib().orc_emit(_p(t, C.c_float), 1, t.shape[1], PER_TENSOR, 0, fmt,
+                        _p(one, C.c_float), _p(out, C.c_uint8))
+    assert rc == 0
+    return out.reshape(-1)
+
+
+def decode_array(fmt: int, codes: np.ndarray) -> np.ndarray:
+    lut = np.array([decode(fmt, c) for c in range(256 if bits(fmt) == 8 else 16)])
+    return lut[np.asarray(codes, dtype=np.int64)]
+
+
+def bits(fmt: int) -> int:
+    return 8 if fmt in (INT8, FP8_E4M3) else 4
+
+
+def qmax(fmt: int) -> float:
+    return float(lib().orc_qmax(fmt))
+
+
+def round_fp16(v) -> float:
+    return float(lib().orc_round_fp16(C.c_float(float(np.float32(v)))))
+
+
+def scale(absmax, ratio, fmt: int, scale_f16: bool = False) -> float:
+    return float(lib().orc_scale(C.c_float(float(np.float32(absmax))),
+                                 C.c_float(float(np.float32(ratio))), fmt, int(scale_f16)))
+
+
+def num_units(rows: int, cols: int, gran: int, group: int = 0) -> int:
+    return int(lib().orc_num_units(rows, cols, gran, group))
+
+
+def max_threads() -> int:
+    return int(lib().orc_max_threads())
+
+
+# ---- sweep / emit ------------------------------------------------------------
+
+@dataclass
+class Sweep:
+    scale: np.ndarray        # [units] fp32 winner scale
+    clip_idx: np.ndarray     # [units] int32 winner candidate
+    err: np.ndarray          # [units] fp64 winner error (sum of squares)
+    table: Optional[np.ndarray]  # [units, n_clip] fp64 error of every candidate, or None
+    units: tuple             # (first, count) range that was computed
+
+
+def sweep(w, fmt: int, gran: int, clip: Sequence[float], group: int = 0,
+          scale_f16: bool = False, unit_first: int = 0, unit_count: Optional[int] = None,
+          want_table: bool = False, threads: int = 0) -> Sweep:
+    """Scale search of one tensor in one format (results indexed by absolute
+    unit; entries outside [unit_first, unit_first+unit_count) are not written)."""
+    w = _f32c(w)
+    rows, cols = w.shape
+    clip = np.ascontiguousarray(clip, dtype=np.float32)
+    nu = num_units(rows, cols, gran, group)
+    if nu < 0:
+        raise ValueError("bad granularity / group")
+    if unit_count is None:
+        unit_count = nu - unit_first
+    sc = np.zeros(nu, dtype=np.float32)
+    ci = np.zeros(nu, dtype=np.int32)
+    er = np.zeros(nu, dtype=np.float64)
+    tb = np.zeros((nu, clip.size), dtype=np.float64) if want_table else None
+    rc = lib().orc_sweep(_p(w, C.c_float), rows, cols, gran, group, fmt, int(scale_f16),
+                         _p(clip, C.c_float), clip.size, unit_first, unit_count,
+                         _p(sc, C.c_float), _p(ci, C.c_int32), _p(er, C.c_double),
+                         _p(tb, C.c_double) if want_table else None, threads)
+    if rc != 0:
+        raise ValueError("orc_sweep rejected its arguments")
+    return Sweep(sc, ci, er, tb, (unit_first, unit_count))
+
+
+def emit(w, fmt: int, gran: int, unit_scale: np.ndarray, group: int = 0) -> np.ndarray:
+    """Codes, one byte per element, of w quantized with the given unit scales."""
+    w = _f32c(w)
+    rows, cols = w.shape
+    unit_scale = np.ascontiguousarray(unit_scale, dtype=np.float32)
+    assert unit_scale.size == num_units(rows, cols, gran, group)
+    out = np.empty((rows, cols), dtype=np.uint8)
+    rc = lib().orc_emit(_p(w, C.c_float), rows, cols, gran, group, fmt,
+                        _p(unit_scale, C.c_float), _p(out, C.c_uint8))
+    if rc != 0:
+        raise ValueError("orc_emit rejected its arguments")
+    return out
+
+
+def pack4(codes: np.ndarray) -> np.ndarray:
+    c = np.ascontiguousarray(codes, dtype=np.uint8).reshape(-1)
+    out = np.empty(c.size // 2, dtype=np.uint8)
+    rc = lib().orc_pack4(_p(c, C.c_uint8), c.size, _p(out, C.c_uint8))
+    if rc != 0:
+        raise ValueError("odd number of 4-bit codes")
+    return out
+
+
+def tensor_err(unit_err: np.ndarray) -> float:
+    e = np.ascontiguousarray(unit_err, dtype=np.float64)
+    return float(lib().orc_tensor_err(_p(e, C.c_double), e.size))
+
+
+def select(errs: Sequence[float]) -> int:
+    e = np.ascontiguousarray(errs, dtype=np.float64)
+    return int(lib().orc_select(_p(e, C.c_double), e.size))
+
+
+# ---- Algorithm 1, one layer ---------------------------------------------------
+
+@dataclass
+class Quantized:
+    fmt: int
+    codes: np.ndarray        # [rows, cols] uint8, one code per element
+    scale: np.ndarray        # [units] fp32
+    clip_idx: np.ndarray     # [units] int32
+    unit_err: np.ndarray     # [units] fp64
+    err: float               # tensor error (sum of squares)
+    table: Optional[np.ndarray] = None
+
+
+def quantize(w, fmt: int, gran: int, clip, group: int = 0, scale_f16: bool = False,
+             want_table: bool = False, threads: int = 0) -> Quantized:
+    sw = sweep(w, fmt, gran, clip, group, scale_f16, want_table=want_table, threads=threads)
+    codes = emit(w, fmt, gran, sw.scale, group)
+    return Quantized(fmt, codes, sw.scale, sw.clip_idx, sw.err, tensor_err(sw.err), sw.table)
+
+
+@dataclass
+class Selected:
+    best: int                # index into candidates
+    errs: list               # error per candidate
+    ref_energy: float        # sum of x^2 (tensor metric) or sum of Y^2 (layer-output metric)
+    w: Quantized             # weights in the chosen format
+    x: Optional[Quantized] = None
+    per_candidate: Optional[list] = None
+
+
+def select_layer_w_only(w, candidates: Sequence[int], gran: int, clip, group: int = 0,
+                        scale_f16: bool = False, want_table: bool = False,
+                        threads: int = 0) -> Selected:
+    """Algorithm 1 for one layer with the tensor-error metric: quantize in each
+    candidate format, keep the strictly smaller error, quantize again with it."""
+    w = _f32c(w)
+    qs = [quantize(w, f, gran, clip, group, scale_f16, want_table, threads) for f in candidates]
+    errs = [q.err for q in qs]
+    best = select(errs)
+    energy = float(np.sum(w.astype(np.float64) ** 2))
+    return Selected(best, errs, energy, qs[best], None, qs)
+
+
+# ---- layer-output error (Section 3.2, layer analysis) -------------------------
+
+def layer_output_error(x, w, qx: Quantized, qw: Quantized, w_gran: int = PER_TENSOR):
+    """E = sum (X W^T - Xq Wq^T)^2 and P = sum (X W^T)^2 in fp64.
+
+    Xq Wq^T = sx * sw[o] * (Gx Gw^T) with the grid-value product exact in fp64
+    (integers for INT8; multiples of 2^-18 below 2^33 for E4M3)."""
+    x64 = np.asarray(x, dtype=np.float64)
+    w64 = np.asarray(w, dtype=np.float64)
+    y = x64 @ w64.T
+    gx = decode_array(qx.fmt, qx.codes)
+    gw = decode_array(qw.fmt, qw.codes)
+    acc = gx @ gw.T
+    sx = np.float64(qx.scale[0])
+    if w_gran == PER_TENSOR:
+        sw = np.float64(qw.scale[0])
+        yq = (sx * sw) * acc
+    else:
+        yq = (sx * qw.scale.astype(np.float64))[None, :] * acc
+    d = y - yq
+    return float(np.sum(d * d)), float(np.sum(y * y))
+
+
+def select_layer_wa(x, w, candidates: Sequence[int], w_gran: int = PER_TENSOR,
+                    threads: int = 0) -> Selected:
+    """Algorithm 1 for one layer in the weight-activation case with the
+    layer-output error: W and X share the candidate format (same data type for
+    all tensors of a layer), X per-tensor, W per-tensor or per-channel, no clip
+    search (ratio 1)."""
+    x = _f32c(x)
+    w = _f32c(w)
+    one = np.ones(1, dtype=np.float32)
+    errs, qxs, qws, energy = [], [], [], 0.0
+    for f in candidates:
+        qx = quantize(x, f, PER_TENSOR, one, threads=threads)
+        qw = quantize(w, f, w_gran, one, threads=threads)
+        e, energy = layer_output_error(x, w, qx, qw, w_gran)
+        errs.append(e)
+        qxs.append(qx)
+        qws.append(qw)
+    best = select(errs)
+    return Selected(best, errs, energy, qws[best], qxs[best], list(zip(qxs, qws)))
