@@ -1,0 +1,189 @@
+/*
+ * mofq.h -- C ABI of the MI355X (gfx950) library for the hot path of
+ * Mixture-of-Formats Quantization (arXiv 2305.12356): quantize a layer's
+ * weights (and, for weight-activation quantization, its input activations) to
+ * each candidate format of one bit-width, score each candidate, keep the best.
+ *
+ * Conventions, valid for every entry point:
+ *   - Tensors are row-major with the input dimension contiguous:
+ *     W = [out_features, in_features], X = [tokens, in_features]
+ *     (the linear layer A_out = W * A_in of Section 3.2).
+ *   - Every pointer is a DEVICE pointer unless the comment says HOST.  The
+ *     caller owns all memory; the library allocates none, keeps no pointer
+ *     after the call and has no global state.
+ *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and never synchronise: results, including the
+ *     chosen format, land in device memory.
+ *   - Return value: MOFQ_OK or a negative mofq_status_t.  Arguments are checked
+ *     on the host before anything is enqueued, so a failed call has no effect.
+ *   - Inputs must be finite; behaviour on NaN/Inf input is unspecified.
+ *   - `data` and every output pointer must be 16-byte aligned; `cols` and `ld`
+ *     must be multiples of 8 elements.
+ *
+ * Arithmetic (the paper leaves it open; this is the reading both this library
+ * and its CPU oracle implement):
+ *   unit   = one tensor, one output channel (row), or `group_size` consecutive
+ *            elements of a row;
+ *   a      = max |x| over the unit;
+ *   s_k    = fl32(fl32(r_k * a) / qmax), qmax = 7 (INT4), 6 (FP4 E2M1),
+ *            127 (INT8), 448 (FP8 E4M3); rounded to fp16 (clamped to 65504)
+ *            when scale_dtype is MOFQ_F16; a scale below 2^-126 becomes 1;
+ *   t      = fl32(x * fl32(1 / s_k));
+ *   INT    : q = clamp(round-half-even(t), qmin, qmax), two's-complement code;
+ *   FP     : nearest value of the format, ties to the even code, saturating,
+ *            sign bit of the code = sign bit of t (E2M1 is Table 1's row without
+ *            NaN/Inf: 0 .5 1 1.5 2 3 4 6; E4M3 is the 448-max variant with no
+ *            infinity);
+ *   error  = sum over the unit of (x - g*s_k)^2 in fp64;
+ *   search = first clip candidate with the smallest unit error;
+ *   select = first candidate format with the smallest tensor (or layer-output)
+ *            error, strict '<' as in Algorithm 1.
+ */
+#ifndef MOFQ_H_
+#define MOFQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Candidate formats (Section 3.2: FP4 = E2M1, FP8 = E4M3; Section 4.2 / Table 1
+ * for the E2M1 value set). */
+typedef enum {
+  MOFQ_INT4 = 0,
+  MOFQ_FP4_E2M1 = 1,
+  MOFQ_INT8 = 2,
+  MOFQ_FP8_E4M3 = 3
+} mofq_format_t;
+
+typedef enum { MOFQ_F32 = 0, MOFQ_F16 = 1, MOFQ_BF16 = 2 } mofq_dtype_t;
+
+/* Scale granularity: per-tensor (activations, Section 3.2), per-channel
+ * (weights, Section 3.2), per-group along the input dimension. */
+typedef enum { MOFQ_PER_TENSOR = 0, MOFQ_PER_CHANNEL = 1, MOFQ_PER_GROUP = 2 } mofq_gran_t;
+
+/* Error metric of Algorithm 1's compute_error (Section 4.1): error of the
+ * quantized tensor itself, or of the layer output with quantized inputs. */
+typedef enum { MOFQ_ERR_TENSOR = 0, MOFQ_ERR_LAYER_OUTPUT = 1 } mofq_metric_t;
+
+typedef enum {
+  MOFQ_OK = 0,
+  MOFQ_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, mixed bit-widths, n_clip < 1 ... */
+  MOFQ_ERR_UNSUPPORTED = -2, /* dtype / granularity / shape combination not implemented */
+  MOFQ_ERR_MISALIGNED = -3,  /* pointer not 16-byte aligned, cols or ld not a multiple of 8 */
+  MOFQ_ERR_WORKSPACE = -4,   /* ws_bytes smaller than mofq_workspace_bytes() */
+  MOFQ_ERR_HIP = -5          /* a launch failed */
+} mofq_status_t;
+
+#define MOFQ_MAX_CLIP 128      /* most clip candidates per call */
+#define MOFQ_MAX_CANDIDATES 4  /* most candidate formats per call */
+
+typedef struct {
+  const void* data; /* device, 16-byte aligned */
+  int32_t dtype;    /* mofq_dtype_t */
+  int64_t rows;     /* out_features (W) or tokens (X) */
+  int64_t cols;     /* in_features */
+  int64_t ld;       /* elements between consecutive rows, >= cols */
+} mofq_tensor_t;
+
+typedef struct {
+  int32_t gran;             /* mofq_gran_t */
+  int32_t group_size;       /* MOFQ_PER_GROUP only: 32, 64, 128 or 256; cols % group_size == 0 */
+  int32_t scale_dtype;      /* MOFQ_F32, or MOFQ_F16: the scale is rounded to fp16 before use */
+  int32_t n_clip;           /* 1 .. MOFQ_MAX_CLIP */
+  const float* clip_ratios; /* HOST array [n_clip], read during the call; candidate order is
+                               the tie order (first smallest wins) */
+} mofq_scale_cfg_t;
+
+/* Quantized tensor, all device memory, caller-allocated.  Units are numbered
+ * row-major: unit = row (per-channel), row*(cols/group)+group (per-group), 0. */
+typedef struct {
+  void* codes;       /* 4-bit formats: rows*cols/2 bytes, element 2j of a row in the low nibble
+                        of byte j (rows are dense, no padding); 8-bit: rows*cols bytes */
+  void* scales;      /* [units] float, or fp16 bits when scale_dtype is MOFQ_F16 */
+  int32_t* clip_idx; /* [units] index of the chosen clip ratio; may be NULL */
+  double* unit_err;  /* [units] error of the chosen candidate; may be NULL */
+} mofq_qout_t;
+
+/* Outcome of Algorithm 1 for one layer; device memory. */
+typedef struct {
+  int32_t best;       /* index into candidates[] of the chosen format */
+  int32_t n;          /* number of candidates */
+  double err[MOFQ_MAX_CANDIDATES]; /* error sum of squares per candidate */
+  double ref_energy;  /* sum x^2 (tensor metric) or sum (X W^T)^2 (layer-output metric):
+                         err/ref_energy is the noise-to-signal power ratio of Section 3.2 */
+} mofq_result_t;
+
+/*
+ * quantize_layer of Algorithm 1 for one tensor and one format: search the
+ * clip ratios per unit, then write codes, scales and (optionally) the chosen
+ * indices and unit errors.  `tensor_err` (device, may be NULL) receives the
+ * tensor error, the sum of the unit errors.
+ */
+int mofq_quantize(const mofq_tensor_t* t, int32_t format, const mofq_scale_cfg_t* cfg,
+                  const mofq_qout_t* out, double* tensor_err,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * compute_error of Algorithm 1 for one candidate format.
+ *   metric = MOFQ_ERR_TENSOR       : x must be NULL; *err = sum (W - Q(W))^2 with the
+ *                                    scale search of w_cfg; *ref_energy = sum W^2.
+ *   metric = MOFQ_ERR_LAYER_OUTPUT : x = A_in; W and X are quantized in `format`
+ *                                    (X per-tensor, W per w_cfg, which must have
+ *                                    n_clip = 1); *err = sum (X W^T - Q(X) Q(W)^T)^2,
+ *                                    *ref_energy = sum (X W^T)^2.  W and X must be
+ *                                    MOFQ_BF16 and `format` an 8-bit format.
+ * `err` and `ref_energy` are device pointers (ref_energy may be NULL).
+ */
+int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, int32_t metric,
+               const mofq_scale_cfg_t* w_cfg, double* err, double* ref_energy,
+               void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Algorithm 1's loop body for one layer: score every candidate (all of one
+ * bit-width, visited in list order), keep the first with the strictly smallest
+ * error, and emit the layer quantized in that format.
+ *   x == NULL : weight-only; metric must be MOFQ_ERR_TENSOR.
+ *   x != NULL : weight-activation; metric must be MOFQ_ERR_LAYER_OUTPUT; W and X
+ *               share the format; x_out receives X's codes and its one scale.
+ * `candidates` is a HOST array.  `result` is device memory.
+ */
+int mofq_select_layer(const mofq_tensor_t* w, const mofq_tensor_t* x,
+                      const int32_t* candidates, int32_t n_candidates, int32_t metric,
+                      const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
+                      const mofq_qout_t* x_out, mofq_result_t* result,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * mofq_select_layer with two caller-owned hipEvent_t (passed as void*, either may
+ * be NULL) recorded on `stream` immediately before and after the error-scoring
+ * kernels (the scale search for the tensor metric, the matrix products for the
+ * layer-output metric), so that a harness can time the dominant kernel inside its
+ * own timed region.  Everything else is identical.
+ */
+int mofq_select_layer_timed(const mofq_tensor_t* w, const mofq_tensor_t* x,
+                            const int32_t* candidates, int32_t n_candidates, int32_t metric,
+                            const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
+                            const mofq_qout_t* x_out, mofq_result_t* result,
+                            void* ws, size_t ws_bytes, void* stream,
+                            void* ev_score_begin, void* ev_score_end);
+
+/* Bytes of workspace the three calls above need for these arguments (the
+ * largest over the three); 0 on invalid arguments.  Workspace contents are
+ * scratch: nothing survives a call, calls sharing a workspace must be ordered
+ * on one stream. */
+size_t mofq_workspace_bytes(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t n_candidates,
+                            int32_t metric, const mofq_scale_cfg_t* w_cfg);
+
+/* Number of scale units of a tensor under a granularity; -1 if invalid. */
+int64_t mofq_num_units(int64_t rows, int64_t cols, int32_t gran, int32_t group_size);
+
+/* Static string for a status code. */
+const char* mofq_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOFQ_H_ */

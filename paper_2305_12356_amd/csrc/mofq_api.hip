@@ -1,0 +1,316 @@
+// The C ABI: argument validation, workspace carving and the order of launches.
+// No device memory is allocated here and nothing synchronises.
+#include <algorithm>
+#include <cstring>
+
+#include "mofq_internal.h"
+
+using namespace mofq;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+bool is4(int f) { return f == MOFQ_INT4 || f == MOFQ_FP4_E2M1; }
+bool is8(int f) { return f == MOFQ_INT8 || f == MOFQ_FP8_E4M3; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_tensor(const mofq_tensor_t* t) {
+  if (!t || !t->data) return MOFQ_ERR_INVALID_ARG;
+  if (t->rows <= 0 || t->cols <= 0 || t->ld < t->cols) return MOFQ_ERR_INVALID_ARG;
+  if (t->dtype != MOFQ_F32 && t->dtype != MOFQ_F16 && t->dtype != MOFQ_BF16) return MOFQ_ERR_INVALID_ARG;
+  if (!aligned16(t->data) || t->cols % 8 != 0 || t->ld % 8 != 0) return MOFQ_ERR_MISALIGNED;
+  return MOFQ_OK;
+}
+
+int check_cfg(const mofq_tensor_t* t, const mofq_scale_cfg_t* c) {
+  if (!c || !c->clip_ratios) return MOFQ_ERR_INVALID_ARG;
+  if (c->n_clip < 1 || c->n_clip > MOFQ_MAX_CLIP) return MOFQ_ERR_INVALID_ARG;
+  if (c->scale_dtype != MOFQ_F32 && c->scale_dtype != MOFQ_F16) return MOFQ_ERR_INVALID_ARG;
+  for (int k = 0; k < c->n_clip; ++k)
+    if (!(c->clip_ratios[k] > 0.0f) || !(c->clip_ratios[k] <= 1.0f)) return MOFQ_ERR_INVALID_ARG;
+  switch (c->gran) {
+    case MOFQ_PER_TENSOR:
+      if (c->n_clip > 8) return MOFQ_ERR_UNSUPPORTED;
+      return MOFQ_OK;
+    case MOFQ_PER_CHANNEL:
+      if (t->cols > 32768) return MOFQ_ERR_UNSUPPORTED;
+      return MOFQ_OK;
+    case MOFQ_PER_GROUP:
+      if (c->group_size != 32 && c->group_size != 64 && c->group_size != 128 && c->group_size != 256)
+        return MOFQ_ERR_UNSUPPORTED;
+      if (t->cols % c->group_size != 0) return MOFQ_ERR_UNSUPPORTED;
+      return MOFQ_OK;
+  }
+  return MOFQ_ERR_INVALID_ARG;
+}
+
+int check_out(const mofq_qout_t* o, bool need_codes) {
+  if (!o) return MOFQ_ERR_INVALID_ARG;
+  if (need_codes && (!o->codes || !o->scales)) return MOFQ_ERR_INVALID_ARG;
+  if (!aligned16(o->codes) || !aligned16(o->scales) || !aligned16(o->clip_idx) || !aligned16(o->unit_err))
+    return MOFQ_ERR_MISALIGNED;
+  return MOFQ_OK;
+}
+
+// Bump allocator over the caller's workspace.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* p) : base(static_cast<char*>(p)) {}
+  template <typename T> T* take(size_t n) {
+    off = (off + kAlign - 1) / kAlign * kAlign;
+    T* r = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += n * sizeof(T);
+    return r;
+  }
+};
+
+struct WOnlyWs {
+  float* scale[MOFQ_MAX_CANDIDATES];
+  int32_t* clip[MOFQ_MAX_CANDIDATES];
+  double* err[MOFQ_MAX_CANDIDATES];
+  double* energy;
+  float* absmax_part;
+  double* sse_part;
+  double* energy_part;
+  size_t bytes;
+};
+
+WOnlyWs carve_w_only(void* ws, int64_t units, int n_cand, int gran, int n_clip) {
+  Carver c(ws);
+  WOnlyWs w{};
+  for (int i = 0; i < n_cand; ++i) {
+    w.scale[i] = c.take<float>(units);
+    w.clip[i] = c.take<int32_t>(units);
+    w.err[i] = c.take<double>(units);
+  }
+  w.energy = c.take<double>(units);
+  if (gran == MOFQ_PER_TENSOR) {
+    w.absmax_part = c.take<float>(kTensorBlocks);
+    w.energy_part = c.take<double>(kTensorBlocks);
+    w.sse_part = c.take<double>(static_cast<size_t>(kTensorBlocks) * kMaxFmt * n_clip);
+  }
+  w.bytes = (c.off + kAlign - 1) / kAlign * kAlign;
+  return w;
+}
+
+// Scale search of all candidates (two formats per launch), results in the workspace.
+int sweep_candidates(const mofq_tensor_t* t, const int32_t* cand, int n_cand,
+                     const mofq_scale_cfg_t* cfg, const WOnlyWs& w, hipStream_t st) {
+  int c0 = 0;
+  while (c0 < n_cand) {
+    // two different formats share one launch (one read of the tensor); a repeated
+    // format is scored on its own
+    const int n = (c0 + 1 < n_cand && cand[c0] != cand[c0 + 1]) ? 2 : 1;
+    SweepParams p{};
+    p.w = t->data;
+    p.dtype = t->dtype;
+    p.rows = t->rows;
+    p.cols = t->cols;
+    p.ld = t->ld;
+    p.gran = cfg->gran;
+    p.group = cfg->group_size;
+    p.scale_f16 = cfg->scale_dtype == MOFQ_F16;
+    p.n_clip = cfg->n_clip;
+    std::memcpy(p.clip, cfg->clip_ratios, sizeof(float) * cfg->n_clip);
+    p.n_fmt = n;
+    // kernels exist for the (INT, FP) order; a reversed pair swaps its record slots
+    int slot[2] = {c0, c0 + 1};
+    if (n == 2 && !(cand[c0] == MOFQ_INT4 || cand[c0] == MOFQ_INT8)) std::swap(slot[0], slot[1]);
+    for (int f = 0; f < n; ++f) {
+      p.fmt[f] = cand[slot[f]];
+      p.rec.scale[f] = w.scale[slot[f]];
+      p.rec.clip[f] = w.clip[slot[f]];
+      p.rec.err[f] = w.err[slot[f]];
+    }
+    p.rec.energy = (c0 == 0) ? w.energy : nullptr;
+    p.absmax_part = w.absmax_part;
+    p.sse_part = w.sse_part;
+    p.energy_part = w.energy_part;
+    const int rc = launch_sweep(p, st);
+    if (rc != MOFQ_OK) return rc;
+    c0 += n;
+  }
+  return MOFQ_OK;
+}
+
+int check_candidates(const int32_t* cand, int n) {
+  if (!cand || n < 1 || n > MOFQ_MAX_CANDIDATES) return MOFQ_ERR_INVALID_ARG;
+  for (int i = 0; i < n; ++i) {
+    if (!is4(cand[i]) && !is8(cand[i])) return MOFQ_ERR_INVALID_ARG;
+    if (is4(cand[i]) != is4(cand[0])) return MOFQ_ERR_INVALID_ARG;  // one bit-width per call
+  }
+  return MOFQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t mofq_num_units(int64_t rows, int64_t cols, int32_t gran, int32_t group_size) {
+  if (rows <= 0 || cols <= 0) return -1;
+  switch (gran) {
+    case MOFQ_PER_TENSOR: return 1;
+    case MOFQ_PER_CHANNEL: return rows;
+    case MOFQ_PER_GROUP:
+      if (group_size <= 0 || cols % group_size != 0) return -1;
+      return rows * (cols / group_size);
+  }
+  return -1;
+}
+
+const char* mofq_status_string(int status) {
+  switch (status) {
+    case MOFQ_OK: return "ok";
+    case MOFQ_ERR_INVALID_ARG: return "invalid argument";
+    case MOFQ_ERR_UNSUPPORTED: return "unsupported dtype / granularity / shape combination";
+    case MOFQ_ERR_MISALIGNED: return "pointer not 16-byte aligned or cols/ld not a multiple of 8";
+    case MOFQ_ERR_WORKSPACE: return "workspace too small";
+    case MOFQ_ERR_HIP: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+size_t mofq_workspace_bytes(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t n_candidates,
+                            int32_t metric, const mofq_scale_cfg_t* w_cfg) {
+  if (!w || !w_cfg || n_candidates < 1 || n_candidates > MOFQ_MAX_CANDIDATES) return 0;
+  const int64_t units = mofq_num_units(w->rows, w->cols, w_cfg->gran, w_cfg->group_size);
+  if (units <= 0 || w_cfg->n_clip < 1 || w_cfg->n_clip > MOFQ_MAX_CLIP) return 0;
+  if (metric == MOFQ_ERR_TENSOR && !x)
+    return carve_w_only(nullptr, units, n_candidates, w_cfg->gran, w_cfg->n_clip).bytes;
+  return 0;
+}
+
+int mofq_quantize(const mofq_tensor_t* t, int32_t format, const mofq_scale_cfg_t* cfg,
+                  const mofq_qout_t* out, double* tensor_err, void* ws, size_t ws_bytes,
+                  void* stream) {
+  int rc = check_tensor(t);
+  if (rc) return rc;
+  if ((rc = check_cfg(t, cfg))) return rc;
+  if ((rc = check_out(out, true))) return rc;
+  if ((rc = check_candidates(&format, 1))) return rc;
+  const int64_t units = mofq_num_units(t->rows, t->cols, cfg->gran, cfg->group_size);
+  const WOnlyWs w = carve_w_only(ws, units, 1, cfg->gran, cfg->n_clip);
+  if (!ws || ws_bytes < w.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = sweep_candidates(t, &format, 1, cfg, w, st))) return rc;
+  if (tensor_err) {
+    DecideParams d{};
+    d.units = units;
+    d.n_cand = 1;
+    d.err[0] = w.err[0];
+    d.tensor_err_out = tensor_err;
+    if ((rc = launch_decide(d, st))) return rc;
+  }
+  EmitParams e{};
+  e.w = t->data;
+  e.dtype = t->dtype;
+  e.rows = t->rows;
+  e.cols = t->cols;
+  e.ld = t->ld;
+  e.gran = cfg->gran;
+  e.group = cfg->group_size;
+  e.scale_f16_out = cfg->scale_dtype == MOFQ_F16;
+  e.n_cand = 1;
+  e.fmt[0] = format;
+  e.scale[0] = w.scale[0];
+  e.clip[0] = w.clip[0];
+  e.err[0] = w.err[0];
+  e.result = nullptr;
+  e.out = *out;
+  return launch_emit(e, st);
+}
+
+int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, int32_t metric,
+               const mofq_scale_cfg_t* w_cfg, double* err, double* ref_energy, void* ws,
+               size_t ws_bytes, void* stream) {
+  int rc = check_tensor(w);
+  if (rc) return rc;
+  if ((rc = check_cfg(w, w_cfg))) return rc;
+  if ((rc = check_candidates(&format, 1))) return rc;
+  if (!err) return MOFQ_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (metric == MOFQ_ERR_TENSOR) {
+    if (x) return MOFQ_ERR_INVALID_ARG;
+    const int64_t units = mofq_num_units(w->rows, w->cols, w_cfg->gran, w_cfg->group_size);
+    const WOnlyWs s = carve_w_only(ws, units, 1, w_cfg->gran, w_cfg->n_clip);
+    if (!ws || ws_bytes < s.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+    if ((rc = sweep_candidates(w, &format, 1, w_cfg, s, st))) return rc;
+    DecideParams d{};
+    d.units = units;
+    d.n_cand = 1;
+    d.err[0] = s.err[0];
+    d.energy = s.energy;
+    d.tensor_err_out = err;
+    d.energy_out = ref_energy;
+    return launch_decide(d, st);
+  }
+  if (metric == MOFQ_ERR_LAYER_OUTPUT) return MOFQ_ERR_UNSUPPORTED;
+  return MOFQ_ERR_INVALID_ARG;
+}
+
+int mofq_select_layer(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* candidates,
+                      int32_t n_candidates, int32_t metric, const mofq_scale_cfg_t* w_cfg,
+                      const mofq_qout_t* w_out, const mofq_qout_t* x_out, mofq_result_t* result,
+                      void* ws, size_t ws_bytes, void* stream) {
+  return mofq_select_layer_timed(w, x, candidates, n_candidates, metric, w_cfg, w_out, x_out,
+                                 result, ws, ws_bytes, stream, nullptr, nullptr);
+}
+
+int mofq_select_layer_timed(const mofq_tensor_t* w, const mofq_tensor_t* x,
+                            const int32_t* candidates, int32_t n_candidates, int32_t metric,
+                            const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
+                            const mofq_qout_t* x_out, mofq_result_t* result, void* ws,
+                            size_t ws_bytes, void* stream, void* ev_score_begin,
+                            void* ev_score_end) {
+  hipEvent_t ev0 = static_cast<hipEvent_t>(ev_score_begin);
+  hipEvent_t ev1 = static_cast<hipEvent_t>(ev_score_end);
+  int rc = check_tensor(w);
+  if (rc) return rc;
+  if ((rc = check_cfg(w, w_cfg))) return rc;
+  if ((rc = check_candidates(candidates, n_candidates))) return rc;
+  if ((rc = check_out(w_out, true))) return rc;
+  if (!result) return MOFQ_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!x) {
+    if (metric != MOFQ_ERR_TENSOR) return MOFQ_ERR_INVALID_ARG;
+    (void)x_out;
+    const int64_t units = mofq_num_units(w->rows, w->cols, w_cfg->gran, w_cfg->group_size);
+    const WOnlyWs s = carve_w_only(ws, units, n_candidates, w_cfg->gran, w_cfg->n_clip);
+    if (!ws || ws_bytes < s.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+    if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return MOFQ_ERR_HIP;
+    if ((rc = sweep_candidates(w, candidates, n_candidates, w_cfg, s, st))) return rc;
+    if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return MOFQ_ERR_HIP;
+    DecideParams d{};
+    d.units = units;
+    d.n_cand = n_candidates;
+    for (int c = 0; c < n_candidates; ++c) d.err[c] = s.err[c];
+    d.energy = s.energy;
+    d.result = result;
+    if ((rc = launch_decide(d, st))) return rc;
+    EmitParams e{};
+    e.w = w->data;
+    e.dtype = w->dtype;
+    e.rows = w->rows;
+    e.cols = w->cols;
+    e.ld = w->ld;
+    e.gran = w_cfg->gran;
+    e.group = w_cfg->group_size;
+    e.scale_f16_out = w_cfg->scale_dtype == MOFQ_F16;
+    e.n_cand = n_candidates;
+    for (int c = 0; c < n_candidates; ++c) {
+      e.fmt[c] = candidates[c];
+      e.scale[c] = s.scale[c];
+      e.clip[c] = s.clip[c];
+      e.err[c] = s.err[c];
+    }
+    e.result = result;
+    e.out = *w_out;
+    return launch_emit(e, st);
+  }
+  if (metric != MOFQ_ERR_LAYER_OUTPUT) return MOFQ_ERR_INVALID_ARG;
+  return MOFQ_ERR_UNSUPPORTED;
+}
+
+}  // extern "C"

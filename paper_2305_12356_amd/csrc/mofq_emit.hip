@@ -1,0 +1,196 @@
+// Tensor-level reduce + format select (Algorithm 1's strict-less rule), and the
+// second quantize_layer call of Algorithm 1: emit the codes of the winning format
+// with the scales the search chose.  Both read the decision from device memory,
+// so a whole model can be processed without a host synchronisation.
+#include "mofq_device.h"
+#include "mofq_internal.h"
+
+namespace mofq {
+
+namespace {
+
+// ---- decide ---------------------------------------------------------------------
+
+constexpr int kDecideThreads = 1024;
+
+// Sum of v[0..n) over the block in a fixed order (thread-strided partials, then
+// wave sums, then the waves in order); the result is valid on thread 0.
+MOFQ_DEV double block_sum(const double* v, int64_t n, double* s_red) {
+  const int tid = threadIdx.x;
+  double t = 0.0;
+  for (int64_t i = tid; i < n; i += kDecideThreads) t += v[i];
+  t = wave_sum(t);
+  __syncthreads();
+  if ((tid & 63) == 0) s_red[tid >> 6] = t;
+  __syncthreads();
+  double r = 0.0;
+  if (tid == 0)
+    for (int w = 0; w < kDecideThreads / 64; ++w) r += s_red[w];
+  return r;
+}
+
+__global__ __launch_bounds__(kDecideThreads) void decide_kernel(const DecideParams p) {
+  __shared__ double s_red[kDecideThreads / 64];
+  double err[MOFQ_MAX_CANDIDATES];
+#pragma unroll
+  for (int c = 0; c < MOFQ_MAX_CANDIDATES; ++c)
+    err[c] = (c < p.n_cand) ? block_sum(p.err[c], p.units, s_red) : 0.0;
+  const double energy = p.energy ? block_sum(p.energy, p.units, s_red) : 0.0;
+  if (threadIdx.x == 0) {
+    // Algorithm 1: min_error starts at infinity, candidates in list order, a
+    // candidate wins only if strictly smaller.
+    double min_err = __builtin_inf();
+    int best = -1;
+#pragma unroll
+    for (int c = 0; c < MOFQ_MAX_CANDIDATES; ++c)
+      if (c < p.n_cand && err[c] < min_err) { min_err = err[c]; best = c; }
+    if (p.result) {
+      p.result->best = best;
+      p.result->n = p.n_cand;
+#pragma unroll
+      for (int c = 0; c < MOFQ_MAX_CANDIDATES; ++c) p.result->err[c] = (c < p.n_cand) ? err[c] : 0.0;
+      p.result->ref_energy = energy;
+    }
+    if (p.tensor_err_out) *p.tensor_err_out = err[0];
+    if (p.energy_out) *p.energy_out = energy;
+  }
+}
+
+// ---- emit -------------------------------------------------------------------------
+
+template <int FMT>
+MOFQ_DEV void encode8(const float (&v)[8], float inv_s, uint32_t (&words)[2]) {
+  if constexpr (Codec<FMT>::BITS == 4) {
+    uint32_t w = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w |= Codec<FMT>::code(v[i] * inv_s) << (4 * i);  // element 2j: low nibble of byte j
+    words[0] = w;
+    words[1] = 0;
+  } else {
+    uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      w0 |= Codec<FMT>::code(v[i] * inv_s) << (8 * i);
+      w1 |= Codec<FMT>::code(v[4 + i] * inv_s) << (8 * i);
+    }
+    words[0] = w0;
+    words[1] = w1;
+  }
+}
+
+struct EmitArgs {
+  const void* w;
+  int64_t rows, cols, ld;
+  int64_t units;
+  int32_t gran, group;
+  int32_t scale_f16_out;
+  int32_t n_cand;
+  int32_t fmt[MOFQ_MAX_CANDIDATES];
+  const float* scale[MOFQ_MAX_CANDIDATES];
+  const int32_t* clip[MOFQ_MAX_CANDIDATES];
+  const double* err[MOFQ_MAX_CANDIDATES];
+  const mofq_result_t* result;
+  mofq_qout_t out;
+};
+
+MOFQ_DEV int chosen(const EmitArgs& a) {
+  int best = a.result ? a.result->best : 0;
+  if (best < 0 || best >= a.n_cand) best = 0;   // no candidate beat infinity: keep the first
+  return __builtin_amdgcn_readfirstlane(best);
+}
+
+template <typename In>
+__global__ __launch_bounds__(256) void emit_codes_kernel(const EmitArgs a) {
+  using L = Load8<In>;
+  const int best = chosen(a);
+  const int fmt = a.fmt[best];
+  const float* scale = a.scale[best];
+  const int64_t cpr = a.cols / 8;
+  const int64_t n_chunks = a.rows * cpr;
+  const bool four = (fmt == MOFQ_INT4 || fmt == MOFQ_FP4_E2M1);
+  for (int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; c < n_chunks;
+       c += static_cast<int64_t>(gridDim.x) * 256) {
+    const int64_t row = c / cpr, col = (c - row * cpr) * 8;
+    int64_t unit = 0;
+    if (a.gran == MOFQ_PER_CHANNEL) unit = row;
+    else if (a.gran == MOFQ_PER_GROUP) unit = row * (a.cols / a.group) + col / a.group;
+    const float inv_s = 1.0f / scale[unit];
+    float v[8];
+    L::load(static_cast<const typename L::elem*>(a.w) + row * a.ld + col, v);
+    uint32_t words[2];
+    switch (fmt) {
+      case MOFQ_INT4: encode8<MOFQ_INT4>(v, inv_s, words); break;
+      case MOFQ_FP4_E2M1: encode8<MOFQ_FP4_E2M1>(v, inv_s, words); break;
+      case MOFQ_INT8: encode8<MOFQ_INT8>(v, inv_s, words); break;
+      default: encode8<MOFQ_FP8_E4M3>(v, inv_s, words); break;
+    }
+    const int64_t e0 = row * a.cols + col;   // dense output rows
+    if (four) {
+      static_cast<uint32_t*>(a.out.codes)[e0 / 8] = words[0];
+    } else {
+      u32x2 o;
+      o[0] = words[0];
+      o[1] = words[1];
+      reinterpret_cast<u32x2*>(a.out.codes)[e0 / 8] = o;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void emit_units_kernel(const EmitArgs a) {
+  const int best = chosen(a);
+  const int64_t u = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (u >= a.units) return;
+  const float s = a.scale[best][u];
+  if (a.out.scales) {
+    if (a.scale_f16_out)
+      static_cast<uint16_t*>(a.out.scales)[u] = __half_as_ushort(__float2half_rn(s));  // exact: s is an fp16 value
+    else
+      static_cast<float*>(a.out.scales)[u] = s;
+  }
+  if (a.out.clip_idx) a.out.clip_idx[u] = a.clip[best][u];
+  if (a.out.unit_err) a.out.unit_err[u] = a.err[best][u];
+}
+
+}  // namespace
+
+int launch_decide(const DecideParams& p, hipStream_t st) {
+  hipLaunchKernelGGL(decide_kernel, dim3(1), dim3(kDecideThreads), 0, st, p);
+  return hip_status(hipGetLastError());
+}
+
+int launch_emit(const EmitParams& p, hipStream_t st) {
+  EmitArgs a{};
+  a.w = p.w;
+  a.rows = p.rows;
+  a.cols = p.cols;
+  a.ld = p.ld;
+  a.gran = p.gran;
+  a.group = p.group;
+  a.scale_f16_out = p.scale_f16_out;
+  a.n_cand = p.n_cand;
+  for (int c = 0; c < MOFQ_MAX_CANDIDATES; ++c) {
+    a.fmt[c] = p.fmt[c];
+    a.scale[c] = p.scale[c];
+    a.clip[c] = p.clip[c];
+    a.err[c] = p.err[c];
+  }
+  a.result = p.result;
+  a.out = p.out;
+  a.units = mofq_num_units(p.rows, p.cols, p.gran, p.group);
+  if (a.units <= 0) return MOFQ_ERR_INVALID_ARG;
+  const int64_t n_chunks = p.rows * (p.cols / 8);
+  const unsigned blocks = static_cast<unsigned>(std::min<int64_t>((n_chunks + 255) / 256, 256 * 32));
+  if (p.out.codes) {
+    switch (p.dtype) {
+      case MOFQ_F32: hipLaunchKernelGGL(emit_codes_kernel<F32>, dim3(blocks), dim3(256), 0, st, a); break;
+      case MOFQ_F16: hipLaunchKernelGGL(emit_codes_kernel<F16>, dim3(blocks), dim3(256), 0, st, a); break;
+      case MOFQ_BF16: hipLaunchKernelGGL(emit_codes_kernel<BF16>, dim3(blocks), dim3(256), 0, st, a); break;
+      default: return MOFQ_ERR_INVALID_ARG;
+    }
+  }
+  if (p.out.scales || p.out.clip_idx || p.out.unit_err)
+    hipLaunchKernelGGL(emit_units_kernel, dim3(static_cast<unsigned>((a.units + 255) / 256)), dim3(256), 0, st, a);
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace mofq

@@ -1,0 +1,555 @@
+// Scale search ("sweep"): for every unit of a tensor and every candidate format,
+// evaluate all clip ratios and keep the first with the smallest error.
+//
+// This is the quantize_layer + compute_error pair of Algorithm 1 with the
+// tensor-error metric (Section 4.1), evaluated for all scale candidates of a
+// unit while the unit's elements sit in registers: the tensor is read from HBM
+// once, however many candidates there are.
+//
+// Work per element and candidate (INT: multiply, round, clamp; FP: multiply,
+// clamp, pick spacing, add/subtract rounding constant; then an fp64 residual and
+// an fp64 fused multiply-add into the error) is plain vector ALU work: with the
+// 100-candidate search the kernel is bound by the vector units, not by HBM.
+#include "mofq_device.h"
+#include "mofq_internal.h"
+
+namespace mofq {
+
+namespace {
+
+struct SweepArgs {
+  const void* w;
+  int64_t rows, cols, ld;
+  int64_t units;
+  int32_t group;
+  int32_t scale_f16;
+  int32_t n_clip;
+  UnitRecords rec;
+  float* absmax_part;
+  double* sse_part;
+  double* energy_part;
+  int32_t n_blocks;  // per-tensor: blocks of the partial passes
+  float clip[MOFQ_MAX_CLIP];
+};
+
+// Squared error of one element at one scale: the grid value is chosen in fp32
+// (the decision arithmetic), the residual and its square are fp64.
+template <int FMT>
+MOFQ_DEV void accumulate(double& acc, float x, double xd, float inv_s, double sd) {
+  const float t = x * inv_s;
+  if constexpr (Codec<FMT>::IS_INT) {
+    const double g = static_cast<double>(Codec<FMT>::grid(t));
+    const double d = __builtin_fma(-g, sd, xd);
+    acc = __builtin_fma(d, d, acc);
+  } else {
+    // sign-symmetric grid: (|x| - |g| s)^2 == (x - g s)^2
+    const double g = static_cast<double>(Codec<FMT>::mag(__builtin_fabsf(t)));
+    const double d = __builtin_fma(-g, sd, __builtin_fabs(xd));
+    acc = __builtin_fma(d, d, acc);
+  }
+}
+
+// ------------------------------------------------------------------------------
+// Per-channel: one workgroup per row; the row lives in registers (CH chunks of 8
+// elements per thread, chunk j of thread t = elements [(j*THREADS + t)*8, +8)).
+// ------------------------------------------------------------------------------
+template <typename In, int FA, int FB, int THREADS, int CH>
+__global__ __launch_bounds__(THREADS) void sweep_channel_kernel(const SweepArgs a) {
+  using L = Load8<In>;
+  constexpr int NF = (FB >= 0) ? 2 : 1;
+  constexpr int FBX = (FB >= 0) ? FB : FA;
+  constexpr int NW = THREADS / 64;
+  constexpr int NE = CH * 8;
+
+  __shared__ float s_scale[NF][MOFQ_MAX_CLIP];
+  __shared__ float s_inv[NF][MOFQ_MAX_CLIP];
+  __shared__ double s_part[NW][NF][MOFQ_MAX_CLIP];
+  __shared__ double s_tot[NF][MOFQ_MAX_CLIP];
+  __shared__ float s_wmax[NW];
+  __shared__ double s_wen[NW];
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t row = blockIdx.x;
+  const typename L::elem* src = static_cast<const typename L::elem*>(a.w) + row * a.ld;
+  const int K = a.n_clip;
+
+  float x[NE];
+  double xd[NE];
+  float amax = 0.0f;
+  double en = 0.0;
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const int64_t c0 = (static_cast<int64_t>(j) * THREADS + tid) * 8;
+    float v[8];
+    if (c0 < a.cols) {
+      L::load(src + c0, v);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = 0.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      x[j * 8 + i] = v[i];
+      xd[j * 8 + i] = static_cast<double>(v[i]);
+      amax = __builtin_fmaxf(amax, __builtin_fabsf(v[i]));
+      en = __builtin_fma(xd[j * 8 + i], xd[j * 8 + i], en);
+    }
+  }
+
+  // unit absmax and energy
+  amax = wave_max(amax);
+  en = wave_sum(en);
+  if ((tid & 63) == 0) { s_wmax[wave] = amax; s_wen[wave] = en; }
+  __syncthreads();
+  amax = s_wmax[0];
+  en = s_wen[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) { amax = __builtin_fmaxf(amax, s_wmax[w]); en += s_wen[w]; }
+
+  // scales of every (format, candidate)
+  for (int idx = tid; idx < NF * K; idx += THREADS) {
+    const int f = idx / K, k = idx - f * K;
+    const float qmax = (f == 0) ? Codec<FA>::QMAX : Codec<FBX>::QMAX;
+    const float s = unit_scale(amax, a.clip[k], qmax, a.scale_f16 != 0);
+    s_scale[f][k] = s;
+    s_inv[f][k] = 1.0f / s;
+  }
+  __syncthreads();
+
+  // which of this wave's chunks hold data (wave-uniform)
+  bool live[CH];
+#pragma unroll
+  for (int j = 0; j < CH; ++j)
+    live[j] = (static_cast<int64_t>(j) * THREADS + wave * 64) * 8 < a.cols;
+
+  for (int k = 0; k < K; ++k) {
+    const float sA = u2f(__builtin_amdgcn_readfirstlane(f2u(s_scale[0][k])));
+    const float iA = u2f(__builtin_amdgcn_readfirstlane(f2u(s_inv[0][k])));
+    const float sB = u2f(__builtin_amdgcn_readfirstlane(f2u(s_scale[NF - 1][k])));
+    const float iB = u2f(__builtin_amdgcn_readfirstlane(f2u(s_inv[NF - 1][k])));
+    const double sAd = static_cast<double>(sA), sBd = static_cast<double>(sB);
+    double accA = 0.0, accB = 0.0;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      if (live[j]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          accumulate<FA>(accA, x[j * 8 + i], xd[j * 8 + i], iA, sAd);
+          if constexpr (NF == 2) accumulate<FBX>(accB, x[j * 8 + i], xd[j * 8 + i], iB, sBd);
+        }
+      }
+    }
+    accA = wave_sum(accA);
+    if constexpr (NF == 2) accB = wave_sum(accB);
+    if ((tid & 63) == 0) {
+      s_part[wave][0][k] = accA;
+      if constexpr (NF == 2) s_part[wave][1][k] = accB;
+    }
+  }
+  __syncthreads();
+
+  for (int idx = tid; idx < NF * K; idx += THREADS) {
+    const int f = idx / K, k = idx - f * K;
+    double t = s_part[0][f][k];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) t += s_part[w][f][k];
+    s_tot[f][k] = t;
+  }
+  __syncthreads();
+
+  // first smallest candidate per format (one wave per format)
+  for (int f = wave; f < NF; f += NW) {
+    const int lane = tid & 63;
+    double best = __builtin_inf();
+    int bk = 0x7FFFFFFF;
+    for (int k = lane; k < K; k += 64) {
+      const double v = s_tot[f][k];
+      if (v < best) { best = v; bk = k; }
+    }
+    wave_argmin(best, bk);
+    if (lane == 0) {
+      a.rec.scale[f][row] = s_scale[f][bk];
+      a.rec.clip[f][row] = bk;
+      a.rec.err[f][row] = best;
+      if (f == 0 && a.rec.energy) a.rec.energy[row] = en;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------
+// Per-group: LPG lanes share one group of GROUP elements; each lane holds
+// GROUP/LPG consecutive elements.  Scales differ per group, so they are per-lane
+// values; the LPG lanes of a group split the scale computations of a batch of LPG
+// candidates and hand them round with DPP.
+// ------------------------------------------------------------------------------
+template <int LPG> MOFQ_DEV double group_sum(double v);
+template <> MOFQ_DEV double group_sum<4>(double v) { return quad_sum(v); }
+template <> MOFQ_DEV double group_sum<16>(double v) { return row16_sum(v); }
+template <int LPG> MOFQ_DEV float group_max(float v);
+template <> MOFQ_DEV float group_max<4>(float v) {
+  v = __builtin_fmaxf(v, dpp_f32<DPP_QUAD_XOR1>(v));
+  return __builtin_fmaxf(v, dpp_f32<DPP_QUAD_XOR2>(v));
+}
+template <> MOFQ_DEV float group_max<16>(float v) {
+  v = group_max<4>(v);
+  v = __builtin_fmaxf(v, dpp_f32<DPP_ROW_HALF_MIRROR>(v));
+  return __builtin_fmaxf(v, dpp_f32<DPP_ROW_MIRROR>(v));
+}
+
+// value held by lane `j` of the caller's quad
+template <int J> MOFQ_DEV float quad_bcast(float v) { return dpp_f32<J * 0x55>(v); }
+
+template <typename In, int FA, int FB, int GROUP>
+__global__ __launch_bounds__(256) void sweep_group_kernel(const SweepArgs a) {
+  using L = Load8<In>;
+  constexpr int NF = (FB >= 0) ? 2 : 1;
+  constexpr int FBX = (FB >= 0) ? FB : FA;
+  constexpr int LPG = 4;
+  constexpr int NE = GROUP / LPG;       // elements per lane
+  constexpr int CH = NE / 8;
+  static_assert(NE % 8 == 0, "group too small for 4 lanes");
+
+  const int tid = threadIdx.x;
+  const int q = tid & (LPG - 1);
+  const int64_t gpr = a.cols / GROUP;   // groups per row
+  int64_t unit = static_cast<int64_t>(blockIdx.x) * (256 / LPG) + tid / LPG;
+  const bool valid = unit < a.units;
+  if (!valid) unit = a.units - 1;       // keep every lane active for the DPP exchanges
+  const int64_t row = unit / gpr, gi = unit - row * gpr;
+  const typename L::elem* src =
+      static_cast<const typename L::elem*>(a.w) + row * a.ld + gi * GROUP + q * NE;
+  const int K = a.n_clip;
+  const bool f16 = a.scale_f16 != 0;
+
+  float x[NE];
+  double xd[NE];
+  float amax = 0.0f;
+  double en = 0.0;
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    float v[8];
+    L::load(src + j * 8, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      x[j * 8 + i] = v[i];
+      xd[j * 8 + i] = static_cast<double>(v[i]);
+      amax = __builtin_fmaxf(amax, __builtin_fabsf(v[i]));
+      en = __builtin_fma(xd[j * 8 + i], xd[j * 8 + i], en);
+    }
+  }
+  amax = group_max<LPG>(amax);
+  en = group_sum<LPG>(en);
+
+  double bestA = __builtin_inf(), bestB = __builtin_inf();
+  int bkA = 0, bkB = 0;
+  float bsA = 1.0f, bsB = 1.0f;
+
+  for (int k0 = 0; k0 < K; k0 += LPG) {
+    // lane q of the group prepares candidate k0+q (clamped; surplus ones are ignored)
+    const int kq = (k0 + q < K) ? k0 + q : K - 1;
+    const float r = a.clip[kq];
+    const float mysA = unit_scale(amax, r, Codec<FA>::QMAX, f16);
+    const float myiA = 1.0f / mysA;
+    float mysB = 0.0f, myiB = 0.0f;
+    if constexpr (NF == 2) {
+      mysB = unit_scale(amax, r, Codec<FBX>::QMAX, f16);
+      myiB = 1.0f / mysB;
+    }
+    auto one = [&](float sA, float iA, float sB, float iB, int k) {
+      if (k < K) {   // uniform over the workgroup
+        const double sAd = static_cast<double>(sA), sBd = static_cast<double>(sB);
+        double accA = 0.0, accB = 0.0;
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+          accumulate<FA>(accA, x[i], xd[i], iA, sAd);
+          if constexpr (NF == 2) accumulate<FBX>(accB, x[i], xd[i], iB, sBd);
+        }
+        accA = group_sum<LPG>(accA);
+        if (accA < bestA) { bestA = accA; bkA = k; bsA = sA; }
+        if constexpr (NF == 2) {
+          accB = group_sum<LPG>(accB);
+          if (accB < bestB) { bestB = accB; bkB = k; bsB = sB; }
+        }
+      }
+    };
+    one(quad_bcast<0>(mysA), quad_bcast<0>(myiA), quad_bcast<0>(mysB), quad_bcast<0>(myiB), k0 + 0);
+    one(quad_bcast<1>(mysA), quad_bcast<1>(myiA), quad_bcast<1>(mysB), quad_bcast<1>(myiB), k0 + 1);
+    one(quad_bcast<2>(mysA), quad_bcast<2>(myiA), quad_bcast<2>(mysB), quad_bcast<2>(myiB), k0 + 2);
+    one(quad_bcast<3>(mysA), quad_bcast<3>(myiA), quad_bcast<3>(mysB), quad_bcast<3>(myiB), k0 + 3);
+  }
+
+  if (valid && q == 0) {
+    a.rec.scale[0][unit] = bsA;
+    a.rec.clip[0][unit] = bkA;
+    a.rec.err[0][unit] = bestA;
+    if constexpr (NF == 2) {
+      a.rec.scale[1][unit] = bsB;
+      a.rec.clip[1][unit] = bkB;
+      a.rec.err[1][unit] = bestB;
+    }
+    if (a.rec.energy) a.rec.energy[unit] = en;
+  }
+}
+
+// ------------------------------------------------------------------------------
+// Per-tensor: absmax pass, then a pass of per-block partial errors, then one
+// block that adds the partials in block order and picks the candidate.
+// ------------------------------------------------------------------------------
+template <typename In>
+__global__ __launch_bounds__(256) void tensor_absmax_kernel(const SweepArgs a) {
+  using L = Load8<In>;
+  __shared__ float s_wmax[4];
+  __shared__ double s_wen[4];
+  const int tid = threadIdx.x;
+  const int64_t cpr = a.cols / 8;                 // chunks per row
+  const int64_t n_chunks = a.rows * cpr;
+  float amax = 0.0f;
+  double en = 0.0;
+  for (int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + tid; c < n_chunks;
+       c += static_cast<int64_t>(gridDim.x) * 256) {
+    const int64_t row = c / cpr, col = (c - row * cpr) * 8;
+    float v[8];
+    L::load(static_cast<const typename L::elem*>(a.w) + row * a.ld + col, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      amax = __builtin_fmaxf(amax, __builtin_fabsf(v[i]));
+      const double d = static_cast<double>(v[i]);
+      en = __builtin_fma(d, d, en);
+    }
+  }
+  amax = wave_max(amax);
+  en = wave_sum(en);
+  if ((tid & 63) == 0) { s_wmax[tid >> 6] = amax; s_wen[tid >> 6] = en; }
+  __syncthreads();
+  if (tid == 0) {
+    a.absmax_part[blockIdx.x] =
+        __builtin_fmaxf(__builtin_fmaxf(s_wmax[0], s_wmax[1]), __builtin_fmaxf(s_wmax[2], s_wmax[3]));
+    a.energy_part[blockIdx.x] = (s_wen[0] + s_wen[1]) + (s_wen[2] + s_wen[3]);
+  }
+}
+
+constexpr int kTensorMaxClip = 8;
+
+MOFQ_DEV float tensor_absmax(const SweepArgs& a, float* s_tmp) {
+  const int tid = threadIdx.x;
+  float m = 0.0f;
+  for (int i = tid; i < a.n_blocks; i += 256) m = __builtin_fmaxf(m, a.absmax_part[i]);
+  m = wave_max(m);
+  if ((tid & 63) == 0) s_tmp[tid >> 6] = m;
+  __syncthreads();
+  return __builtin_fmaxf(__builtin_fmaxf(s_tmp[0], s_tmp[1]), __builtin_fmaxf(s_tmp[2], s_tmp[3]));
+}
+
+template <typename In, int FA, int FB>
+__global__ __launch_bounds__(256) void tensor_score_kernel(const SweepArgs a) {
+  using L = Load8<In>;
+  constexpr int NF = (FB >= 0) ? 2 : 1;
+  constexpr int FBX = (FB >= 0) ? FB : FA;
+  __shared__ float s_tmp[4];
+  __shared__ float s_scale[NF][kTensorMaxClip];
+  __shared__ float s_inv[NF][kTensorMaxClip];
+  __shared__ double s_part[4][NF][kTensorMaxClip];
+  const int tid = threadIdx.x;
+  const int K = a.n_clip;
+  const float amax = tensor_absmax(a, s_tmp);
+  if (tid < NF * K) {
+    const int f = tid / K, k = tid - f * K;
+    const float s = unit_scale(amax, a.clip[k], f == 0 ? Codec<FA>::QMAX : Codec<FBX>::QMAX,
+                               a.scale_f16 != 0);
+    s_scale[f][k] = s;
+    s_inv[f][k] = 1.0f / s;
+  }
+  __syncthreads();
+
+  double acc[NF][kTensorMaxClip];
+#pragma unroll
+  for (int f = 0; f < NF; ++f)
+#pragma unroll
+    for (int k = 0; k < kTensorMaxClip; ++k) acc[f][k] = 0.0;
+
+  const int64_t cpr = a.cols / 8;
+  const int64_t n_chunks = a.rows * cpr;
+  for (int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + tid; c < n_chunks;
+       c += static_cast<int64_t>(gridDim.x) * 256) {
+    const int64_t row = c / cpr, col = (c - row * cpr) * 8;
+    float v[8];
+    L::load(static_cast<const typename L::elem*>(a.w) + row * a.ld + col, v);
+#pragma unroll
+    for (int k = 0; k < kTensorMaxClip; ++k) {
+      if (k < K) {
+        const float iA = s_inv[0][k], iB = s_inv[NF - 1][k];
+        const double sAd = static_cast<double>(s_scale[0][k]);
+        const double sBd = static_cast<double>(s_scale[NF - 1][k]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const double xd = static_cast<double>(v[i]);
+          accumulate<FA>(acc[0][k], v[i], xd, iA, sAd);
+          if constexpr (NF == 2) accumulate<FBX>(acc[1][k], v[i], xd, iB, sBd);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int f = 0; f < NF; ++f)
+#pragma unroll
+    for (int k = 0; k < kTensorMaxClip; ++k) {
+      if (k < K) {
+        const double t = wave_sum(acc[f][k]);
+        if ((tid & 63) == 0) s_part[tid >> 6][f][k] = t;
+      }
+    }
+  __syncthreads();
+  if (tid < NF * K) {
+    const int f = tid / K, k = tid - f * K;
+    a.sse_part[(static_cast<int64_t>(blockIdx.x) * NF + f) * K + k] =
+        (s_part[0][f][k] + s_part[1][f][k]) + (s_part[2][f][k] + s_part[3][f][k]);
+  }
+}
+
+template <int FA, int FB>
+__global__ __launch_bounds__(256) void tensor_finalize_kernel(const SweepArgs a) {
+  constexpr int NF = (FB >= 0) ? 2 : 1;
+  constexpr int FBX = (FB >= 0) ? FB : FA;
+  __shared__ float s_tmp[4];
+  __shared__ double s_red[4];
+  __shared__ double s_tot[NF][kTensorMaxClip];
+  const int tid = threadIdx.x;
+  const int K = a.n_clip;
+  const float amax = tensor_absmax(a, s_tmp);
+  for (int f = 0; f < NF; ++f)
+    for (int k = 0; k < K; ++k) {
+      double t = 0.0;
+      for (int b = tid; b < a.n_blocks; b += 256)
+        t += a.sse_part[(static_cast<int64_t>(b) * NF + f) * K + k];
+      t = wave_sum(t);
+      __syncthreads();
+      if ((tid & 63) == 0) s_red[tid >> 6] = t;
+      __syncthreads();
+      if (tid == 0) s_tot[f][k] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+    }
+  double en = 0.0;
+  for (int b = tid; b < a.n_blocks; b += 256) en += a.energy_part[b];
+  en = wave_sum(en);
+  __syncthreads();
+  if ((tid & 63) == 0) s_red[tid >> 6] = en;
+  __syncthreads();
+  if (tid == 0) {
+    for (int f = 0; f < NF; ++f) {
+      double best = __builtin_inf();
+      int bk = 0;
+      for (int k = 0; k < K; ++k)
+        if (s_tot[f][k] < best) { best = s_tot[f][k]; bk = k; }
+      a.rec.scale[f][0] = unit_scale(amax, a.clip[bk], f == 0 ? Codec<FA>::QMAX : Codec<FBX>::QMAX,
+                                     a.scale_f16 != 0);
+      a.rec.clip[f][0] = bk;
+      a.rec.err[f][0] = best;
+    }
+    if (a.rec.energy) a.rec.energy[0] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+  }
+}
+
+// ---- dispatch ---------------------------------------------------------------------
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+template <typename In, int FA, int FB>
+int launch_channel(const SweepArgs& a, hipStream_t st) {
+  const dim3 grid(static_cast<unsigned>(a.rows));
+  const int64_t chunks = a.cols / 8;
+#define MOFQ_CH(THREADS, CH)                                                            \
+  if (chunks <= static_cast<int64_t>(THREADS) * (CH)) {                                  \
+    hipLaunchKernelGGL((sweep_channel_kernel<In, FA, FB, THREADS, CH>), grid, dim3(THREADS), 0, st, a); \
+    return hip_status(hipGetLastError());                                                \
+  }
+  MOFQ_CH(256, 1)    //  2048 columns
+  MOFQ_CH(256, 2)    //  4096
+  MOFQ_CH(256, 4)    //  8192
+  MOFQ_CH(256, 6)    // 12288
+  MOFQ_CH(512, 6)    // 24576
+  MOFQ_CH(1024, 4)   // 32768
+#undef MOFQ_CH
+  return MOFQ_ERR_UNSUPPORTED;
+}
+
+template <typename In, int FA, int FB>
+int launch_group(const SweepArgs& a, hipStream_t st) {
+  const dim3 grid(static_cast<unsigned>(ceil_div(a.units, 64)));
+  switch (a.group) {
+#define MOFQ_G(G)                                                                        \
+  case G:                                                                                \
+    hipLaunchKernelGGL((sweep_group_kernel<In, FA, FB, G>), grid, dim3(256), 0, st, a);  \
+    return hip_status(hipGetLastError());
+    MOFQ_G(32)
+    MOFQ_G(64)
+    MOFQ_G(128)
+    MOFQ_G(256)
+#undef MOFQ_G
+  }
+  return MOFQ_ERR_UNSUPPORTED;
+}
+
+template <typename In, int FA, int FB>
+int launch_tensor(SweepArgs a, hipStream_t st) {
+  if (a.n_clip > kTensorMaxClip) return MOFQ_ERR_UNSUPPORTED;
+  const int64_t n_chunks = a.rows * (a.cols / 8);
+  a.n_blocks = static_cast<int32_t>(std::min<int64_t>(kTensorBlocks, ceil_div(n_chunks, 256)));
+  hipLaunchKernelGGL((tensor_absmax_kernel<In>), dim3(a.n_blocks), dim3(256), 0, st, a);
+  hipLaunchKernelGGL((tensor_score_kernel<In, FA, FB>), dim3(a.n_blocks), dim3(256), 0, st, a);
+  hipLaunchKernelGGL((tensor_finalize_kernel<FA, FB>), dim3(1), dim3(256), 0, st, a);
+  return hip_status(hipGetLastError());
+}
+
+template <typename In, int FA, int FB>
+int launch_gran(const SweepParams& p, const SweepArgs& a, hipStream_t st) {
+  switch (p.gran) {
+    case MOFQ_PER_CHANNEL: return launch_channel<In, FA, FB>(a, st);
+    case MOFQ_PER_GROUP: return launch_group<In, FA, FB>(a, st);
+    case MOFQ_PER_TENSOR: return launch_tensor<In, FA, FB>(a, st);
+  }
+  return MOFQ_ERR_INVALID_ARG;
+}
+
+template <typename In>
+int launch_fmt(const SweepParams& p, const SweepArgs& a, hipStream_t st) {
+  const int fa = p.fmt[0], fb = p.n_fmt == 2 ? p.fmt[1] : -1;
+#define MOFQ_F(A, B) \
+  if (fa == (A) && fb == (B)) return launch_gran<In, A, B>(p, a, st);
+  MOFQ_F(MOFQ_INT4, -1)
+  MOFQ_F(MOFQ_FP4_E2M1, -1)
+  MOFQ_F(MOFQ_INT8, -1)
+  MOFQ_F(MOFQ_FP8_E4M3, -1)
+  MOFQ_F(MOFQ_INT4, MOFQ_FP4_E2M1)   // pairs come in (INT, FP) order; the caller maps slots
+  MOFQ_F(MOFQ_INT8, MOFQ_FP8_E4M3)
+#undef MOFQ_F
+  return MOFQ_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+int launch_sweep(const SweepParams& p, hipStream_t st) {
+  SweepArgs a{};
+  a.w = p.w;
+  a.rows = p.rows;
+  a.cols = p.cols;
+  a.ld = p.ld;
+  a.group = p.group;
+  a.scale_f16 = p.scale_f16;
+  a.n_clip = p.n_clip;
+  a.rec = p.rec;
+  a.absmax_part = p.absmax_part;
+  a.sse_part = p.sse_part;
+  a.energy_part = p.energy_part;
+  a.units = mofq_num_units(p.rows, p.cols, p.gran, p.group);
+  for (int k = 0; k < p.n_clip; ++k) a.clip[k] = p.clip[k];
+  if (a.units <= 0) return MOFQ_ERR_INVALID_ARG;
+  // same format twice in one launch is handled as two single launches by the caller
+  switch (p.dtype) {
+    case MOFQ_F32: return launch_fmt<F32>(p, a, st);
+    case MOFQ_F16: return launch_fmt<F16>(p, a, st);
+    case MOFQ_BF16: return launch_fmt<BF16>(p, a, st);
+  }
+  return MOFQ_ERR_INVALID_ARG;
+}
+
+}  // namespace mofq

@@ -1,0 +1,106 @@
+"""The C-ABI library loads on a host without a GPU and exports every symbol that
+include/mofq.h declares; host-only entry points and argument validation (which
+happens before anything is enqueued) behave as documented."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2305_12356_amd import build as b
+    if not os.path.exists(b.LIB):
+        b.build()
+    from paper_2305_12356_amd import binding
+    return binding
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "mofq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mofq_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(lib):
+    names = _declared()
+    assert {"mofq_quantize", "mofq_score", "mofq_select_layer", "mofq_workspace_bytes",
+            "mofq_num_units", "mofq_status_string"} <= set(names)
+    raw = C.CDLL(lib.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), n
+
+
+def test_struct_layout_matches_header(lib):
+    assert C.sizeof(lib.TensorDesc) == 40
+    assert C.sizeof(lib.ScaleCfg) == 24
+    assert C.sizeof(lib.QOut) == 32
+    assert C.sizeof(lib.Result) == 8 + 8 * 4 + 8
+
+
+def test_num_units_and_status_strings(lib):
+    assert lib.num_units(4096, 11008, lib.PER_CHANNEL) == 4096
+    assert lib.num_units(4096, 11008, lib.PER_GROUP, 128) == 4096 * 86
+    assert lib.num_units(4096, 11008, lib.PER_TENSOR) == 1
+    assert lib.num_units(4096, 11000, lib.PER_GROUP, 128) == -1
+    assert lib.num_units(0, 8, lib.PER_CHANNEL) == -1
+    for s in (0, -1, -2, -3, -4, -5):
+        assert lib.status_string(s) and "unknown" not in lib.status_string(s)
+    assert "unknown" in lib.status_string(-99)
+
+
+def test_host_side_validation_without_gpu(lib):
+    """Errors are detected on the host before anything is enqueued."""
+    L = lib._lib
+    clip = np.ones(1, dtype=np.float32)
+    cfg = lib.ScaleCfg(lib.PER_CHANNEL, 0, lib.F32, 1, clip.ctypes.data_as(C.POINTER(C.c_float)))
+    good = lib.TensorDesc(0x1000, lib.F16, 16, 64, 64)
+    out = lib.QOut(0x2000, 0x3000, None, None)
+    ws = C.c_void_p(0x4000)
+    # null tensor, null data
+    assert L.mofq_quantize(None, 0, C.byref(cfg), C.byref(out), None, ws, 1 << 20, None) == -1
+    bad = lib.TensorDesc(None, lib.F16, 16, 64, 64)
+    assert L.mofq_quantize(C.byref(bad), 0, C.byref(cfg), C.byref(out), None, ws, 1 << 20, None) == -1
+    # cols not a multiple of 8, misaligned data
+    bad = lib.TensorDesc(0x1000, lib.F16, 16, 60, 64)
+    assert L.mofq_quantize(C.byref(bad), 0, C.byref(cfg), C.byref(out), None, ws, 1 << 20, None) == -3
+    bad = lib.TensorDesc(0x1004, lib.F16, 16, 64, 64)
+    assert L.mofq_quantize(C.byref(bad), 0, C.byref(cfg), C.byref(out), None, ws, 1 << 20, None) == -3
+    # unknown format, too many clip ratios, bad ratio
+    assert L.mofq_quantize(C.byref(good), 9, C.byref(cfg), C.byref(out), None, ws, 1 << 20, None) == -1
+    cfg2 = lib.ScaleCfg(lib.PER_CHANNEL, 0, lib.F32, 1000, clip.ctypes.data_as(C.POINTER(C.c_float)))
+    assert L.mofq_quantize(C.byref(good), 0, C.byref(cfg2), C.byref(out), None, ws, 1 << 20, None) == -1
+    zero = np.zeros(1, dtype=np.float32)
+    cfg3 = lib.ScaleCfg(lib.PER_CHANNEL, 0, lib.F32, 1, zero.ctypes.data_as(C.POINTER(C.c_float)))
+    assert L.mofq_quantize(C.byref(good), 0, C.byref(cfg3), C.byref(out), None, ws, 1 << 20, None) == -1
+    # group size that does not divide the row
+    cfg4 = lib.ScaleCfg(lib.PER_GROUP, 128, lib.F32, 1, clip.ctypes.data_as(C.POINTER(C.c_float)))
+    assert L.mofq_quantize(C.byref(good), 0, C.byref(cfg4), C.byref(out), None, ws, 1 << 20, None) == -2
+    # workspace too small / missing
+    assert L.mofq_quantize(C.byref(good), 0, C.byref(cfg), C.byref(out), None, ws, 16, None) == -4
+    assert L.mofq_quantize(C.byref(good), 0, C.byref(cfg), C.byref(out), None, None, 1 << 20, None) == -4
+    # candidates of different bit-widths
+    cands = (C.c_int32 * 2)(lib.INT4, lib.FP8_E4M3)
+    res = C.c_void_p(0x5000)
+    assert L.mofq_select_layer(C.byref(good), None, cands, 2, lib.ERR_TENSOR, C.byref(cfg),
+                               C.byref(out), None, res, ws, 1 << 20, None) == -1
+    # weight-only select with the layer-output metric
+    cands = (C.c_int32 * 2)(lib.INT4, lib.FP4_E2M1)
+    assert L.mofq_select_layer(C.byref(good), None, cands, 2, lib.ERR_LAYER_OUTPUT, C.byref(cfg),
+                               C.byref(out), None, res, ws, 1 << 20, None) == -1
+
+
+def test_workspace_bytes_host_only(lib):
+    L = lib._lib
+    clip = np.ones(4, dtype=np.float32)
+    cfg = lib.ScaleCfg(lib.PER_GROUP, 128, lib.F16, 4, clip.ctypes.data_as(C.POINTER(C.c_float)))
+    t = lib.TensorDesc(0x1000, lib.F16, 4096, 11008, 11008)
+    n1 = L.mofq_workspace_bytes(C.byref(t), None, 1, lib.ERR_TENSOR, C.byref(cfg))
+    n2 = L.mofq_workspace_bytes(C.byref(t), None, 2, lib.ERR_TENSOR, C.byref(cfg))
+    units = 4096 * 86
+    assert n1 >= units * (4 + 4 + 8 + 8) and n2 >= units * (2 * 16 + 8) and n2 > n1
+    assert L.mofq_workspace_bytes(C.byref(t), None, 0, lib.ERR_TENSOR, C.byref(cfg)) == 0
