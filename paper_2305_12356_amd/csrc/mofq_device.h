@@ -41,16 +41,14 @@ template <> struct Load8<F32> {
   }
 };
 
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
 template <> struct Load8<F16> {
   using elem = uint16_t;
   MOFQ_DEV static void load(const elem* p, float (&v)[8]) {
-    const u32x4 a = *reinterpret_cast<const u32x4*>(p);
+    const f16x8 h = *reinterpret_cast<const f16x8*>(p);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const __half2 h = __builtin_bit_cast(__half2, a[i]);
-      v[2 * i] = __low2float(h);      // fp16 -> fp32 is exact (subnormals included)
-      v[2 * i + 1] = __high2float(h);
-    }
+    for (int i = 0; i < 8; ++i) v[i] = static_cast<float>(h[i]);  // exact, subnormals included
   }
 };
 
