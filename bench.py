@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--model", default="7b", choices=["7b"])
     ap.add_argument("--blocks", type=int, default=0, help="debug: use only the first N blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -155,30 +157,35 @@ def main():
     elem_cand = n_elems * N_CLIP * N_FMT
     value = elem_cand / (elapsed / args.steps)
 
-    # ---- dominant kernel: the scale search of the 11008-wide / 11008-row tensors ---
-    # (gate, up, down: two thirds of all elements; one kernel instance, one launch per
-    # tensor).  Duration from the HIP events the library recorded around each launch.
-    by_shape = {}
+    # ---- dominant kernel: the scale-search instance for 4096-column rows ------------
+    # (q, k, v, o, gate, up: 78 % of all elements; one launch per tensor).  Duration
+    # from the HIP events the library recorded around each launch.
+    by_cols = {}
     for i, e0, e1 in events:
         _, _, o, n = shapes[i]
-        key = "wide" if n > 8192 else ("ffn" if o > 8192 else "attn")
-        by_shape.setdefault(key, []).append((o * n, e0.elapsed_time(e1) * 1e-3))
-    dom = by_shape.get("wide", []) + by_shape.get("ffn", [])
-    if not dom:
-        dom = by_shape["attn"]
+        by_cols.setdefault(n, []).append((o * n, e0.elapsed_time(e1) * 1e-3))
+    dom_cols = max(by_cols, key=lambda c: sum(e for e, _ in by_cols[c]))
+    dom = by_cols[dom_cols]
     dom_flops = sum(e for e, _ in dom) * N_CLIP * N_FMT * FLOPS_PER_ELEM_CAND_FMT
     dom_time = sum(t for _, t in dom)
     achieved = dom_flops / dom_time / 1e12
-    search_time = sum(t for v in by_shape.values() for _, t in v) / args.steps
+    search_time = sum(t for v in by_cols.values() for _, t in v) / args.steps
     roofline = {
         "bound": "alu", "achieved": achieved, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
         "frac": achieved / ALU_PEAK_TFLOPS, "traffic": None,
-        "kernel": "sweep_channel_kernel (fp16, INT4+E2M1) on the 11008x4096 / 4096x11008 tensors",
+        "kernel": f"sweep_channel_kernel<F16, INT4, FP4_E2M1> instance for {dom_cols}-column rows",
         "avg_launch_ms": dom_time / len(dom) * 1e3, "launches": len(dom),
         "flops_per_elem_cand_fmt": FLOPS_PER_ELEM_CAND_FMT,
         "hbm_GBps_at_this_rate": sum(e for e, _ in dom) * 2 / dom_time / 1e9,
         "search_ms_per_step": search_time * 1e3,
     }
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     res = mq.read_results(results)
     fp_pct = 100.0 * sum(1 for r in res if r.best == 1) / len(res)
