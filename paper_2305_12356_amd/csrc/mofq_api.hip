@@ -144,6 +144,118 @@ int check_candidates(const int32_t* cand, int n) {
   return MOFQ_OK;
 }
 
+
+// ---- weight-activation (layer-output metric) ------------------------------------
+
+const float kOne = 1.0f;
+
+mofq_scale_cfg_t x_cfg() {   // activations: per-tensor, no clip search (Section 3.2)
+  mofq_scale_cfg_t c{};
+  c.gran = MOFQ_PER_TENSOR;
+  c.group_size = 0;
+  c.scale_dtype = MOFQ_F32;
+  c.n_clip = 1;
+  c.clip_ratios = &kOne;
+  return c;
+}
+
+int check_wa(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand, int n_cand,
+             const mofq_scale_cfg_t* w_cfg) {
+  int rc = check_tensor(x);
+  if (rc) return rc;
+  if (x->cols != w->cols) return MOFQ_ERR_INVALID_ARG;
+  for (int c = 0; c < n_cand; ++c)
+    if (!is8(cand[c])) return MOFQ_ERR_UNSUPPORTED;          // low-bit matmul units are 8-bit
+  if (w->dtype != MOFQ_BF16 || x->dtype != MOFQ_BF16) return MOFQ_ERR_UNSUPPORTED;
+  if (w_cfg->n_clip != 1 || w_cfg->scale_dtype != MOFQ_F32) return MOFQ_ERR_UNSUPPORTED;
+  if (w_cfg->gran != MOFQ_PER_TENSOR && w_cfg->gran != MOFQ_PER_CHANNEL) return MOFQ_ERR_UNSUPPORTED;
+  if (w->cols % 64 != 0) return MOFQ_ERR_UNSUPPORTED;
+  if (w->rows > (1 << 30) || x->rows > (1 << 30) || w->cols > 32768) return MOFQ_ERR_UNSUPPORTED;
+  return MOFQ_OK;
+}
+
+struct WaWs {
+  WOnlyWs xrec, wrec;
+  uint8_t* xq[2];   // [0] INT8 codes, [1] E4M3 codes (fp8-unit mode) or bf16 grid values
+  uint8_t* wq[2];
+  double* part[3];  // INT8 error, E4M3 error, reference energy; one value per output tile
+  int blocks;
+  size_t bytes;
+};
+
+WaWs carve_wa(void* ws, const mofq_tensor_t* w, const mofq_tensor_t* x, int n_cand, int w_gran) {
+  WaWs a{};
+  const int64_t units_w = mofq_num_units(w->rows, w->cols, w_gran, 0);
+  a.xrec = carve_w_only(ws, 1, n_cand, MOFQ_PER_TENSOR, 1);
+  char* base = static_cast<char*>(ws);
+  size_t off = a.xrec.bytes;
+  a.wrec = carve_w_only(base ? base + off : nullptr, units_w, n_cand, w_gran, 1);
+  off += a.wrec.bytes;
+  Carver c(base ? base + off : nullptr);
+  for (int f = 0; f < 2; ++f) {
+    a.xq[f] = c.take<uint8_t>(static_cast<size_t>(x->rows) * x->cols * (f ? 2 : 1));
+    a.wq[f] = c.take<uint8_t>(static_cast<size_t>(w->rows) * w->cols * (f ? 2 : 1));
+  }
+  a.blocks = wa_gemm_blocks(x->rows, w->rows);
+  for (int i = 0; i < 3; ++i) a.part[i] = c.take<double>(a.blocks);
+  a.bytes = off + (c.off + kAlign - 1) / kAlign * kAlign;
+  return a;
+}
+
+// Quantize X and W in every candidate format, then one pass over the matrix cores
+// that leaves per-tile partial errors in the workspace.
+int wa_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand, int n_cand,
+             const mofq_scale_cfg_t* w_cfg, bool fp8_unit, const WaWs& a, hipStream_t st,
+             hipEvent_t ev0, hipEvent_t ev1) {
+  const mofq_scale_cfg_t xc = x_cfg();
+  int rc;
+  if ((rc = sweep_candidates(x, cand, n_cand, &xc, a.xrec, st))) return rc;
+  if ((rc = sweep_candidates(w, cand, n_cand, w_cfg, a.wrec, st))) return rc;
+  WaGemmParams g{};
+  for (int f = 0; f < 2; ++f) {
+    const int fmt = f == 0 ? MOFQ_INT8 : MOFQ_FP8_E4M3;
+    int slot = -1;
+    for (int c = n_cand - 1; c >= 0; --c)
+      if (cand[c] == fmt) slot = c;
+    if (slot < 0) continue;
+    for (int which = 0; which < 2; ++which) {   // 0: X, 1: W
+      const mofq_tensor_t* t = which ? w : x;
+      const WOnlyWs& rec = which ? a.wrec : a.xrec;
+      EmitParams e{};
+      e.w = t->data;
+      e.dtype = t->dtype;
+      e.rows = t->rows;
+      e.cols = t->cols;
+      e.ld = t->ld;
+      e.gran = which ? w_cfg->gran : MOFQ_PER_TENSOR;
+      e.group = 0;
+      e.n_cand = 1;
+      e.fmt[0] = fmt;
+      e.scale[0] = rec.scale[slot];
+      e.clip[0] = rec.clip[slot];
+      e.err[0] = rec.err[slot];
+      e.result = nullptr;
+      e.out.codes = which ? a.wq[f] : a.xq[f];
+      e.as_bf16_values = (f == 1 && !fp8_unit);
+      if ((rc = launch_emit(e, st))) return rc;
+    }
+    if (f == 0) { g.xi = a.xq[0]; g.wi = a.wq[0]; g.sx_i = a.xrec.scale[slot]; g.sw_i = a.wrec.scale[slot]; g.part_i = a.part[0]; }
+    else {
+      if (fp8_unit) { g.xf = a.xq[1]; g.wf = a.wq[1]; } else { g.xg = a.xq[1]; g.wg = a.wq[1]; }
+      g.sx_f = a.xrec.scale[slot]; g.sw_f = a.wrec.scale[slot]; g.part_f = a.part[1];
+    }
+  }
+  g.x = x->data; g.ldx = x->ld;
+  g.w = w->data; g.ldw = w->ld;
+  g.w_per_channel = w_cfg->gran == MOFQ_PER_CHANNEL;
+  g.M = x->rows; g.N = w->rows; g.K = w->cols;
+  g.part_p = a.part[2];
+  if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return MOFQ_ERR_HIP;
+  if ((rc = launch_wa_gemm(g, st))) return rc;
+  if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return MOFQ_ERR_HIP;
+  return MOFQ_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -179,6 +291,10 @@ size_t mofq_workspace_bytes(const mofq_tensor_t* w, const mofq_tensor_t* x, int3
   if (units <= 0 || w_cfg->n_clip < 1 || w_cfg->n_clip > MOFQ_MAX_CLIP) return 0;
   if (metric == MOFQ_ERR_TENSOR && !x)
     return carve_w_only(nullptr, units, n_candidates, w_cfg->gran, w_cfg->n_clip).bytes;
+  if ((metric == MOFQ_ERR_LAYER_OUTPUT || metric == MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT) && x &&
+      x->rows > 0 && x->cols == w->cols &&
+      (w_cfg->gran == MOFQ_PER_TENSOR || w_cfg->gran == MOFQ_PER_CHANNEL))
+    return carve_wa(nullptr, w, x, n_candidates, w_cfg->gran).bytes;
   return 0;
 }
 
@@ -246,7 +362,23 @@ int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, i
     d.energy_out = ref_energy;
     return launch_decide(d, st);
   }
-  if (metric == MOFQ_ERR_LAYER_OUTPUT) return MOFQ_ERR_UNSUPPORTED;
+  if (metric == MOFQ_ERR_LAYER_OUTPUT || metric == MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT) {
+    if (!x) return MOFQ_ERR_INVALID_ARG;
+    if ((rc = check_wa(w, x, &format, 1, w_cfg))) return rc;
+    const WaWs a = carve_wa(ws, w, x, 1, w_cfg->gran);
+    if (!ws || ws_bytes < a.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+    if ((rc = wa_score(w, x, &format, 1, w_cfg, metric == MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT, a, st,
+                       nullptr, nullptr)))
+      return rc;
+    DecideParams d{};
+    d.units = a.blocks;
+    d.n_cand = 1;
+    d.err[0] = format == MOFQ_INT8 ? a.part[0] : a.part[1];
+    d.energy = a.part[2];
+    d.tensor_err_out = err;
+    d.energy_out = ref_energy;
+    return launch_decide(d, st);
+  }
   return MOFQ_ERR_INVALID_ARG;
 }
 
@@ -309,8 +441,48 @@ int mofq_select_layer_timed(const mofq_tensor_t* w, const mofq_tensor_t* x,
     e.out = *w_out;
     return launch_emit(e, st);
   }
-  if (metric != MOFQ_ERR_LAYER_OUTPUT) return MOFQ_ERR_INVALID_ARG;
-  return MOFQ_ERR_UNSUPPORTED;
+  if (metric != MOFQ_ERR_LAYER_OUTPUT && metric != MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT)
+    return MOFQ_ERR_INVALID_ARG;
+  if ((rc = check_wa(w, x, candidates, n_candidates, w_cfg))) return rc;
+  if (x_out && (rc = check_out(x_out, true))) return rc;
+  const WaWs a = carve_wa(ws, w, x, n_candidates, w_cfg->gran);
+  if (!ws || ws_bytes < a.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+  if ((rc = wa_score(w, x, candidates, n_candidates, w_cfg,
+                     metric == MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT, a, st, ev0, ev1)))
+    return rc;
+  DecideParams d{};
+  d.units = a.blocks;
+  d.n_cand = n_candidates;
+  for (int c = 0; c < n_candidates; ++c) d.err[c] = candidates[c] == MOFQ_INT8 ? a.part[0] : a.part[1];
+  d.energy = a.part[2];
+  d.result = result;
+  if ((rc = launch_decide(d, st))) return rc;
+  // second quantize_layer call of Algorithm 1: W and X in the chosen format
+  for (int which = 0; which < 2; ++which) {
+    const mofq_tensor_t* t = which ? w : x;
+    const mofq_qout_t* o = which ? w_out : x_out;
+    if (!o) continue;
+    const WOnlyWs& rec = which ? a.wrec : a.xrec;
+    EmitParams e{};
+    e.w = t->data;
+    e.dtype = t->dtype;
+    e.rows = t->rows;
+    e.cols = t->cols;
+    e.ld = t->ld;
+    e.gran = which ? w_cfg->gran : MOFQ_PER_TENSOR;
+    e.group = 0;
+    e.n_cand = n_candidates;
+    for (int c = 0; c < n_candidates; ++c) {
+      e.fmt[c] = candidates[c];
+      e.scale[c] = rec.scale[c];
+      e.clip[c] = rec.clip[c];
+      e.err[c] = rec.err[c];
+    }
+    e.result = result;
+    e.out = *o;
+    if ((rc = launch_emit(e, st))) return rc;
+  }
+  return MOFQ_OK;
 }
 
 }  // extern "C"

@@ -91,6 +91,7 @@ struct EmitArgs {
   const double* err[MOFQ_MAX_CANDIDATES];
   const mofq_result_t* result;
   mofq_qout_t out;
+  int32_t as_bf16_values;   // write dequantised grid values (bf16, unscaled) instead of codes
 };
 
 MOFQ_DEV int chosen(const EmitArgs& a) {
@@ -125,7 +126,23 @@ __global__ __launch_bounds__(256) void emit_codes_kernel(const EmitArgs a) {
       default: encode8<MOFQ_FP8_E4M3>(v, inv_s, words); break;
     }
     const int64_t e0 = row * a.cols + col;   // dense output rows
-    if (four) {
+    if (a.as_bf16_values) {
+      // 8-bit grid values have at most 7 significant bits: exact in bf16 (top half of fp32)
+      u32x4 o;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float g0, g1;
+        if (fmt == MOFQ_INT8) {
+          g0 = Codec<MOFQ_INT8>::grid(v[2 * i] * inv_s);
+          g1 = Codec<MOFQ_INT8>::grid(v[2 * i + 1] * inv_s);
+        } else {
+          g0 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i] * inv_s);
+          g1 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i + 1] * inv_s);
+        }
+        o[i] = (f2u(g0) >> 16) | (f2u(g1) & 0xFFFF0000u);
+      }
+      reinterpret_cast<u32x4*>(a.out.codes)[e0 / 8] = o;
+    } else if (four) {
       static_cast<uint32_t*>(a.out.codes)[e0 / 8] = words[0];
     } else {
       u32x2 o;
@@ -176,6 +193,8 @@ int launch_emit(const EmitParams& p, hipStream_t st) {
   }
   a.result = p.result;
   a.out = p.out;
+  a.as_bf16_values = p.as_bf16_values;
+  if (p.as_bf16_values && !(p.fmt[0] == MOFQ_INT8 || p.fmt[0] == MOFQ_FP8_E4M3)) return MOFQ_ERR_INVALID_ARG;
   a.units = mofq_num_units(p.rows, p.cols, p.gran, p.group);
   if (a.units <= 0) return MOFQ_ERR_INVALID_ARG;
   const int64_t n_chunks = p.rows * (p.cols / 8);

@@ -71,8 +71,26 @@ struct EmitParams {
   const double* err[MOFQ_MAX_CANDIDATES];
   const mofq_result_t* result;   // device, may be nullptr (then candidate 0)
   mofq_qout_t out;
+  int32_t as_bf16_values;        // 8-bit formats: out.codes receives the grid values as bf16
 };
 int launch_emit(const EmitParams& p, hipStream_t stream);
+
+// Layer-output error of one linear layer: partial sums per 128x128 output tile.
+// A null xi/wi (or xf/wf) pair skips that format.
+struct WaGemmParams {
+  const void* x; int64_t ldx;      // bf16 [M][K]
+  const void* w; int64_t ldw;      // bf16 [N][K]
+  const uint8_t* xi; const uint8_t* wi;   // INT8 codes, dense rows
+  const uint8_t* xf; const uint8_t* wf;   // E4M3 codes, dense rows (fp8 matrix cores)
+  const void* xg; const void* wg;         // or: E4M3 grid values as bf16, dense rows (exact product)
+  const float* sx_i; const float* sw_i;   // device scales (sw: 1 or N values)
+  const float* sx_f; const float* sw_f;
+  int32_t w_per_channel;
+  int64_t M, N, K;
+  double* part_i; double* part_f; double* part_p;   // [wa_gemm_blocks(M, N)]
+};
+int wa_gemm_blocks(int64_t M, int64_t N);
+int launch_wa_gemm(const WaGemmParams& p, hipStream_t stream);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? MOFQ_OK : MOFQ_ERR_HIP; }
 

@@ -1,0 +1,183 @@
+"""GPU parity of the weight-activation path (per-tensor / per-channel 8-bit
+quantization of W and X, layer-output error through the matrix cores, select)
+against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import mofq_inputs as mi
+from oracle import mofq_oracle as orc
+from tests.gpu_util import scales_to_f32, unpack_codes
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+I8, FP8 = orc.INT8, orc.FP8_E4M3
+# fp32 accumulation inside the matrix cores (the oracle adds in fp64): K <= 11008
+# terms, relative error of a sum ~ sqrt(K)*2^-24 of |Y|, and the quantization
+# differences are >= 1e-2 |Y|, so error sums agree to ~1e-6; the target is 1e-5.
+E_RTOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def mq():
+    from paper_2305_12356_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def run_wa_select(mq, x, w, cands, w_gran):
+    cfg = mq.Cfg(w_gran, mi.clip_ratios(1))
+    xcfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
+    w_out = mq.alloc_qbuffers(w.shape[0], w.shape[1], 8, cfg, DEV)
+    x_out = mq.alloc_qbuffers(x.shape[0], x.shape[1], 8, xcfg, DEV)
+    res = mq.alloc_result(DEV)
+    n = mq.workspace_bytes(w, x, len(cands), mq.ERR_LAYER_OUTPUT, cfg)
+    assert n > 0
+    ws = torch.empty(n, dtype=torch.uint8, device=DEV)
+    mq.select_layer(w, x, cands, mq.ERR_LAYER_OUTPUT, cfg, w_out, x_out, res, ws)
+    torch.cuda.synchronize()
+    return mq.read_result(res), w_out, x_out
+
+
+def run_wa_score(mq, x, w, fmt, w_gran):
+    cfg = mq.Cfg(w_gran, mi.clip_ratios(1))
+    err = torch.zeros(1, dtype=torch.float64, device=DEV)
+    en = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ws = torch.empty(mq.workspace_bytes(w, x, 1, mq.ERR_LAYER_OUTPUT, cfg), dtype=torch.uint8, device=DEV)
+    mq.score(w, x, fmt, mq.ERR_LAYER_OUTPUT, cfg, err, en, ws)
+    torch.cuda.synchronize()
+    return err.item(), en.item()
+
+
+def check_layer(mq, x, w, cands, w_gran, label):
+    print(f"[case] {label} X={tuple(x.shape)} W={tuple(w.shape)} w_gran={w_gran} cands={cands}", flush=True)
+    x32, w32 = mi.to_f32_numpy(x), mi.to_f32_numpy(w)
+    ref = orc.select_layer_wa(x32, w32, cands, w_gran)
+    r, w_out, x_out = run_wa_select(mq, x, w, cands, w_gran)
+    assert r.n == len(cands)
+    assert np.allclose(list(r.err)[:len(cands)], ref.errs, rtol=E_RTOL, atol=1e-300), (list(r.err), ref.errs)
+    assert np.isclose(r.ref_energy, ref.ref_energy, rtol=E_RTOL)
+    assert r.best == ref.best
+    # codes and scales of the winner, bit for bit
+    assert np.array_equal(unpack_codes(w_out.codes, *w.shape, 8), ref.w.codes)
+    assert np.array_equal(unpack_codes(x_out.codes, *x.shape, 8), ref.x.codes)
+    assert np.array_equal(scales_to_f32(w_out.scales), ref.w.scale)
+    assert np.array_equal(scales_to_f32(x_out.scales), ref.x.scale)
+    assert np.allclose(w_out.unit_err.cpu().numpy(), ref.w.unit_err, rtol=1e-9, atol=1e-300)
+    for f in set(cands):
+        e, p = run_wa_score(mq, x, w, f, w_gran)
+        assert np.isclose(e, ref.errs[cands.index(f)], rtol=E_RTOL, atol=1e-300)
+        assert np.isclose(p, ref.ref_energy, rtol=E_RTOL)
+    return r
+
+
+@pytest.mark.parametrize("w_gran", [orc.PER_TENSOR, orc.PER_CHANNEL])
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (200, 300, 256), (96, 520, 1024), (257, 129, 11008)])
+def test_layer_output_ragged_tiles(mq, w_gran, M, N, K):
+    x = mi.activations(M, K, seed=300 + M, device=DEV)
+    w = mi.llama_like_weight(N, K, seed=400 + N, dtype=torch.bfloat16, device=DEV)
+    check_layer(mq, x, w, [I8, FP8], w_gran, "ragged")
+
+
+def test_candidate_orders(mq):
+    x = mi.activations(130, 512, seed=20, device=DEV)
+    w = mi.llama_like_weight(140, 512, seed=21, dtype=torch.bfloat16, device=DEV)
+    check_layer(mq, x, w, [FP8, I8], orc.PER_TENSOR, "reversed")
+    check_layer(mq, x, w, [FP8], orc.PER_CHANNEL, "single-fp8")
+    check_layer(mq, x, w, [I8], orc.PER_TENSOR, "single-int8")
+
+
+def test_tame_activations_prefer_int8(mq):
+    x = mi.activations(256, 1024, seed=22, n_outlier=0, device=DEV)
+    w = mi.llama_like_weight(384, 1024, seed=23, dtype=torch.bfloat16, device=DEV)
+    r = check_layer(mq, x, w, [I8, FP8], orc.PER_CHANNEL, "tame")
+    assert r.best == 0
+
+
+def test_small_integers_exact(mq):
+    """Small-integer operands: every product and sum is exact in every precision, so
+    the INT8 error is exactly zero and the energy equals the integer sum."""
+    g = torch.Generator().manual_seed(5)
+    M, N, K = 150, 170, 192
+    x = torch.randint(-5, 6, (M, K), generator=g).float()
+    w = torch.randint(-5, 6, (N, K), generator=g).float()
+    x[0, 0] = 127.0
+    w[0, 0] = 127.0
+    r, _, _ = run_wa_select(mq, x.to(torch.bfloat16).to(DEV), w.to(torch.bfloat16).to(DEV), [I8, FP8], orc.PER_TENSOR)
+    y = x.double() @ w.double().T
+    assert list(r.err)[0] == 0.0 and r.best == 0
+    assert r.ref_energy == float((y * y).sum())
+
+
+@pytest.mark.parametrize("fmt", [I8, FP8])
+def test_on_grid_with_per_channel_power_of_two_scales(mq, fmt):
+    """W rows on the 8-bit grid with a different power-of-two scale per row, X on the
+    grid: the error is exactly zero only if each output column meets its own scale."""
+    rng = np.random.default_rng(6)
+    M, N, K = 160, 200, 128
+    if fmt == I8:
+        gx = rng.integers(-127, 128, size=(M, K)).astype(np.float64)
+        gw = rng.integers(-127, 128, size=(N, K)).astype(np.float64)
+        top = 127.0
+    else:
+        gx = orc.decode_array(fmt, rng.integers(0, 127, size=(M, K))) * rng.choice([-1.0, 1.0], size=(M, K))
+        gw = orc.decode_array(fmt, rng.integers(0, 127, size=(N, K))) * rng.choice([-1.0, 1.0], size=(N, K))
+        top = 448.0
+    # 8-bit grid values have at most 7 significant bits: exact in bf16
+    gx[0, 0] = top
+    gw[:, 0] = top
+    e = rng.integers(-8, 1, size=N)
+    x = torch.from_numpy(gx * 2.0 ** -2).to(torch.bfloat16)
+    w = torch.from_numpy(gw * (2.0 ** e)[:, None]).to(torch.bfloat16)
+    assert np.array_equal(x.float().numpy(), (gx * 2.0 ** -2).astype(np.float32))
+    assert np.array_equal(w.float().numpy(), (gw * (2.0 ** e)[:, None]).astype(np.float32))
+    err, en = run_wa_score(mq, x.to(DEV), w.to(DEV), fmt, orc.PER_CHANNEL)
+    assert err == 0.0 and en > 0
+
+
+def test_fp8_unit_metric_is_close_but_not_exact(mq):
+    """The variant that runs the E4M3 product on the fp8 matrix cores: same INT8
+    error, FP8 error within the documented deviation of that unit (its internal
+    alignment truncates small addends), same decision on these inputs."""
+    x = mi.activations(384, 1024, seed=26, device=DEV)
+    w = mi.llama_like_weight(512, 1024, seed=27, dtype=torch.bfloat16, device=DEV)
+    ref = orc.select_layer_wa(mi.to_f32_numpy(x), mi.to_f32_numpy(w), [I8, FP8], orc.PER_TENSOR)
+    cfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
+    w_out = mq.alloc_qbuffers(512, 1024, 8, cfg, DEV)
+    res = mq.alloc_result(DEV)
+    ws = torch.empty(mq.workspace_bytes(w, x, 2, mq.ERR_LAYER_OUTPUT_FP8_UNIT, cfg), dtype=torch.uint8, device=DEV)
+    mq.select_layer(w, x, [I8, FP8], mq.ERR_LAYER_OUTPUT_FP8_UNIT, cfg, w_out, None, res, ws)
+    torch.cuda.synchronize()
+    r = mq.read_result(res)
+    assert np.isclose(r.err[0], ref.errs[0], rtol=E_RTOL)
+    assert np.isclose(r.err[1], ref.errs[1], rtol=2e-3)
+    print(f"fp8-unit deviation of the FP8 error sum: {r.err[1] / ref.errs[1] - 1:+.3e}", flush=True)
+    assert r.best == ref.best
+    assert np.array_equal(unpack_codes(w_out.codes, 512, 1024, 8), ref.w.codes)
+
+
+def test_llama_shaped_linear(mq):
+    """One full-size linear of the 7B shape: 2048 tokens x 4096 -> 4096."""
+    x = mi.activations(2048, 4096, seed=mi.tensor_seed(3, 0, 0, 1), device=DEV)
+    w = mi.llama_like_weight(4096, 4096, seed=mi.tensor_seed(3, 0, 0), dtype=torch.bfloat16, device=DEV)
+    r = check_layer(mq, x, w, [I8, FP8], orc.PER_TENSOR, "llama-q")
+    assert r.best == 1        # FP8 wins with outlier channels (Section 3.2)
+
+
+def test_wa_argument_errors(mq):
+    x = mi.activations(64, 128, seed=24, device=DEV)
+    w16 = mi.llama_like_weight(64, 128, seed=25, dtype=torch.float16, device=DEV)
+    wb = w16.to(torch.bfloat16)
+    cfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
+    err = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
+    with pytest.raises(mq.MofqError) as e:      # fp16 weights are not accepted for the bf16 reference product
+        mq.score(w16, x, I8, mq.ERR_LAYER_OUTPUT, cfg, err, None, ws)
+    assert e.value.status == -2
+    with pytest.raises(mq.MofqError) as e:      # 4-bit candidates have no matrix-core path
+        mq.score(wb, x, orc.INT4, mq.ERR_LAYER_OUTPUT, cfg, err, None, ws)
+    assert e.value.status == -2
+    with pytest.raises(mq.MofqError) as e:      # inner dimensions differ
+        mq.score(wb[:, :64].contiguous(), x, I8, mq.ERR_LAYER_OUTPUT, cfg, err, None, ws)
+    assert e.value.status == -1
