@@ -49,33 +49,106 @@ MOFQ_DEV void accumulate(double& acc, float x, double xd, float inv_s, double sd
   }
 }
 
+// ---- grid value of a scaled element, two elements at a time ---------------------
+//
+// FP formats use the gfx950 pack-convert instructions (round to nearest even,
+// subnormals, saturation); they agree with Codec<>::mag / code on every finite fp32
+// bit pattern (checked exhaustively on the part), and cost about half the vector
+// cycles of the add/subtract-constant form.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// `carry` is the register the fp4 encode merges its byte into; its other bytes are
+// never read, so it is simply handed from call to call (no clearing instruction).
+template <int FMT> MOFQ_DEV f32x2 grid2(float t0, float t1, uint32_t& carry) {
+  f32x2 g;
+  if constexpr (FMT == MOFQ_FP4_E2M1) {
+    carry = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(carry, t0, t1, 1.0f, 0);
+    g = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(carry, 1.0f, 0);
+  } else if constexpr (FMT == MOFQ_FP8_E4M3) {
+    const int p = __builtin_amdgcn_cvt_pk_fp8_f32(med3(t0, -448.0f, 448.0f), med3(t1, -448.0f, 448.0f), 0, false);
+    g = __builtin_amdgcn_cvt_pk_f32_fp8(p, false);
+  } else {
+    g[0] = Codec<FMT>::grid(t0);
+    g[1] = Codec<FMT>::grid(t1);
+  }
+  return g;
+}
+
+// Phase 1 of the search: squared error of two elements in fp32 (fused residual and
+// accumulation, relative error of a unit's sum below 60 * 2^-24).
+template <int FMT> MOFQ_DEV void score2_f32(float& acc, float x0, float x1, float inv_s, float s, uint32_t& carry) {
+  const f32x2 g = grid2<FMT>(x0 * inv_s, x1 * inv_s, carry);
+  const float d0 = __builtin_fmaf(-g[0], s, x0);
+  const float d1 = __builtin_fmaf(-g[1], s, x1);
+  acc = __builtin_fmaf(d0, d0, acc);
+  acc = __builtin_fmaf(d1, d1, acc);
+}
+
+// Phase 2: the same two elements with the residual and its square in fp64.
+template <int FMT> MOFQ_DEV void score2_f64(double& acc, float x0, float x1, float inv_s, double sd, uint32_t& carry) {
+  const f32x2 g = grid2<FMT>(x0 * inv_s, x1 * inv_s, carry);
+  const double d0 = __builtin_fma(-static_cast<double>(g[0]), sd, static_cast<double>(x0));
+  const double d1 = __builtin_fma(-static_cast<double>(g[1]), sd, static_cast<double>(x1));
+  acc = __builtin_fma(d0, d0, acc);
+  acc = __builtin_fma(d1, d1, acc);
+}
+
+// Sum over the wave in six DPP steps; the total is valid in lanes 48..63 only.
+MOFQ_DEV float wave_sum_f32_hi(float v) {
+  v += dpp_f32<DPP_QUAD_XOR1>(v);
+  v += dpp_f32<DPP_QUAD_XOR2>(v);
+  v += dpp_f32<DPP_ROW_HALF_MIRROR>(v);
+  v += dpp_f32<DPP_ROW_MIRROR>(v);           // every lane: sum of its row of 16
+  // rows 1 and 3 add the row before them, then rows 2 and 3 add lane 31 (rows 0+1)
+  v += u2f(static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(f2u(v)), 0x142, 0xA, 0xF, false)));
+  v += u2f(static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(f2u(v)), 0x143, 0xC, 0xF, false)));
+  return v;
+}
+
+// Candidates whose fp32 error is within this factor of the smallest fp32 error are
+// re-scored in fp64.  The fp32 sum of a unit is within (1 +- 60*2^-24) of the exact
+// sum for the same grid choices, so the fp64 winner is always among them.
+constexpr float kShortlistFactor = 1.0f + 1.0e-5f;
+// Below this the fp32 sums may have lost terms to underflow: re-score everything.
+constexpr float kTinySum = 0x1p-80f;
+
 // ------------------------------------------------------------------------------
 // Per-channel: one workgroup per row; the row lives in registers (CH chunks of 8
 // elements per thread, chunk j of thread t = elements [(j*THREADS + t)*8, +8)).
+//
+// Phase 1 scores every (format, candidate) in fp32; phase 2 re-scores in fp64 the
+// candidates that fp32 cannot separate from the best one and picks the first
+// smallest of those, which is the first smallest of all.
 // ------------------------------------------------------------------------------
 template <typename In, int FA, int FB, int THREADS, int CH>
-__global__ __launch_bounds__(THREADS) void sweep_channel_kernel(const SweepArgs a) {
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(CH <= 4 ? 8 : 5))) void sweep_channel_kernel(const SweepArgs a) {
   using L = Load8<In>;
   constexpr int NF = (FB >= 0) ? 2 : 1;
   constexpr int FBX = (FB >= 0) ? FB : FA;
   constexpr int NW = THREADS / 64;
   constexpr int NE = CH * 8;
+  constexpr int MAXL = NF * MOFQ_MAX_CLIP;
 
   __shared__ float s_scale[NF][MOFQ_MAX_CLIP];
   __shared__ float s_inv[NF][MOFQ_MAX_CLIP];
-  __shared__ double s_part[NW][NF][MOFQ_MAX_CLIP];
-  __shared__ double s_tot[NF][MOFQ_MAX_CLIP];
+  __shared__ float s_p1[NW][MOFQ_MAX_CLIP][NF];   // phase-1 partial sums per wave
+  __shared__ float s_tot[NF][MOFQ_MAX_CLIP];
   __shared__ float s_wmax[NW];
   __shared__ double s_wen[NW];
+  __shared__ float s_thr[NF];
+  __shared__ int s_list[MAXL];                    // shortlisted (format, candidate) pairs
+  __shared__ int s_nlist;
+  __shared__ double s_p2[NW];
+  __shared__ double s_val[MAXL];                  // fp64 error of the shortlisted pairs
 
   const int tid = threadIdx.x;
+  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t row = blockIdx.x;
   const typename L::elem* src = static_cast<const typename L::elem*>(a.w) + row * a.ld;
   const int K = a.n_clip;
 
   float x[NE];
-  double xd[NE];
   float amax = 0.0f;
   double en = 0.0;
 #pragma unroll
@@ -91,16 +164,16 @@ __global__ __launch_bounds__(THREADS) void sweep_channel_kernel(const SweepArgs 
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       x[j * 8 + i] = v[i];
-      xd[j * 8 + i] = static_cast<double>(v[i]);
       amax = __builtin_fmaxf(amax, __builtin_fabsf(v[i]));
-      en = __builtin_fma(xd[j * 8 + i], xd[j * 8 + i], en);
+      const double xd = static_cast<double>(v[i]);
+      en = __builtin_fma(xd, xd, en);
     }
   }
 
   // unit absmax and energy
   amax = wave_max(amax);
   en = wave_sum(en);
-  if ((tid & 63) == 0) { s_wmax[wave] = amax; s_wen[wave] = en; }
+  if (lane == 0) { s_wmax[wave] = amax; s_wen[wave] = en; }
   __syncthreads();
   amax = s_wmax[0];
   en = s_wen[0];
@@ -123,57 +196,105 @@ __global__ __launch_bounds__(THREADS) void sweep_channel_kernel(const SweepArgs 
   for (int j = 0; j < CH; ++j)
     live[j] = (static_cast<int64_t>(j) * THREADS + wave * 64) * 8 < a.cols;
 
+  uint32_t carry = 0;
+  // ---- phase 1: fp32 error of every candidate ------------------------------------
   for (int k = 0; k < K; ++k) {
     const float sA = u2f(__builtin_amdgcn_readfirstlane(f2u(s_scale[0][k])));
     const float iA = u2f(__builtin_amdgcn_readfirstlane(f2u(s_inv[0][k])));
     const float sB = u2f(__builtin_amdgcn_readfirstlane(f2u(s_scale[NF - 1][k])));
     const float iB = u2f(__builtin_amdgcn_readfirstlane(f2u(s_inv[NF - 1][k])));
-    const double sAd = static_cast<double>(sA), sBd = static_cast<double>(sB);
-    double accA = 0.0, accB = 0.0;
+    float accA = 0.0f, accB = 0.0f;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
       if (live[j]) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          accumulate<FA>(accA, x[j * 8 + i], xd[j * 8 + i], iA, sAd);
-          if constexpr (NF == 2) accumulate<FBX>(accB, x[j * 8 + i], xd[j * 8 + i], iB, sBd);
+        for (int i = 0; i < 8; i += 2) {
+          score2_f32<FA>(accA, x[j * 8 + i], x[j * 8 + i + 1], iA, sA, carry);
+          if constexpr (NF == 2) score2_f32<FBX>(accB, x[j * 8 + i], x[j * 8 + i + 1], iB, sB, carry);
         }
       }
     }
-    accA = wave_sum(accA);
-    if constexpr (NF == 2) accB = wave_sum(accB);
-    if ((tid & 63) == 0) {
-      s_part[wave][0][k] = accA;
-      if constexpr (NF == 2) s_part[wave][1][k] = accB;
+    accA = wave_sum_f32_hi(accA);
+    if constexpr (NF == 2) accB = wave_sum_f32_hi(accB);
+    if (lane == 63) {
+      s_p1[wave][k][0] = accA;
+      if constexpr (NF == 2) s_p1[wave][k][1] = accB;
     }
   }
   __syncthreads();
 
   for (int idx = tid; idx < NF * K; idx += THREADS) {
     const int f = idx / K, k = idx - f * K;
-    double t = s_part[0][f][k];
+    float t = 0.0f;
 #pragma unroll
-    for (int w = 1; w < NW; ++w) t += s_part[w][f][k];
+    for (int r = 0; r < NW; ++r) t += s_p1[r][k][f];
     s_tot[f][k] = t;
   }
   __syncthreads();
 
-  // first smallest candidate per format (one wave per format)
+  // ---- shortlist: candidates fp32 cannot tell from the best ----------------------
   for (int f = wave; f < NF; f += NW) {
-    const int lane = tid & 63;
+    float m = __builtin_inff();
+    for (int k = lane; k < K; k += 64) m = __builtin_fminf(m, s_tot[f][k]);
+    m = -wave_max(-m);
+    if (lane == 0) s_thr[f] = (m >= kTinySum && m < __builtin_inff()) ? m * kShortlistFactor : __builtin_inff();
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int n = 0;
+    for (int f = 0; f < NF; ++f)
+      for (int k = 0; k < K; ++k)
+        if (s_tot[f][k] <= s_thr[f] || !(s_tot[f][k] == s_tot[f][k])) s_list[n++] = f * MOFQ_MAX_CLIP + k;
+    s_nlist = n;
+  }
+  __syncthreads();
+  const int n_list = s_nlist;
+
+  // ---- phase 2: fp64 error of the shortlisted candidates ---------------------------
+  for (int e = 0; e < n_list; ++e) {
+    const int fk = s_list[e];
+    const int f = __builtin_amdgcn_readfirstlane(fk / MOFQ_MAX_CLIP);
+    const int k = __builtin_amdgcn_readfirstlane(fk % MOFQ_MAX_CLIP);
+    const float s = s_scale[f][k], inv = s_inv[f][k];
+    const double sd = static_cast<double>(s);
+    double acc = 0.0;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      if (live[j]) {
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) {
+          if (f == 0) score2_f64<FA>(acc, x[j * 8 + i], x[j * 8 + i + 1], inv, sd, carry);
+          else score2_f64<FBX>(acc, x[j * 8 + i], x[j * 8 + i + 1], inv, sd, carry);
+        }
+      }
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) s_p2[wave] = acc;
+    __syncthreads();
+    if (tid == 0) {
+      double t = s_p2[0];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) t += s_p2[w];
+      s_val[e] = t;
+    }
+    __syncthreads();
+  }
+
+  // first smallest fp64 error per format (the list is in candidate order)
+  if (tid < NF) {
+    const int f = tid;
     double best = __builtin_inf();
-    int bk = 0x7FFFFFFF;
-    for (int k = lane; k < K; k += 64) {
-      const double v = s_tot[f][k];
-      if (v < best) { best = v; bk = k; }
+    int bk = -1;
+    for (int e = 0; e < n_list; ++e) {
+      const int fk = s_list[e];
+      if (fk / MOFQ_MAX_CLIP != f) continue;
+      if (s_val[e] < best) { best = s_val[e]; bk = fk % MOFQ_MAX_CLIP; }
     }
-    wave_argmin(best, bk);
-    if (lane == 0) {
-      a.rec.scale[f][row] = s_scale[f][bk];
-      a.rec.clip[f][row] = bk;
-      a.rec.err[f][row] = best;
-      if (f == 0 && a.rec.energy) a.rec.energy[row] = en;
-    }
+    if (bk < 0) { bk = 0; best = __builtin_nan(""); }   // only on non-finite input
+    a.rec.scale[f][row] = s_scale[f][bk];
+    a.rec.clip[f][row] = bk;
+    a.rec.err[f][row] = best;
+    if (f == 0 && a.rec.energy) a.rec.energy[row] = en;
   }
 }
 
@@ -462,8 +583,11 @@ int launch_channel(const SweepArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((sweep_channel_kernel<In, FA, FB, THREADS, CH>), grid, dim3(THREADS), 0, st, a); \
     return hip_status(hipGetLastError());                                                \
   }
-  MOFQ_CH(256, 1)    //  2048 columns
-  MOFQ_CH(256, 2)    //  4096
+  // 32 to 48 elements per lane: enough work per candidate to amortise the cross-lane
+  // reduction, few enough registers for many waves per SIMD
+  MOFQ_CH(64, 1)     //   512 columns
+  MOFQ_CH(64, 4)     //  2048
+  MOFQ_CH(128, 4)    //  4096
   MOFQ_CH(256, 4)    //  8192
   MOFQ_CH(256, 6)    // 12288
   MOFQ_CH(512, 6)    // 24576
