@@ -42,6 +42,9 @@ constexpr int kTensorBlocks = 1024;  // partial results of per-tensor passes
 
 // Enqueue the scale search.  Returns a mofq_status_t.
 int launch_sweep(const SweepParams& p, hipStream_t stream);
+// Sort-based search for per-channel 4-bit searches on 16-bit inputs; returns
+// MOFQ_ERR_UNSUPPORTED (nothing enqueued) outside that domain.
+int launch_sweep_sorted(const SweepParams& p, hipStream_t stream);
 
 // Tensor-level reduce + Algorithm 1's strict-less select over n_cand formats
 // whose unit errors live in `err[c]` (units entries each).

@@ -652,6 +652,10 @@ int launch_fmt(const SweepParams& p, const SweepArgs& a, hipStream_t st) {
 }  // namespace
 
 int launch_sweep(const SweepParams& p, hipStream_t st) {
+  {
+    const int rc = launch_sweep_sorted(p, st);
+    if (rc != MOFQ_ERR_UNSUPPORTED) return rc;
+  }
   SweepArgs a{};
   a.w = p.w;
   a.rows = p.rows;

@@ -1,0 +1,529 @@
+// Scale search for one output channel per workgroup without scoring every
+// (element, candidate) pair.
+//
+// For a fixed scale the quantized value of an element is a non-decreasing step
+// function of the element, so the elements that fall on one grid level form a
+// contiguous run of the sorted row.  The squared error of a candidate is then
+//
+//   sum (x - g s)^2 = sum x^2  -  2 s * sum_L g_L * S_L  +  s^2 * sum_L g_L^2 * n_L ,
+//
+// with S_L, n_L the sum and count of the elements on level L.  The kernel sorts the
+// row once (LDS radix sort of the 16-bit patterns), builds prefix sums of the sorted
+// values, and finds every level boundary of every candidate by binary search with
+// the exact fp32 decision arithmetic (t = fl32(x * fl32(1/s)) against the rounding
+// threshold of the boundary).  That is O(n log n + K * levels * log n) per row
+// instead of O(n * K).
+//
+// The formula cancels (the error is ~1 % of sum x^2) and is only used as a filter:
+// every candidate whose filtered error is within a rigorous bound of the smallest is
+// re-scored element by element in fp64, exactly like the direct kernel, and the
+// first smallest of those wins.  Exact ties (zero error on several candidates) and
+// the reported unit error therefore come from the element-wise arithmetic.
+//
+// Applies to 16-bit inputs (fp16 / bf16) and the 4-bit formats (16 levels); other
+// cases use the direct kernel in mofq_sweep.hip.
+#include <cmath>
+
+#include "mofq_device.h"
+#include "mofq_internal.h"
+
+namespace mofq {
+
+namespace {
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+struct SortedArgs {
+  const void* w;
+  int64_t rows, cols, ld;
+  int32_t scale_f16, n_clip;
+  UnitRecords rec;
+  float clip[MOFQ_MAX_CLIP];
+  // per format slot: level(t) <= b  <=>  t <= thr[b];  levels ascending g_0 < g_1 < ...
+  float thr[2][16];
+  float dg[2][16];    // g_b - g_{b+1}
+  float dg2[2][16];   // g_b^2 - g_{b+1}^2
+  float g_last[2];    // largest level
+  float g_absmax[2];  // largest |level|
+  int32_t nb[2];      // number of boundaries (levels - 1)
+};
+
+// ---- order-preserving 16-bit keys ----------------------------------------------------
+MOFQ_DEV uint32_t to_key(uint32_t h) { return (h & 0x8000u) ? (~h & 0xFFFFu) : (h | 0x8000u); }
+MOFQ_DEV uint32_t from_key(uint32_t k) { return (k & 0x8000u) ? (k ^ 0x8000u) : (~k & 0xFFFFu); }
+
+template <typename In> MOFQ_DEV float bits_to_float(uint32_t h);
+template <> MOFQ_DEV float bits_to_float<F16>(uint32_t h) {
+  return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
+}
+template <> MOFQ_DEV float bits_to_float<BF16>(uint32_t h) { return u2f(h << 16); }
+
+// Padded position of sorted element i (in elements): a 2-element gap after every 64.
+// Additive over sums of distinct powers of two, which the search below relies on.
+MOFQ_DEV constexpr int phys(int i) { return i + ((i >> 6) << 1); }
+// inverse on non-gap positions: 66 padded elements hold 64
+MOFQ_DEV int unphys(int p) { return p - 2 * static_cast<int>(__umulhi(static_cast<uint32_t>(p), 65075263u)); }
+
+// exclusive prefix over the wave (Hillis-Steele with shuffles), and the wave total
+MOFQ_DEV uint32_t wave_excl_scan_u32(uint32_t v, uint32_t& total) {
+  const int lane = threadIdx.x & 63;
+  uint32_t inc = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += o;
+  }
+  total = __shfl(inc, 63, 64);
+  return inc - v;
+}
+MOFQ_DEV double wave_excl_scan_f64(double v, double& total) {
+  const int lane = threadIdx.x & 63;
+  double inc = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const double o = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += o;
+  }
+  total = __shfl(inc, 63, 64);
+  return inc - v;
+}
+
+// exact re-score of two elements (same arithmetic as the direct kernel's second phase)
+template <int FMT> MOFQ_DEV void rescore2(double& acc, float x0, float x1, float inv_s, double sd, uint32_t& carry) {
+  f32x2 g;
+  if constexpr (FMT == MOFQ_FP4_E2M1) {
+    carry = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(carry, x0 * inv_s, x1 * inv_s, 1.0f, 0);
+    g = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(carry, 1.0f, 0);
+  } else {
+    g[0] = Codec<FMT>::grid(x0 * inv_s);
+    g[1] = Codec<FMT>::grid(x1 * inv_s);
+  }
+  const double d0 = __builtin_fma(-static_cast<double>(g[0]), sd, static_cast<double>(x0));
+  const double d1 = __builtin_fma(-static_cast<double>(g[1]), sd, static_cast<double>(x1));
+  acc = __builtin_fma(d0, d0, acc);
+  acc = __builtin_fma(d1, d1, acc);
+}
+
+constexpr int Q = 4;   // candidates a lane searches at once (independent chains hide LDS latency)
+
+template <typename In, int FA, int FB, int THREADS, int CH>
+__global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs a) {
+  using L = Load8<In>;
+  constexpr int NF = (FB >= 0) ? 2 : 1;
+  constexpr int FBX = (FB >= 0) ? FB : FA;
+  constexpr int NW = THREADS / 64;
+  constexpr int E = CH * 8;            // keys per thread
+  constexpr int NP = THREADS * E;      // padded row length
+  constexpr int MAXL = NF * MOFQ_MAX_CLIP;
+  constexpr int HALVES = THREADS / 32; // candidates searched side by side (one per 32 lanes)
+
+  // ---- LDS.  During the sort: two key buffers + digit counters.  The sorted row ends up
+  // in the first buffer in a padded layout (one 4-byte gap after every 64 elements, so that
+  // the power-of-two strides of a binary search do not all fall on one bank), followed by
+  // NaN sentinels up to twice the padded row length (the search may probe up to 2^steps - 2).
+  // The counters then hold the prefix sums (one exclusive prefix every BS positions).
+  constexpr int KEYE = NP + NP / 32 + 16;                 // elements of one key buffer (padded layout + slack)
+  constexpr int KEYB = KEYE * 2;
+  constexpr int CNTB = 16 * THREADS * 4;                  // bytes of the digit counters
+  constexpr int BS = (8 * (NP / 2 + 1) <= CNTB) ? 2 : ((8 * (NP / 4 + 1) <= CNTB) ? 4 : 8);
+  constexpr int NBLK = NP / BS;
+  static_assert(8 * (NBLK + 1) <= CNTB, "prefix sums do not fit");
+  static_assert(KEYB % 16 == 0, "key buffers must stay 16-byte aligned");
+  __shared__ __attribute__((aligned(16))) unsigned char s_raw[2 * KEYB + CNTB];
+  uint16_t* const s_keys0 = reinterpret_cast<uint16_t*>(s_raw);
+  uint16_t* const s_keys1 = reinterpret_cast<uint16_t*>(s_raw + KEYB);
+  uint32_t (*const s_cnt)[THREADS] = reinterpret_cast<uint32_t (*)[THREADS]>(s_raw + 2 * KEYB);
+  double* const s_blk = reinterpret_cast<double*>(s_raw + 2 * KEYB);   // [NBLK + 1], valid after the sort
+  __shared__ uint32_t s_dig_tot[16];
+  __shared__ float s_scale[NF][MOFQ_MAX_CLIP];
+  __shared__ float s_inv[NF][MOFQ_MAX_CLIP];
+  __shared__ double s_fast[NF][MOFQ_MAX_CLIP];
+  __shared__ float s_wmax[NW];
+  __shared__ double s_wsum[3][NW];
+  __shared__ double s_thr[NF];
+  __shared__ int s_list[MAXL];
+  __shared__ int s_nlist;
+  __shared__ double s_p2[NW];
+  __shared__ double s_val[MAXL];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t row = blockIdx.x;
+  const typename L::elem* src = static_cast<const typename L::elem*>(a.w) + row * a.ld;
+  const int K = a.n_clip;
+  const int n = static_cast<int>(a.cols);
+
+  // ---- load the row: absmax, energy, and the sort keys ------------------------------
+  float amax = 0.0f;
+  double en = 0.0, l1 = 0.0;
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const int64_t c0 = (static_cast<int64_t>(j) * THREADS + tid) * 8;
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    const bool ok = c0 < a.cols;
+    if (ok) raw = *reinterpret_cast<const u32x4*>(src + c0);
+    u32x4 keys;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t h0 = raw[i] & 0xFFFFu, h1 = raw[i] >> 16;
+      const float v0 = bits_to_float<In>(h0), v1 = bits_to_float<In>(h1);
+      amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fabsf(v0), __builtin_fabsf(v1)));
+      const double d0 = static_cast<double>(v0), d1 = static_cast<double>(v1);
+      en = __builtin_fma(d0, d0, en);
+      en = __builtin_fma(d1, d1, en);
+      l1 += __builtin_fabs(d0) + __builtin_fabs(d1);
+      keys[i] = ok ? (to_key(h0) | (to_key(h1) << 16)) : 0xFFFFFFFFu;   // padding sorts last
+    }
+    *reinterpret_cast<u32x4*>(&s_keys0[tid * E + j * 8]) = keys;
+  }
+  amax = wave_max(amax);
+  en = wave_sum(en);
+  l1 = wave_sum(l1);
+  if (lane == 0) { s_wmax[wave] = amax; s_wsum[0][wave] = en; s_wsum[1][wave] = l1; }
+  __syncthreads();
+  amax = s_wmax[0];
+  en = s_wsum[0][0];
+  l1 = s_wsum[1][0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) {
+    amax = __builtin_fmaxf(amax, s_wmax[w]);
+    en += s_wsum[0][w];
+    l1 += s_wsum[1][w];
+  }
+  for (int idx = tid; idx < NF * K; idx += THREADS) {
+    const int f = idx / K, k = idx - f * K;
+    const float qmax = (f == 0) ? Codec<FA>::QMAX : Codec<FBX>::QMAX;
+    const float s = unit_scale(amax, a.clip[k], qmax, a.scale_f16 != 0);
+    s_scale[f][k] = s;
+    s_inv[f][k] = 1.0f / s;
+  }
+
+  // ---- LSD radix sort of the keys, 4 bits per pass; thread t owns positions [tE, tE+E) ---
+#pragma unroll 1
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = pass * 4;
+    const uint16_t* from = (pass & 1) ? s_keys1 : s_keys0;
+    uint16_t* to = (pass & 1) ? s_keys0 : s_keys1;
+#pragma unroll
+    for (int d = 0; d < 16; ++d) s_cnt[d][tid] = 0;
+    uint32_t kreg[E / 2];
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(&from[tid * E + j * 8]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) kreg[j * 4 + i] = v[i];
+    }
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const uint32_t key = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
+      atomicAdd(&s_cnt[(key >> shift) & 15u][tid], 1u);   // own column: plain LDS add
+    }
+    __syncthreads();
+    // per digit: exclusive scan of the counts across threads; digit totals aside
+    for (int d = wave; d < 16; d += NW) {
+      constexpr int PER = THREADS / 64;
+      uint32_t c[PER], sum = 0;
+#pragma unroll
+      for (int i = 0; i < PER; ++i) { c[i] = s_cnt[d][lane * PER + i]; sum += c[i]; }
+      uint32_t total;
+      uint32_t base = wave_excl_scan_u32(sum, total);
+#pragma unroll
+      for (int i = 0; i < PER; ++i) { s_cnt[d][lane * PER + i] = base; base += c[i]; }
+      if (lane == 0) s_dig_tot[d] = total;
+    }
+    __syncthreads();
+    // start of each digit's run, added to this thread's own counters
+    {
+      uint32_t run = 0;
+#pragma unroll
+      for (int d = 0; d < 16; ++d) {
+        if (run) atomicAdd(&s_cnt[d][tid], run);
+        run += s_dig_tot[d];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const uint32_t key = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
+      const uint32_t pos = atomicAdd(&s_cnt[(key >> shift) & 15u][tid], 1u);   // stable: thread order, then i
+      // last pass: back to bit patterns, into the padded layout
+      if (pass == 3) to[phys(static_cast<int>(pos))] = static_cast<uint16_t>(from_key(key));
+      else to[pos] = static_cast<uint16_t>(key);
+    }
+    __syncthreads();
+  }
+  // Four passes: the result is back in the first buffer, as the elements' own bit
+  // patterns in ascending order of value.  Padding became the pattern 0x7FFF (a NaN in
+  // fp16 and bf16), which fails every "<= threshold" test; one more sits at [NP].
+  const uint16_t* sorted = s_keys0;      // padded layout: element i at sorted[phys(i)]
+  for (int e = phys(NP) + tid; e < 2 * KEYE; e += THREADS) s_keys0[e] = 0x7FFFu;   // runs on into the second buffer
+
+  // ---- prefix sums of the sorted values: exclusive prefix at every BS-th position ----------
+  {
+    constexpr int NB8 = 8 / BS;             // prefix entries per 8 elements
+    double bs[CH][NB8], tsum = 0.0;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const uint32_t* cp = reinterpret_cast<const uint32_t*>(&sorted[phys(tid * E + j * 8)]);
+      const uint32_t v[4] = {cp[0], cp[1], cp[2], cp[3]};
+#pragma unroll
+      for (int g = 0; g < NB8; ++g) {
+        double b = 0.0;
+#pragma unroll
+        for (int i = g * BS; i < (g + 1) * BS; ++i) {
+          const uint32_t h = (v[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
+          const int pos = tid * E + j * 8 + i;
+          const double val = static_cast<double>(bits_to_float<In>(h));
+          b += (pos < n) ? val : 0.0;
+        }
+        bs[j][g] = b;
+        tsum += b;
+      }
+    }
+    double wtot;
+    double base = wave_excl_scan_f64(tsum, wtot);
+    if (lane == 0) s_wsum[2][wave] = wtot;
+    __syncthreads();                       // also: every thread is done reading the sort buffers
+    double wbase = 0.0;
+    for (int w = 0; w < wave; ++w) wbase += s_wsum[2][w];
+    base += wbase;
+#pragma unroll
+    for (int j = 0; j < CH; ++j)
+#pragma unroll
+      for (int g = 0; g < NB8; ++g) { s_blk[(tid * CH + j) * NB8 + g] = base; base += bs[j][g]; }
+    if (tid == THREADS - 1) s_blk[NBLK] = base;
+    __syncthreads();
+  }
+  const double s_total = s_blk[NBLK];
+
+  // ---- level boundaries of every candidate by binary search ------------------------------
+  {
+    const int b = lane & 15;
+    const int f = (lane >> 4) & 1;
+    const bool lane_live = (f < NF) && (b < a.nb[f]);
+    const float thr = lane_live ? a.thr[f][b] : 0.0f;
+    const double dg = lane_live ? static_cast<double>(a.dg[f][b]) : 0.0;
+    const double dg2 = lane_live ? static_cast<double>(a.dg2[f][b]) : 0.0;
+    const int steps = 32 - __builtin_clz(static_cast<unsigned>(n));   // 2^steps > n
+    const int fi = (f < NF) ? f : 0;
+    for (int k0 = 0; k0 < K; k0 += HALVES * Q) {
+      int kq[Q], ppos[Q];   // ppos: padded byte offset of the search position
+      float inv[Q];
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+        kq[q] = k0 + (tid >> 5) * Q + q;
+        inv[q] = s_inv[fi][kq[q] < K ? kq[q] : K - 1];
+        ppos[q] = 0;
+      }
+      // branch-free lower bound: position = number of elements on levels <= b.  Every
+      // element before the position passes the test; the NaN padding stops it at n.
+      for (int stp = 1 << (steps - 1); stp > 0; stp >>= 1) {
+        const int probe = 2 * phys(stp - 1), inc = 2 * phys(stp);   // wave-uniform byte offsets
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+          const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + (ppos[q] + probe));
+          const float t = bits_to_float<In>(h) * inv[q];
+          ppos[q] += (t <= thr) ? inc : 0;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+        const int j = unphys(ppos[q] >> 1);
+        constexpr int LB = (BS == 2) ? 1 : (BS == 4 ? 2 : 3);
+        double p = s_blk[j >> LB];
+        const int j0 = phys(j & ~(BS - 1));
+#pragma unroll
+        for (int i = 0; i < BS - 1; ++i) {
+          const bool in = i < (j & (BS - 1));
+          const double val = static_cast<double>(bits_to_float<In>(sorted[in ? j0 + i : 0]));
+          p += in ? val : 0.0;
+        }
+        double ca = lane_live ? p * dg : 0.0;
+        // counts times level-square differences are small multiples of 1/4: exact in fp32
+        float cbf = lane_live ? static_cast<float>(j) * static_cast<float>(dg2) : 0.0f;
+        ca = row16_sum(ca);
+        cbf += dpp_f32<DPP_QUAD_XOR1>(cbf);
+        cbf += dpp_f32<DPP_QUAD_XOR2>(cbf);
+        cbf += dpp_f32<DPP_ROW_HALF_MIRROR>(cbf);
+        cbf += dpp_f32<DPP_ROW_MIRROR>(cbf);
+        const double cb = static_cast<double>(cbf);
+        if (b == 0 && f < NF && kq[q] < K) {
+          const double gl = static_cast<double>(a.g_last[f]);
+          const double A = ca + gl * s_total;
+          const double B = cb + gl * gl * static_cast<double>(n);
+          const double s = static_cast<double>(s_scale[f][kq[q]]);
+          s_fast[f][kq[q]] = (en - 2.0 * s * A) + s * s * B;
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- shortlist: candidates the filter cannot separate from the best ---------------------
+  // |filtered - exact| <= ~3e4 * 2^-53 * (sum x^2 + 2 s g_max sum|x| + s^2 g_max^2 n); the
+  // margin below is 2^-34 of that magnitude (about 15 times the bound).
+  for (int f = wave; f < NF; f += NW) {
+    double m = __builtin_inf();
+    float smax = 0.0f;
+    for (int k = lane; k < K; k += 64) {
+      m = __builtin_fmin(m, s_fast[f][k]);
+      smax = __builtin_fmaxf(smax, s_scale[f][k]);
+    }
+    int dummy = 0;
+    wave_argmin(m, dummy);
+    smax = wave_max(smax);
+    const double sm = static_cast<double>(smax), gm = static_cast<double>(a.g_absmax[f]);
+    const double mag = en + 2.0 * sm * gm * l1 + sm * sm * gm * gm * static_cast<double>(n);
+    if (lane == 0) s_thr[f] = m + 0x1p-33 * mag;   // twice the margin: both values carry the error
+  }
+  if (tid == 0) s_nlist = 0;
+  __syncthreads();
+  for (int idx = tid; idx < NF * K; idx += THREADS) {
+    const int f = idx / K, k = idx - f * K;
+    if (!(s_fast[f][k] > s_thr[f])) s_list[atomicAdd(&s_nlist, 1)] = f * MOFQ_MAX_CLIP + k;   // any order
+  }
+  __syncthreads();
+  const int n_list = s_nlist;
+
+  // ---- exact fp64 re-score of the shortlist, element by element (sorted order) ------------
+  uint32_t carry = 0;
+  for (int e = 0; e < n_list; ++e) {
+    const int fk = s_list[e];
+    const int f = __builtin_amdgcn_readfirstlane(fk / MOFQ_MAX_CLIP);
+    const int k = __builtin_amdgcn_readfirstlane(fk % MOFQ_MAX_CLIP);
+    const float s = s_scale[f][k], inv = s_inv[f][k];
+    const double sd = static_cast<double>(s);
+    double acc = 0.0;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const int p0 = tid * E + j * 8;
+      if (__builtin_amdgcn_readfirstlane(wave * 64 * E + j * 8) < n) {   // wave-uniform: any data here?
+        const uint32_t* cp = reinterpret_cast<const uint32_t*>(&sorted[phys(p0)]);
+        const uint32_t v[4] = {cp[0], cp[1], cp[2], cp[3]};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float x0 = (p0 + 2 * i < n) ? bits_to_float<In>(v[i] & 0xFFFFu) : 0.0f;
+          const float x1 = (p0 + 2 * i + 1 < n) ? bits_to_float<In>(v[i] >> 16) : 0.0f;
+          if (f == 0) rescore2<FA>(acc, x0, x1, inv, sd, carry);
+          else rescore2<FBX>(acc, x0, x1, inv, sd, carry);
+        }
+      }
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) s_p2[wave] = acc;
+    __syncthreads();
+    if (tid == 0) {
+      double t = s_p2[0];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) t += s_p2[w];
+      s_val[e] = t;
+    }
+    __syncthreads();
+  }
+
+  if (tid < NF) {
+    const int f = tid;
+    double best = __builtin_inf();
+    int bk = -1;
+    for (int e = 0; e < n_list; ++e) {   // smallest error, then smallest index: the first smallest
+      const int fk = s_list[e];
+      if (fk / MOFQ_MAX_CLIP != f) continue;
+      const int k = fk % MOFQ_MAX_CLIP;
+      if (s_val[e] < best || (s_val[e] == best && k < bk)) { best = s_val[e]; bk = k; }
+    }
+    if (bk < 0) { bk = 0; best = __builtin_nan(""); }   // only on non-finite input
+    a.rec.scale[f][row] = s_scale[f][bk];
+    a.rec.clip[f][row] = bk;
+    a.rec.err[f][row] = best;
+    if (f == 0 && a.rec.energy) a.rec.energy[row] = en;
+  }
+}
+
+// ---- host: rounding thresholds of the level boundaries ---------------------------------------
+
+// Levels of a 4-bit format in ascending order, and for each boundary b the largest fp32 t
+// that still lands on level b or below.
+void fill_levels(int fmt, SortedArgs& a, int slot) {
+  double lv[16];
+  bool up_is_even[16];   // at the midpoint between lv[b] and lv[b+1], does the tie go to lv[b+1]?
+  int nl = 0;
+  if (fmt == MOFQ_INT4) {
+    for (int q = -8; q <= 7; ++q) lv[nl++] = q;
+    for (int b = 0; b + 1 < nl; ++b) up_is_even[b] = (static_cast<int>(lv[b + 1]) % 2 == 0);
+  } else {  // E2M1: magnitudes by code 0..7; the even code wins a tie
+    const double mag[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+    for (int c = 7; c >= 1; --c) lv[nl++] = -mag[c];
+    lv[nl++] = 0.0;
+    for (int c = 1; c <= 7; ++c) lv[nl++] = mag[c];
+    for (int b = 0; b + 1 < nl; ++b) {
+      // magnitude code of the upper level: index b+1 -> code |b+1-7|
+      const int code_up = std::abs(b + 1 - 7), code_lo = std::abs(b - 7);
+      (void)code_lo;
+      up_is_even[b] = (code_up % 2 == 0);
+    }
+  }
+  a.nb[slot] = nl - 1;
+  a.g_last[slot] = static_cast<float>(lv[nl - 1]);
+  a.g_absmax[slot] = static_cast<float>(std::fmax(std::fabs(lv[0]), std::fabs(lv[nl - 1])));
+  for (int b = 0; b < 16; ++b) { a.thr[slot][b] = 0.0f; a.dg[slot][b] = 0.0f; a.dg2[slot][b] = 0.0f; }
+  for (int b = 0; b + 1 < nl; ++b) {
+    const float mid = static_cast<float>(0.5 * (lv[b] + lv[b + 1]));   // exact in fp32
+    // tie goes up  -> level <= b needs t <  mid -> t <= the float just below mid
+    // tie goes down-> level <= b needs t <= mid
+    a.thr[slot][b] = up_is_even[b] ? std::nextafterf(mid, -INFINITY) : mid;
+    a.dg[slot][b] = static_cast<float>(lv[b] - lv[b + 1]);
+    a.dg2[slot][b] = static_cast<float>(lv[b] * lv[b] - lv[b + 1] * lv[b + 1]);
+  }
+}
+
+template <typename In, int FA, int FB>
+int launch_shape(const SortedArgs& a, hipStream_t st) {
+  const dim3 grid(static_cast<unsigned>(a.rows));
+  const int64_t chunks = a.cols / 8;
+#define MOFQ_SORTED(THREADS, CH)                                                          \
+  if (chunks <= static_cast<int64_t>(THREADS) * (CH)) {                                    \
+    hipLaunchKernelGGL((sweep_sorted_kernel<In, FA, FB, THREADS, CH>), grid, dim3(THREADS), 0, st, a); \
+    return hip_status(hipGetLastError());                                                  \
+  }
+  MOFQ_SORTED(256, 1)   //  2048 columns
+  MOFQ_SORTED(256, 2)   //  4096
+  MOFQ_SORTED(256, 4)   //  8192
+  MOFQ_SORTED(256, 6)   // 12288
+  MOFQ_SORTED(512, 6)   // 24576
+#undef MOFQ_SORTED
+  return MOFQ_ERR_UNSUPPORTED;
+}
+
+template <typename In>
+int launch_fmt(const SweepParams& p, const SortedArgs& a, hipStream_t st) {
+  const int fa = p.fmt[0], fb = p.n_fmt == 2 ? p.fmt[1] : -1;
+  if (fa == MOFQ_INT4 && fb == MOFQ_FP4_E2M1) return launch_shape<In, MOFQ_INT4, MOFQ_FP4_E2M1>(a, st);
+  if (fa == MOFQ_INT4 && fb == -1) return launch_shape<In, MOFQ_INT4, -1>(a, st);
+  if (fa == MOFQ_FP4_E2M1 && fb == -1) return launch_shape<In, MOFQ_FP4_E2M1, -1>(a, st);
+  return MOFQ_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+// Returns MOFQ_ERR_UNSUPPORTED when the configuration is outside this kernel's domain
+// (the caller then uses the direct kernel); nothing has been enqueued in that case.
+int launch_sweep_sorted(const SweepParams& p, hipStream_t st) {
+  if (p.gran != MOFQ_PER_CHANNEL) return MOFQ_ERR_UNSUPPORTED;
+  if (p.dtype != MOFQ_F16 && p.dtype != MOFQ_BF16) return MOFQ_ERR_UNSUPPORTED;
+  if (p.n_clip < 8 || p.cols < 1024 || p.cols > 24576) return MOFQ_ERR_UNSUPPORTED;
+  for (int f = 0; f < p.n_fmt; ++f)
+    if (p.fmt[f] != MOFQ_INT4 && p.fmt[f] != MOFQ_FP4_E2M1) return MOFQ_ERR_UNSUPPORTED;
+  SortedArgs a{};
+  a.w = p.w;
+  a.rows = p.rows;
+  a.cols = p.cols;
+  a.ld = p.ld;
+  a.scale_f16 = p.scale_f16;
+  a.n_clip = p.n_clip;
+  a.rec = p.rec;
+  for (int k = 0; k < p.n_clip; ++k) a.clip[k] = p.clip[k];
+  for (int f = 0; f < p.n_fmt; ++f) fill_levels(p.fmt[f], a, f);
+  return p.dtype == MOFQ_F16 ? launch_fmt<F16>(p, a, st) : launch_fmt<BF16>(p, a, st);
+}
+
+}  // namespace mofq
