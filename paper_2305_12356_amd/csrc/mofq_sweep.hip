@@ -197,8 +197,8 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(CH <= 4
     live[j] = (static_cast<int64_t>(j) * THREADS + wave * 64) * 8 < a.cols;
 
   uint32_t carry = 0;
-  // ---- phase 1: fp32 error of every candidate ------------------------------------
-  for (int k = 0; k < K; ++k) {
+  // ---- phase 1: fp32 error of every candidate (nothing to filter with one candidate) --
+  for (int k = 0; k < K && K > 1; ++k) {
     const float sA = u2f(__builtin_amdgcn_readfirstlane(f2u(s_scale[0][k])));
     const float iA = u2f(__builtin_amdgcn_readfirstlane(f2u(s_inv[0][k])));
     const float sB = u2f(__builtin_amdgcn_readfirstlane(f2u(s_scale[NF - 1][k])));
@@ -226,9 +226,11 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(CH <= 4
   for (int idx = tid; idx < NF * K; idx += THREADS) {
     const int f = idx / K, k = idx - f * K;
     float t = 0.0f;
+    if (K > 1) {
 #pragma unroll
-    for (int r = 0; r < NW; ++r) t += s_p1[r][k][f];
-    s_tot[f][k] = t;
+      for (int r = 0; r < NW; ++r) t += s_p1[r][k][f];
+    }
+    s_tot[f][k] = t;   // K == 1: zero, which shortlists the only candidate
   }
   __syncthreads();
 
