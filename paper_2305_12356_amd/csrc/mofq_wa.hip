@@ -34,9 +34,7 @@ typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 
-constexpr int TM = 128, TN = 128, TK = 64;      // workgroup tile
-constexpr int LDB = TK + 8;                     // bf16 row stride in LDS (elements): 144 B, staggers banks
-constexpr int LDQ = TK + 16;                    // 8-bit row stride in LDS (bytes): 80 B
+constexpr int TM = 128, TN = 128;               // workgroup tile; 4 waves, 64 x 64 each
 
 struct GemmArgs {
   const uint16_t* x; int64_t ldx;               // bf16 [M][K]
@@ -52,35 +50,104 @@ struct GemmArgs {
   double* part_i; double* part_f; double* part_p;   // [blocks]
 };
 
-// 16-byte chunk global -> LDS, zero beyond the matrix edge
-MOFQ_DEV u32x4 load_chunk(const void* base, int64_t row_stride_bytes, int row, int rows, int byte_off) {
-  u32x4 v = {0u, 0u, 0u, 0u};
-  if (row < rows)
-    v = *reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + row * row_stride_bytes + byte_off);
-  return v;
-}
-
 constexpr int FP8_NONE = 0, FP8_NATIVE = 1, FP8_EXACT = 2;
+
+// ---- LDS tiles --------------------------------------------------------------------
+// A tile holds 128 rows of RB bytes (RB = 32, 64 or 128), i.e. C = RB/16 chunks of 16
+// bytes per row, with no padding.  Tiles are filled by global_load_lds (each lane of a
+// wave instruction deposits 16 bytes at consecutive LDS addresses), so the layout is
+// chosen through WHICH global chunk a lane fetches: chunk slot p of row R holds logical
+// chunk p ^ swz(R), a rotation that spreads the 16-byte column read by the matrix-core
+// fragment loads over all bank groups.
+template <int C> MOFQ_DEV int swz(int row) {
+  if constexpr (C == 8) return row & 7;
+  else if constexpr (C == 4) return (row >> 1) & 3;
+  else return (row >> 2) & 1;
+}
+template <int C> MOFQ_DEV int chunk_off(int row, int kc) { return (row * C + (kc ^ swz<C>(row))) * 16; }
+
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// Issue this wave's share of one tile load (tile = 128*C chunks = 2*C wave instructions,
+// instruction i of the tile is issued by wave i % 4).  `src` is this lane's global
+// pointer for instruction 0 of its wave's share at k = 0; rows/chunks per instruction are
+// fixed, so advancing K only adds a constant.
+template <int C>
+struct TileLoader {
+  static constexpr int PER_WAVE = (2 * C + 3) / 4;   // instructions per wave (C=2: 1, C=4: 2, C=8: 4)
+  const char* src[PER_WAVE];
+  MOFQ_DEV void init(const void* base, int64_t row_bytes, int row0, int rows, int wave, int lane) {
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) {
+      const int i = wave + 4 * j;                    // instruction index within the tile
+      const int c = i * 64 + lane;                   // LDS chunk slot
+      const int row = c / C, p = c % C;
+      const int kc = p ^ swz<C>(row);
+      int grow = row0 + row;
+      grow = grow < rows ? grow : rows - 1;          // rows past the edge repeat the last one (masked later)
+      src[j] = static_cast<const char*>(base) + static_cast<int64_t>(grow) * row_bytes + kc * 16;
+    }
+  }
+  MOFQ_DEV void issue(unsigned char* tile, int wave, int64_t k_bytes) const {
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) {
+      const int i = wave + 4 * j;
+      if (i < 2 * C)
+        __builtin_amdgcn_global_load_lds((gptr_t)(src[j] + k_bytes), (lptr_t)(tile + i * 1024), 16, 0, 0);
+    }
+  }
+};
 
 template <bool DO_I8, int FP8>
 __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
   constexpr bool DO_F8 = FP8 != FP8_NONE;
-  __shared__ __attribute__((aligned(16))) uint16_t sXb[TM * LDB];
-  __shared__ __attribute__((aligned(16))) uint16_t sWb[TN * LDB];
-  __shared__ __attribute__((aligned(16))) uint8_t sXi[DO_I8 ? TM * LDQ : 16];
-  __shared__ __attribute__((aligned(16))) uint8_t sWi[DO_I8 ? TN * LDQ : 16];
-  __shared__ __attribute__((aligned(16))) uint8_t sXf[FP8 == FP8_NATIVE ? TM * LDQ : 16];
-  __shared__ __attribute__((aligned(16))) uint8_t sWf[FP8 == FP8_NATIVE ? TN * LDQ : 16];
-  __shared__ __attribute__((aligned(16))) uint16_t sXg[FP8 == FP8_EXACT ? TM * LDB : 8];
-  __shared__ __attribute__((aligned(16))) uint16_t sWg[FP8 == FP8_EXACT ? TN * LDB : 8];
+  constexpr int TK = (FP8 == FP8_NATIVE) ? 64 : 32;      // the fp8 instruction consumes K = 64
+  constexpr int CB = TK * 2 / 16;                        // chunks per row, 16-bit tiles
+  constexpr int CQ = TK / 16;                            // chunks per row, 8-bit tiles
+  constexpr int SZB = TM * TK * 2, SZQ = TM * TK;        // bytes per tile
+  // stage layout
+  constexpr int O_XB = 0, O_WB = O_XB + SZB;
+  constexpr int O_XG = O_WB + SZB, O_WG = O_XG + (FP8 == FP8_EXACT ? SZB : 0);
+  constexpr int O_XI = O_WG + (FP8 == FP8_EXACT ? SZB : 0), O_WI = O_XI + (DO_I8 ? SZQ : 0);
+  constexpr int O_XF = O_WI + (DO_I8 ? SZQ : 0), O_WF = O_XF + (FP8 == FP8_NATIVE ? SZQ : 0);
+  constexpr int STAGE = O_WF + (FP8 == FP8_NATIVE ? SZQ : 0);
+  __shared__ __attribute__((aligned(1024))) unsigned char s_buf[2 * STAGE];
   __shared__ double s_red[3][4];
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;      // 2 x 2 waves, 64 x 64 each
   const int r = lane & 31, g = lane >> 5;
   const int bm = blockIdx.x / a.tiles_n, bn = blockIdx.x - bm * a.tiles_n;
   const int m0 = bm * TM, n0 = bn * TN;
+
+  TileLoader<CB> lxb, lwb, lxg, lwg;
+  TileLoader<CQ> lxi, lwi, lxf, lwf;
+  lxb.init(a.x, a.ldx * 2, m0, a.M, wave, lane);
+  lwb.init(a.w, a.ldw * 2, n0, a.N, wave, lane);
+  if constexpr (FP8 == FP8_EXACT) {
+    lxg.init(a.xg, static_cast<int64_t>(a.K) * 2, m0, a.M, wave, lane);
+    lwg.init(a.wg, static_cast<int64_t>(a.K) * 2, n0, a.N, wave, lane);
+  }
+  if constexpr (DO_I8) {
+    lxi.init(a.xi, a.K, m0, a.M, wave, lane);
+    lwi.init(a.wi, a.K, n0, a.N, wave, lane);
+  }
+  if constexpr (FP8 == FP8_NATIVE) {
+    lxf.init(a.xf, a.K, m0, a.M, wave, lane);
+    lwf.init(a.wf, a.K, n0, a.N, wave, lane);
+  }
+  auto issue_stage = [&](int kt) {
+    unsigned char* st = s_buf + (kt & 1) * STAGE;
+    const int64_t kb = static_cast<int64_t>(kt) * TK;     // k offset in elements
+    lxb.issue(st + O_XB, wave, kb * 2);
+    lwb.issue(st + O_WB, wave, kb * 2);
+    if constexpr (FP8 == FP8_EXACT) { lxg.issue(st + O_XG, wave, kb * 2); lwg.issue(st + O_WG, wave, kb * 2); }
+    if constexpr (DO_I8) { lxi.issue(st + O_XI, wave, kb); lwi.issue(st + O_WI, wave, kb); }
+    if constexpr (FP8 == FP8_NATIVE) { lxf.issue(st + O_XF, wave, kb); lwf.issue(st + O_WF, wave, kb); }
+  };
 
   f32x16 acc_r[2][2];
   i32x16 acc_i[2][2];
@@ -92,43 +159,23 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) { acc_r[i][j][e] = 0.0f; acc_i[i][j][e] = 0; acc_f[i][j][e] = 0.0f; }
 
-  for (int k0 = 0; k0 < a.K; k0 += TK) {
-    // ---- global -> LDS (K % 64 == 0, so only row edges need zero fill)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int c = tid + 256 * j, row = c >> 3, kc = c & 7;
-      const u32x4 vx = load_chunk(a.x, a.ldx * 2, m0 + row, a.M, (k0 + kc * 8) * 2);
-      const u32x4 vw = load_chunk(a.w, a.ldw * 2, n0 + row, a.N, (k0 + kc * 8) * 2);
-      *reinterpret_cast<u32x4*>(&sXb[row * LDB + kc * 8]) = vx;
-      *reinterpret_cast<u32x4*>(&sWb[row * LDB + kc * 8]) = vw;
-      if constexpr (FP8 == FP8_EXACT) {
-        *reinterpret_cast<u32x4*>(&sXg[row * LDB + kc * 8]) = load_chunk(a.xg, a.K * 2, m0 + row, a.M, (k0 + kc * 8) * 2);
-        *reinterpret_cast<u32x4*>(&sWg[row * LDB + kc * 8]) = load_chunk(a.wg, a.K * 2, n0 + row, a.N, (k0 + kc * 8) * 2);
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int c = tid + 256 * j, row = c >> 2, kc = c & 3;
-      if constexpr (DO_I8) {
-        *reinterpret_cast<u32x4*>(&sXi[row * LDQ + kc * 16]) = load_chunk(a.xi, a.K, m0 + row, a.M, k0 + kc * 16);
-        *reinterpret_cast<u32x4*>(&sWi[row * LDQ + kc * 16]) = load_chunk(a.wi, a.K, n0 + row, a.N, k0 + kc * 16);
-      }
-      if constexpr (FP8 == FP8_NATIVE) {
-        *reinterpret_cast<u32x4*>(&sXf[row * LDQ + kc * 16]) = load_chunk(a.xf, a.K, m0 + row, a.M, k0 + kc * 16);
-        *reinterpret_cast<u32x4*>(&sWf[row * LDQ + kc * 16]) = load_chunk(a.wf, a.K, n0 + row, a.N, k0 + kc * 16);
-      }
-    }
-    __syncthreads();
+  const int KT = a.K / TK;
+  issue_stage(0);
+  for (int kt = 0; kt < KT; ++kt) {
+    __builtin_amdgcn_s_waitcnt(0);     // this wave's deposits of stage kt have landed
+    __syncthreads();                   // ... and everyone's; also: all waves are done with stage kt-1
+    if (kt + 1 < KT) issue_stage(kt + 1);   // overlaps with the matrix work below
+    const unsigned char* st = s_buf + (kt & 1) * STAGE;
 
-    // ---- matrix cores.  Lane (r, g) supplies row r of the 32-row operand tile and
-    // the g-th half of the instruction's K range, for A and B alike.
+    // Lane (r, g) supplies row r of a 32-row operand tile and the g-th half of the
+    // instruction's K range, for A and B alike.
 #pragma unroll
     for (int ks = 0; ks < TK / 16; ++ks) {
       bf16x8 fa[2], fb[2];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        fa[i] = *reinterpret_cast<const bf16x8*>(&sXb[(wm * 64 + i * 32 + r) * LDB + ks * 16 + g * 8]);
-        fb[i] = *reinterpret_cast<const bf16x8*>(&sWb[(wn * 64 + i * 32 + r) * LDB + ks * 16 + g * 8]);
+        fa[i] = *reinterpret_cast<const bf16x8*>(st + O_XB + chunk_off<CB>(wm * 64 + i * 32 + r, ks * 2 + g));
+        fb[i] = *reinterpret_cast<const bf16x8*>(st + O_WB + chunk_off<CB>(wn * 64 + i * 32 + r, ks * 2 + g));
       }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
@@ -138,8 +185,8 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
       if constexpr (FP8 == FP8_EXACT) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-          fa[i] = *reinterpret_cast<const bf16x8*>(&sXg[(wm * 64 + i * 32 + r) * LDB + ks * 16 + g * 8]);
-          fb[i] = *reinterpret_cast<const bf16x8*>(&sWg[(wn * 64 + i * 32 + r) * LDB + ks * 16 + g * 8]);
+          fa[i] = *reinterpret_cast<const bf16x8*>(st + O_XG + chunk_off<CB>(wm * 64 + i * 32 + r, ks * 2 + g));
+          fb[i] = *reinterpret_cast<const bf16x8*>(st + O_WG + chunk_off<CB>(wn * 64 + i * 32 + r, ks * 2 + g));
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -154,8 +201,8 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
         i32x4 fa[2], fb[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-          fa[i] = *reinterpret_cast<const i32x4*>(&sXi[(wm * 64 + i * 32 + r) * LDQ + ks * 32 + g * 16]);
-          fb[i] = *reinterpret_cast<const i32x4*>(&sWi[(wn * 64 + i * 32 + r) * LDQ + ks * 32 + g * 16]);
+          fa[i] = *reinterpret_cast<const i32x4*>(st + O_XI + chunk_off<CQ>(wm * 64 + i * 32 + r, ks * 2 + g));
+          fb[i] = *reinterpret_cast<const i32x4*>(st + O_WI + chunk_off<CQ>(wn * 64 + i * 32 + r, ks * 2 + g));
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -168,10 +215,10 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
       i32x8 fa[2], fb[2];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const i32x4 a0 = *reinterpret_cast<const i32x4*>(&sXf[(wm * 64 + i * 32 + r) * LDQ + g * 32]);
-        const i32x4 a1 = *reinterpret_cast<const i32x4*>(&sXf[(wm * 64 + i * 32 + r) * LDQ + g * 32 + 16]);
-        const i32x4 b0 = *reinterpret_cast<const i32x4*>(&sWf[(wn * 64 + i * 32 + r) * LDQ + g * 32]);
-        const i32x4 b1 = *reinterpret_cast<const i32x4*>(&sWf[(wn * 64 + i * 32 + r) * LDQ + g * 32 + 16]);
+        const i32x4 a0 = *reinterpret_cast<const i32x4*>(st + O_XF + chunk_off<CQ>(wm * 64 + i * 32 + r, 2 * g));
+        const i32x4 a1 = *reinterpret_cast<const i32x4*>(st + O_XF + chunk_off<CQ>(wm * 64 + i * 32 + r, 2 * g + 1));
+        const i32x4 b0 = *reinterpret_cast<const i32x4*>(st + O_WF + chunk_off<CQ>(wn * 64 + i * 32 + r, 2 * g));
+        const i32x4 b1 = *reinterpret_cast<const i32x4*>(st + O_WF + chunk_off<CQ>(wn * 64 + i * 32 + r, 2 * g + 1));
 #pragma unroll
         for (int e = 0; e < 4; ++e) { fa[i][e] = a0[e]; fa[i][4 + e] = a1[e]; fb[i][e] = b0[e]; fb[i][4 + e] = b1[e]; }
       }
@@ -182,32 +229,37 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
         for (int j = 0; j < 2; ++j)
           acc_f[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa[i], fb[j], acc_f[i][j], 0, 0, 0, 127, 0, 127);
     }
-    __syncthreads();
   }
 
-  // ---- epilogue: squared differences in fp64.  All 16 accumulator values of a lane
-  // in one 32x32 tile belong to output column (lane % 32) of that tile.
+  // ---- epilogue: squared differences in fp64.  Accumulator value e of a lane in one
+  // 32x32 tile is output (row 8*(e/4) + 4*g + e%4, column lane%32) of that tile; rows and
+  // columns past the matrix edge hold repeats of the last row and are skipped.
   const double sxi = DO_I8 ? static_cast<double>(*a.sx_i) : 0.0;
   const double sxf = DO_F8 ? static_cast<double>(*a.sx_f) : 0.0;
   double e_i = 0.0, e_f = 0.0, p = 0.0;
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int n = n0 + wn * 64 + j * 32 + r;
-    const int ns = (a.w_per_channel && n < a.N) ? n : 0;
+    const bool col_ok = n < a.N;
+    const int ns = (a.w_per_channel && col_ok) ? n : 0;
     const double ci = DO_I8 ? sxi * static_cast<double>(a.sw_i[ns]) : 0.0;
     const double cf = DO_F8 ? sxf * static_cast<double>(a.sw_f[ns]) : 0.0;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const double y = static_cast<double>(acc_r[i][j][e]);
+        const int m = m0 + wm * 64 + i * 32 + 8 * (e / 4) + 4 * g + (e % 4);
+        const bool ok = col_ok && m < a.M;
+        const double y = ok ? static_cast<double>(acc_r[i][j][e]) : 0.0;
         p = __builtin_fma(y, y, p);
         if constexpr (DO_I8) {
-          const double d = __builtin_fma(-ci, static_cast<double>(acc_i[i][j][e]), y);
+          const double q = ok ? static_cast<double>(acc_i[i][j][e]) : 0.0;
+          const double d = __builtin_fma(-ci, q, y);
           e_i = __builtin_fma(d, d, e_i);
         }
         if constexpr (DO_F8) {
-          const double d = __builtin_fma(-cf, static_cast<double>(acc_f[i][j][e]), y);
+          const double q = ok ? static_cast<double>(acc_f[i][j][e]) : 0.0;
+          const double d = __builtin_fma(-cf, q, y);
           e_f = __builtin_fma(d, d, e_f);
         }
       }
@@ -231,7 +283,7 @@ int wa_gemm_blocks(int64_t M, int64_t N) {
 }
 
 int launch_wa_gemm(const WaGemmParams& p, hipStream_t st) {
-  if (p.K % TK != 0) return MOFQ_ERR_UNSUPPORTED;
+  if (p.K % 64 != 0) return MOFQ_ERR_UNSUPPORTED;
   GemmArgs a{};
   a.x = static_cast<const uint16_t*>(p.x); a.ldx = p.ldx;
   a.w = static_cast<const uint16_t*>(p.w); a.ldw = p.ldw;
