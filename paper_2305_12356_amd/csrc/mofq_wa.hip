@@ -66,8 +66,18 @@ template <int C> MOFQ_DEV int swz(int row) {
 }
 template <int C> MOFQ_DEV int chunk_off(int row, int kc) { return (row * C + (kc ^ swz<C>(row))) * 16; }
 
-typedef __attribute__((address_space(1))) const void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
+// One wave instruction: lane l fetches 16 bytes at its own global address and deposits
+// them at LDS address lds_base + 16*l.  Written as inline assembly so that the compiler
+// does not serialise later LDS reads of OTHER buffers behind the deposit; completion is
+// tracked by hand with s_waitcnt vmcnt (deposits of a wave retire in order).
+MOFQ_DEV void lds_deposit(const char* gsrc, const unsigned char* lds_dst) {
+  const uint32_t lds_addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+      (__attribute__((address_space(3))) const unsigned char*)lds_dst));
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gsrc)
+               : "memory");   // m0 is not otherwise used by these kernels
+}
 
 // Issue this wave's share of one tile load (tile = 128*C chunks = 2*C wave instructions,
 // instruction i of the tile is issued by wave i % 4).  `src` is this lane's global
@@ -93,8 +103,7 @@ struct TileLoader {
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j) {
       const int i = wave + 4 * j;
-      if (i < 2 * C)
-        __builtin_amdgcn_global_load_lds((gptr_t)(src[j] + k_bytes), (lptr_t)(tile + i * 1024), 16, 0, 0);
+      if (i < 2 * C) lds_deposit(src[j] + k_bytes, tile + i * 1024);
     }
   }
 };
@@ -112,7 +121,13 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
   constexpr int O_XI = O_WG + (FP8 == FP8_EXACT ? SZB : 0), O_WI = O_XI + (DO_I8 ? SZQ : 0);
   constexpr int O_XF = O_WI + (DO_I8 ? SZQ : 0), O_WF = O_XF + (FP8 == FP8_NATIVE ? SZQ : 0);
   constexpr int STAGE = O_WF + (FP8 == FP8_NATIVE ? SZQ : 0);
-  __shared__ __attribute__((aligned(1024))) unsigned char s_buf[2 * STAGE];
+  // Stages in flight: a tile deposit takes a few thousand clocks to arrive while one stage
+  // of matrix work is ~700, so loads are issued two stages ahead where LDS allows it.
+  constexpr int NST = (3 * STAGE <= 150 * 1024) ? 3 : 2;
+  // load instructions one wave issues per stage (they retire in order)
+  constexpr int LPS = 2 * TileLoader<CB>::PER_WAVE * (FP8 == FP8_EXACT ? 2 : 1) +
+                      2 * TileLoader<CQ>::PER_WAVE * ((DO_I8 ? 1 : 0) + (FP8 == FP8_NATIVE ? 1 : 0));
+  __shared__ __attribute__((aligned(1024))) unsigned char s_buf[NST * STAGE];
   __shared__ double s_red[3][4];
 
   const int tid = threadIdx.x;
@@ -140,7 +155,7 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
     lwf.init(a.wf, a.K, n0, a.N, wave, lane);
   }
   auto issue_stage = [&](int kt) {
-    unsigned char* st = s_buf + (kt & 1) * STAGE;
+    unsigned char* st = s_buf + (kt % NST) * STAGE;
     const int64_t kb = static_cast<int64_t>(kt) * TK;     // k offset in elements
     lxb.issue(st + O_XB, wave, kb * 2);
     lwb.issue(st + O_WB, wave, kb * 2);
@@ -160,12 +175,19 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
       for (int e = 0; e < 16; ++e) { acc_r[i][j][e] = 0.0f; acc_i[i][j][e] = 0; acc_f[i][j][e] = 0.0f; }
 
   const int KT = a.K / TK;
+  // s_waitcnt immediates: vmcnt = n, expcnt / lgkmcnt unconstrained
+  constexpr int WAIT_ALL = 0 | (7 << 4) | (15 << 8);
+  constexpr int WAIT_BUT_ONE_STAGE = (LPS & 15) | (7 << 4) | (15 << 8) | ((LPS >> 4) << 14);
   issue_stage(0);
+  if (NST == 3 && KT > 1) issue_stage(1);
   for (int kt = 0; kt < KT; ++kt) {
-    __builtin_amdgcn_s_waitcnt(0);     // this wave's deposits of stage kt have landed
-    __syncthreads();                   // ... and everyone's; also: all waves are done with stage kt-1
-    if (kt + 1 < KT) issue_stage(kt + 1);   // overlaps with the matrix work below
-    const unsigned char* st = s_buf + (kt & 1) * STAGE;
+    // this wave's deposits of stage kt have landed (the stage after it may still be in flight)
+    if (NST == 3 && kt + 1 < KT) __builtin_amdgcn_s_waitcnt(WAIT_BUT_ONE_STAGE);
+    else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+    __builtin_amdgcn_s_barrier();      // ... and everyone's; also: all waves are done with stage kt-1
+    asm volatile("" ::: "memory");     // LDS reads below must not move above the barrier
+    if (kt + NST - 1 < KT) issue_stage(kt + NST - 1);   // into the buffer stage kt-1 just left
+    const unsigned char* st = s_buf + (kt % NST) * STAGE;
 
     // Lane (r, g) supplies row r of a 32-row operand tile and the g-th half of the
     // instruction's K range, for A and B alike.
