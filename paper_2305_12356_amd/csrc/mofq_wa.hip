@@ -59,12 +59,12 @@ constexpr int FP8_NONE = 0, FP8_NATIVE = 1, FP8_EXACT = 2;
 // chosen through WHICH global chunk a lane fetches: chunk slot p of row R holds logical
 // chunk p ^ swz(R), a rotation that spreads the 16-byte column read by the matrix-core
 // fragment loads over all bank groups.
-template <int C> MOFQ_DEV int swz(int row) {
-  if constexpr (C == 8) return row & 7;
-  else if constexpr (C == 4) return (row >> 1) & 3;
-  else return (row >> 2) & 1;
-}
-template <int C> MOFQ_DEV int chunk_off(int row, int kc) { return (row * C + (kc ^ swz<C>(row))) * 16; }
+// A 128-bit LDS read is served 16 lanes (256 bytes, all 64 banks) per clock; the 16
+// lanes of one pass read the same logical chunk of 16 consecutive rows, which cover
+// 16/C distinct 256-byte offsets by themselves, so the rotation advances once every
+// 16/C rows.
+MOFQ_DEV constexpr int swz(int C, int row) { return (row / (16 / C)) % C; }
+MOFQ_DEV constexpr int chunk_off(int C, int row, int kc) { return (row * C + (kc ^ swz(C, row))) * 16; }
 
 // One wave instruction: lane l fetches 16 bytes at its own global address and deposits
 // them at LDS address lds_base + 16*l.  Written as inline assembly so that the compiler
@@ -79,54 +79,72 @@ MOFQ_DEV void lds_deposit(const char* gsrc, const unsigned char* lds_dst) {
                : "memory");   // m0 is not otherwise used by these kernels
 }
 
-// Issue this wave's share of one tile load (tile = 128*C chunks = 2*C wave instructions,
-// instruction i of the tile is issued by wave i % 4).  `src` is this lane's global
-// pointer for instruction 0 of its wave's share at k = 0; rows/chunks per instruction are
-// fixed, so advancing K only adds a constant.
-template <int C>
-struct TileLoader {
-  static constexpr int PER_WAVE = (2 * C + 3) / 4;   // instructions per wave (C=2: 1, C=4: 2, C=8: 4)
-  const char* src[PER_WAVE];
-  MOFQ_DEV void init(const void* base, int64_t row_bytes, int row0, int rows, int wave, int lane) {
-#pragma unroll
-    for (int j = 0; j < PER_WAVE; ++j) {
-      const int i = wave + 4 * j;                    // instruction index within the tile
-      const int c = i * 64 + lane;                   // LDS chunk slot
-      const int row = c / C, p = c % C;
-      const int kc = p ^ swz<C>(row);
-      int grow = row0 + row;
-      grow = grow < rows ? grow : rows - 1;          // rows past the edge repeat the last one (masked later)
-      src[j] = static_cast<const char*>(base) + static_cast<int64_t>(grow) * row_bytes + kc * 16;
-    }
+// Compile-time plan of one K step: which operand tiles a stage holds, which deposits one
+// wave issues for it ("slots"), and the order of the matrix-core groups (4 instructions
+// on one 64 x 64 wave tile each).  A tile of C chunks per row is 2*C wave deposits,
+// deposit i issued by wave i % 4.
+enum : int { K_REF = 0, K_GRID = 1, K_I8 = 2, K_F8 = 3 };
+struct Slot { int kind, is_w, off, C, j; };
+struct Group { int kind, ks; };
+
+template <bool DO_I8, int FP8>
+struct Plan {
+  static constexpr int TK = (FP8 == FP8_NATIVE) ? 64 : 32;   // the fp8 instruction consumes K = 64
+  static constexpr int CB = TK * 2 / 16;                     // chunks per row, 16-bit tiles
+  static constexpr int CQ = TK / 16;                         // chunks per row, 8-bit tiles
+  static constexpr int SZB = TM * TK * 2, SZQ = TM * TK;     // bytes per tile
+  static constexpr bool GRID = FP8 == FP8_EXACT, F8 = FP8 == FP8_NATIVE;
+  static constexpr int O_XB = 0, O_WB = O_XB + SZB;
+  static constexpr int O_XG = O_WB + SZB, O_WG = O_XG + (GRID ? SZB : 0);
+  static constexpr int O_XI = O_WG + (GRID ? SZB : 0), O_WI = O_XI + (DO_I8 ? SZQ : 0);
+  static constexpr int O_XF = O_WI + (DO_I8 ? SZQ : 0), O_WF = O_XF + (F8 ? SZQ : 0);
+  static constexpr int STAGE = O_WF + (F8 ? SZQ : 0);
+  // Stages in flight: a deposit takes a few thousand clocks to arrive while one stage of
+  // matrix work is ~700, so loads are issued two stages ahead where LDS allows it.
+  static constexpr int NST = (3 * STAGE <= 150 * 1024) ? 3 : 2;
+  static constexpr int PWB = CB / 2, PWQ = CQ / 2;           // deposits per wave per tile
+  static constexpr int LPS = 2 * PWB * (GRID ? 2 : 1) + 2 * PWQ * ((DO_I8 ? 1 : 0) + (F8 ? 1 : 0));
+  static constexpr int off_of(int kind, int is_w) {
+    return kind == K_REF ? (is_w ? O_WB : O_XB) : kind == K_GRID ? (is_w ? O_WG : O_XG)
+         : kind == K_I8 ? (is_w ? O_WI : O_XI) : (is_w ? O_WF : O_XF);
   }
-  MOFQ_DEV void issue(unsigned char* tile, int wave, int64_t k_bytes) const {
-#pragma unroll
-    for (int j = 0; j < PER_WAVE; ++j) {
-      const int i = wave + 4 * j;
-      if (i < 2 * C) lds_deposit(src[j] + k_bytes, tile + i * 1024);
+  static constexpr Slot slot(int s) {
+    const int kinds[4] = {K_REF, K_GRID, K_I8, K_F8};
+    const bool on[4] = {true, GRID, DO_I8, F8};
+    for (int q = 0; q < 4; ++q) {
+      if (!on[q]) continue;
+      const int pw = (q < 2) ? PWB : PWQ;
+      for (int is_w = 0; is_w < 2; ++is_w) {
+        if (s < pw) return Slot{kinds[q], is_w, off_of(kinds[q], is_w), (q < 2) ? CB : CQ, s};
+        s -= pw;
+      }
     }
+    return Slot{0, 0, 0, CB, 0};
+  }
+  // Matrix-core groups of one stage, ordered so that the three products alternate.
+  static constexpr int NREF = TK / 16, NI8 = DO_I8 ? TK / 32 : 0;
+  static constexpr int NG = NREF * (GRID ? 2 : 1) + NI8 + (F8 ? 1 : 0);
+  static constexpr Group group(int g) {
+    if (GRID) {                       // ref0 grid0 ref1 grid1 [i8]
+      if (g < 2 * NREF) return Group{(g & 1) ? K_GRID : K_REF, g >> 1};
+      return Group{K_I8, g - 2 * NREF};
+    }
+    if (F8) {                         // TK = 64: ref0 ref1 [i8_0] ref2 ref3 [i8_1] f8
+      if (g == NG - 1) return Group{K_F8, 0};
+      if (!DO_I8) return Group{K_REF, g};
+      if (g % 3 == 2) return Group{K_I8, g / 3};
+      return Group{K_REF, (g / 3) * 2 + g % 3};
+    }
+    if (g < NREF) return Group{K_REF, g};   // ref0 ref1 i8
+    return Group{K_I8, g - NREF};
   }
 };
 
 template <bool DO_I8, int FP8>
 __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
+  using P = Plan<DO_I8, FP8>;
   constexpr bool DO_F8 = FP8 != FP8_NONE;
-  constexpr int TK = (FP8 == FP8_NATIVE) ? 64 : 32;      // the fp8 instruction consumes K = 64
-  constexpr int CB = TK * 2 / 16;                        // chunks per row, 16-bit tiles
-  constexpr int CQ = TK / 16;                            // chunks per row, 8-bit tiles
-  constexpr int SZB = TM * TK * 2, SZQ = TM * TK;        // bytes per tile
-  // stage layout
-  constexpr int O_XB = 0, O_WB = O_XB + SZB;
-  constexpr int O_XG = O_WB + SZB, O_WG = O_XG + (FP8 == FP8_EXACT ? SZB : 0);
-  constexpr int O_XI = O_WG + (FP8 == FP8_EXACT ? SZB : 0), O_WI = O_XI + (DO_I8 ? SZQ : 0);
-  constexpr int O_XF = O_WI + (DO_I8 ? SZQ : 0), O_WF = O_XF + (FP8 == FP8_NATIVE ? SZQ : 0);
-  constexpr int STAGE = O_WF + (FP8 == FP8_NATIVE ? SZQ : 0);
-  // Stages in flight: a tile deposit takes a few thousand clocks to arrive while one stage
-  // of matrix work is ~700, so loads are issued two stages ahead where LDS allows it.
-  constexpr int NST = (3 * STAGE <= 150 * 1024) ? 3 : 2;
-  // load instructions one wave issues per stage (they retire in order)
-  constexpr int LPS = 2 * TileLoader<CB>::PER_WAVE * (FP8 == FP8_EXACT ? 2 : 1) +
-                      2 * TileLoader<CQ>::PER_WAVE * ((DO_I8 ? 1 : 0) + (FP8 == FP8_NATIVE ? 1 : 0));
+  constexpr int TK = P::TK, NST = P::NST, LPS = P::LPS, NG = P::NG, STAGE = P::STAGE;
   __shared__ __attribute__((aligned(1024))) unsigned char s_buf[NST * STAGE];
   __shared__ double s_red[3][4];
 
@@ -138,30 +156,36 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
   const int bm = blockIdx.x / a.tiles_n, bn = blockIdx.x - bm * a.tiles_n;
   const int m0 = bm * TM, n0 = bn * TN;
 
-  TileLoader<CB> lxb, lwb, lxg, lwg;
-  TileLoader<CQ> lxi, lwi, lxf, lwf;
-  lxb.init(a.x, a.ldx * 2, m0, a.M, wave, lane);
-  lwb.init(a.w, a.ldw * 2, n0, a.N, wave, lane);
-  if constexpr (FP8 == FP8_EXACT) {
-    lxg.init(a.xg, static_cast<int64_t>(a.K) * 2, m0, a.M, wave, lane);
-    lwg.init(a.wg, static_cast<int64_t>(a.K) * 2, n0, a.N, wave, lane);
+  // This lane's global source of each deposit slot at k = 0; advancing K adds a constant.
+  const char* src[LPS];
+#pragma unroll
+  for (int s = 0; s < LPS; ++s) {
+    const Slot sl = P::slot(s);
+    const int c = (wave + 4 * sl.j) * 64 + lane;          // LDS chunk slot within the tile
+    const int row = c / sl.C, kc = (c % sl.C) ^ swz(sl.C, row);
+    const int rows = sl.is_w ? a.N : a.M;
+    int grow = (sl.is_w ? n0 : m0) + row;
+    grow = grow < rows ? grow : rows - 1;                 // rows past the edge repeat the last one (masked later)
+    const char* base;
+    int64_t row_bytes;
+    switch (sl.kind) {
+      case K_REF: base = reinterpret_cast<const char*>(sl.is_w ? a.w : a.x); row_bytes = (sl.is_w ? a.ldw : a.ldx) * 2; break;
+      case K_GRID: base = reinterpret_cast<const char*>(sl.is_w ? a.wg : a.xg); row_bytes = static_cast<int64_t>(a.K) * 2; break;
+      case K_I8: base = reinterpret_cast<const char*>(sl.is_w ? a.wi : a.xi); row_bytes = a.K; break;
+      default: base = reinterpret_cast<const char*>(sl.is_w ? a.wf : a.xf); row_bytes = a.K; break;
+    }
+    src[s] = base + static_cast<int64_t>(grow) * row_bytes + kc * 16;
   }
-  if constexpr (DO_I8) {
-    lxi.init(a.xi, a.K, m0, a.M, wave, lane);
-    lwi.init(a.wi, a.K, n0, a.N, wave, lane);
-  }
-  if constexpr (FP8 == FP8_NATIVE) {
-    lxf.init(a.xf, a.K, m0, a.M, wave, lane);
-    lwf.init(a.wf, a.K, n0, a.N, wave, lane);
-  }
-  auto issue_stage = [&](int kt) {
+  // Deposits [lo, hi) of this wave for stage kt.
+  auto issue = [&](int kt, int lo, int hi) {
     unsigned char* st = s_buf + (kt % NST) * STAGE;
     const int64_t kb = static_cast<int64_t>(kt) * TK;     // k offset in elements
-    lxb.issue(st + O_XB, wave, kb * 2);
-    lwb.issue(st + O_WB, wave, kb * 2);
-    if constexpr (FP8 == FP8_EXACT) { lxg.issue(st + O_XG, wave, kb * 2); lwg.issue(st + O_WG, wave, kb * 2); }
-    if constexpr (DO_I8) { lxi.issue(st + O_XI, wave, kb); lwi.issue(st + O_WI, wave, kb); }
-    if constexpr (FP8 == FP8_NATIVE) { lxf.issue(st + O_XF, wave, kb); lwf.issue(st + O_WF, wave, kb); }
+#pragma unroll
+    for (int s = 0; s < LPS; ++s) {
+      if (s < lo || s >= hi) continue;
+      const Slot sl = P::slot(s);
+      lds_deposit(src[s] + kb * (sl.kind <= K_GRID ? 2 : 1), st + sl.off + (wave + 4 * sl.j) * 1024);
+    }
   };
 
   f32x16 acc_r[2][2];
@@ -174,82 +198,74 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) { acc_r[i][j][e] = 0.0f; acc_i[i][j][e] = 0; acc_f[i][j][e] = 0.0f; }
 
+  // Fragment loads of one group: lane (r, g) supplies row r of a 32-row operand tile and
+  // the g-th half of the instruction's K range, for A and B alike.  f[0..1] = A tiles,
+  // f[2..3] = B tiles (the fp8 group needs two 16-byte chunks each: f[4..7]).
+  auto load_group = [&](const unsigned char* st, int gi, i32x4 (&f)[8]) {
+    const Group gr = P::group(gi);
+    const int C = gr.kind <= K_GRID ? P::CB : P::CQ;
+    const int ox = P::off_of(gr.kind, 0), ow = P::off_of(gr.kind, 1);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int ra = wm * 64 + i * 32 + r, rb = wn * 64 + i * 32 + r;
+      if (gr.kind == K_F8) {
+        f[i] = *reinterpret_cast<const i32x4*>(st + ox + chunk_off(C, ra, 2 * g));
+        f[4 + i] = *reinterpret_cast<const i32x4*>(st + ox + chunk_off(C, ra, 2 * g + 1));
+        f[2 + i] = *reinterpret_cast<const i32x4*>(st + ow + chunk_off(C, rb, 2 * g));
+        f[6 + i] = *reinterpret_cast<const i32x4*>(st + ow + chunk_off(C, rb, 2 * g + 1));
+      } else {
+        f[i] = *reinterpret_cast<const i32x4*>(st + ox + chunk_off(C, ra, gr.ks * 2 + g));
+        f[2 + i] = *reinterpret_cast<const i32x4*>(st + ow + chunk_off(C, rb, gr.ks * 2 + g));
+      }
+    }
+  };
+  auto run_group = [&](int gi, const i32x4 (&f)[8]) {
+    const Group gr = P::group(gi);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        if (gr.kind == K_REF) {
+          acc_r[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f[i]), __builtin_bit_cast(bf16x8, f[2 + j]), acc_r[i][j], 0, 0, 0);
+        } else if (gr.kind == K_GRID) {
+          acc_f[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f[i]), __builtin_bit_cast(bf16x8, f[2 + j]), acc_f[i][j], 0, 0, 0);
+        } else if (gr.kind == K_I8) {
+          acc_i[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f[i], f[2 + j], acc_i[i][j], 0, 0, 0);
+        } else {
+          i32x8 fa, fb;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { fa[e] = f[i][e]; fa[4 + e] = f[4 + i][e]; fb[e] = f[2 + j][e]; fb[4 + e] = f[6 + j][e]; }
+          // format selectors 0 = E4M3 for both operands; block scales 2^0 (exponent byte 127)
+          acc_f[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa, fb, acc_f[i][j], 0, 0, 0, 127, 0, 127);
+        }
+      }
+  };
+
   const int KT = a.K / TK;
   // s_waitcnt immediates: vmcnt = n, expcnt / lgkmcnt unconstrained
   constexpr int WAIT_ALL = 0 | (7 << 4) | (15 << 8);
   constexpr int WAIT_BUT_ONE_STAGE = (LPS & 15) | (7 << 4) | (15 << 8) | ((LPS >> 4) << 14);
-  issue_stage(0);
-  if (NST == 3 && KT > 1) issue_stage(1);
+  issue(0, 0, LPS);
+  if (NST == 3 && KT > 1) issue(1, 0, LPS);
   for (int kt = 0; kt < KT; ++kt) {
     // this wave's deposits of stage kt have landed (the stage after it may still be in flight)
     if (NST == 3 && kt + 1 < KT) __builtin_amdgcn_s_waitcnt(WAIT_BUT_ONE_STAGE);
     else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
     __builtin_amdgcn_s_barrier();      // ... and everyone's; also: all waves are done with stage kt-1
     asm volatile("" ::: "memory");     // LDS reads below must not move above the barrier
-    if (kt + NST - 1 < KT) issue_stage(kt + NST - 1);   // into the buffer stage kt-1 just left
     const unsigned char* st = s_buf + (kt % NST) * STAGE;
+    const bool more = kt + NST - 1 < KT;   // next deposits go into the buffer stage kt-1 just left
 
-    // Lane (r, g) supplies row r of a 32-row operand tile and the g-th half of the
-    // instruction's K range, for A and B alike.
+    // Software pipeline over the groups: fragments of group g+1 are requested before the
+    // matrix instructions of group g are issued, and the stage's deposits are spread over
+    // the groups so that the texture path works while the matrix cores do.
+    i32x4 f[2][8];
+    load_group(st, 0, f[0]);
 #pragma unroll
-    for (int ks = 0; ks < TK / 16; ++ks) {
-      bf16x8 fa[2], fb[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        fa[i] = *reinterpret_cast<const bf16x8*>(st + O_XB + chunk_off<CB>(wm * 64 + i * 32 + r, ks * 2 + g));
-        fb[i] = *reinterpret_cast<const bf16x8*>(st + O_WB + chunk_off<CB>(wn * 64 + i * 32 + r, ks * 2 + g));
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc_r[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc_r[i][j], 0, 0, 0);
-      if constexpr (FP8 == FP8_EXACT) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          fa[i] = *reinterpret_cast<const bf16x8*>(st + O_XG + chunk_off<CB>(wm * 64 + i * 32 + r, ks * 2 + g));
-          fb[i] = *reinterpret_cast<const bf16x8*>(st + O_WG + chunk_off<CB>(wn * 64 + i * 32 + r, ks * 2 + g));
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc_f[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc_f[i][j], 0, 0, 0);
-      }
-    }
-    if constexpr (DO_I8) {
-#pragma unroll
-      for (int ks = 0; ks < TK / 32; ++ks) {
-        i32x4 fa[2], fb[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          fa[i] = *reinterpret_cast<const i32x4*>(st + O_XI + chunk_off<CQ>(wm * 64 + i * 32 + r, ks * 2 + g));
-          fb[i] = *reinterpret_cast<const i32x4*>(st + O_WI + chunk_off<CQ>(wn * 64 + i * 32 + r, ks * 2 + g));
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc_i[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc_i[i][j], 0, 0, 0);
-      }
-    }
-    if constexpr (FP8 == FP8_NATIVE) {
-      i32x8 fa[2], fb[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const i32x4 a0 = *reinterpret_cast<const i32x4*>(st + O_XF + chunk_off<CQ>(wm * 64 + i * 32 + r, 2 * g));
-        const i32x4 a1 = *reinterpret_cast<const i32x4*>(st + O_XF + chunk_off<CQ>(wm * 64 + i * 32 + r, 2 * g + 1));
-        const i32x4 b0 = *reinterpret_cast<const i32x4*>(st + O_WF + chunk_off<CQ>(wn * 64 + i * 32 + r, 2 * g));
-        const i32x4 b1 = *reinterpret_cast<const i32x4*>(st + O_WF + chunk_off<CQ>(wn * 64 + i * 32 + r, 2 * g + 1));
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { fa[i][e] = a0[e]; fa[i][4 + e] = a1[e]; fb[i][e] = b0[e]; fb[i][4 + e] = b1[e]; }
-      }
-      // format selectors 0 = E4M3 for both operands; block scales 2^0 (exponent byte 127)
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc_f[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa[i], fb[j], acc_f[i][j], 0, 0, 0, 127, 0, 127);
+    for (int gi = 0; gi < NG; ++gi) {
+      if (gi + 1 < NG) load_group(st, gi + 1, f[(gi + 1) & 1]);
+      if (more) issue(kt + NST - 1, gi * LPS / NG, (gi + 1) * LPS / NG);
+      run_group(gi, f[gi & 1]);
     }
   }
 
