@@ -4,10 +4,20 @@
 //     E_f = sum_{t,o} ( Y[t,o] - sx_f * sw_f[o] * (Qx_f Qw_f^T)[t,o] )^2 ,  P = sum Y^2 ,
 //     Y = X W^T .
 //
-// One kernel computes, per 128x128 output tile, the reference product on the bf16
-// matrix cores, the INT8 code product on the int8 matrix cores and the FP8-E4M3
-// code product, then reduces the squared differences in fp64.  Y is never written
-// to memory.
+// One kernel computes, per 256x128 output tile, the reference product on the bf16
+// matrix cores, then the INT8 code product on the int8 matrix cores and the FP8-E4M3
+// code product, one after the other: each product is a K loop of its own over its own
+// operand arrays, the reference accumulators stay in registers for the whole kernel and
+// the quantized accumulators are reduced against them (squared differences in fp64) as
+// soon as their loop ends.  Y is never written to memory.
+//
+// Why the products run in sequence and not side by side: the loop is bound by how many
+// bytes can be in flight from L2 into LDS (measured ~1 us from issue to arrival under
+// load) and by the texture path, which handles one 128-byte line every ~2.2 clocks
+// whatever part of the line is used.  One product at a time lets a stage hold whole
+// 128-byte lines of every operand row (48 KB, three stages resident), and two
+// accumulator sets (256 registers) leave room for a 256x128 tile, which needs 25 %
+// fewer operand bytes per flop than 128x128.
 //
 // Exactness: bf16 x bf16 products are exact in fp32 and are accumulated in fp32;
 // int8 products are accumulated exactly in int32 (|sum| <= 32768*127*127 < 2^31).
@@ -21,6 +31,8 @@
 //                below 2^-13 of the group's largest product are truncated, which
 //                shifts the error sum by ~1e-5..1e-4 relative on tensors with
 //                outlier channels.
+#include <type_traits>
+
 #include "mofq_device.h"
 #include "mofq_internal.h"
 
@@ -34,7 +46,9 @@ typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 
-constexpr int TM = 128, TN = 128;               // workgroup tile; 4 waves, 64 x 64 each
+constexpr int TM = 256, TN = 128;               // workgroup tile; 4 waves, 128 x 64 each
+constexpr int WM = 128, WN = 64;                // wave tile: 4 x 2 matrix-core tiles of 32 x 32
+constexpr int TI = WM / 32, TJ = WN / 32;
 
 struct GemmArgs {
   const uint16_t* x; int64_t ldx;               // bf16 [M][K]
@@ -46,25 +60,30 @@ struct GemmArgs {
   const float* sx_f; const float* sw_f;
   int32_t w_per_channel;
   int32_t M, N, K;
-  int32_t tiles_n;
+  int32_t tiles_m, tiles_n;
   double* part_i; double* part_f; double* part_p;   // [blocks]
 };
 
 constexpr int FP8_NONE = 0, FP8_NATIVE = 1, FP8_EXACT = 2;
 
-// ---- LDS tiles --------------------------------------------------------------------
-// A tile holds 128 rows of RB bytes (RB = 32, 64 or 128), i.e. C = RB/16 chunks of 16
-// bytes per row, with no padding.  Tiles are filled by global_load_lds (each lane of a
-// wave instruction deposits 16 bytes at consecutive LDS addresses), so the layout is
-// chosen through WHICH global chunk a lane fetches: chunk slot p of row R holds logical
-// chunk p ^ swz(R), a rotation that spreads the 16-byte column read by the matrix-core
-// fragment loads over all bank groups.
-// A 128-bit LDS read is served 16 lanes (256 bytes, all 64 banks) per clock; the 16
-// lanes of one pass read the same logical chunk of 16 consecutive rows, which cover
-// 16/C distinct 256-byte offsets by themselves, so the rotation advances once every
-// 16/C rows.
-MOFQ_DEV constexpr int swz(int C, int row) { return (row / (16 / C)) % C; }
-MOFQ_DEV constexpr int chunk_off(int C, int row, int kc) { return (row * C + (kc ^ swz(C, row))) * 16; }
+// ---- LDS stage ----------------------------------------------------------------------
+// A stage holds one K slab of both operand tiles: 256 rows of X then 128 rows of W, each
+// row ROW_B = 128 bytes (64 sixteen-bit or 128 eight-bit elements, one cache line), i.e.
+// 8 chunks of 16 bytes, no padding.  Stages are filled by global_load_lds (each lane of a wave
+// instruction deposits 16 bytes at consecutive LDS addresses), so the layout is chosen
+// through WHICH global chunk a lane fetches: chunk slot p of row R holds logical chunk
+// p ^ swz(R).  A 128-bit LDS read is served 16 lanes (256 bytes, all 64 banks) per
+// clock; the 16 lanes of one pass read the same logical chunk of 16 consecutive rows,
+// which by themselves cover 2 distinct 128-byte offsets, so the rotation advances once
+// every 2 rows.
+constexpr int ROW_B = 128;
+constexpr int CH = ROW_B / 16;                  // chunks per row
+constexpr int STAGE_ROWS = TM + TN;
+constexpr int STAGE = STAGE_ROWS * ROW_B;       // 48 KB
+constexpr int NST = 3;                          // stages resident
+constexpr int AHEAD = NST - 1;                  // stage kt + AHEAD is issued during step kt
+constexpr int DEP = STAGE / 1024 / 4;           // deposits per wave per stage (12)
+MOFQ_DEV constexpr int swz(int row) { return (row >> 1) & (CH - 1); }
 
 // One wave instruction: lane l fetches 16 bytes at its own global address and deposits
 // them at LDS address lds_base + 16*l.  Written as inline assembly so that the compiler
@@ -79,238 +98,276 @@ MOFQ_DEV void lds_deposit(const char* gsrc, const unsigned char* lds_dst) {
                : "memory");   // m0 is not otherwise used by these kernels
 }
 
-// Compile-time plan of one K step: which operand tiles a stage holds, which deposits one
-// wave issues for it ("slots"), and the order of the matrix-core groups (4 instructions
-// on one 64 x 64 wave tile each).  A tile of C chunks per row is 2*C wave deposits,
-// deposit i issued by wave i % 4.
-enum : int { K_REF = 0, K_GRID = 1, K_I8 = 2, K_F8 = 3 };
-struct Slot { int kind, is_w, off, C, j; };
-struct Group { int kind, ks; };
+// s_waitcnt with only the vector-memory counter constrained (6 bits, split field).
+template <int N> MOFQ_DEV void wait_deposits_but() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
 
-template <bool DO_I8, int FP8>
-struct Plan {
-  static constexpr int TK = (FP8 == FP8_NATIVE) ? 64 : 32;   // the fp8 instruction consumes K = 64
-  static constexpr int CB = TK * 2 / 16;                     // chunks per row, 16-bit tiles
-  static constexpr int CQ = TK / 16;                         // chunks per row, 8-bit tiles
-  static constexpr int SZB = TM * TK * 2, SZQ = TM * TK;     // bytes per tile
-  static constexpr bool GRID = FP8 == FP8_EXACT, F8 = FP8 == FP8_NATIVE;
-  static constexpr int O_XB = 0, O_WB = O_XB + SZB;
-  static constexpr int O_XG = O_WB + SZB, O_WG = O_XG + (GRID ? SZB : 0);
-  static constexpr int O_XI = O_WG + (GRID ? SZB : 0), O_WI = O_XI + (DO_I8 ? SZQ : 0);
-  static constexpr int O_XF = O_WI + (DO_I8 ? SZQ : 0), O_WF = O_XF + (F8 ? SZQ : 0);
-  static constexpr int STAGE = O_WF + (F8 ? SZQ : 0);
-  // Stages in flight: a deposit takes a few thousand clocks to arrive while one stage of
-  // matrix work is ~700, so loads are issued two stages ahead where LDS allows it.
-  static constexpr int NST = (3 * STAGE <= 150 * 1024) ? 3 : 2;
-  static constexpr int PWB = CB / 2, PWQ = CQ / 2;           // deposits per wave per tile
-  static constexpr int LPS = 2 * PWB * (GRID ? 2 : 1) + 2 * PWQ * ((DO_I8 ? 1 : 0) + (F8 ? 1 : 0));
-  static constexpr int off_of(int kind, int is_w) {
-    return kind == K_REF ? (is_w ? O_WB : O_XB) : kind == K_GRID ? (is_w ? O_WG : O_XG)
-         : kind == K_I8 ? (is_w ? O_WI : O_XI) : (is_w ? O_WF : O_XF);
-  }
-  static constexpr Slot slot(int s) {
-    const int kinds[4] = {K_REF, K_GRID, K_I8, K_F8};
-    const bool on[4] = {true, GRID, DO_I8, F8};
-    for (int q = 0; q < 4; ++q) {
-      if (!on[q]) continue;
-      const int pw = (q < 2) ? PWB : PWQ;
-      for (int is_w = 0; is_w < 2; ++is_w) {
-        if (s < pw) return Slot{kinds[q], is_w, off_of(kinds[q], is_w), (q < 2) ? CB : CQ, s};
-        s -= pw;
-      }
-    }
-    return Slot{0, 0, 0, CB, 0};
-  }
-  // Matrix-core groups of one stage, ordered so that the three products alternate.
-  static constexpr int NREF = TK / 16, NI8 = DO_I8 ? TK / 32 : 0;
-  static constexpr int NG = NREF * (GRID ? 2 : 1) + NI8 + (F8 ? 1 : 0);
-  static constexpr Group group(int g) {
-    if (GRID) {                       // ref0 grid0 ref1 grid1 [i8]
-      if (g < 2 * NREF) return Group{(g & 1) ? K_GRID : K_REF, g >> 1};
-      return Group{K_I8, g - 2 * NREF};
-    }
-    if (F8) {                         // TK = 64: ref0 ref1 [i8_0] ref2 ref3 [i8_1] f8
-      if (g == NG - 1) return Group{K_F8, 0};
-      if (!DO_I8) return Group{K_REF, g};
-      if (g % 3 == 2) return Group{K_I8, g / 3};
-      return Group{K_REF, (g / 3) * 2 + g % 3};
-    }
-    if (g < NREF) return Group{K_REF, g};   // ref0 ref1 i8
-    return Group{K_I8, g - NREF};
-  }
-};
+enum : int { K_REF = 0, K_GRID = 1, K_I8 = 2, K_F8 = 3 };
 
 template <bool DO_I8, int FP8>
 __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
-  using P = Plan<DO_I8, FP8>;
-  constexpr bool DO_F8 = FP8 != FP8_NONE;
-  constexpr int TK = P::TK, NST = P::NST, LPS = P::LPS, NG = P::NG, STAGE = P::STAGE;
   __shared__ __attribute__((aligned(1024))) unsigned char s_buf[NST * STAGE];
   __shared__ double s_red[3][4];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;      // 2 x 2 waves, 64 x 64 each
+  const int wm = wave >> 1, wn = wave & 1;      // 2 x 2 waves
   const int r = lane & 31, g = lane >> 5;
-  const int bm = blockIdx.x / a.tiles_n, bn = blockIdx.x - bm * a.tiles_n;
+
+  // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (8 of them, each
+  // with its own L2), so ids are first regrouped so that one XCD works on a contiguous
+  // range of tiles, and a range is walked in bands of 4 tile rows: the 32 workgroups
+  // resident on an XCD then share 4 X tiles and 8 W tiles.
+  int t = blockIdx.x;
+  {
+    const int total = a.tiles_m * a.tiles_n;
+    const int per_xcd = total / 8;
+    if (t < per_xcd * 8) t = (t & 7) * per_xcd + (t >> 3);
+    constexpr int BAND = 4;
+    const int band = t / (BAND * a.tiles_n);
+    const int first_m = band * BAND;
+    const int rows_in_band = (a.tiles_m - first_m) < BAND ? (a.tiles_m - first_m) : BAND;
+    const int in_band = t - band * BAND * a.tiles_n;
+    const int bm_ = first_m + in_band % rows_in_band;
+    const int bn_ = in_band / rows_in_band;
+    t = bm_ * a.tiles_n + bn_;
+  }
+  const int bm = t / a.tiles_n, bn = t - bm * a.tiles_n;
   const int m0 = bm * TM, n0 = bn * TN;
 
-  // This lane's global source of each deposit slot at k = 0; advancing K adds a constant.
-  const char* src[LPS];
+  // LDS byte offsets of this lane's fragment rows inside a stage, and of the chunks it
+  // reads: lane (r, g) supplies row r of a 32-row operand tile and the g-th half of the
+  // instruction's K range, for A and B alike.
+  const int sw = swz(r);                                   // same for all of the lane's rows (multiples of 32 apart)
+  const int row_a = (wm * WM + r) * ROW_B;                 // + i * 32 * ROW_B
+  const int row_b = (TM + wn * WN + r) * ROW_B;            // + j * 32 * ROW_B
+  int ch_k[CH / 2], ch_f[CH / 2];
 #pragma unroll
-  for (int s = 0; s < LPS; ++s) {
-    const Slot sl = P::slot(s);
-    const int c = (wave + 4 * sl.j) * 64 + lane;          // LDS chunk slot within the tile
-    const int row = c / sl.C, kc = (c % sl.C) ^ swz(sl.C, row);
-    const int rows = sl.is_w ? a.N : a.M;
-    int grow = (sl.is_w ? n0 : m0) + row;
-    grow = grow < rows ? grow : rows - 1;                 // rows past the edge repeat the last one (masked later)
-    const char* base;
-    int64_t row_bytes;
-    switch (sl.kind) {
-      case K_REF: base = reinterpret_cast<const char*>(sl.is_w ? a.w : a.x); row_bytes = (sl.is_w ? a.ldw : a.ldx) * 2; break;
-      case K_GRID: base = reinterpret_cast<const char*>(sl.is_w ? a.wg : a.xg); row_bytes = static_cast<int64_t>(a.K) * 2; break;
-      case K_I8: base = reinterpret_cast<const char*>(sl.is_w ? a.wi : a.xi); row_bytes = a.K; break;
-      default: base = reinterpret_cast<const char*>(sl.is_w ? a.wf : a.xf); row_bytes = a.K; break;
-    }
-    src[s] = base + static_cast<int64_t>(grow) * row_bytes + kc * 16;
+  for (int q = 0; q < CH / 2; ++q) {
+    ch_k[q] = ((2 * q + g) ^ sw) * 16;                       // K slice q of a stage, 16 bytes per lane
+    ch_f[q] = ((4 * (q >> 1) + 2 * g + (q & 1)) ^ sw) * 16;  // fp8 instruction q/2: 32 bytes per lane, half q%2
   }
-  // Deposits [lo, hi) of this wave for stage kt.
-  auto issue = [&](int kt, int lo, int hi) {
-    unsigned char* st = s_buf + (kt % NST) * STAGE;
-    const int64_t kb = static_cast<int64_t>(kt) * TK;     // k offset in elements
-#pragma unroll
-    for (int s = 0; s < LPS; ++s) {
-      if (s < lo || s >= hi) continue;
-      const Slot sl = P::slot(s);
-      lds_deposit(src[s] + kb * (sl.kind <= K_GRID ? 2 : 1), st + sl.off + (wave + 4 * sl.j) * 1024);
-    }
-  };
 
-  f32x16 acc_r[2][2];
-  i32x16 acc_i[2][2];
-  f32x16 acc_f[2][2];
+  f32x16 acc_r[TI][TJ];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TJ; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { acc_r[i][j][e] = 0.0f; acc_i[i][j][e] = 0; acc_f[i][j][e] = 0.0f; }
+      for (int e = 0; e < 16; ++e) acc_r[i][j][e] = 0.0f;
 
-  // Fragment loads of one group: lane (r, g) supplies row r of a 32-row operand tile and
-  // the g-th half of the instruction's K range, for A and B alike.  f[0..1] = A tiles,
-  // f[2..3] = B tiles (the fp8 group needs two 16-byte chunks each: f[4..7]).
-  auto load_group = [&](const unsigned char* st, int gi, i32x4 (&f)[8]) {
-    const Group gr = P::group(gi);
-    const int C = gr.kind <= K_GRID ? P::CB : P::CQ;
-    const int ox = P::off_of(gr.kind, 0), ow = P::off_of(gr.kind, 1);
+  // ---- one product: K loop over its own operand arrays ---------------------------------
+  // KIND selects arrays, element size and matrix instruction; acc is f32x16 or i32x16.
+  auto product = [&](auto kind_c, auto& acc) {
+    constexpr int KIND = decltype(kind_c)::value;
+    constexpr int EB = (KIND == K_REF || KIND == K_GRID) ? 2 : 1;   // bytes per element
+    constexpr int TK = ROW_B / EB;                                  // K elements per stage
+    constexpr int NG = (KIND == K_F8) ? CH / 4 : CH / 2;            // matrix groups per stage (8 instructions each)
+    constexpr int NF = (KIND == K_F8) ? 2 : 1;                      // 16-byte chunks per fragment
+    const char* xb; const char* wb; int64_t xrow, wrow;
+    if constexpr (KIND == K_REF) { xb = reinterpret_cast<const char*>(a.x); wb = reinterpret_cast<const char*>(a.w); xrow = a.ldx * 2; wrow = a.ldw * 2; }
+    else if constexpr (KIND == K_GRID) { xb = reinterpret_cast<const char*>(a.xg); wb = reinterpret_cast<const char*>(a.wg); xrow = wrow = static_cast<int64_t>(a.K) * 2; }
+    else if constexpr (KIND == K_I8) { xb = reinterpret_cast<const char*>(a.xi); wb = reinterpret_cast<const char*>(a.wi); xrow = wrow = a.K; }
+    else { xb = reinterpret_cast<const char*>(a.xf); wb = reinterpret_cast<const char*>(a.wf); xrow = wrow = a.K; }
+
+    // This lane's global source of each of its wave's deposits at k = 0 (deposit i of a
+    // stage covers chunk slots 64 i .. 64 i + 63 and is issued by wave i % 4).
+    const char* src[DEP];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int ra = wm * 64 + i * 32 + r, rb = wn * 64 + i * 32 + r;
-      if (gr.kind == K_F8) {
-        f[i] = *reinterpret_cast<const i32x4*>(st + ox + chunk_off(C, ra, 2 * g));
-        f[4 + i] = *reinterpret_cast<const i32x4*>(st + ox + chunk_off(C, ra, 2 * g + 1));
-        f[2 + i] = *reinterpret_cast<const i32x4*>(st + ow + chunk_off(C, rb, 2 * g));
-        f[6 + i] = *reinterpret_cast<const i32x4*>(st + ow + chunk_off(C, rb, 2 * g + 1));
+    for (int d = 0; d < DEP; ++d) {
+      const int c = (wave + 4 * d) * 64 + lane;
+      const int row = c / CH, kc = (c % CH) ^ swz(row);
+      if (row < TM) {
+        int gr = m0 + row;
+        gr = gr < a.M ? gr : a.M - 1;          // rows past the edge repeat the last one (masked later)
+        src[d] = xb + static_cast<int64_t>(gr) * xrow + kc * 16;
       } else {
-        f[i] = *reinterpret_cast<const i32x4*>(st + ox + chunk_off(C, ra, gr.ks * 2 + g));
-        f[2 + i] = *reinterpret_cast<const i32x4*>(st + ow + chunk_off(C, rb, gr.ks * 2 + g));
+        int gr = n0 + row - TM;
+        gr = gr < a.N ? gr : a.N - 1;
+        src[d] = wb + static_cast<int64_t>(gr) * wrow + kc * 16;
       }
     }
-  };
-  auto run_group = [&](int gi, const i32x4 (&f)[8]) {
-    const Group gr = P::group(gi);
+    // K is a multiple of 64 elements, so the last stage of an 8-bit product may hold only
+    // half a row (64 bytes).  Its deposits then fetch the valid half twice (addresses stay
+    // inside the row) and the matrix groups of the missing half are skipped.
+    const int KT = (a.K + TK - 1) / TK;
+    const bool half_tail = (EB == 1) && (a.K % TK) != 0;   // 16-bit stages hold 64 elements: never
+    auto issue = [&](int kt, int lo, int hi) {   // deposits [lo, hi) of stage kt
+      unsigned char* st = s_buf + (kt % NST) * STAGE;
+      const int64_t kb = static_cast<int64_t>(kt) * ROW_B;
+      const bool tail = half_tail && kt == KT - 1;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        if (gr.kind == K_REF) {
-          acc_r[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f[i]), __builtin_bit_cast(bf16x8, f[2 + j]), acc_r[i][j], 0, 0, 0);
-        } else if (gr.kind == K_GRID) {
-          acc_f[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f[i]), __builtin_bit_cast(bf16x8, f[2 + j]), acc_f[i][j], 0, 0, 0);
-        } else if (gr.kind == K_I8) {
-          acc_i[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f[i], f[2 + j], acc_i[i][j], 0, 0, 0);
-        } else {
-          i32x8 fa, fb;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) { fa[e] = f[i][e]; fa[4 + e] = f[4 + i][e]; fb[e] = f[2 + j][e]; fb[4 + e] = f[6 + j][e]; }
-          // format selectors 0 = E4M3 for both operands; block scales 2^0 (exponent byte 127)
-          acc_f[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa, fb, acc_f[i][j], 0, 0, 0, 127, 0, 127);
+      for (int d = 0; d < DEP; ++d)
+        if (d >= lo && d < hi) {
+          const char* g_src = src[d] + kb;
+          if (tail) {
+            const int c = (wave + 4 * d) * 64 + lane;
+            if (((c % CH) ^ swz(c / CH)) >= CH / 2) g_src -= ROW_B / 2;
+          }
+          lds_deposit(g_src, st + (wave + 4 * d) * 1024);
         }
+    };
+    // Fragments of group gi of a stage: f[0 .. TI*NF) = A tiles, f[TI*NF ..) = B tiles.
+    auto load_group = [&](const unsigned char* st, int gi, i32x4 (&f)[(TI + TJ) * NF]) {
+#pragma unroll
+      for (int h = 0; h < NF; ++h) {
+        const int ch = (KIND == K_F8) ? ch_f[2 * gi + h] : ch_k[gi];
+#pragma unroll
+        for (int i = 0; i < TI; ++i) f[i * NF + h] = *reinterpret_cast<const i32x4*>(st + row_a + i * 32 * ROW_B + ch);
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) f[(TI + j) * NF + h] = *reinterpret_cast<const i32x4*>(st + row_b + j * 32 * ROW_B + ch);
       }
+    };
+    // The 8 matrix instructions of one group, with the deposits [lo, hi) of stage kt_dep
+    // spread between them: a wave issues in order, so a burst of deposits (each occupies
+    // the texture path for ~18 clocks, and four waves share it) would hold back the
+    // matrix instructions behind it while the matrix pipe runs dry.
+    auto run_group = [&](const i32x4 (&f)[(TI + TJ) * NF], bool more, int kt_dep, int lo, int hi) {
+#pragma unroll
+      for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+          {
+            const int m = i * TJ + j, n = hi - lo;
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) issue(kt_dep, lo + m * n / (TI * TJ), lo + (m + 1) * n / (TI * TJ));
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if constexpr (KIND == K_REF || KIND == K_GRID) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f[i]), __builtin_bit_cast(bf16x8, f[TI + j]), acc[i][j], 0, 0, 0);
+          } else if constexpr (KIND == K_I8) {
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f[i], f[TI + j], acc[i][j], 0, 0, 0);
+          } else {
+            i32x8 fa, fb;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { fa[e] = f[i * 2][e]; fa[4 + e] = f[i * 2 + 1][e]; fb[e] = f[(TI + j) * 2][e]; fb[4 + e] = f[(TI + j) * 2 + 1][e]; }
+            // format selectors 0 = E4M3 for both operands; block scales 2^0 (exponent byte 127)
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa, fb, acc[i][j], 0, 0, 0, 127, 0, 127);
+          }
+        }
+    };
+    // Wait until this wave's deposits of stage kt have landed; those of stage kt+1 (if
+    // there is one) may stay in flight.
+    auto wait_stage = [&](int kt) {
+      if (kt + 1 < KT) wait_deposits_but<DEP>();
+      else wait_deposits_but<0>();
+    };
+
+    // Prologue: AHEAD stages on their way.
+#pragma unroll
+    for (int s = 0; s < AHEAD; ++s)
+      if (s < KT) issue(s, 0, DEP);
+
+    // One K step: the barrier makes stage kt visible to everyone and tells everyone that
+    // stage kt-1 is no longer read, which is the buffer the deposits of stage kt+AHEAD go
+    // to.  Inside the step the fragments of group g+1 are requested before the matrix
+    // instructions of group g are issued, and the deposits are spread over the groups so
+    // that the texture path works while the matrix cores do.
+    auto step = [&](int kt, auto groups_c) {
+      constexpr int GROUPS = decltype(groups_c)::value;
+      wait_stage(kt);
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");     // LDS reads below must not move above the barrier
+      const unsigned char* st = s_buf + (kt % NST) * STAGE;
+      const bool more = kt + AHEAD < KT;
+      i32x4 f[2][(TI + TJ) * NF];
+      load_group(st, 0, f[0]);
+#pragma unroll
+      for (int gi = 0; gi < GROUPS; ++gi) {
+        if (gi + 1 < GROUPS) load_group(st, gi + 1, f[(gi + 1) & 1]);
+        run_group(f[gi & 1], more, kt + AHEAD, gi * DEP / GROUPS, (gi + 1) * DEP / GROUPS);
+      }
+    };
+    const int KT_full = half_tail ? KT - 1 : KT;
+    for (int kt = 0; kt < KT_full; ++kt) step(kt, std::integral_constant<int, NG>{});
+    if constexpr (EB == 1)
+      if (half_tail) step(KT - 1, std::integral_constant<int, NG / 2>{});
+    // All deposits of this product have landed (the last wait allowed none in flight);
+    // the next product's prologue overwrites buffers only after everyone is here.
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
   };
 
-  const int KT = a.K / TK;
-  // s_waitcnt immediates: vmcnt = n, expcnt / lgkmcnt unconstrained
-  constexpr int WAIT_ALL = 0 | (7 << 4) | (15 << 8);
-  constexpr int WAIT_BUT_ONE_STAGE = (LPS & 15) | (7 << 4) | (15 << 8) | ((LPS >> 4) << 14);
-  issue(0, 0, LPS);
-  if (NST == 3 && KT > 1) issue(1, 0, LPS);
-  for (int kt = 0; kt < KT; ++kt) {
-    // this wave's deposits of stage kt have landed (the stage after it may still be in flight)
-    if (NST == 3 && kt + 1 < KT) __builtin_amdgcn_s_waitcnt(WAIT_BUT_ONE_STAGE);
-    else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-    __builtin_amdgcn_s_barrier();      // ... and everyone's; also: all waves are done with stage kt-1
-    asm volatile("" ::: "memory");     // LDS reads below must not move above the barrier
-    const unsigned char* st = s_buf + (kt % NST) * STAGE;
-    const bool more = kt + NST - 1 < KT;   // next deposits go into the buffer stage kt-1 just left
-
-    // Software pipeline over the groups: fragments of group g+1 are requested before the
-    // matrix instructions of group g are issued, and the stage's deposits are spread over
-    // the groups so that the texture path works while the matrix cores do.
-    i32x4 f[2][8];
-    load_group(st, 0, f[0]);
+  // ---- squared differences in fp64.  Accumulator value e of a lane in one 32x32 tile is
+  // output (row 8*(e/4) + 4*g + e%4, column lane%32) of that tile; rows and columns past
+  // the matrix edge hold repeats of the last row and are skipped.  The first reduction
+  // also sums Y^2.
+  double p = 0.0;
+  auto sq_diff = [&](auto with_p_c, const auto& acc_q, const float* sx, const float* sw_) {
+    constexpr bool WITH_P = decltype(with_p_c)::value;
+    __builtin_amdgcn_sched_barrier(0);
+    const double sxd = static_cast<double>(*sx);
+    double e_q = 0.0;
+    // rows of this lane's accumulators that exist: 32 i + 8 (e/4) + e%4 < row_lim.  Opaque,
+    // so that each reduction computes its own masks instead of keeping 128 of them live.
+    int row_lim = a.M - (m0 + wm * WM + 4 * g);
+    asm volatile("" : "+v"(row_lim));
 #pragma unroll
-    for (int gi = 0; gi < NG; ++gi) {
-      if (gi + 1 < NG) load_group(st, gi + 1, f[(gi + 1) & 1]);
-      if (more) issue(kt + NST - 1, gi * LPS / NG, (gi + 1) * LPS / NG);
-      run_group(gi, f[gi & 1]);
+    for (int j = 0; j < TJ; ++j) {
+      const int n = n0 + wn * WN + j * 32 + r;
+      const bool col_ok = n < a.N;
+      const int ns = (a.w_per_channel && col_ok) ? n : 0;
+      const double cq = sxd * static_cast<double>(sw_[ns]);
+#pragma unroll
+      for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const bool ok = col_ok && (i * 32 + 8 * (e / 4) + (e % 4)) < row_lim;
+          // Opaque copy, ordered after the previous element's sum.  Without it the fp64
+          // image of all 128 reference values is kept (spilled) across the next product's
+          // K loop for reuse in its reduction, and the conversions of all elements are
+          // hoisted ahead of the two summation chains, which spills as well: every
+          // register is in use here.
+          float yf = acc_r[i][j][e];
+          asm volatile("" : "+v"(yf) : "v"(e_q));
+          const double y = ok ? static_cast<double>(yf) : 0.0;
+          const double q = ok ? static_cast<double>(acc_q[i][j][e]) : 0.0;
+          const double d = __builtin_fma(-cq, q, y);
+          e_q = __builtin_fma(d, d, e_q);
+          if constexpr (WITH_P) p = __builtin_fma(y, y, p);
+        }
     }
-  }
+    // Pin the sums here: otherwise the Y^2 chain is sunk to the end of the kernel and
+    // its 128 fp64 inputs are spilled across the next product.
+    asm volatile("" : "+v"(e_q), "+v"(p));
+    __builtin_amdgcn_sched_barrier(0);   // and keep the next product's set-up out of this reduction
+    return wave_sum(e_q);
+  };
 
-  // ---- epilogue: squared differences in fp64.  Accumulator value e of a lane in one
-  // 32x32 tile is output (row 8*(e/4) + 4*g + e%4, column lane%32) of that tile; rows and
-  // columns past the matrix edge hold repeats of the last row and are skipped.
-  const double sxi = DO_I8 ? static_cast<double>(*a.sx_i) : 0.0;
-  const double sxf = DO_F8 ? static_cast<double>(*a.sx_f) : 0.0;
-  double e_i = 0.0, e_f = 0.0, p = 0.0;
+  product(std::integral_constant<int, K_REF>{}, acc_r);
+  double e_i = 0.0, e_f = 0.0;
+  if constexpr (DO_I8) {
+    i32x16 acc_i[TI][TJ];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int n = n0 + wn * 64 + j * 32 + r;
-    const bool col_ok = n < a.N;
-    const int ns = (a.w_per_channel && col_ok) ? n : 0;
-    const double ci = DO_I8 ? sxi * static_cast<double>(a.sw_i[ns]) : 0.0;
-    const double cf = DO_F8 ? sxf * static_cast<double>(a.sw_f[ns]) : 0.0;
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < TJ; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (e / 4) + 4 * g + (e % 4);
-        const bool ok = col_ok && m < a.M;
-        const double y = ok ? static_cast<double>(acc_r[i][j][e]) : 0.0;
-        p = __builtin_fma(y, y, p);
-        if constexpr (DO_I8) {
-          const double q = ok ? static_cast<double>(acc_i[i][j][e]) : 0.0;
-          const double d = __builtin_fma(-ci, q, y);
-          e_i = __builtin_fma(d, d, e_i);
-        }
-        if constexpr (DO_F8) {
-          const double q = ok ? static_cast<double>(acc_f[i][j][e]) : 0.0;
-          const double d = __builtin_fma(-cf, q, y);
-          e_f = __builtin_fma(d, d, e_f);
-        }
-      }
+        for (int e = 0; e < 16; ++e) acc_i[i][j][e] = 0;
+    product(std::integral_constant<int, K_I8>{}, acc_i);
+    e_i = sq_diff(std::true_type{}, acc_i, a.sx_i, a.sw_i);
   }
-  e_i = wave_sum(e_i);
-  e_f = wave_sum(e_f);
+  if constexpr (FP8 != FP8_NONE) {
+    f32x16 acc_f[TI][TJ];
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_f[i][j][e] = 0.0f;
+    product(std::integral_constant<int, FP8 == FP8_EXACT ? K_GRID : K_F8>{}, acc_f);
+    e_f = sq_diff(std::integral_constant<bool, !DO_I8>{}, acc_f, a.sx_f, a.sw_f);
+  }
   p = wave_sum(p);
   if (lane == 0) { s_red[0][wave] = e_i; s_red[1][wave] = e_f; s_red[2][wave] = p; }
   __syncthreads();
   if (tid == 0) {
-    if (a.part_i) a.part_i[blockIdx.x] = (s_red[0][0] + s_red[0][1]) + (s_red[0][2] + s_red[0][3]);
-    if (a.part_f) a.part_f[blockIdx.x] = (s_red[1][0] + s_red[1][1]) + (s_red[1][2] + s_red[1][3]);
-    a.part_p[blockIdx.x] = (s_red[2][0] + s_red[2][1]) + (s_red[2][2] + s_red[2][3]);
+    const int out = bm * a.tiles_n + bn;
+    if (a.part_i) a.part_i[out] = (s_red[0][0] + s_red[0][1]) + (s_red[0][2] + s_red[0][3]);
+    if (a.part_f) a.part_f[out] = (s_red[1][0] + s_red[1][1]) + (s_red[1][2] + s_red[1][3]);
+    a.part_p[out] = (s_red[2][0] + s_red[2][1]) + (s_red[2][2] + s_red[2][3]);
   }
 }
 
@@ -330,6 +387,7 @@ int launch_wa_gemm(const WaGemmParams& p, hipStream_t st) {
   a.sx_i = p.sx_i; a.sw_i = p.sw_i; a.sx_f = p.sx_f; a.sw_f = p.sw_f;
   a.w_per_channel = p.w_per_channel;
   a.M = static_cast<int32_t>(p.M); a.N = static_cast<int32_t>(p.N); a.K = static_cast<int32_t>(p.K);
+  a.tiles_m = static_cast<int32_t>((p.M + TM - 1) / TM);
   a.tiles_n = static_cast<int32_t>((p.N + TN - 1) / TN);
   a.part_i = p.part_i; a.part_f = p.part_f; a.part_p = p.part_p;
   const dim3 grid(static_cast<unsigned>(wa_gemm_blocks(p.M, p.N)));
