@@ -11,13 +11,15 @@
 // the quantized accumulators are reduced against them (squared differences in fp64) as
 // soon as their loop ends.  Y is never written to memory.
 //
-// Why the products run in sequence and not side by side: the loop is bound by how many
-// bytes can be in flight from L2 into LDS (measured ~1 us from issue to arrival under
-// load) and by the texture path, which handles one 128-byte line every ~2.2 clocks
-// whatever part of the line is used.  One product at a time lets a stage hold whole
-// 128-byte lines of every operand row (48 KB, three stages resident), and two
-// accumulator sets (256 registers) leave room for a 256x128 tile, which needs 25 %
-// fewer operand bytes per flop than 128x128.
+// Why the products run in sequence and not side by side: the loop is bound by the
+// texture path (one 128-byte line every ~2.2 clocks per compute unit, whatever part of
+// the line is used), by LDS bandwidth and by how many bytes can be in flight from L2
+// into LDS.  One product at a time lets a stage hold whole 128-byte lines of every
+// operand row (48 KB, three stages resident) and keeps a wave at two accumulator sets
+// (128 registers for its 64x64 share), so that eight waves, two per SIMD, fit: while
+// one waits at the stage barrier or for its fragments the other keeps the matrix core
+// busy.  The 256x128 workgroup tile needs 25 % fewer operand bytes per flop than
+// 128x128.
 //
 // Exactness: bf16 x bf16 products are exact in fp32 and are accumulated in fp32;
 // int8 products are accumulated exactly in int32 (|sum| <= 32768*127*127 < 2^31).
@@ -46,8 +48,9 @@ typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 
-constexpr int TM = 256, TN = 128;               // workgroup tile; 4 waves, 128 x 64 each
-constexpr int WM = 128, WN = 64;                // wave tile: 4 x 2 matrix-core tiles of 32 x 32
+constexpr int TM = 256, TN = 128;               // workgroup tile; 8 waves (two per SIMD), 64 x 64 each
+constexpr int WM = 64, WN = 64;                 // wave tile: 2 x 2 matrix-core tiles of 32 x 32
+constexpr int NW = (TM / WM) * (TN / WN);       // waves per workgroup
 constexpr int TI = WM / 32, TJ = WN / 32;
 
 struct GemmArgs {
@@ -82,7 +85,7 @@ constexpr int STAGE_ROWS = TM + TN;
 constexpr int STAGE = STAGE_ROWS * ROW_B;       // 48 KB
 constexpr int NST = 3;                          // stages resident
 constexpr int AHEAD = NST - 1;                  // stage kt + AHEAD is issued during step kt
-constexpr int DEP = STAGE / 1024 / 4;           // deposits per wave per stage (12)
+constexpr int DEP = STAGE / 1024 / NW;          // deposits per wave per stage (6)
 MOFQ_DEV constexpr int swz(int row) { return (row >> 1) & (CH - 1); }
 
 // One wave instruction: lane l fetches 16 bytes at its own global address and deposits
@@ -106,14 +109,14 @@ template <int N> MOFQ_DEV void wait_deposits_but() {
 enum : int { K_REF = 0, K_GRID = 1, K_I8 = 2, K_F8 = 3 };
 
 template <bool DO_I8, int FP8>
-__global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void wa_gemm_kernel(const GemmArgs a) {
   __shared__ __attribute__((aligned(1024))) unsigned char s_buf[NST * STAGE];
-  __shared__ double s_red[3][4];
+  __shared__ double s_red[3][NW];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;      // 2 x 2 waves
+  const int wm = wave >> 1, wn = wave & 1;      // 4 x 2 waves
   const int r = lane & 31, g = lane >> 5;
 
   // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (8 of them, each
@@ -164,7 +167,7 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
     constexpr int KIND = decltype(kind_c)::value;
     constexpr int EB = (KIND == K_REF || KIND == K_GRID) ? 2 : 1;   // bytes per element
     constexpr int TK = ROW_B / EB;                                  // K elements per stage
-    constexpr int NG = (KIND == K_F8) ? CH / 4 : CH / 2;            // matrix groups per stage (8 instructions each)
+    constexpr int NG = (KIND == K_F8) ? CH / 4 : CH / 2;            // matrix groups per stage (TI*TJ instructions each)
     constexpr int NF = (KIND == K_F8) ? 2 : 1;                      // 16-byte chunks per fragment
     const char* xb; const char* wb; int64_t xrow, wrow;
     if constexpr (KIND == K_REF) { xb = reinterpret_cast<const char*>(a.x); wb = reinterpret_cast<const char*>(a.w); xrow = a.ldx * 2; wrow = a.ldw * 2; }
@@ -173,11 +176,11 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
     else { xb = reinterpret_cast<const char*>(a.xf); wb = reinterpret_cast<const char*>(a.wf); xrow = wrow = a.K; }
 
     // This lane's global source of each of its wave's deposits at k = 0 (deposit i of a
-    // stage covers chunk slots 64 i .. 64 i + 63 and is issued by wave i % 4).
+    // stage covers chunk slots 64 i .. 64 i + 63 and is issued by wave i % NW).
     const char* src[DEP];
 #pragma unroll
     for (int d = 0; d < DEP; ++d) {
-      const int c = (wave + 4 * d) * 64 + lane;
+      const int c = (wave + NW * d) * 64 + lane;
       const int row = c / CH, kc = (c % CH) ^ swz(row);
       if (row < TM) {
         int gr = m0 + row;
@@ -203,10 +206,10 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
         if (d >= lo && d < hi) {
           const char* g_src = src[d] + kb;
           if (tail) {
-            const int c = (wave + 4 * d) * 64 + lane;
+            const int c = (wave + NW * d) * 64 + lane;
             if (((c % CH) ^ swz(c / CH)) >= CH / 2) g_src -= ROW_B / 2;
           }
-          lds_deposit(g_src, st + (wave + 4 * d) * 1024);
+          lds_deposit(g_src, st + (wave + NW * d) * 1024);
         }
     };
     // Fragments of group gi of a stage: f[0 .. TI*NF) = A tiles, f[TI*NF ..) = B tiles.
@@ -220,9 +223,9 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
         for (int j = 0; j < TJ; ++j) f[(TI + j) * NF + h] = *reinterpret_cast<const i32x4*>(st + row_b + j * 32 * ROW_B + ch);
       }
     };
-    // The 8 matrix instructions of one group, with the deposits [lo, hi) of stage kt_dep
+    // The matrix instructions of one group, with the deposits [lo, hi) of stage kt_dep
     // spread between them: a wave issues in order, so a burst of deposits (each occupies
-    // the texture path for ~18 clocks, and four waves share it) would hold back the
+    // the texture path for ~18 clocks, and all waves share it) would hold back the
     // matrix instructions behind it while the matrix pipe runs dry.
     auto run_group = [&](const i32x4 (&f)[(TI + TJ) * NF], bool more, int kt_dep, int lo, int hi) {
 #pragma unroll
@@ -365,9 +368,12 @@ __global__ __launch_bounds__(256) void wa_gemm_kernel(const GemmArgs a) {
   __syncthreads();
   if (tid == 0) {
     const int out = bm * a.tiles_n + bn;
-    if (a.part_i) a.part_i[out] = (s_red[0][0] + s_red[0][1]) + (s_red[0][2] + s_red[0][3]);
-    if (a.part_f) a.part_f[out] = (s_red[1][0] + s_red[1][1]) + (s_red[1][2] + s_red[1][3]);
-    a.part_p[out] = (s_red[2][0] + s_red[2][1]) + (s_red[2][2] + s_red[2][3]);
+    double t[3] = {0.0, 0.0, 0.0};
+    for (int q = 0; q < 3; ++q)
+      for (int w = 0; w < NW; ++w) t[q] += s_red[q][w];   // fixed order
+    if (a.part_i) a.part_i[out] = t[0];
+    if (a.part_f) a.part_f[out] = t[1];
+    a.part_p[out] = t[2];
   }
 }
 
@@ -394,7 +400,7 @@ int launch_wa_gemm(const WaGemmParams& p, hipStream_t st) {
   const bool di = p.xi != nullptr;
   const int f8 = p.xg ? FP8_EXACT : (p.xf ? FP8_NATIVE : FP8_NONE);
 #define MOFQ_WA(DI, F8) \
-  if (di == DI && f8 == F8) hipLaunchKernelGGL((wa_gemm_kernel<DI, F8>), grid, dim3(256), 0, st, a);
+  if (di == DI && f8 == F8) hipLaunchKernelGGL((wa_gemm_kernel<DI, F8>), grid, dim3(NW * 64), 0, st, a);
   if (!di && f8 == FP8_NONE) return MOFQ_ERR_INVALID_ARG;
   MOFQ_WA(true, FP8_NONE) MOFQ_WA(true, FP8_NATIVE) MOFQ_WA(true, FP8_EXACT)
   MOFQ_WA(false, FP8_NATIVE) MOFQ_WA(false, FP8_EXACT)
