@@ -11,6 +11,11 @@ Prints ONE JSON line: the elements x candidates scored per second (and the
 full-model select time), the roofline of the dominant kernel measured with HIP
 events inside the timed region, and the CPU oracle timed on a bounded sample of
 the same workload on the host cores.
+
+`--workload` selects two further workloads of the same path, each with its own
+JSON line (same keys; no CPU baseline): `w4_group128` (group-wise scales, 50 clip
+ratios) and `w8a8` (weight-activation, layer-output error through the matrix
+cores, 2048 tokens).  The default, `w4_channel`, is the headline workload.
 """
 from __future__ import annotations
 
@@ -25,7 +30,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 N_CLIP = 100
+N_CLIP_GROUP = 50
+GROUP = 128
+TOKENS = 2048
 N_FMT = 2
+# Published dense matrix-core peaks (TFLOP/s or TOP/s) per operand type.
+MFMA_PEAK = {"bf16": 2500.0, "int8": 5000.0, "fp8": 5000.0}
 # Algorithmic work of the scale search per element, candidate and format: scale
 # (1 multiply), round (1), clamp/saturate (1), residual x - g*s (2), error
 # accumulation d*d + acc (2).
@@ -42,6 +52,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--model", default="7b", choices=["7b"])
+    ap.add_argument("--workload", default="w4_channel", choices=["w4_channel", "w4_group128", "w8a8"])
+    ap.add_argument("--fp8-unit", action="store_true",
+                    help="w8a8: E4M3 code product on the fp8 matrix cores (not within 1e-5 of the exact sum)")
     ap.add_argument("--blocks", type=int, default=0, help="debug: use only the first N blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -92,6 +105,95 @@ def cpu_baseline(weights, outs, clip, cands):
     }
 
 
+def run_w8a8(args, shapes, dev):
+    """configs[3]: per linear, X [2048, in] bf16 with outlier channels, W bf16; per-tensor
+    INT8 vs FP8-E4M3 for both; layer-output error through the matrix cores; select + emit."""
+    import torch
+
+    import mofq_inputs as mi
+    from paper_2305_12356_amd import binding as mq
+
+    metric = mq.ERR_LAYER_OUTPUT_FP8_UNIT if args.fp8_unit else mq.ERR_LAYER_OUTPUT
+    cands = [mq.INT8, mq.FP8_E4M3]
+    cfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
+    xs = {}
+    weights, wouts, xouts = [], [], {}
+    results = mq.alloc_result(dev, len(shapes))
+    ws_bytes = 0
+    for b, name, o, n in shapes:
+        if n not in xs:
+            xs[n] = mi.activations(TOKENS, n, seed=mi.tensor_seed(3, 0, 0, n), device=dev)
+            xouts[n] = mq.alloc_qbuffers(TOKENS, n, 8, cfg, dev)
+        w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, mi.LINEAR_NAMES.index(name)),
+                                 dtype=torch.bfloat16, device=dev)
+        weights.append(w)
+        ws_bytes = max(ws_bytes, mq.workspace_bytes(w, xs[n], len(cands), metric, cfg))
+    # one output buffer per distinct weight shape (the codes are not read back here)
+    for b, name, o, n in shapes:
+        if (o, n) not in xouts:
+            xouts[(o, n)] = mq.alloc_qbuffers(o, n, 8, cfg, dev)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(events=None):
+        for i, w in enumerate(weights):
+            _, _, o, n = shapes[i]
+            e0 = e1 = None
+            if events is not None:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                events.append((i, e0, e1))
+            mq.select_layer(w, xs[n], cands, metric, cfg, xouts[(o, n)], xouts[n], results[i], ws,
+                            stream, e0, e1)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # dominant kernel: the fused three-product GEMM; one launch per linear
+    mnk = sum(TOKENS * o * n for _, _, o, n in shapes)
+    gemm_time = sum(e0.elapsed_time(e1) for _, e0, e1 in events) * 1e-3 / args.steps
+    kinds = ["bf16", "int8", "fp8" if args.fp8_unit else "bf16"]
+    flops = 2.0 * mnk * len(kinds)
+    ideal = sum(2.0 * mnk / (MFMA_PEAK[k] * 1e12) for k in kinds)
+    achieved = flops / gemm_time / 1e12
+    peak = flops / ideal / 1e12
+    res = mq.read_results(results)
+    out = {
+        "metric": "W8A8 layer-output MoFQ select time over the LLaMA-7B linear shapes",
+        "value": ms_per_step / 1e3, "unit": "s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 reference product, int8 codes, " +
+                 ("fp8 codes on the fp8 matrix cores" if args.fp8_unit else "e4m3 grid values on the bf16 matrix cores") +
+                 ", f64 error sums",
+        "data": "synthetic",
+        "config": {"workload": f"configs[3]: {len(shapes)} linears of the LLaMA-7B shape, X [{TOKENS} x in] bf16 "
+                               "with 6 outlier channels x60, W bf16, per-tensor INT8 vs FP8-E4M3, "
+                               "layer-output error, per-layer select + emit",
+                   "fp8_product": "fp8 matrix cores" if args.fp8_unit else "exact (bf16 matrix cores)",
+                   "fp_percent": 100.0 * sum(1 for r in res if r.best == 1) / len(res)},
+        "roofline": {
+            "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+            "frac": achieved / peak, "traffic": None,
+            "kernel": "wa_gemm_kernel (reference, INT8-code and E4M3 products of one linear)",
+            "note": "three products per launch, " + " + ".join(kinds) + "; peak is the rate at which the "
+                    "three would finish if each ran at the published dense peak of its own type "
+                    "(bf16 2.5, int8 5.0, fp8 5.0 PFLOP/s)",
+            "gemm_ms_per_step": gemm_time * 1e3, "launches": len(events),
+            "flops_per_launch_avg": flops / len(shapes),
+        },
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -114,9 +216,14 @@ def main():
     shapes = mi.model_linear_shapes(args.model)
     if args.blocks:
         shapes = [s for s in shapes if s[0] < args.blocks]
-    clip = mi.clip_ratios(N_CLIP)
+    if args.workload == "w8a8":
+        run_w8a8(args, shapes, dev)
+        return
+    group = args.workload == "w4_group128"
+    n_clip = N_CLIP_GROUP if group else N_CLIP
+    clip = mi.clip_ratios(n_clip)
     cands = [mq.INT4, mq.FP4_E2M1]
-    cfg = mq.Cfg(mq.PER_CHANNEL, clip)
+    cfg = mq.Cfg(mq.PER_GROUP, clip, GROUP, True) if group else mq.Cfg(mq.PER_CHANNEL, clip)
 
     # ---- resident inputs and caller-owned outputs ---------------------------------
     weights, qouts = [], []
@@ -153,7 +260,7 @@ def main():
     elapsed = time.perf_counter() - t0
 
     ms_per_step = elapsed / args.steps * 1e3
-    elem_cand = n_elems * N_CLIP * N_FMT
+    elem_cand = n_elems * n_clip * N_FMT
     value = elem_cand / (elapsed / args.steps)
 
     # ---- dominant kernel: the scale-search instance for 4096-column rows ------------
@@ -165,17 +272,19 @@ def main():
         by_cols.setdefault(n, []).append((o * n, e0.elapsed_time(e1) * 1e-3))
     dom_cols = max(by_cols, key=lambda c: sum(e for e, _ in by_cols[c]))
     dom = by_cols[dom_cols]
-    dom_flops = sum(e for e, _ in dom) * N_CLIP * N_FMT * FLOPS_PER_ELEM_CAND_FMT
+    dom_flops = sum(e for e, _ in dom) * n_clip * N_FMT * FLOPS_PER_ELEM_CAND_FMT
     dom_time = sum(t for _, t in dom)
     achieved = dom_flops / dom_time / 1e12
     search_time = sum(t for v in by_cols.values() for _, t in v) / args.steps
     roofline = {
         "bound": "alu", "achieved": achieved, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
         "frac": achieved / ALU_PEAK_TFLOPS, "traffic": None,
-        "kernel": f"sweep_sorted_kernel<F16, INT4, FP4_E2M1> instance for {dom_cols}-column rows",
-        "note": "achieved counts the flop of the exhaustive element x candidate scoring (the "
-                "algorithmic work); the kernel reaches the same result by sorting each row once and "
-                "locating level boundaries by binary search, so frac can exceed 1",
+        "kernel": (f"sweep_group_kernel<F16, INT4, FP4_E2M1, {GROUP}> on {dom_cols}-column rows" if group else
+                   f"sweep_sorted_kernel<F16, INT4, FP4_E2M1> instance for {dom_cols}-column rows"),
+        "note": ("achieved counts the flop of the exhaustive element x candidate scoring" if group else
+                 "achieved counts the flop of the exhaustive element x candidate scoring (the "
+                 "algorithmic work); the kernel reaches the same result by sorting each row once and "
+                 "locating level boundaries by binary search, so frac can exceed 1"),
         "avg_launch_ms": dom_time / len(dom) * 1e3, "launches": len(dom),
         "flops_per_elem_cand_fmt": FLOPS_PER_ELEM_CAND_FMT,
         "hbm_GBps_at_this_rate": sum(e for e, _ in dom) * 2 / dom_time / 1e9,
@@ -199,13 +308,17 @@ def main():
         "select_time_s": ms_per_step / 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 decisions, f64 errors", "data": "synthetic",
-        "config": {"workload": "configs[1]: LLaMA-7B-shaped fp16 weight set, "
-                               f"{len(shapes)} linears, {n_elems} weights, 4-bit W-only per-channel, "
-                               "100 clip ratios in [0.5,1], INT4 vs FP4-E2M1, per-layer select + emit",
-                   "n_clip": N_CLIP, "formats": ["INT4", "FP4_E2M1"], "fp_percent": fp_pct},
+        "config": {"workload": ("configs[2]: LLaMA-7B-shaped fp16 weight set, "
+                                f"{len(shapes)} linears, {n_elems} weights, 4-bit W-only group-wise "
+                                "(128 along the input dim, fp16 scales), 50 clip ratios in [0.5,1], "
+                                "INT4 vs FP4-E2M1, per-layer select + emit") if group else
+                               ("configs[1]: LLaMA-7B-shaped fp16 weight set, "
+                                f"{len(shapes)} linears, {n_elems} weights, 4-bit W-only per-channel, "
+                                "100 clip ratios in [0.5,1], INT4 vs FP4-E2M1, per-layer select + emit"),
+                   "n_clip": n_clip, "formats": ["INT4", "FP4_E2M1"], "fp_percent": fp_pct},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not group:
         outs = [(qouts[i], res[i]) for i in range(len(shapes))]
         out["cpu_baseline"] = cpu_baseline(weights, outs, clip, cands)
     print(json.dumps(out))
