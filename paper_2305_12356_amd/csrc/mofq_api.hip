@@ -74,6 +74,7 @@ struct WOnlyWs {
   float* absmax_part;
   double* sse_part;
   double* energy_part;
+  double* decide_part;
   size_t bytes;
 };
 
@@ -86,6 +87,7 @@ WOnlyWs carve_w_only(void* ws, int64_t units, int n_cand, int gran, int n_clip) 
     w.err[i] = c.take<double>(units);
   }
   w.energy = c.take<double>(units);
+  w.decide_part = c.take<double>(static_cast<size_t>(MOFQ_MAX_CANDIDATES + 1) * kDecideBlocks);
   if (gran == MOFQ_PER_TENSOR) {
     w.absmax_part = c.take<float>(kTensorBlocks);
     w.energy_part = c.take<double>(kTensorBlocks);
@@ -316,6 +318,7 @@ int mofq_quantize(const mofq_tensor_t* t, int32_t format, const mofq_scale_cfg_t
     d.units = units;
     d.n_cand = 1;
     d.err[0] = w.err[0];
+    d.part = w.decide_part;
     d.tensor_err_out = tensor_err;
     if ((rc = launch_decide(d, st))) return rc;
   }
@@ -358,6 +361,7 @@ int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, i
     d.n_cand = 1;
     d.err[0] = s.err[0];
     d.energy = s.energy;
+    d.part = s.decide_part;
     d.tensor_err_out = err;
     d.energy_out = ref_energy;
     return launch_decide(d, st);
@@ -419,6 +423,7 @@ int mofq_select_layer_timed(const mofq_tensor_t* w, const mofq_tensor_t* x,
     d.n_cand = n_candidates;
     for (int c = 0; c < n_candidates; ++c) d.err[c] = s.err[c];
     d.energy = s.energy;
+    d.part = s.decide_part;
     d.result = result;
     if ((rc = launch_decide(d, st))) return rc;
     EmitParams e{};

@@ -29,6 +29,28 @@ MOFQ_DEV double block_sum(const double* v, int64_t n, double* s_red) {
   return r;
 }
 
+// First stage for tensors with many units: workgroup b adds units [b*chunk, (b+1)*chunk)
+// of every candidate (and of the energies) in the same fixed order; the decide kernel
+// then adds the kDecideBlocks partials.
+struct PartialArgs {
+  DecideParams p;
+  int64_t chunk;
+};
+__global__ __launch_bounds__(kDecideThreads) void decide_partial_kernel(const PartialArgs a) {
+  __shared__ double s_red[kDecideThreads / 64];
+  const DecideParams& p = a.p;
+  const int64_t lo = static_cast<int64_t>(blockIdx.x) * a.chunk;
+  int64_t n = p.units - lo;
+  n = n < 0 ? 0 : (n < a.chunk ? n : a.chunk);
+#pragma unroll
+  for (int c = 0; c <= MOFQ_MAX_CANDIDATES; ++c) {
+    const double* v = (c < MOFQ_MAX_CANDIDATES) ? (c < p.n_cand ? p.err[c] : nullptr) : p.energy;
+    if (!v) continue;    // uniform
+    const double t = block_sum(v + lo, n, s_red);
+    if (threadIdx.x == 0) p.part[c * kDecideBlocks + blockIdx.x] = t;
+  }
+}
+
 __global__ __launch_bounds__(kDecideThreads) void decide_kernel(const DecideParams p) {
   __shared__ double s_red[kDecideThreads / 64];
   double err[MOFQ_MAX_CANDIDATES];
@@ -171,6 +193,16 @@ __global__ __launch_bounds__(256) void emit_units_kernel(const EmitArgs a) {
 }  // namespace
 
 int launch_decide(const DecideParams& p, hipStream_t st) {
+  if (p.part && p.units > 16 * 1024) {
+    PartialArgs a{p, (p.units + kDecideBlocks - 1) / kDecideBlocks};
+    hipLaunchKernelGGL(decide_partial_kernel, dim3(kDecideBlocks), dim3(kDecideThreads), 0, st, a);
+    DecideParams d = p;
+    d.units = kDecideBlocks;
+    for (int c = 0; c < MOFQ_MAX_CANDIDATES; ++c) d.err[c] = c < p.n_cand ? p.part + c * kDecideBlocks : nullptr;
+    d.energy = p.energy ? p.part + MOFQ_MAX_CANDIDATES * kDecideBlocks : nullptr;
+    hipLaunchKernelGGL(decide_kernel, dim3(1), dim3(kDecideThreads), 0, st, d);
+    return hip_status(hipGetLastError());
+  }
   hipLaunchKernelGGL(decide_kernel, dim3(1), dim3(kDecideThreads), 0, st, p);
   return hip_status(hipGetLastError());
 }

@@ -56,7 +56,10 @@ struct DecideParams {
   mofq_result_t* result;         // device
   double* tensor_err_out;        // optional: err of candidate 0 (device) or nullptr
   double* energy_out;            // optional (device) or nullptr
+  double* part;                  // optional scratch, (MOFQ_MAX_CANDIDATES + 1) * kDecideBlocks doubles:
+                                 // with it, many units are first reduced by kDecideBlocks workgroups
 };
+constexpr int kDecideBlocks = 256;
 int launch_decide(const DecideParams& p, hipStream_t stream);
 
 // Emit codes and per-unit outputs for the format chosen in *result (or slot 0 if

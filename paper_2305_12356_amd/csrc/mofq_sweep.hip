@@ -10,6 +10,8 @@
 // clamp, pick spacing, add/subtract rounding constant; then an fp64 residual and
 // an fp64 fused multiply-add into the error) is plain vector ALU work: with the
 // 100-candidate search the kernel is bound by the vector units, not by HBM.
+#include <type_traits>
+
 #include "mofq_device.h"
 #include "mofq_internal.h"
 
@@ -323,6 +325,24 @@ template <> MOFQ_DEV float group_max<16>(float v) {
 // value held by lane `j` of the caller's quad
 template <int J> MOFQ_DEV float quad_bcast(float v) { return dpp_f32<J * 0x55>(v); }
 
+MOFQ_DEV float quad_sum_f32(float v) {
+  v += dpp_f32<DPP_QUAD_XOR1>(v);
+  return v + dpp_f32<DPP_QUAD_XOR2>(v);    // the same value in all four lanes
+}
+MOFQ_DEV uint32_t quad_or(uint32_t v) {
+  v |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), DPP_QUAD_XOR1, 0xF, 0xF, false));
+  return v | static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), DPP_QUAD_XOR2, 0xF, 0xF, false));
+}
+
+constexpr int kGroupQuads = 256 / 4;             // groups per workgroup
+constexpr int kMaskWords = MOFQ_MAX_CLIP / 32;
+
+// Phase 1 scores every candidate of a group in fp32 (hardware fp4/fp8 converts) and
+// parks the sums in LDS; the candidates fp32 cannot tell from the group's best are
+// collected in a bit mask per group and re-scored in fp64 in candidate order, the j-th
+// survivor of all 16 groups of a wave at the same time.  The fp32 sum of a group (32
+// terms per lane, two more additions across the quad) is within (1 +- 40*2^-24) of the
+// exact sum for the same grid choices, so the fp64 winner is always among the survivors.
 template <typename In, int FA, int FB, int GROUP>
 __global__ __launch_bounds__(256) void sweep_group_kernel(const SweepArgs a) {
   using L = Load8<In>;
@@ -333,20 +353,26 @@ __global__ __launch_bounds__(256) void sweep_group_kernel(const SweepArgs a) {
   constexpr int CH = NE / 8;
   static_assert(NE % 8 == 0, "group too small for 4 lanes");
 
+  extern __shared__ float s_dyn[];      // clip[K], then p1[NF][K][kGroupQuads]
+  const int K = a.n_clip;
+  float* s_clip = s_dyn;
+  float* s_p1 = s_dyn + MOFQ_MAX_CLIP;
+
   const int tid = threadIdx.x;
   const int q = tid & (LPG - 1);
+  const int quad = tid >> 2;
   const int64_t gpr = a.cols / GROUP;   // groups per row
-  int64_t unit = static_cast<int64_t>(blockIdx.x) * (256 / LPG) + tid / LPG;
+  int64_t unit = static_cast<int64_t>(blockIdx.x) * kGroupQuads + quad;
   const bool valid = unit < a.units;
   if (!valid) unit = a.units - 1;       // keep every lane active for the DPP exchanges
   const int64_t row = unit / gpr, gi = unit - row * gpr;
   const typename L::elem* src =
       static_cast<const typename L::elem*>(a.w) + row * a.ld + gi * GROUP + q * NE;
-  const int K = a.n_clip;
   const bool f16 = a.scale_f16 != 0;
 
+  for (int k = tid; k < K; k += 256) s_clip[k] = a.clip[k];
+
   float x[NE];
-  double xd[NE];
   float amax = 0.0f;
   double en = 0.0;
 #pragma unroll
@@ -356,57 +382,125 @@ __global__ __launch_bounds__(256) void sweep_group_kernel(const SweepArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       x[j * 8 + i] = v[i];
-      xd[j * 8 + i] = static_cast<double>(v[i]);
       amax = __builtin_fmaxf(amax, __builtin_fabsf(v[i]));
-      en = __builtin_fma(xd[j * 8 + i], xd[j * 8 + i], en);
+      const double xd = static_cast<double>(v[i]);
+      en = __builtin_fma(xd, xd, en);
     }
   }
   amax = group_max<LPG>(amax);
   en = group_sum<LPG>(en);
+  __syncthreads();                       // clip table in place
 
-  double bestA = __builtin_inf(), bestB = __builtin_inf();
-  int bkA = 0, bkB = 0;
-  float bsA = 1.0f, bsB = 1.0f;
-
-  for (int k0 = 0; k0 < K; k0 += LPG) {
-    // lane q of the group prepares candidate k0+q (clamped; surplus ones are ignored)
-    const int kq = (k0 + q < K) ? k0 + q : K - 1;
-    const float r = a.clip[kq];
-    const float mysA = unit_scale(amax, r, Codec<FA>::QMAX, f16);
-    const float myiA = 1.0f / mysA;
-    float mysB = 0.0f, myiB = 0.0f;
-    if constexpr (NF == 2) {
-      mysB = unit_scale(amax, r, Codec<FBX>::QMAX, f16);
-      myiB = 1.0f / mysB;
-    }
-    auto one = [&](float sA, float iA, float sB, float iB, int k) {
-      if (k < K) {   // uniform over the workgroup
-        const double sAd = static_cast<double>(sA), sBd = static_cast<double>(sB);
-        double accA = 0.0, accB = 0.0;
+  uint32_t carry = 0;
+  uint32_t maskA[kMaskWords], maskB[kMaskWords];
 #pragma unroll
-        for (int i = 0; i < NE; ++i) {
-          accumulate<FA>(accA, x[i], xd[i], iA, sAd);
-          if constexpr (NF == 2) accumulate<FBX>(accB, x[i], xd[i], iB, sBd);
+  for (int w = 0; w < kMaskWords; ++w) { maskA[w] = 0; maskB[w] = 0; }
+
+  if (K > 1) {
+    // ---- phase 1 ----------------------------------------------------------------
+    float minA = __builtin_inff(), minB = __builtin_inff();
+    for (int k0 = 0; k0 < K; k0 += LPG) {
+      // lane q of the group prepares candidate k0+q (clamped; surplus ones are ignored)
+      const int kq = (k0 + q < K) ? k0 + q : K - 1;
+      const float r = s_clip[kq];
+      const float mysA = unit_scale(amax, r, Codec<FA>::QMAX, f16);
+      const float myiA = 1.0f / mysA;
+      float mysB = 0.0f, myiB = 0.0f;
+      if constexpr (NF == 2) {
+        mysB = unit_scale(amax, r, Codec<FBX>::QMAX, f16);
+        myiB = 1.0f / mysB;
+      }
+      auto one = [&](float sA, float iA, float sB, float iB, int k) {
+        if (k < K) {   // uniform over the workgroup
+          float accA = 0.0f, accB = 0.0f;
+#pragma unroll
+          for (int i = 0; i < NE; i += 2) {
+            score2_f32<FA>(accA, x[i], x[i + 1], iA, sA, carry);
+            if constexpr (NF == 2) score2_f32<FBX>(accB, x[i], x[i + 1], iB, sB, carry);
+          }
+          accA = quad_sum_f32(accA);
+          minA = __builtin_fminf(minA, accA);
+          if (q == 0) s_p1[k * kGroupQuads + quad] = accA;
+          if constexpr (NF == 2) {
+            accB = quad_sum_f32(accB);
+            minB = __builtin_fminf(minB, accB);
+            if (q == 1) s_p1[(K + k) * kGroupQuads + quad] = accB;
+          }
         }
-        accA = group_sum<LPG>(accA);
-        if (accA < bestA) { bestA = accA; bkA = k; bsA = sA; }
-        if constexpr (NF == 2) {
-          accB = group_sum<LPG>(accB);
-          if (accB < bestB) { bestB = accB; bkB = k; bsB = sB; }
+      };
+      one(quad_bcast<0>(mysA), quad_bcast<0>(myiA), quad_bcast<0>(mysB), quad_bcast<0>(myiB), k0 + 0);
+      one(quad_bcast<1>(mysA), quad_bcast<1>(myiA), quad_bcast<1>(mysB), quad_bcast<1>(myiB), k0 + 1);
+      one(quad_bcast<2>(mysA), quad_bcast<2>(myiA), quad_bcast<2>(mysB), quad_bcast<2>(myiB), k0 + 2);
+      one(quad_bcast<3>(mysA), quad_bcast<3>(myiA), quad_bcast<3>(mysB), quad_bcast<3>(myiB), k0 + 3);
+    }
+    __syncthreads();                     // the sums parked by lanes 0 and 1 are visible to the quad
+
+    // ---- survivors: lane q tests candidates q, q+4, ... ----------------------------
+    const float thrA = (minA >= kTinySum && minA < __builtin_inff()) ? minA * kShortlistFactor : __builtin_inff();
+    const float thrB = (minB >= kTinySum && minB < __builtin_inff()) ? minB * kShortlistFactor : __builtin_inff();
+    for (int k = q; k < K; k += LPG) {
+      const float vA = s_p1[k * kGroupQuads + quad];
+      const uint32_t bit = 1u << (k & 31);
+      const bool keepA = vA <= thrA || !(vA == vA);
+      bool keepB = false;
+      if constexpr (NF == 2) {
+        const float vB = s_p1[(K + k) * kGroupQuads + quad];
+        keepB = vB <= thrB || !(vB == vB);
+      }
+#pragma unroll
+      for (int w = 0; w < kMaskWords; ++w) {
+        if ((k >> 5) == w) {
+          if (keepA) maskA[w] |= bit;
+          if (keepB) maskB[w] |= bit;
         }
       }
-    };
-    one(quad_bcast<0>(mysA), quad_bcast<0>(myiA), quad_bcast<0>(mysB), quad_bcast<0>(myiB), k0 + 0);
-    one(quad_bcast<1>(mysA), quad_bcast<1>(myiA), quad_bcast<1>(mysB), quad_bcast<1>(myiB), k0 + 1);
-    one(quad_bcast<2>(mysA), quad_bcast<2>(myiA), quad_bcast<2>(mysB), quad_bcast<2>(myiB), k0 + 2);
-    one(quad_bcast<3>(mysA), quad_bcast<3>(myiA), quad_bcast<3>(mysB), quad_bcast<3>(myiB), k0 + 3);
+    }
+#pragma unroll
+    for (int w = 0; w < kMaskWords; ++w) {
+      maskA[w] = quad_or(maskA[w]);
+      if constexpr (NF == 2) maskB[w] = quad_or(maskB[w]);
+    }
+  } else {
+    maskA[0] = 1u;
+    if constexpr (NF == 2) maskB[0] = 1u;
   }
 
+  // ---- phase 2: fp64 error of the survivors, first smallest wins -------------------
+  double bestA = __builtin_inf(), bestB = __builtin_inf();
+  int bkA = -1, bkB = -1;
+  float bsA = 1.0f, bsB = 1.0f;
+  auto rescore = [&](auto fmt_c, uint32_t (&mask)[kMaskWords], double& best, int& bk, float& bs) {
+    constexpr int FMT = decltype(fmt_c)::value;
+    for (;;) {
+      int k = -1;                        // this group's next survivor, in candidate order
+#pragma unroll
+      for (int w = 0; w < kMaskWords; ++w) {
+        if (k < 0 && mask[w] != 0) {
+          k = w * 32 + __builtin_ctz(mask[w]);
+          mask[w] &= mask[w] - 1;
+        }
+      }
+      if (__builtin_amdgcn_ballot_w64(k >= 0) == 0) break;
+      const float s = unit_scale(amax, s_clip[k >= 0 ? k : 0], Codec<FMT>::QMAX, f16);
+      const float inv = 1.0f / s;
+      const double sd = static_cast<double>(s);
+      double acc = 0.0;
+#pragma unroll
+      for (int i = 0; i < NE; i += 2) score2_f64<FMT>(acc, x[i], x[i + 1], inv, sd, carry);
+      acc = group_sum<LPG>(acc);
+      if (k >= 0 && acc < best) { best = acc; bk = k; bs = s; }
+    }
+  };
+  rescore(std::integral_constant<int, FA>{}, maskA, bestA, bkA, bsA);
+  if constexpr (NF == 2) rescore(std::integral_constant<int, FBX>{}, maskB, bestB, bkB, bsB);
+
   if (valid && q == 0) {
+    if (bkA < 0) { bkA = 0; bestA = __builtin_nan(""); bsA = unit_scale(amax, s_clip[0], Codec<FA>::QMAX, f16); }   // only on non-finite input
     a.rec.scale[0][unit] = bsA;
     a.rec.clip[0][unit] = bkA;
     a.rec.err[0][unit] = bestA;
     if constexpr (NF == 2) {
+      if (bkB < 0) { bkB = 0; bestB = __builtin_nan(""); bsB = unit_scale(amax, s_clip[0], Codec<FBX>::QMAX, f16); }
       a.rec.scale[1][unit] = bsB;
       a.rec.clip[1][unit] = bkB;
       a.rec.err[1][unit] = bestB;
@@ -600,11 +694,13 @@ int launch_channel(const SweepArgs& a, hipStream_t st) {
 
 template <typename In, int FA, int FB>
 int launch_group(const SweepArgs& a, hipStream_t st) {
-  const dim3 grid(static_cast<unsigned>(ceil_div(a.units, 64)));
+  const dim3 grid(static_cast<unsigned>(ceil_div(a.units, kGroupQuads)));
+  constexpr int NF = (FB >= 0) ? 2 : 1;
+  const size_t lds = sizeof(float) * (MOFQ_MAX_CLIP + static_cast<size_t>(NF) * a.n_clip * kGroupQuads);
   switch (a.group) {
 #define MOFQ_G(G)                                                                        \
   case G:                                                                                \
-    hipLaunchKernelGGL((sweep_group_kernel<In, FA, FB, G>), grid, dim3(256), 0, st, a);  \
+    hipLaunchKernelGGL((sweep_group_kernel<In, FA, FB, G>), grid, dim3(256), lds, st, a);  \
     return hip_status(hipGetLastError());
     MOFQ_G(32)
     MOFQ_G(64)
