@@ -117,6 +117,23 @@ def test_group_wise_fp32_scales_and_odd_k(mq):
     check_tensor(mq, w, [orc.INT4, orc.FP4_E2M1], orc.PER_GROUP, mi.clip_ratios(7), 128, False, label="group-f32")
 
 
+@pytest.mark.parametrize("n_clip", [1, 2, 33, 64, 128])
+def test_group_wise_candidate_counts(mq, n_clip):
+    """Candidate counts around the 32-candidate words of the survivor masks, the single
+    candidate (no first pass) and the maximum."""
+    w = mi.llama_like_weight(7, 2048, seed=300 + n_clip, device=DEV, outlier_frac=2e-3)
+    check_tensor(mq, w, [orc.INT4, orc.FP4_E2M1], orc.PER_GROUP, mi.clip_ratios(n_clip), 128, True,
+                 label="group-k")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_group_wise_other_dtypes_and_formats(mq, dtype):
+    w = mi.llama_like_weight(5, 1536, seed=41, dtype=dtype, device=DEV)
+    check_tensor(mq, w, [orc.INT4, orc.FP4_E2M1], orc.PER_GROUP, mi.clip_ratios(12), 64, False, label="group-dtype")
+    check_tensor(mq, w, [orc.INT8, orc.FP8_E4M3], orc.PER_GROUP, mi.clip_ratios(6), 128, True, label="group-8bit")
+    check_tensor(mq, w, [orc.FP4_E2M1], orc.PER_GROUP, mi.clip_ratios(9), 128, True, label="group-single")
+
+
 @pytest.mark.parametrize("fmt_pair", [(orc.INT8, orc.FP8_E4M3), (orc.INT4, orc.FP4_E2M1)])
 def test_per_tensor(mq, fmt_pair):
     x = mi.activations(300, 1024, seed=10, device=DEV)
