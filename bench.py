@@ -51,7 +51,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--model", default="7b", choices=["7b"])
+    ap.add_argument("--model", default="7b", choices=["7b", "65b"],
+                    help="65b = configs[4]: 560 linears, 129.5 GB of fp16 weights resident in HBM")
     ap.add_argument("--workload", default="w4_channel", choices=["w4_channel", "w4_group128", "w8a8"])
     ap.add_argument("--fp8-unit", action="store_true",
                     help="w8a8: E4M3 code product on the fp8 matrix cores (not within 1e-5 of the exact sum)")
@@ -302,7 +303,7 @@ def main():
     fp_pct = 100.0 * sum(1 for r in res if r.best == 1) / len(res)
 
     out = {
-        "metric": "weight-elems x candidates scored/sec (+ LLaMA-7B full-model MoFQ select time)",
+        "metric": f"weight-elems x candidates scored/sec (+ LLaMA-{args.model.upper()} full-model MoFQ select time)",
         "value": value, "unit": "elem*cand/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "select_time_s": ms_per_step / 1e3,
@@ -312,13 +313,14 @@ def main():
                                 f"{len(shapes)} linears, {n_elems} weights, 4-bit W-only group-wise "
                                 "(128 along the input dim, fp16 scales), 50 clip ratios in [0.5,1], "
                                 "INT4 vs FP4-E2M1, per-layer select + emit") if group else
-                               ("configs[1]: LLaMA-7B-shaped fp16 weight set, "
+                               (("configs[4]: LLaMA-65B-shaped" if args.model == "65b" else
+                                 "configs[1]: LLaMA-7B-shaped") + " fp16 weight set, "
                                 f"{len(shapes)} linears, {n_elems} weights, 4-bit W-only per-channel, "
                                 "100 clip ratios in [0.5,1], INT4 vs FP4-E2M1, per-layer select + emit"),
                    "n_clip": n_clip, "formats": ["INT4", "FP4_E2M1"], "fp_percent": fp_pct},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline and not group:
+    if not args.no_cpu_baseline and not group and args.model == "7b":
         outs = [(qouts[i], res[i]) for i in range(len(shapes))]
         out["cpu_baseline"] = cpu_baseline(weights, outs, clip, cands)
     print(json.dumps(out))
