@@ -104,7 +104,6 @@ template <int FMT> MOFQ_DEV void rescore2(double& acc, float x0, float x1, float
   acc = __builtin_fma(d1, d1, acc);
 }
 
-constexpr int Q = 4;   // candidates a lane searches at once (independent chains hide LDS latency)
 
 template <typename In, int FA, int FB, int THREADS, int CH>
 __global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs a) {
@@ -116,6 +115,9 @@ __global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs 
   constexpr int NP = THREADS * E;      // padded row length
   constexpr int MAXL = NF * MOFQ_MAX_CLIP;
   constexpr int HALVES = THREADS / 32; // candidates searched side by side (one per 32 lanes)
+  // candidates a lane searches at once (independent chains hide LDS latency); chosen so
+  // that 100 candidates fill whole rounds: 8 halves x 13 or 16 halves x 7
+  constexpr int Q = (THREADS <= 256) ? 13 : 7;
 
   // ---- LDS.  During the sort: two key buffers + digit counters.  The sorted row ends up
   // in the first buffer in a padded layout (one 4-byte gap after every 64 elements, so that
