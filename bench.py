@@ -44,6 +44,10 @@ FLOPS_PER_ELEM_CAND_FMT = 7
 # (published fp32 vector peak 157.3 TFLOP/s) and 4 are fp64 (published fp64 vector peak
 # 78.6 TFLOP/s): 7 / (3/157.3 + 4/78.6) = 100.0 TFLOP/s.
 ALU_PEAK_TFLOPS = 7.0 / (3.0 / 157.3 + 4.0 / 78.6)
+# HBM bytes per launch of the search kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command,
+# scaled by what the same counters read for a plain 1 GiB copy (profiles/w_only_7b_k100_hbm_traffic.txt):
+# KiB read and written per launch, by tensor shape.  Only the 7B per-channel workload has been measured.
+MEASURED_TRAFFIC_KIB = {(4096, 4096): (33124, 896), (11008, 4096): (88420, 2408), (4096, 11008): (88662, 896)}
 
 
 def parse():
@@ -276,10 +280,14 @@ def main():
     dom_flops = sum(e for e, _ in dom) * n_clip * N_FMT * FLOPS_PER_ELEM_CAND_FMT
     dom_time = sum(t for _, t in dom)
     achieved = dom_flops / dom_time / 1e12
+    traffic = None
+    if not group and args.model == "7b":
+        per = [sum(MEASURED_TRAFFIC_KIB[(o, n)]) * 1024.0 for _, _, o, n in shapes if n == dom_cols]
+        traffic = sum(per) / len(per)
     search_time = sum(t for v in by_cols.values() for _, t in v) / args.steps
     roofline = {
         "bound": "alu", "achieved": achieved, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
-        "frac": achieved / ALU_PEAK_TFLOPS, "traffic": None,
+        "frac": achieved / ALU_PEAK_TFLOPS, "traffic": traffic,
         "kernel": (f"sweep_group_kernel<F16, INT4, FP4_E2M1, {GROUP}> on {dom_cols}-column rows" if group else
                    f"sweep_sorted_kernel<F16, INT4, FP4_E2M1> instance for {dom_cols}-column rows"),
         "note": ("achieved counts the flop of the exhaustive element x candidate scoring" if group else
@@ -287,6 +295,7 @@ def main():
                  "algorithmic work); the kernel reaches the same result by sorting each row once and "
                  "locating level boundaries by binary search, so frac can exceed 1"),
         "avg_launch_ms": dom_time / len(dom) * 1e3, "launches": len(dom),
+        "algorithmic_bytes_per_launch": sum(e for e, _ in dom) * 2 / len(dom),
         "flops_per_elem_cand_fmt": FLOPS_PER_ELEM_CAND_FMT,
         "hbm_GBps_at_this_rate": sum(e for e, _ in dom) * 2 / dom_time / 1e9,
         "search_ms_per_step": search_time * 1e3,
