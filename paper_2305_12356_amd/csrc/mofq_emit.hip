@@ -80,12 +80,36 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(const DecidePara
 
 // ---- emit -------------------------------------------------------------------------
 
+// Codes of 8 scaled elements.  4-bit: one word, element 2j in the low nibble of byte j;
+// 8-bit: two words, one byte per element.  The FP formats use the gfx950 pack-convert
+// instructions (round to nearest even, subnormals kept, saturating; the E4M3 convert
+// needs its input clamped to +-448 first), which agree with Codec<>::code on every
+// finite fp32 bit pattern.
 template <int FMT>
 MOFQ_DEV void encode8(const float (&v)[8], float inv_s, uint32_t (&words)[2]) {
-  if constexpr (Codec<FMT>::BITS == 4) {
+  if constexpr (FMT == MOFQ_FP4_E2M1) {
+    uint32_t w = 0;
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[0] * inv_s, v[1] * inv_s, 1.0f, 0);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[2] * inv_s, v[3] * inv_s, 1.0f, 1);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[4] * inv_s, v[5] * inv_s, 1.0f, 2);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[6] * inv_s, v[7] * inv_s, 1.0f, 3);
+    words[0] = w;
+    words[1] = 0;
+  } else if constexpr (FMT == MOFQ_FP8_E4M3) {
+    float t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = med3(v[i] * inv_s, -448.0f, 448.0f);
+    int w0 = 0, w1 = 0;
+    w0 = __builtin_amdgcn_cvt_pk_fp8_f32(t[0], t[1], w0, false);
+    w0 = __builtin_amdgcn_cvt_pk_fp8_f32(t[2], t[3], w0, true);
+    w1 = __builtin_amdgcn_cvt_pk_fp8_f32(t[4], t[5], w1, false);
+    w1 = __builtin_amdgcn_cvt_pk_fp8_f32(t[6], t[7], w1, true);
+    words[0] = static_cast<uint32_t>(w0);
+    words[1] = static_cast<uint32_t>(w1);
+  } else if constexpr (Codec<FMT>::BITS == 4) {
     uint32_t w = 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) w |= Codec<FMT>::code(v[i] * inv_s) << (4 * i);  // element 2j: low nibble of byte j
+    for (int i = 0; i < 8; ++i) w |= Codec<FMT>::code(v[i] * inv_s) << (4 * i);
     words[0] = w;
     words[1] = 0;
   } else {
@@ -122,6 +146,51 @@ MOFQ_DEV int chosen(const EmitArgs& a) {
   return __builtin_amdgcn_readfirstlane(best);
 }
 
+// One 8-element chunk: quantize with the unit's scale and store.
+template <typename In>
+MOFQ_DEV void emit_chunk(const EmitArgs& a, int fmt, const float* scale, int64_t cpr, int64_t c, const float (&v)[8]) {
+  const int64_t row = c / cpr, col = (c - row * cpr) * 8;
+  int64_t unit = 0;
+  if (a.gran == MOFQ_PER_CHANNEL) unit = row;
+  else if (a.gran == MOFQ_PER_GROUP) unit = row * (a.cols / a.group) + col / a.group;
+  const float inv_s = 1.0f / scale[unit];
+  uint32_t words[2];
+  switch (fmt) {
+    case MOFQ_INT4: encode8<MOFQ_INT4>(v, inv_s, words); break;
+    case MOFQ_FP4_E2M1: encode8<MOFQ_FP4_E2M1>(v, inv_s, words); break;
+    case MOFQ_INT8: encode8<MOFQ_INT8>(v, inv_s, words); break;
+    default: encode8<MOFQ_FP8_E4M3>(v, inv_s, words); break;
+  }
+  const int64_t e0 = row * a.cols + col;   // dense output rows
+  if (a.as_bf16_values) {
+    // 8-bit grid values have at most 7 significant bits: exact in bf16 (top half of fp32)
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float g0, g1;
+      if (fmt == MOFQ_INT8) {
+        g0 = Codec<MOFQ_INT8>::grid(v[2 * i] * inv_s);
+        g1 = Codec<MOFQ_INT8>::grid(v[2 * i + 1] * inv_s);
+      } else {
+        g0 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i] * inv_s);
+        g1 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i + 1] * inv_s);
+      }
+      o[i] = (f2u(g0) >> 16) | (f2u(g1) & 0xFFFF0000u);
+    }
+    reinterpret_cast<u32x4*>(a.out.codes)[e0 / 8] = o;
+  } else if (fmt == MOFQ_INT4 || fmt == MOFQ_FP4_E2M1) {
+    static_cast<uint32_t*>(a.out.codes)[e0 / 8] = words[0];
+  } else {
+    u32x2 o;
+    o[0] = words[0];
+    o[1] = words[1];
+    reinterpret_cast<u32x2*>(a.out.codes)[e0 / 8] = o;
+  }
+}
+
+// Grid-stride over 8-element chunks, kEmitUnroll chunks per thread and iteration so that
+// several 16-byte loads are in flight per lane (the pass is HBM-bound).
+constexpr int kEmitUnroll = 4;
 template <typename In>
 __global__ __launch_bounds__(256) void emit_codes_kernel(const EmitArgs a) {
   using L = Load8<In>;
@@ -130,48 +199,24 @@ __global__ __launch_bounds__(256) void emit_codes_kernel(const EmitArgs a) {
   const float* scale = a.scale[best];
   const int64_t cpr = a.cols / 8;
   const int64_t n_chunks = a.rows * cpr;
-  const bool four = (fmt == MOFQ_INT4 || fmt == MOFQ_FP4_E2M1);
-  for (int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; c < n_chunks;
-       c += static_cast<int64_t>(gridDim.x) * 256) {
-    const int64_t row = c / cpr, col = (c - row * cpr) * 8;
-    int64_t unit = 0;
-    if (a.gran == MOFQ_PER_CHANNEL) unit = row;
-    else if (a.gran == MOFQ_PER_GROUP) unit = row * (a.cols / a.group) + col / a.group;
-    const float inv_s = 1.0f / scale[unit];
-    float v[8];
-    L::load(static_cast<const typename L::elem*>(a.w) + row * a.ld + col, v);
-    uint32_t words[2];
-    switch (fmt) {
-      case MOFQ_INT4: encode8<MOFQ_INT4>(v, inv_s, words); break;
-      case MOFQ_FP4_E2M1: encode8<MOFQ_FP4_E2M1>(v, inv_s, words); break;
-      case MOFQ_INT8: encode8<MOFQ_INT8>(v, inv_s, words); break;
-      default: encode8<MOFQ_FP8_E4M3>(v, inv_s, words); break;
-    }
-    const int64_t e0 = row * a.cols + col;   // dense output rows
-    if (a.as_bf16_values) {
-      // 8-bit grid values have at most 7 significant bits: exact in bf16 (top half of fp32)
-      u32x4 o;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * 256;
+  int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  for (; c + (kEmitUnroll - 1) * stride < n_chunks; c += kEmitUnroll * stride) {
+    float v[kEmitUnroll][8];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float g0, g1;
-        if (fmt == MOFQ_INT8) {
-          g0 = Codec<MOFQ_INT8>::grid(v[2 * i] * inv_s);
-          g1 = Codec<MOFQ_INT8>::grid(v[2 * i + 1] * inv_s);
-        } else {
-          g0 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i] * inv_s);
-          g1 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i + 1] * inv_s);
-        }
-        o[i] = (f2u(g0) >> 16) | (f2u(g1) & 0xFFFF0000u);
-      }
-      reinterpret_cast<u32x4*>(a.out.codes)[e0 / 8] = o;
-    } else if (four) {
-      static_cast<uint32_t*>(a.out.codes)[e0 / 8] = words[0];
-    } else {
-      u32x2 o;
-      o[0] = words[0];
-      o[1] = words[1];
-      reinterpret_cast<u32x2*>(a.out.codes)[e0 / 8] = o;
+    for (int u = 0; u < kEmitUnroll; ++u) {
+      const int64_t cu = c + u * stride;
+      const int64_t row = cu / cpr, col = (cu - row * cpr) * 8;
+      L::load(static_cast<const typename L::elem*>(a.w) + row * a.ld + col, v[u]);
     }
+#pragma unroll
+    for (int u = 0; u < kEmitUnroll; ++u) emit_chunk<In>(a, fmt, scale, cpr, c + u * stride, v[u]);
+  }
+  for (; c < n_chunks; c += stride) {
+    float v[8];
+    const int64_t row = c / cpr, col = (c - row * cpr) * 8;
+    L::load(static_cast<const typename L::elem*>(a.w) + row * a.ld + col, v);
+    emit_chunk<In>(a, fmt, scale, cpr, c, v);
   }
 }
 
@@ -230,7 +275,9 @@ int launch_emit(const EmitParams& p, hipStream_t st) {
   a.units = mofq_num_units(p.rows, p.cols, p.gran, p.group);
   if (a.units <= 0) return MOFQ_ERR_INVALID_ARG;
   const int64_t n_chunks = p.rows * (p.cols / 8);
-  const unsigned blocks = static_cast<unsigned>(std::min<int64_t>((n_chunks + 255) / 256, 256 * 32));
+  // full occupancy (8 workgroups of 256 on each of 256 compute units), several chunks per thread
+  const unsigned blocks = static_cast<unsigned>(
+      std::max<int64_t>(1, std::min<int64_t>((n_chunks + 256 * kEmitUnroll - 1) / (256 * kEmitUnroll), 256 * 8)));
   if (p.out.codes) {
     switch (p.dtype) {
       case MOFQ_F32: hipLaunchKernelGGL(emit_codes_kernel<F32>, dim3(blocks), dim3(256), 0, st, a); break;

@@ -303,6 +303,90 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(CH <= 4
 }
 
 // ------------------------------------------------------------------------------
+// Per-channel with a single candidate (absmax scale, no search): a memory-bound pass.
+// Same register-resident row, but no candidate tables and two barriers in all; not
+// held to the register budget of the search kernel.
+// ------------------------------------------------------------------------------
+#ifndef K1_WAVES
+#define K1_WAVES 4
+#endif
+template <typename In, int FA, int FB, int THREADS, int CH>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(K1_WAVES))) void sweep_channel_single_kernel(const SweepArgs a) {
+  using L = Load8<In>;
+  constexpr int NF = (FB >= 0) ? 2 : 1;
+  constexpr int FBX = (FB >= 0) ? FB : FA;
+  constexpr int NW = THREADS / 64;
+  constexpr int NE = CH * 8;
+  __shared__ float s_wmax[NW];
+  __shared__ double s_wen[NW];
+  __shared__ double s_acc[2][NW];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t row = blockIdx.x;
+  const typename L::elem* src = static_cast<const typename L::elem*>(a.w) + row * a.ld;
+
+  float x[NE];
+  float amax = 0.0f;
+  double en = 0.0;
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const int64_t c0 = (static_cast<int64_t>(j) * THREADS + tid) * 8;
+    float v[8];
+    if (c0 < a.cols) {
+      L::load(src + c0, v);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = 0.0f;   // zeros past the row's end add nothing
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      x[j * 8 + i] = v[i];
+      amax = __builtin_fmaxf(amax, __builtin_fabsf(v[i]));
+      const double xd = static_cast<double>(v[i]);
+      en = __builtin_fma(xd, xd, en);
+    }
+  }
+  amax = wave_max(amax);
+  en = wave_sum(en);
+  if (lane == 0) { s_wmax[wave] = amax; s_wen[wave] = en; }
+  __syncthreads();
+  amax = s_wmax[0];
+  en = s_wen[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) { amax = __builtin_fmaxf(amax, s_wmax[w]); en += s_wen[w]; }
+
+  const float sA = unit_scale(amax, a.clip[0], Codec<FA>::QMAX, a.scale_f16 != 0);
+  const float sB = unit_scale(amax, a.clip[0], Codec<FBX>::QMAX, a.scale_f16 != 0);
+  const float iA = 1.0f / sA, iB = 1.0f / sB;
+  const double sAd = static_cast<double>(sA), sBd = static_cast<double>(sB);
+  double accA = 0.0, accB = 0.0;
+  uint32_t carry = 0;
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+      score2_f64<FA>(accA, x[j * 8 + i], x[j * 8 + i + 1], iA, sAd, carry);
+      if constexpr (NF == 2) score2_f64<FBX>(accB, x[j * 8 + i], x[j * 8 + i + 1], iB, sBd, carry);
+    }
+  }
+  accA = wave_sum(accA);
+  if constexpr (NF == 2) accB = wave_sum(accB);
+  if (lane == 0) { s_acc[0][wave] = accA; s_acc[1][wave] = accB; }
+  __syncthreads();
+  if (tid < NF) {
+    double t = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) t += s_acc[tid][w];
+    a.rec.scale[tid][row] = tid == 0 ? sA : sB;
+    a.rec.clip[tid][row] = 0;
+    a.rec.err[tid][row] = t;
+    if (tid == 0 && a.rec.energy) a.rec.energy[row] = en;
+  }
+}
+
+// ------------------------------------------------------------------------------
 // Per-group: LPG lanes share one group of GROUP elements; each lane holds
 // GROUP/LPG consecutive elements.  Scales differ per group, so they are per-lane
 // values; the LPG lanes of a group split the scale computations of a batch of LPG
@@ -676,7 +760,10 @@ int launch_channel(const SweepArgs& a, hipStream_t st) {
   const int64_t chunks = a.cols / 8;
 #define MOFQ_CH(THREADS, CH)                                                            \
   if (chunks <= static_cast<int64_t>(THREADS) * (CH)) {                                  \
-    hipLaunchKernelGGL((sweep_channel_kernel<In, FA, FB, THREADS, CH>), grid, dim3(THREADS), 0, st, a); \
+    if (a.n_clip == 1)                                                                   \
+      hipLaunchKernelGGL((sweep_channel_single_kernel<In, FA, FB, THREADS, CH>), grid, dim3(THREADS), 0, st, a); \
+    else                                                                                 \
+      hipLaunchKernelGGL((sweep_channel_kernel<In, FA, FB, THREADS, CH>), grid, dim3(THREADS), 0, st, a); \
     return hip_status(hipGetLastError());                                                \
   }
   // 32 to 48 elements per lane: enough work per candidate to amortise the cross-lane
