@@ -15,7 +15,9 @@ the same workload on the host cores.
 `--workload` selects two further workloads of the same path, each with its own
 JSON line (same keys; no CPU baseline): `w4_group128` (group-wise scales, 50 clip
 ratios) and `w8a8` (weight-activation, layer-output error through the matrix
-cores, 2048 tokens).  The default, `w4_channel`, is the headline workload.
+cores, 2048 tokens).  `k1_hbm` is the memory-bound case: configs[0]'s recipe (fp32,
+absmax scale, no clip search) on a 16384 x 16384 tensor (1 GiB).  The default,
+`w4_channel`, is the headline workload.
 """
 from __future__ import annotations
 
@@ -57,7 +59,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--model", default="7b", choices=["7b", "65b"],
                     help="65b = configs[4]: 560 linears, 129.5 GB of fp16 weights resident in HBM")
-    ap.add_argument("--workload", default="w4_channel", choices=["w4_channel", "w4_group128", "w8a8"])
+    ap.add_argument("--workload", default="w4_channel",
+                    choices=["w4_channel", "w4_group128", "w8a8", "k1_hbm"])
     ap.add_argument("--fp8-unit", action="store_true",
                     help="w8a8: E4M3 code product on the fp8 matrix cores (not within 1e-5 of the exact sum)")
     ap.add_argument("--blocks", type=int, default=0, help="debug: use only the first N blocks")
@@ -199,6 +202,62 @@ def run_w8a8(args, shapes, dev):
     print(json.dumps(out))
 
 
+def run_k1_hbm(args, dev):
+    """configs[0]'s recipe at a size that does not fit in the caches: one 16384 x 16384 fp32
+    tensor, per-channel absmax scale (one candidate), INT4 vs FP4-E2M1, select + emit."""
+    import torch
+
+    import mofq_inputs as mi
+    from paper_2305_12356_amd import binding as mq
+
+    n = 16384
+    w = mi.config0_weight(seed=0, rows=n, cols=n, device=dev)
+    cfg = mq.Cfg(mq.PER_CHANNEL, mi.clip_ratios(1))
+    cands = [mq.INT4, mq.FP4_E2M1]
+    out = mq.alloc_qbuffers(n, n, 4, cfg, dev)
+    res = mq.alloc_result(dev)
+    ws = torch.empty(mq.workspace_bytes(w, None, 2, mq.ERR_TENSOR, cfg), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        mq.select_layer(w, None, cands, mq.ERR_TENSOR, cfg, out, None, res, ws, stream)
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        events.append((e0, e1))
+        mq.select_layer(w, None, cands, mq.ERR_TENSOR, cfg, out, None, res, ws, stream, e0, e1)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    sweep_s = sum(e0.elapsed_time(e1) for e0, e1 in events) * 1e-3 / args.steps
+    read_bytes = n * n * 4
+    achieved = read_bytes / sweep_s / 1e9
+    r = mq.read_result(res)
+    print(json.dumps({
+        "metric": "weight-elems x candidates scored/sec (memory-bound case: one scale candidate)",
+        "value": n * n * N_FMT / (elapsed / args.steps), "unit": "elem*cand/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 decisions, f64 errors", "data": "synthetic",
+        "config": {"workload": "configs[0]'s recipe on a 16384 x 16384 fp32 tensor (1 GiB): N(0, 0.02^2), 0.1 % of "
+                               "entries x10, per-channel absmax scale, INT4 vs FP4-E2M1, tensor error, select + emit",
+                   "best": int(r.best), "err": [float(r.err[0]), float(r.err[1])]},
+        "roofline": {
+            "bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
+            # FETCH_SIZE / WRITE_SIZE of this kernel, scaled by a plain copy's (profiles/k1_hbm_fp32_16384_kernel_stats.txt)
+            "traffic": (1048666 + 3642) * 1024.0,
+            "kernel": "sweep_channel_single_kernel<F32, INT4, FP4_E2M1, 512 threads, 4 chunks>",
+            "note": "algorithmic bytes = 4 B per element read once by the scoring kernel; the emit pass "
+                    "(4 B read + 0.5 B written per element) is in ms_per_step but not in this kernel",
+            "avg_launch_ms": sweep_s * 1e3, "launches": len(events),
+            "algorithmic_bytes_per_launch": read_bytes,
+            "select_emit_GBps": n * n * 4.5 / (elapsed / args.steps - sweep_s) / 1e9,
+        },
+    }))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -223,6 +282,9 @@ def main():
         shapes = [s for s in shapes if s[0] < args.blocks]
     if args.workload == "w8a8":
         run_w8a8(args, shapes, dev)
+        return
+    if args.workload == "k1_hbm":
+        run_k1_hbm(args, dev)
         return
     group = args.workload == "w4_group128"
     n_clip = N_CLIP_GROUP if group else N_CLIP

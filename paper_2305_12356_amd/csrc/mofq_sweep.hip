@@ -773,6 +773,7 @@ int launch_channel(const SweepArgs& a, hipStream_t st) {
   MOFQ_CH(128, 4)    //  4096
   MOFQ_CH(256, 4)    //  8192
   MOFQ_CH(256, 6)    // 12288
+  MOFQ_CH(512, 4)    // 16384
   MOFQ_CH(512, 6)    // 24576
   MOFQ_CH(1024, 4)   // 32768
 #undef MOFQ_CH
