@@ -295,3 +295,47 @@ def select_layer_wa(x, w, candidates: Sequence[int], w_gran: int = PER_TENSOR,
         qws.append(qw)
     best = select(errs)
     return Selected(best, errs, energy, qws[best], qxs[best], list(zip(qxs, qws)))
+
+
+def layer_output_error_w_only(x, w, qw: Quantized, w_gran: int = PER_CHANNEL):
+    """Weight-only layer-output error (Section 3.2, layer analysis, with the input
+    left in 16 bits): E = sum (X W^T - X What^T)^2 and P = sum (X W^T)^2 in fp64, with
+    What[o, i] = gw[o, i] * sw[o] (per-channel) or gw[o, i] * sw (per-tensor).
+
+    The quantized product is formed as sw[o] * (X Gw^T): every product of a 16-bit input
+    and a 4-bit grid value is exact in fp64 and so is their sum (at most 12 + 15 bits of
+    length), so the only roundings are the final scaling and the subtraction."""
+    x64 = np.asarray(x, dtype=np.float64)
+    w64 = np.asarray(w, dtype=np.float64)
+    y = x64 @ w64.T
+    gw = decode_array(qw.fmt, qw.codes)
+    acc = x64 @ gw.T
+    if w_gran == PER_TENSOR:
+        yq = np.float64(qw.scale[0]) * acc
+    elif w_gran == PER_CHANNEL:
+        yq = qw.scale.astype(np.float64)[None, :] * acc
+    else:
+        raise ValueError("layer-output error needs one scale per output channel or per tensor")
+    d = y - yq
+    return float(np.sum(d * d)), float(np.sum(y * y))
+
+
+def select_layer_w_only_output(x, w, candidates: Sequence[int], w_gran: int = PER_CHANNEL,
+                               clip=(1.0,), scale_f16: bool = False, threads: int = 0) -> Selected:
+    """Algorithm 1 for one layer in the weight-only case with the layer-output error as
+    the metric: each candidate format quantizes W (scales searched over `clip` by tensor
+    error, as in quantize()), the layer is run on the 16-bit input X with the original
+    and with the quantized weights, and the format with the smaller output error wins
+    (strict less-than, first candidate on ties)."""
+    x = _f32c(x)
+    w = _f32c(w)
+    clip = np.asarray(clip, dtype=np.float32)
+    errs, qws, energy = [], [], 0.0
+    for f in candidates:
+        qw = quantize(w, f, w_gran, clip, 0, scale_f16, threads=threads)
+        e, energy = layer_output_error_w_only(x, w, qw, w_gran)
+        errs.append(e)
+        qws.append(qw)
+    best = select(errs)
+    return Selected(best, errs, energy, qws[best], None, [(None, q) for q in qws])
+
