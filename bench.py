@@ -60,7 +60,7 @@ def parse():
     ap.add_argument("--model", default="7b", choices=["7b", "65b"],
                     help="65b = configs[4]: 560 linears, 129.5 GB of fp16 weights resident in HBM")
     ap.add_argument("--workload", default="w4_channel",
-                    choices=["w4_channel", "w4_group128", "w8a8", "k1_hbm"])
+                    choices=["w4_channel", "w4_group128", "w8a8", "w4a16_output", "k1_hbm"])
     ap.add_argument("--fp8-unit", action="store_true",
                     help="w8a8: E4M3 code product on the fp8 matrix cores (not within 1e-5 of the exact sum)")
     ap.add_argument("--blocks", type=int, default=0, help="debug: use only the first N blocks")
@@ -113,9 +113,11 @@ def cpu_baseline(weights, outs, clip, cands):
     }
 
 
-def run_w8a8(args, shapes, dev):
+def run_w8a8(args, shapes, dev, w_only=False):
     """configs[3]: per linear, X [2048, in] bf16 with outlier channels, W bf16; per-tensor
-    INT8 vs FP8-E4M3 for both; layer-output error through the matrix cores; select + emit."""
+    INT8 vs FP8-E4M3 for both; layer-output error through the matrix cores; select + emit.
+    With w_only: the weight-only select by layer-output error (X stays bf16; W per-channel
+    absmax scales, INT4 vs FP4-E2M1)."""
     import torch
 
     import mofq_inputs as mi
@@ -124,6 +126,11 @@ def run_w8a8(args, shapes, dev):
     metric = mq.ERR_LAYER_OUTPUT_FP8_UNIT if args.fp8_unit else mq.ERR_LAYER_OUTPUT
     cands = [mq.INT8, mq.FP8_E4M3]
     cfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
+    bits = 8
+    if w_only:
+        metric, cands, bits = mq.ERR_LAYER_OUTPUT_W_ONLY, [mq.INT4, mq.FP4_E2M1], 4
+        cfg = mq.Cfg(mq.PER_CHANNEL, mi.clip_ratios(1))
+    xcfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
     xs = {}
     weights, wouts, xouts = [], [], {}
     results = mq.alloc_result(dev, len(shapes))
@@ -131,7 +138,7 @@ def run_w8a8(args, shapes, dev):
     for b, name, o, n in shapes:
         if n not in xs:
             xs[n] = mi.activations(TOKENS, n, seed=mi.tensor_seed(3, 0, 0, n), device=dev)
-            xouts[n] = mq.alloc_qbuffers(TOKENS, n, 8, cfg, dev)
+            xouts[n] = None if w_only else mq.alloc_qbuffers(TOKENS, n, 8, xcfg, dev)
         w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, mi.LINEAR_NAMES.index(name)),
                                  dtype=torch.bfloat16, device=dev)
         weights.append(w)
@@ -139,7 +146,7 @@ def run_w8a8(args, shapes, dev):
     # one output buffer per distinct weight shape (the codes are not read back here)
     for b, name, o, n in shapes:
         if (o, n) not in xouts:
-            xouts[(o, n)] = mq.alloc_qbuffers(o, n, 8, cfg, dev)
+            xouts[(o, n)] = mq.alloc_qbuffers(o, n, bits, cfg, dev)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
@@ -168,24 +175,28 @@ def run_w8a8(args, shapes, dev):
     # dominant kernel: the fused three-product GEMM; one launch per linear
     mnk = sum(TOKENS * o * n for _, _, o, n in shapes)
     gemm_time = sum(e0.elapsed_time(e1) for _, e0, e1 in events) * 1e-3 / args.steps
-    kinds = ["bf16", "int8", "fp8" if args.fp8_unit else "bf16"]
+    kinds = ["bf16", "bf16", "bf16"] if w_only else ["bf16", "int8", "fp8" if args.fp8_unit else "bf16"]
     flops = 2.0 * mnk * len(kinds)
     ideal = sum(2.0 * mnk / (MFMA_PEAK[k] * 1e12) for k in kinds)
     achieved = flops / gemm_time / 1e12
     peak = flops / ideal / 1e12
     res = mq.read_results(results)
     out = {
-        "metric": "W8A8 layer-output MoFQ select time over the LLaMA-7B linear shapes",
+        "metric": ("W4A16" if w_only else "W8A8") + " layer-output MoFQ select time over the LLaMA-7B linear shapes",
         "value": ms_per_step / 1e3, "unit": "s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 reference product, int8 codes, " +
-                 ("fp8 codes on the fp8 matrix cores" if args.fp8_unit else "e4m3 grid values on the bf16 matrix cores") +
-                 ", f64 error sums",
+        "dtype": ("bf16 reference product, 4-bit grid values on the bf16 matrix cores, f64 error sums" if w_only else
+                  "bf16 reference product, int8 codes, " +
+                  ("fp8 codes on the fp8 matrix cores" if args.fp8_unit else "e4m3 grid values on the bf16 matrix cores") +
+                  ", f64 error sums"),
         "data": "synthetic",
-        "config": {"workload": f"configs[3]: {len(shapes)} linears of the LLaMA-7B shape, X [{TOKENS} x in] bf16 "
-                               "with 6 outlier channels x60, W bf16, per-tensor INT8 vs FP8-E4M3, "
-                               "layer-output error, per-layer select + emit",
+        "config": {"workload": (f"weight-only select by layer-output error: {len(shapes)} linears of the LLaMA-7B shape, "
+                                f"X [{TOKENS} x in] bf16 unquantized, W bf16, per-channel absmax scales, "
+                                "INT4 vs FP4-E2M1, per-layer select + emit") if w_only else
+                               (f"configs[3]: {len(shapes)} linears of the LLaMA-7B shape, X [{TOKENS} x in] bf16 "
+                                "with 6 outlier channels x60, W bf16, per-tensor INT8 vs FP8-E4M3, "
+                                "layer-output error, per-layer select + emit"),
                    "fp8_product": "fp8 matrix cores" if args.fp8_unit else "exact (bf16 matrix cores)",
                    "fp_percent": 100.0 * sum(1 for r in res if r.best == 1) / len(res)},
         "roofline": {
@@ -280,8 +291,8 @@ def main():
     shapes = mi.model_linear_shapes(args.model)
     if args.blocks:
         shapes = [s for s in shapes if s[0] < args.blocks]
-    if args.workload == "w8a8":
-        run_w8a8(args, shapes, dev)
+    if args.workload in ("w8a8", "w4a16_output"):
+        run_w8a8(args, shapes, dev, w_only=args.workload == "w4a16_output")
         return
     if args.workload == "k1_hbm":
         run_k1_hbm(args, dev)

@@ -75,7 +75,13 @@ typedef enum {
    * instruction, addends below 2^-13 of the largest product of each group of 8, so
    * the FP8 error sum carries a relative deviation of order 1e-5..1e-4 on tensors
    * with outlier channels.  The INT8 product is exact in both modes. */
-  MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT = 2
+  MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT = 2,
+  /* Layer-output error of the weight-only case (Section 4.1 names tensor error and
+   * layer-output error as the two metrics that suffice there): the input stays in 16
+   * bits, only W is quantized: sum (X W^T - X Q(W)^T)^2.  Q(W) is the quantization the
+   * tensor-error path produces for the format (scales searched over w_cfg's clip
+   * ratios by tensor error). */
+  MOFQ_ERR_LAYER_OUTPUT_W_ONLY = 3
 } mofq_metric_t;
 
 typedef enum {
@@ -145,6 +151,11 @@ int mofq_quantize(const mofq_tensor_t* t, int32_t format, const mofq_scale_cfg_t
  *                                    n_clip = 1); *err = sum (X W^T - Q(X) Q(W)^T)^2,
  *                                    *ref_energy = sum (X W^T)^2.  W and X must be
  *                                    MOFQ_BF16 and `format` an 8-bit format.
+ *   metric = MOFQ_ERR_LAYER_OUTPUT_W_ONLY : x = A_in stays unquantized (MOFQ_BF16, dense
+ *                                    rows: ld = cols); W (MOFQ_BF16) is quantized in
+ *                                    `format` (4-bit or 8-bit) per w_cfg (per-tensor or
+ *                                    per-channel, any n_clip); *err = sum (X W^T -
+ *                                    X Q(W)^T)^2, *ref_energy = sum (X W^T)^2.
  * `err` and `ref_energy` are device pointers (ref_energy may be NULL).
  */
 int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, int32_t metric,
@@ -161,6 +172,10 @@ int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, i
  *               tensors MOFQ_BF16, cols a multiple of 64, w_cfg per-tensor or
  *               per-channel with n_clip = 1, X per-tensor at ratio 1); x_out (may be
  *               NULL) receives X's codes and its one scale.
+ *   x != NULL, metric = MOFQ_ERR_LAYER_OUTPUT_W_ONLY : weight-only select by the layer
+ *               output on the 16-bit input x (at most 2 candidates; W and X MOFQ_BF16, X
+ *               with ld = cols, cols a multiple of 64, w_cfg per-tensor or per-channel);
+ *               x_out is ignored.
  * `candidates` is a HOST array.  `result` is device memory.
  */
 int mofq_select_layer(const mofq_tensor_t* w, const mofq_tensor_t* x,

@@ -17,7 +17,7 @@ import torch
 INT4, FP4_E2M1, INT8, FP8_E4M3 = 0, 1, 2, 3
 F32, F16, BF16 = 0, 1, 2
 PER_TENSOR, PER_CHANNEL, PER_GROUP = 0, 1, 2
-ERR_TENSOR, ERR_LAYER_OUTPUT, ERR_LAYER_OUTPUT_FP8_UNIT = 0, 1, 2
+ERR_TENSOR, ERR_LAYER_OUTPUT, ERR_LAYER_OUTPUT_FP8_UNIT, ERR_LAYER_OUTPUT_W_ONLY = 0, 1, 2, 3
 MAX_CANDIDATES = 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

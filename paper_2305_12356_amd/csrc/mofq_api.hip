@@ -204,6 +204,88 @@ WaWs carve_wa(void* ws, const mofq_tensor_t* w, const mofq_tensor_t* x, int n_ca
   return a;
 }
 
+// ---- weight-only select with the layer-output error (Section 4.1: tensor error or
+// layer-output error suffices for the weight-only case).  The input stays in 16 bits; each
+// candidate's weights are quantized as in the tensor-error path (scales searched by
+// tensor error), and the kernel compares X W^T with s[o] * (X G^T).
+int check_wo_output(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand, int n_cand,
+                    const mofq_scale_cfg_t* w_cfg) {
+  int rc = check_tensor(x);
+  if (rc) return rc;
+  if (x->cols != w->cols) return MOFQ_ERR_INVALID_ARG;
+  if (n_cand > 2) return MOFQ_ERR_UNSUPPORTED;                 // two quantized products per launch
+  if (w->dtype != MOFQ_BF16 || x->dtype != MOFQ_BF16) return MOFQ_ERR_UNSUPPORTED;
+  if (x->ld != x->cols) return MOFQ_ERR_UNSUPPORTED;            // X is also the dense operand of the quantized products
+  if (w_cfg->gran != MOFQ_PER_TENSOR && w_cfg->gran != MOFQ_PER_CHANNEL) return MOFQ_ERR_UNSUPPORTED;
+  if (w->cols % 64 != 0) return MOFQ_ERR_UNSUPPORTED;
+  if (w->rows > (1 << 30) || x->rows > (1 << 30) || w->cols > 32768) return MOFQ_ERR_UNSUPPORTED;
+  return MOFQ_OK;
+}
+
+struct WoOutWs {
+  WOnlyWs wrec;
+  uint8_t* wg[2];   // grid values of W per candidate, bf16, dense
+  double* part[3];  // error per candidate, reference energy; one value per output tile
+  int blocks;
+  size_t bytes;
+};
+
+WoOutWs carve_wo_output(void* ws, const mofq_tensor_t* w, const mofq_tensor_t* x, int n_cand,
+                        const mofq_scale_cfg_t* cfg) {
+  WoOutWs a{};
+  const int64_t units_w = mofq_num_units(w->rows, w->cols, cfg->gran, 0);
+  a.wrec = carve_w_only(ws, units_w, n_cand, cfg->gran, cfg->n_clip);
+  char* base = static_cast<char*>(ws);
+  Carver c(base ? base + a.wrec.bytes : nullptr);
+  for (int f = 0; f < n_cand; ++f) a.wg[f] = c.take<uint8_t>(static_cast<size_t>(w->rows) * w->cols * 2);
+  a.blocks = wa_gemm_blocks(x->rows, w->rows);
+  for (int i = 0; i < 3; ++i) a.part[i] = c.take<double>(a.blocks);
+  a.bytes = a.wrec.bytes + (c.off + kAlign - 1) / kAlign * kAlign;
+  return a;
+}
+
+int wo_output_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand, int n_cand,
+                    const mofq_scale_cfg_t* w_cfg, const WoOutWs& a, hipStream_t st,
+                    hipEvent_t ev0, hipEvent_t ev1) {
+  int rc;
+  if ((rc = sweep_candidates(w, cand, n_cand, w_cfg, a.wrec, st))) return rc;
+  WaGemmParams g{};
+  for (int c = 0; c < n_cand; ++c) {
+    EmitParams e{};
+    e.w = w->data;
+    e.dtype = w->dtype;
+    e.rows = w->rows;
+    e.cols = w->cols;
+    e.ld = w->ld;
+    e.gran = w_cfg->gran;
+    e.group = 0;
+    e.n_cand = 1;
+    e.fmt[0] = cand[c];
+    e.scale[0] = a.wrec.scale[c];
+    e.clip[0] = a.wrec.clip[c];
+    e.err[0] = a.wrec.err[c];
+    e.result = nullptr;
+    e.out.codes = a.wg[c];
+    e.as_bf16_values = 1;
+    if ((rc = launch_emit(e, st))) return rc;
+    g.q[c].kind = WA_GRID_BF16;
+    g.q[c].x = x->data;          // the unquantized input, scale 1
+    g.q[c].w = a.wg[c];
+    g.q[c].sx = nullptr;
+    g.q[c].sw = a.wrec.scale[c];
+    g.q[c].part = a.part[c];
+  }
+  g.x = x->data; g.ldx = x->ld;
+  g.w = w->data; g.ldw = w->ld;
+  g.w_per_channel = w_cfg->gran == MOFQ_PER_CHANNEL;
+  g.M = x->rows; g.N = w->rows; g.K = w->cols;
+  g.part_p = a.part[2];
+  if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return MOFQ_ERR_HIP;
+  if ((rc = launch_wa_gemm(g, st))) return rc;
+  if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return MOFQ_ERR_HIP;
+  return MOFQ_OK;
+}
+
 // Quantize X and W in every candidate format, then one pass over the matrix cores
 // that leaves per-tile partial errors in the workspace.
 int wa_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand, int n_cand,
@@ -214,6 +296,7 @@ int wa_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand
   if ((rc = sweep_candidates(x, cand, n_cand, &xc, a.xrec, st))) return rc;
   if ((rc = sweep_candidates(w, cand, n_cand, w_cfg, a.wrec, st))) return rc;
   WaGemmParams g{};
+  int n_q = 0;
   for (int f = 0; f < 2; ++f) {
     const int fmt = f == 0 ? MOFQ_INT8 : MOFQ_FP8_E4M3;
     int slot = -1;
@@ -241,11 +324,13 @@ int wa_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand
       e.as_bf16_values = (f == 1 && !fp8_unit);
       if ((rc = launch_emit(e, st))) return rc;
     }
-    if (f == 0) { g.xi = a.xq[0]; g.wi = a.wq[0]; g.sx_i = a.xrec.scale[slot]; g.sw_i = a.wrec.scale[slot]; g.part_i = a.part[0]; }
-    else {
-      if (fp8_unit) { g.xf = a.xq[1]; g.wf = a.wq[1]; } else { g.xg = a.xq[1]; g.wg = a.wq[1]; }
-      g.sx_f = a.xrec.scale[slot]; g.sw_f = a.wrec.scale[slot]; g.part_f = a.part[1];
-    }
+    WaProduct& q = g.q[n_q++];
+    q.kind = f == 0 ? WA_INT8 : (fp8_unit ? WA_FP8 : WA_GRID_BF16);
+    q.x = a.xq[f];
+    q.w = a.wq[f];
+    q.sx = a.xrec.scale[slot];
+    q.sw = a.wrec.scale[slot];
+    q.part = a.part[f];
   }
   g.x = x->data; g.ldx = x->ld;
   g.w = w->data; g.ldw = w->ld;
@@ -297,6 +382,9 @@ size_t mofq_workspace_bytes(const mofq_tensor_t* w, const mofq_tensor_t* x, int3
       x->rows > 0 && x->cols == w->cols &&
       (w_cfg->gran == MOFQ_PER_TENSOR || w_cfg->gran == MOFQ_PER_CHANNEL))
     return carve_wa(nullptr, w, x, n_candidates, w_cfg->gran).bytes;
+  if (metric == MOFQ_ERR_LAYER_OUTPUT_W_ONLY && x && x->rows > 0 && x->cols == w->cols && n_candidates <= 2 &&
+      (w_cfg->gran == MOFQ_PER_TENSOR || w_cfg->gran == MOFQ_PER_CHANNEL))
+    return carve_wo_output(nullptr, w, x, n_candidates, w_cfg).bytes;
   return 0;
 }
 
@@ -362,6 +450,21 @@ int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, i
     d.err[0] = s.err[0];
     d.energy = s.energy;
     d.part = s.decide_part;
+    d.tensor_err_out = err;
+    d.energy_out = ref_energy;
+    return launch_decide(d, st);
+  }
+  if (metric == MOFQ_ERR_LAYER_OUTPUT_W_ONLY) {
+    if (!x) return MOFQ_ERR_INVALID_ARG;
+    if ((rc = check_wo_output(w, x, &format, 1, w_cfg))) return rc;
+    const WoOutWs a = carve_wo_output(ws, w, x, 1, w_cfg);
+    if (!ws || ws_bytes < a.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+    if ((rc = wo_output_score(w, x, &format, 1, w_cfg, a, st, nullptr, nullptr))) return rc;
+    DecideParams d{};
+    d.units = a.blocks;
+    d.n_cand = 1;
+    d.err[0] = a.part[0];
+    d.energy = a.part[2];
     d.tensor_err_out = err;
     d.energy_out = ref_energy;
     return launch_decide(d, st);
@@ -441,6 +544,39 @@ int mofq_select_layer_timed(const mofq_tensor_t* w, const mofq_tensor_t* x,
       e.scale[c] = s.scale[c];
       e.clip[c] = s.clip[c];
       e.err[c] = s.err[c];
+    }
+    e.result = result;
+    e.out = *w_out;
+    return launch_emit(e, st);
+  }
+  if (metric == MOFQ_ERR_LAYER_OUTPUT_W_ONLY) {
+    if ((rc = check_wo_output(w, x, candidates, n_candidates, w_cfg))) return rc;
+    const WoOutWs a = carve_wo_output(ws, w, x, n_candidates, w_cfg);
+    if (!ws || ws_bytes < a.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+    if ((rc = wo_output_score(w, x, candidates, n_candidates, w_cfg, a, st, ev0, ev1))) return rc;
+    DecideParams d{};
+    d.units = a.blocks;
+    d.n_cand = n_candidates;
+    for (int c = 0; c < n_candidates; ++c) d.err[c] = a.part[c];
+    d.energy = a.part[2];
+    d.result = result;
+    if ((rc = launch_decide(d, st))) return rc;
+    // second quantize_layer call of Algorithm 1: W in the chosen format
+    EmitParams e{};
+    e.w = w->data;
+    e.dtype = w->dtype;
+    e.rows = w->rows;
+    e.cols = w->cols;
+    e.ld = w->ld;
+    e.gran = w_cfg->gran;
+    e.group = 0;
+    e.scale_f16_out = w_cfg->scale_dtype == MOFQ_F16;
+    e.n_cand = n_candidates;
+    for (int c = 0; c < n_candidates; ++c) {
+      e.fmt[c] = candidates[c];
+      e.scale[c] = a.wrec.scale[c];
+      e.clip[c] = a.wrec.clip[c];
+      e.err[c] = a.wrec.err[c];
     }
     e.result = result;
     e.out = *w_out;

@@ -163,17 +163,16 @@ MOFQ_DEV void emit_chunk(const EmitArgs& a, int fmt, const float* scale, int64_t
   }
   const int64_t e0 = row * a.cols + col;   // dense output rows
   if (a.as_bf16_values) {
-    // 8-bit grid values have at most 7 significant bits: exact in bf16 (top half of fp32)
+    // grid values have at most 7 significant bits: exact in bf16 (top half of fp32)
     u32x4 o;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float g0, g1;
-      if (fmt == MOFQ_INT8) {
-        g0 = Codec<MOFQ_INT8>::grid(v[2 * i] * inv_s);
-        g1 = Codec<MOFQ_INT8>::grid(v[2 * i + 1] * inv_s);
-      } else {
-        g0 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i] * inv_s);
-        g1 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i + 1] * inv_s);
+      switch (fmt) {
+        case MOFQ_INT4: g0 = Codec<MOFQ_INT4>::grid(v[2 * i] * inv_s); g1 = Codec<MOFQ_INT4>::grid(v[2 * i + 1] * inv_s); break;
+        case MOFQ_FP4_E2M1: g0 = Codec<MOFQ_FP4_E2M1>::grid(v[2 * i] * inv_s); g1 = Codec<MOFQ_FP4_E2M1>::grid(v[2 * i + 1] * inv_s); break;
+        case MOFQ_INT8: g0 = Codec<MOFQ_INT8>::grid(v[2 * i] * inv_s); g1 = Codec<MOFQ_INT8>::grid(v[2 * i + 1] * inv_s); break;
+        default: g0 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i] * inv_s); g1 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i + 1] * inv_s); break;
       }
       o[i] = (f2u(g0) >> 16) | (f2u(g1) & 0xFFFF0000u);
     }
@@ -271,7 +270,6 @@ int launch_emit(const EmitParams& p, hipStream_t st) {
   a.result = p.result;
   a.out = p.out;
   a.as_bf16_values = p.as_bf16_values;
-  if (p.as_bf16_values && !(p.fmt[0] == MOFQ_INT8 || p.fmt[0] == MOFQ_FP8_E4M3)) return MOFQ_ERR_INVALID_ARG;
   a.units = mofq_num_units(p.rows, p.cols, p.gran, p.group);
   if (a.units <= 0) return MOFQ_ERR_INVALID_ARG;
   const int64_t n_chunks = p.rows * (p.cols / 8);

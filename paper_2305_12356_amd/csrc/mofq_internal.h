@@ -83,17 +83,28 @@ int launch_emit(const EmitParams& p, hipStream_t stream);
 
 // Layer-output error of one linear layer: partial sums per 128x128 output tile.
 // A null xi/wi (or xf/wf) pair skips that format.
+// One quantized product of the layer-output kernel: sum_i Gx[t,i] * Gw[o,i], scaled by
+// sx * sw[o] in the reduction.  Operand arrays are dense ([M][K] and [N][K]).
+enum WaKind : int32_t {
+  WA_NONE = 0,
+  WA_GRID_BF16 = 1,   // grid values stored as bf16 (exact), bf16 matrix cores
+  WA_INT8 = 2,        // int8 codes, int8 matrix cores
+  WA_FP8 = 3,         // e4m3 codes, fp8 matrix cores
+};
+struct WaProduct {
+  int32_t kind;
+  const void* x; const void* w;
+  const float* sx;                 // device, one value; nullptr = 1 (unquantized input)
+  const float* sw;                 // device, 1 or N values
+  double* part;                    // [wa_gemm_blocks(M, N)] squared-difference partials
+};
 struct WaGemmParams {
   const void* x; int64_t ldx;      // bf16 [M][K]
   const void* w; int64_t ldw;      // bf16 [N][K]
-  const uint8_t* xi; const uint8_t* wi;   // INT8 codes, dense rows
-  const uint8_t* xf; const uint8_t* wf;   // E4M3 codes, dense rows (fp8 matrix cores)
-  const void* xg; const void* wg;         // or: E4M3 grid values as bf16, dense rows (exact product)
-  const float* sx_i; const float* sw_i;   // device scales (sw: 1 or N values)
-  const float* sx_f; const float* sw_f;
+  WaProduct q[2];                  // up to two quantized products (kind WA_NONE = unused)
   int32_t w_per_channel;
   int64_t M, N, K;
-  double* part_i; double* part_f; double* part_p;   // [wa_gemm_blocks(M, N)]
+  double* part_p;                  // [wa_gemm_blocks(M, N)] sum of Y^2
 };
 int wa_gemm_blocks(int64_t M, int64_t N);
 int launch_wa_gemm(const WaGemmParams& p, hipStream_t stream);

@@ -5,8 +5,8 @@
 //     Y = X W^T .
 //
 // One kernel computes, per 256x128 output tile, the reference product on the bf16
-// matrix cores, then the INT8 code product on the int8 matrix cores and the FP8-E4M3
-// code product, one after the other: each product is a K loop of its own over its own
+// matrix cores, then up to two quantized products (for W8A8: the INT8 code product on the
+// int8 matrix cores and the FP8-E4M3 code product), one after the other: each product is a K loop of its own over its own
 // operand arrays, the reference accumulators stay in registers for the whole kernel and
 // the quantized accumulators are reduced against them (squared differences in fp64) as
 // soon as their loop ends.  Y is never written to memory.
@@ -23,16 +23,18 @@
 //
 // Exactness: bf16 x bf16 products are exact in fp32 and are accumulated in fp32;
 // int8 products are accumulated exactly in int32 (|sum| <= 32768*127*127 < 2^31).
-// The E4M3 code product has two modes:
-//   FP8_EXACT  : the grid values (exact in bf16) go through the bf16 matrix cores,
-//                products exact, fp32 accumulation -- the mode that meets the 1e-5
-//                tolerance on the error sum;
-//   FP8_NATIVE : the codes go through the fp8 matrix cores (the low-bit matmul units
-//                the WA case of Algorithm 1 targets).  Measured on the part: inside
-//                one instruction, products are aligned per group of 8 and addends
-//                below 2^-13 of the group's largest product are truncated, which
-//                shifts the error sum by ~1e-5..1e-4 relative on tensors with
-//                outlier channels.
+// A quantized product is one of three kinds:
+//   WA_INT8      : int8 codes on the int8 matrix cores (exact);
+//   WA_GRID_BF16 : grid values stored as bf16 (exact for 4-bit and 8-bit grids) on the
+//                  bf16 matrix cores, products exact, fp32 accumulation -- the E4M3
+//                  product that meets the 1e-5 tolerance on the error sum, and the
+//                  4-bit products of the weight-only layer-output metric, where the
+//                  "quantized" input is the 16-bit input itself (scale 1);
+//   WA_FP8       : e4m3 codes on the fp8 matrix cores (the low-bit matmul units the WA
+//                  case of Algorithm 1 targets).  Measured on the part: inside one
+//                  instruction, products are aligned per group of 8 and addends below
+//                  2^-13 of the group's largest product are truncated, which shifts the
+//                  error sum by ~1e-5..1e-4 relative on tensors with outlier channels.
 #include <type_traits>
 
 #include "mofq_device.h"
@@ -53,21 +55,20 @@ constexpr int WM = 64, WN = 64;                 // wave tile: 2 x 2 matrix-core 
 constexpr int NW = (TM / WM) * (TN / WN);       // waves per workgroup
 constexpr int TI = WM / 32, TJ = WN / 32;
 
+struct QProd {
+  const void* x; const void* w;                 // dense [M][K], [N][K] in the product's operand type
+  const float* sx; const float* sw;             // scales: sx one value or null (= 1); sw one value or [N]
+  double* part;                                 // [blocks]
+};
 struct GemmArgs {
   const uint16_t* x; int64_t ldx;               // bf16 [M][K]
   const uint16_t* w; int64_t ldw;               // bf16 [N][K]
-  const uint8_t* xi; const uint8_t* wi;         // int8 codes, dense [M][K], [N][K]
-  const uint8_t* xf; const uint8_t* wf;         // e4m3 codes (FP8_NATIVE)
-  const uint16_t* xg; const uint16_t* wg;       // e4m3 grid values as bf16 (FP8_EXACT)
-  const float* sx_i; const float* sw_i;         // scales: sx one value; sw one value or [N]
-  const float* sx_f; const float* sw_f;
+  QProd q[2];
   int32_t w_per_channel;
   int32_t M, N, K;
   int32_t tiles_m, tiles_n;
-  double* part_i; double* part_f; double* part_p;   // [blocks]
+  double* part_p;                               // [blocks]
 };
-
-constexpr int FP8_NONE = 0, FP8_NATIVE = 1, FP8_EXACT = 2;
 
 // ---- LDS stage ----------------------------------------------------------------------
 // A stage holds one K slab of both operand tiles: 256 rows of X then 128 rows of W, each
@@ -106,9 +107,9 @@ template <int N> MOFQ_DEV void wait_deposits_but() {
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-enum : int { K_REF = 0, K_GRID = 1, K_I8 = 2, K_F8 = 3 };
+enum : int { K_REF = 100, K_GRID = WA_GRID_BF16, K_I8 = WA_INT8, K_F8 = WA_FP8 };   // K_REF: the 16-bit inputs themselves
 
-template <bool DO_I8, int FP8>
+template <int KIND1, int KIND2>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void wa_gemm_kernel(const GemmArgs a) {
   __shared__ __attribute__((aligned(1024))) unsigned char s_buf[NST * STAGE];
   __shared__ double s_red[3][NW];
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   // ---- one product: K loop over its own operand arrays ---------------------------------
   // KIND selects arrays, element size and matrix instruction; acc is f32x16 or i32x16.
-  auto product = [&](auto kind_c, auto& acc) {
+  auto product = [&](auto kind_c, auto& acc, const void* xq, const void* wq) {
     constexpr int KIND = decltype(kind_c)::value;
     constexpr int EB = (KIND == K_REF || KIND == K_GRID) ? 2 : 1;   // bytes per element
     constexpr int TK = ROW_B / EB;                                  // K elements per stage
@@ -171,9 +172,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int NF = (KIND == K_F8) ? 2 : 1;                      // 16-byte chunks per fragment
     const char* xb; const char* wb; int64_t xrow, wrow;
     if constexpr (KIND == K_REF) { xb = reinterpret_cast<const char*>(a.x); wb = reinterpret_cast<const char*>(a.w); xrow = a.ldx * 2; wrow = a.ldw * 2; }
-    else if constexpr (KIND == K_GRID) { xb = reinterpret_cast<const char*>(a.xg); wb = reinterpret_cast<const char*>(a.wg); xrow = wrow = static_cast<int64_t>(a.K) * 2; }
-    else if constexpr (KIND == K_I8) { xb = reinterpret_cast<const char*>(a.xi); wb = reinterpret_cast<const char*>(a.wi); xrow = wrow = a.K; }
-    else { xb = reinterpret_cast<const char*>(a.xf); wb = reinterpret_cast<const char*>(a.wf); xrow = wrow = a.K; }
+    else { xb = static_cast<const char*>(xq); wb = static_cast<const char*>(wq); xrow = wrow = static_cast<int64_t>(a.K) * EB; }
 
     // This lane's global source of each of its wave's deposits at k = 0 (deposit i of a
     // stage covers chunk slots 64 i .. 64 i + 63 and is issued by wave i % NW).
@@ -301,7 +300,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   auto sq_diff = [&](auto with_p_c, const auto& acc_q, const float* sx, const float* sw_) {
     constexpr bool WITH_P = decltype(with_p_c)::value;
     __builtin_amdgcn_sched_barrier(0);
-    const double sxd = static_cast<double>(*sx);
+    const double sxd = sx ? static_cast<double>(*sx) : 1.0;
     double e_q = 0.0;
     // rows of this lane's accumulators that exist: 32 i + 8 (e/4) + e%4 < row_lim.  Opaque,
     // so that each reduction computes its own masks instead of keeping 128 of them live.
@@ -339,40 +338,37 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     return wave_sum(e_q);
   };
 
-  product(std::integral_constant<int, K_REF>{}, acc_r);
-  double e_i = 0.0, e_f = 0.0;
-  if constexpr (DO_I8) {
-    i32x16 acc_i[TI][TJ];
+  product(std::integral_constant<int, K_REF>{}, acc_r, nullptr, nullptr);
+  double e_q[2] = {0.0, 0.0};
+  auto quantized = [&](auto kind_c, auto slot_c) {
+    constexpr int KIND = decltype(kind_c)::value;
+    constexpr int SLOT = decltype(slot_c)::value;
+    if constexpr (KIND != WA_NONE) {
+      using acc_t = std::conditional_t<KIND == K_I8, i32x16, f32x16>;
+      acc_t acc_q[TI][TJ];
 #pragma unroll
-    for (int i = 0; i < TI; ++i)
+      for (int i = 0; i < TI; ++i)
 #pragma unroll
-      for (int j = 0; j < TJ; ++j)
+        for (int j = 0; j < TJ; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc_i[i][j][e] = 0;
-    product(std::integral_constant<int, K_I8>{}, acc_i);
-    e_i = sq_diff(std::true_type{}, acc_i, a.sx_i, a.sw_i);
-  }
-  if constexpr (FP8 != FP8_NONE) {
-    f32x16 acc_f[TI][TJ];
-#pragma unroll
-    for (int i = 0; i < TI; ++i)
-#pragma unroll
-      for (int j = 0; j < TJ; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc_f[i][j][e] = 0.0f;
-    product(std::integral_constant<int, FP8 == FP8_EXACT ? K_GRID : K_F8>{}, acc_f);
-    e_f = sq_diff(std::integral_constant<bool, !DO_I8>{}, acc_f, a.sx_f, a.sw_f);
-  }
+          for (int e = 0; e < 16; ++e) acc_q[i][j][e] = 0;
+      product(kind_c, acc_q, a.q[SLOT].x, a.q[SLOT].w);
+      // the first reduction also sums Y^2
+      e_q[SLOT] = sq_diff(std::integral_constant<bool, SLOT == 0>{}, acc_q, a.q[SLOT].sx, a.q[SLOT].sw);
+    }
+  };
+  quantized(std::integral_constant<int, KIND1>{}, std::integral_constant<int, 0>{});
+  quantized(std::integral_constant<int, KIND2>{}, std::integral_constant<int, 1>{});
   p = wave_sum(p);
-  if (lane == 0) { s_red[0][wave] = e_i; s_red[1][wave] = e_f; s_red[2][wave] = p; }
+  if (lane == 0) { s_red[0][wave] = e_q[0]; s_red[1][wave] = e_q[1]; s_red[2][wave] = p; }
   __syncthreads();
   if (tid == 0) {
     const int out = bm * a.tiles_n + bn;
     double t[3] = {0.0, 0.0, 0.0};
     for (int q = 0; q < 3; ++q)
       for (int w = 0; w < NW; ++w) t[q] += s_red[q][w];   // fixed order
-    if (a.part_i) a.part_i[out] = t[0];
-    if (a.part_f) a.part_f[out] = t[1];
+    if (a.q[0].part) a.q[0].part[out] = t[0];
+    if (a.q[1].part) a.q[1].part[out] = t[1];
     a.part_p[out] = t[2];
   }
 }
@@ -385,26 +381,25 @@ int wa_gemm_blocks(int64_t M, int64_t N) {
 
 int launch_wa_gemm(const WaGemmParams& p, hipStream_t st) {
   if (p.K % 64 != 0) return MOFQ_ERR_UNSUPPORTED;
+  if (p.q[0].kind == WA_NONE) return MOFQ_ERR_INVALID_ARG;   // the first slot carries the Y^2 sum
   GemmArgs a{};
   a.x = static_cast<const uint16_t*>(p.x); a.ldx = p.ldx;
   a.w = static_cast<const uint16_t*>(p.w); a.ldw = p.ldw;
-  a.xi = p.xi; a.wi = p.wi; a.xf = p.xf; a.wf = p.wf;
-  a.xg = static_cast<const uint16_t*>(p.xg); a.wg = static_cast<const uint16_t*>(p.wg);
-  a.sx_i = p.sx_i; a.sw_i = p.sw_i; a.sx_f = p.sx_f; a.sw_f = p.sw_f;
+  for (int i = 0; i < 2; ++i) a.q[i] = QProd{p.q[i].x, p.q[i].w, p.q[i].sx, p.q[i].sw, p.q[i].part};
   a.w_per_channel = p.w_per_channel;
   a.M = static_cast<int32_t>(p.M); a.N = static_cast<int32_t>(p.N); a.K = static_cast<int32_t>(p.K);
   a.tiles_m = static_cast<int32_t>((p.M + TM - 1) / TM);
   a.tiles_n = static_cast<int32_t>((p.N + TN - 1) / TN);
-  a.part_i = p.part_i; a.part_f = p.part_f; a.part_p = p.part_p;
+  a.part_p = p.part_p;
   const dim3 grid(static_cast<unsigned>(wa_gemm_blocks(p.M, p.N)));
-  const bool di = p.xi != nullptr;
-  const int f8 = p.xg ? FP8_EXACT : (p.xf ? FP8_NATIVE : FP8_NONE);
-#define MOFQ_WA(DI, F8) \
-  if (di == DI && f8 == F8) hipLaunchKernelGGL((wa_gemm_kernel<DI, F8>), grid, dim3(NW * 64), 0, st, a);
-  if (!di && f8 == FP8_NONE) return MOFQ_ERR_INVALID_ARG;
-  MOFQ_WA(true, FP8_NONE) MOFQ_WA(true, FP8_NATIVE) MOFQ_WA(true, FP8_EXACT)
-  MOFQ_WA(false, FP8_NATIVE) MOFQ_WA(false, FP8_EXACT)
+  const int k1 = p.q[0].kind, k2 = p.q[1].kind;
+  bool launched = false;
+#define MOFQ_WA(A, B) \
+  if (k1 == (A) && k2 == (B)) { hipLaunchKernelGGL((wa_gemm_kernel<A, B>), grid, dim3(NW * 64), 0, st, a); launched = true; }
+  MOFQ_WA(WA_INT8, WA_GRID_BF16) MOFQ_WA(WA_INT8, WA_FP8) MOFQ_WA(WA_INT8, WA_NONE)
+  MOFQ_WA(WA_GRID_BF16, WA_NONE) MOFQ_WA(WA_FP8, WA_NONE) MOFQ_WA(WA_GRID_BF16, WA_GRID_BF16)
 #undef MOFQ_WA
+  if (!launched) return MOFQ_ERR_UNSUPPORTED;
   return hip_status(hipGetLastError());
 }
 
