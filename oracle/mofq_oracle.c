@@ -48,10 +48,10 @@
 #include <omp.h>
 #endif
 
-enum { ORC_INT4 = 0, ORC_FP4_E2M1 = 1, ORC_INT8 = 2, ORC_FP8_E4M3 = 3, ORC_FP4_E2M1_IEEE = 4 };
+enum { ORC_INT4 = 0, ORC_FP4_E2M1 = 1, ORC_INT8 = 2, ORC_FP8_E4M3 = 3, ORC_FP4_E2M1_IEEE = 4, ORC_FP8_E5M2 = 5 };
 enum { ORC_PER_TENSOR = 0, ORC_PER_CHANNEL = 1, ORC_PER_GROUP = 2 };
 
-#define ORC_NFMT 5
+#define ORC_NFMT 6
 
 /* ---- formats -------------------------------------------------------------- */
 
@@ -60,7 +60,7 @@ enum { ORC_PER_TENSOR = 0, ORC_PER_CHANNEL = 1, ORC_PER_GROUP = 2 };
 static const double E2M1_MAG[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
 
 int orc_is_int(int fmt) { return fmt == ORC_INT4 || fmt == ORC_INT8; }
-int orc_bits(int fmt) { return (fmt == ORC_INT8 || fmt == ORC_FP8_E4M3) ? 8 : 4; }
+int orc_bits(int fmt) { return (fmt == ORC_INT8 || fmt == ORC_FP8_E4M3 || fmt == ORC_FP8_E5M2) ? 8 : 4; }
 
 /* Largest magnitude the scale maps the (clipped) absmax onto. */
 double orc_qmax(int fmt) {
@@ -70,6 +70,7 @@ double orc_qmax(int fmt) {
     case ORC_INT8: return 127.0;
     case ORC_FP8_E4M3: return 448.0;
     case ORC_FP4_E2M1_IEEE: return 3.0;
+    case ORC_FP8_E5M2: return 57344.0;   /* 1.75 * 2^15, the largest finite value */
   }
   return NAN;
 }
@@ -80,6 +81,7 @@ static int fp_num_mag(int fmt) {
     case ORC_FP4_E2M1: return 8;
     case ORC_FP4_E2M1_IEEE: return 6;   /* Table 1, row "w/ NaN&Inf": 0 .. 3 */
     case ORC_FP8_E4M3: return 127;      /* 0x00 .. 0x7E; 0x7F is NaN */
+    case ORC_FP8_E5M2: return 124;      /* 0x00 .. 0x7B; 0x7C is Inf, 0x7D..0x7F NaN */
   }
   return 0;
 }
@@ -87,7 +89,10 @@ static int fp_num_mag(int fmt) {
 /* Value of a code.  INT codes are two's complement in 4 or 8 bits.  E4M3 is
  * sign / 4 exponent bits (bias 7) / 3 mantissa bits: exponent field 0 is
  * subnormal m*2^-9, otherwise (1+m/8)*2^(e-7); there is no infinity, and the
- * single pattern with all exponent and mantissa bits set is NaN. */
+ * single pattern with all exponent and mantissa bits set is NaN.  E5M2 (the other
+ * 8-bit option named in Section 2.2) keeps the IEEE layout: sign / 5 exponent bits
+ * (bias 15) / 2 mantissa bits, exponent field 0 subnormal m*2^-16, all-ones exponent
+ * Inf (m = 0) or NaN. */
 double orc_decode(int fmt, int code) {
   switch (fmt) {
     case ORC_INT4: {
@@ -113,6 +118,14 @@ double orc_decode(int fmt, int code) {
       if (e == 15 && m == 7) return NAN;
       if (e == 0) mag = ldexp((double)m, -9);
       else mag = ldexp(1.0 + (double)m / 8.0, e - 7);
+      return (code & 0x80) ? -mag : mag;
+    }
+    case ORC_FP8_E5M2: {
+      int e = (code >> 2) & 0x1F, m = code & 3;
+      double mag;
+      if (e == 31) mag = (m == 0) ? INFINITY : NAN;
+      else if (e == 0) mag = ldexp((double)m, -16);
+      else mag = ldexp(1.0 + (double)m / 4.0, e - 15);
       return (code & 0x80) ? -mag : mag;
     }
   }

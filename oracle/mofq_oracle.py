@@ -18,7 +18,7 @@ from typing import Optional, Sequence
 
 import numpy as np
 
-INT4, FP4_E2M1, INT8, FP8_E4M3, FP4_E2M1_IEEE = 0, 1, 2, 3, 4
+INT4, FP4_E2M1, INT8, FP8_E4M3, FP4_E2M1_IEEE, FP8_E5M2 = 0, 1, 2, 3, 4, 5
 PER_TENSOR, PER_CHANNEL, PER_GROUP = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -116,7 +116,7 @@ def decode_array(fmt: int, codes: np.ndarray) -> np.ndarray:
 
 
 def bits(fmt: int) -> int:
-    return 8 if fmt in (INT8, FP8_E4M3) else 4
+    return 8 if fmt in (INT8, FP8_E4M3, FP8_E5M2) else 4
 
 
 def qmax(fmt: int) -> float:

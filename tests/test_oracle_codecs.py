@@ -10,6 +10,7 @@ import numpy as np
 import pytest
 import torch
 
+import mofq_inputs as mi
 from oracle import mofq_oracle as orc
 
 FP4, FP4I, FP8, I4, I8 = orc.FP4_E2M1, orc.FP4_E2M1_IEEE, orc.FP8_E4M3, orc.INT4, orc.INT8
@@ -217,3 +218,58 @@ def test_scale_formula():
         assert orc.scale(1e-44, 1.0, fmt) == 1.0
         assert orc.scale(1e-9, 1.0, fmt, True) == 1.0     # rounds to fp16 zero
         assert orc.scale(1e7, 1.0, I4, True) == 65504.0
+
+
+# ---- E5M2, the other 8-bit floating-point option of Section 2.2 ---------------------------
+
+FP8B = orc.FP8_E5M2
+
+
+def test_e5m2_decode_matches_torch_cast():
+    """All 256 E5M2 bit patterns against torch's own float8_e5m2 decoding (IEEE layout:
+    infinities at 0x7C / 0xFC, NaN above them)."""
+    codes = torch.arange(256, dtype=torch.int32).to(torch.uint8)
+    ref = codes.view(torch.float8_e5m2).to(torch.float32).numpy()
+    for c in range(256):
+        got = orc.decode(FP8B, c)
+        if np.isnan(ref[c]):
+            assert math.isnan(got) and (c & 0x7F) > 0x7C
+        else:
+            assert got == float(ref[c]) and math.copysign(1, got) == math.copysign(1, ref[c]), c
+    assert orc.decode(FP8B, 0x7B) == 57344.0 == orc.qmax(FP8B)
+    assert orc.decode(FP8B, 0x01) == 2.0 ** -16 and orc.decode(FP8B, 0x04) == 2.0 ** -14
+    assert orc.bits(FP8B) == 8
+
+
+def test_e5m2_encode_matches_torch_cast_and_saturates():
+    """torch rounds fp32 to float8_e5m2 to nearest even; inside the finite range the
+    oracle must agree bit for bit; beyond it the oracle saturates at +-57344 (no Inf)."""
+    rng = np.random.default_rng(5)
+    t = np.concatenate([
+        rng.standard_normal(200000).astype(np.float32) * 1000,
+        rng.standard_normal(100000).astype(np.float32) * 1e-4,
+        (rng.random(100000).astype(np.float32) * 2 - 1) * 57344,
+        (rng.random(50000).astype(np.float32) * 2 - 1) * 2.0 ** -14,
+        np.array([orc.decode(FP8B, c) for c in range(0x7C)], dtype=np.float32),
+        np.array([0.5 * (orc.decode(FP8B, c) + orc.decode(FP8B, c + 1)) for c in range(0x7B)], dtype=np.float32),
+    ])
+    t = np.concatenate([t, -t])
+    # torch rounds values at or above the midpoint between 57344 and 65536 to Inf
+    t = t[np.abs(t) < 61440].astype(np.float32)
+    ref = torch.from_numpy(t).to(torch.float8_e5m2).view(torch.uint8).numpy()
+    assert np.array_equal(orc.encode_array(FP8B, t), ref)
+    for big in (61440.0, 65504.0, 1e9, 3.4e38):
+        assert orc.encode(FP8B, np.float32(big)) == 0x7B and orc.encode(FP8B, np.float32(-big)) == 0xFB
+    for c in range(256):
+        if (c & 0x7F) < 0x7C:
+            assert orc.encode(FP8B, np.float32(orc.decode(FP8B, c))) == c
+
+
+def test_e5m2_trades_precision_for_range_against_e4m3():
+    """Two mantissa bits instead of three: on Gaussian weights (no range problem) the
+    E5M2 tensor error is about 4x the E4M3 one (step twice as coarse)."""
+    w = mi.to_f32_numpy(mi.llama_like_weight(32, 1024, seed=21))
+    one = np.ones(1, dtype=np.float32)
+    r = orc.quantize(w, FP8B, orc.PER_CHANNEL, one).err / orc.quantize(w, FP8, orc.PER_CHANNEL, one).err
+    assert 3.0 < r < 5.5
+
