@@ -60,7 +60,7 @@ def parse():
     ap.add_argument("--model", default="7b", choices=["7b", "65b"],
                     help="65b = configs[4]: 560 linears, 129.5 GB of fp16 weights resident in HBM")
     ap.add_argument("--workload", default="w4_channel",
-                    choices=["w4_channel", "w4_group128", "w8a8", "w4a16_output", "k1_hbm"])
+                    choices=["w4_channel", "w4_group128", "w8a8", "w4a16_output", "k1_hbm", "fp4_variants"])
     ap.add_argument("--fp8-unit", action="store_true",
                     help="w8a8: E4M3 code product on the fp8 matrix cores (not within 1e-5 of the exact sum)")
     ap.add_argument("--blocks", type=int, default=0, help="debug: use only the first N blocks")
@@ -269,6 +269,50 @@ def run_k1_hbm(args, dev):
     }))
 
 
+def run_fp4_variants(args, shapes, dev):
+    """Section 4.2 in kind, on the synthetic 7B-shaped set: tensor error of the redesigned
+    FP4 (Table 1, without NaN/Inf) against the IEEE-aligned FP4, per-channel absmax scales,
+    and how many layers prefer each FP4 over INT4."""
+    import torch
+
+    import mofq_inputs as mi
+    from paper_2305_12356_amd import binding as mq
+
+    cfg = mq.Cfg(mq.PER_CHANNEL, mi.clip_ratios(1))
+    sets = {"redesigned": [mq.INT4, mq.FP4_E2M1], "ieee": [mq.INT4, mq.FP4_E2M1_IEEE]}
+    results = {k: mq.alloc_result(dev, len(shapes)) for k in sets}
+    stream = torch.cuda.current_stream()
+    ws = out = None
+    t0 = time.perf_counter()
+    for i, (b, name, o, n) in enumerate(shapes):
+        w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, mi.LINEAR_NAMES.index(name)), device=dev)
+        need = mq.workspace_bytes(w, None, 2, mq.ERR_TENSOR, cfg)
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        out = mq.alloc_qbuffers(o, n, 4, cfg, dev)
+        for k, cands in sets.items():
+            mq.select_layer(w, None, cands, mq.ERR_TENSOR, cfg, out, None, results[k][i], ws, stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    res = {k: mq.read_results(v) for k, v in results.items()}
+    e_int = sum(r.err[0] for r in res["redesigned"])
+    e_new = sum(r.err[1] for r in res["redesigned"])
+    e_ieee = sum(r.err[1] for r in res["ieee"])
+    per_layer = [r1.err[1] / r2.err[1] for r1, r2 in zip(res["redesigned"], res["ieee"])]
+    print(json.dumps({
+        "metric": "tensor error of the redesigned FP4 relative to the IEEE-aligned FP4 (synthetic 7B-shaped weights)",
+        "value": e_new / e_ieee, "unit": "ratio", "n_gpus": 1, "steps": 1, "warmup": 0,
+        "ms_per_step": elapsed * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 decisions, f64 errors", "data": "synthetic",
+        "config": {"workload": f"{len(shapes)} linears of the LLaMA-7B shape, fp16, per-channel absmax scales (one candidate)",
+                   "error_reduction_percent": 100.0 * (1.0 - e_new / e_ieee),
+                   "per_layer_ratio_min_max": [min(per_layer), max(per_layer)],
+                   "int4_error_relative_to_redesigned_fp4": e_int / e_new,
+                   "layers_preferring_fp4_over_int4_percent": {
+                       k: 100.0 * sum(1 for r in v if r.best == 1) / len(v) for k, v in res.items()}},
+    }))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -296,6 +340,9 @@ def main():
         return
     if args.workload == "k1_hbm":
         run_k1_hbm(args, dev)
+        return
+    if args.workload == "fp4_variants":
+        run_fp4_variants(args, shapes, dev)
         return
     group = args.workload == "w4_group128"
     n_clip = N_CLIP_GROUP if group else N_CLIP

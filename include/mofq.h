@@ -55,7 +55,16 @@ typedef enum {
   MOFQ_INT4 = 0,
   MOFQ_FP4_E2M1 = 1,
   MOFQ_INT8 = 2,
-  MOFQ_FP8_E4M3 = 3
+  MOFQ_FP8_E4M3 = 3,
+  /* The IEEE-aligned FP4 of Table 1 (row "w/ NaN&Inf"): the same codes 0..5 (0 .. 3),
+   * codes 6 and 7 are Inf / NaN and never produced; values beyond 3 saturate at 3.
+   * The comparison format of Section 4.2. */
+  MOFQ_FP4_E2M1_IEEE = 4,
+  /* The other 8-bit floating-point option named in Section 2.2: sign / 5 exponent bits
+   * (bias 15) / 2 mantissa bits, subnormals m*2^-16, largest finite value 57344;
+   * saturating (Inf / NaN codes are never produced).  Scored and emitted like any
+   * other format; the W8A8 layer-output metric takes only MOFQ_INT8 / MOFQ_FP8_E4M3. */
+  MOFQ_FP8_E5M2 = 5
 } mofq_format_t;
 
 typedef enum { MOFQ_F32 = 0, MOFQ_F16 = 1, MOFQ_BF16 = 2 } mofq_dtype_t;

@@ -14,7 +14,7 @@ from typing import Optional, Sequence
 import numpy as np
 import torch
 
-INT4, FP4_E2M1, INT8, FP8_E4M3 = 0, 1, 2, 3
+INT4, FP4_E2M1, INT8, FP8_E4M3, FP4_E2M1_IEEE, FP8_E5M2 = 0, 1, 2, 3, 4, 5
 F32, F16, BF16 = 0, 1, 2
 PER_TENSOR, PER_CHANNEL, PER_GROUP = 0, 1, 2
 ERR_TENSOR, ERR_LAYER_OUTPUT, ERR_LAYER_OUTPUT_FP8_UNIT, ERR_LAYER_OUTPUT_W_ONLY = 0, 1, 2, 3

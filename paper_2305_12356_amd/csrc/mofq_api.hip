@@ -11,8 +11,13 @@ namespace {
 
 constexpr size_t kAlign = 256;
 
-bool is4(int f) { return f == MOFQ_INT4 || f == MOFQ_FP4_E2M1; }
-bool is8(int f) { return f == MOFQ_INT8 || f == MOFQ_FP8_E4M3; }
+bool is4(int f) { return f == MOFQ_INT4 || f == MOFQ_FP4_E2M1 || f == MOFQ_FP4_E2M1_IEEE; }
+bool is8(int f) { return f == MOFQ_INT8 || f == MOFQ_FP8_E4M3 || f == MOFQ_FP8_E5M2; }
+// format pairs the search kernels score in one launch (one read of the tensor)
+bool paired(int a, int b) {
+  return (a == MOFQ_INT4 && b == MOFQ_FP4_E2M1) || (a == MOFQ_FP4_E2M1 && b == MOFQ_INT4) ||
+         (a == MOFQ_INT8 && b == MOFQ_FP8_E4M3) || (a == MOFQ_FP8_E4M3 && b == MOFQ_INT8);
+}
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int check_tensor(const mofq_tensor_t* t) {
@@ -104,7 +109,7 @@ int sweep_candidates(const mofq_tensor_t* t, const int32_t* cand, int n_cand,
   while (c0 < n_cand) {
     // two different formats share one launch (one read of the tensor); a repeated
     // format is scored on its own
-    const int n = (c0 + 1 < n_cand && cand[c0] != cand[c0 + 1]) ? 2 : 1;
+    const int n = (c0 + 1 < n_cand && paired(cand[c0], cand[c0 + 1])) ? 2 : 1;
     SweepParams p{};
     p.w = t->data;
     p.dtype = t->dtype;
@@ -167,7 +172,7 @@ int check_wa(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand
   if (rc) return rc;
   if (x->cols != w->cols) return MOFQ_ERR_INVALID_ARG;
   for (int c = 0; c < n_cand; ++c)
-    if (!is8(cand[c])) return MOFQ_ERR_UNSUPPORTED;          // low-bit matmul units are 8-bit
+    if (cand[c] != MOFQ_INT8 && cand[c] != MOFQ_FP8_E4M3) return MOFQ_ERR_UNSUPPORTED;   // the low-bit matmul units
   if (w->dtype != MOFQ_BF16 || x->dtype != MOFQ_BF16) return MOFQ_ERR_UNSUPPORTED;
   if (w_cfg->n_clip != 1 || w_cfg->scale_dtype != MOFQ_F32) return MOFQ_ERR_UNSUPPORTED;
   if (w_cfg->gran != MOFQ_PER_TENSOR && w_cfg->gran != MOFQ_PER_CHANNEL) return MOFQ_ERR_UNSUPPORTED;

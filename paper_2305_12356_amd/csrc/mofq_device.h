@@ -135,6 +135,38 @@ template <> struct Codec<MOFQ_FP8_E4M3> {
   }
 };
 
+// Table 1, row "w/ NaN&Inf": the same grid up to 3, saturating there (codes 6 and 7 are
+// Inf / NaN and never produced).
+template <> struct Codec<MOFQ_FP4_E2M1_IEEE> {
+  static constexpr float QMAX = 3.0f;
+  static constexpr bool IS_INT = false;
+  static constexpr int BITS = 4;
+  MOFQ_DEV static float mag(float at) { return Codec<MOFQ_FP4_E2M1>::mag(__builtin_fminf(at, 3.0f)); }
+  MOFQ_DEV static float grid(float t) { return __builtin_copysignf(mag(__builtin_fabsf(t)), t); }
+  MOFQ_DEV static uint32_t code(float t) { return Codec<MOFQ_FP4_E2M1>::code(med3(t, -3.0f, 3.0f)); }
+};
+
+template <> struct Codec<MOFQ_FP8_E5M2> {
+  static constexpr float QMAX = 57344.0f;
+  static constexpr bool IS_INT = false;
+  static constexpr int BITS = 8;
+  // normal (1+m/4)*2^(e-15), e = 1..30 (max 1.75*2^15 = 57344); subnormal m*2^-16
+  MOFQ_DEV static float mag(float at) {
+    const float c = __builtin_fminf(at, 57344.0f);
+    const float a = __builtin_fmaxf(c, 0x1p-14f);
+    const float m = u2f((f2u(a) & 0x7F800000u) + 0x0AC00000u);  // 1.5 * 2^(e+21)
+    return (c + m) - m;
+  }
+  MOFQ_DEV static float grid(float t) { return __builtin_copysignf(mag(__builtin_fabsf(t)), t); }
+  MOFQ_DEV static uint32_t code(float t) {
+    const float g = mag(__builtin_fabsf(t));
+    const uint32_t normal = (f2u(g) >> 21) - 448u;                // ((e+15) << 2) | mantissa
+    const uint32_t sub = static_cast<uint32_t>(g * 65536.0f);     // m of m*2^-16
+    const uint32_t m = (g >= 0x1p-14f) ? normal : sub;
+    return m | ((f2u(t) >> 24) & 0x80u);
+  }
+};
+
 // ---- scale of a unit ----------------------------------------------------------
 
 // Nearest fp16 (ties to even, fp16 subnormals kept) clamped to 65504, as fp32.

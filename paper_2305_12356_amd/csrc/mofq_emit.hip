@@ -159,6 +159,8 @@ MOFQ_DEV void emit_chunk(const EmitArgs& a, int fmt, const float* scale, int64_t
     case MOFQ_INT4: encode8<MOFQ_INT4>(v, inv_s, words); break;
     case MOFQ_FP4_E2M1: encode8<MOFQ_FP4_E2M1>(v, inv_s, words); break;
     case MOFQ_INT8: encode8<MOFQ_INT8>(v, inv_s, words); break;
+    case MOFQ_FP4_E2M1_IEEE: encode8<MOFQ_FP4_E2M1_IEEE>(v, inv_s, words); break;
+    case MOFQ_FP8_E5M2: encode8<MOFQ_FP8_E5M2>(v, inv_s, words); break;
     default: encode8<MOFQ_FP8_E4M3>(v, inv_s, words); break;
   }
   const int64_t e0 = row * a.cols + col;   // dense output rows
@@ -172,12 +174,14 @@ MOFQ_DEV void emit_chunk(const EmitArgs& a, int fmt, const float* scale, int64_t
         case MOFQ_INT4: g0 = Codec<MOFQ_INT4>::grid(v[2 * i] * inv_s); g1 = Codec<MOFQ_INT4>::grid(v[2 * i + 1] * inv_s); break;
         case MOFQ_FP4_E2M1: g0 = Codec<MOFQ_FP4_E2M1>::grid(v[2 * i] * inv_s); g1 = Codec<MOFQ_FP4_E2M1>::grid(v[2 * i + 1] * inv_s); break;
         case MOFQ_INT8: g0 = Codec<MOFQ_INT8>::grid(v[2 * i] * inv_s); g1 = Codec<MOFQ_INT8>::grid(v[2 * i + 1] * inv_s); break;
+        case MOFQ_FP4_E2M1_IEEE: g0 = Codec<MOFQ_FP4_E2M1_IEEE>::grid(v[2 * i] * inv_s); g1 = Codec<MOFQ_FP4_E2M1_IEEE>::grid(v[2 * i + 1] * inv_s); break;
+        case MOFQ_FP8_E5M2: g0 = Codec<MOFQ_FP8_E5M2>::grid(v[2 * i] * inv_s); g1 = Codec<MOFQ_FP8_E5M2>::grid(v[2 * i + 1] * inv_s); break;
         default: g0 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i] * inv_s); g1 = Codec<MOFQ_FP8_E4M3>::grid(v[2 * i + 1] * inv_s); break;
       }
       o[i] = (f2u(g0) >> 16) | (f2u(g1) & 0xFFFF0000u);
     }
     reinterpret_cast<u32x4*>(a.out.codes)[e0 / 8] = o;
-  } else if (fmt == MOFQ_INT4 || fmt == MOFQ_FP4_E2M1) {
+  } else if (fmt == MOFQ_INT4 || fmt == MOFQ_FP4_E2M1 || fmt == MOFQ_FP4_E2M1_IEEE) {
     static_cast<uint32_t*>(a.out.codes)[e0 / 8] = words[0];
   } else {
     u32x2 o;

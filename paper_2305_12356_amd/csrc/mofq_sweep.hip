@@ -66,6 +66,10 @@ template <int FMT> MOFQ_DEV f32x2 grid2(float t0, float t1, uint32_t& carry) {
   if constexpr (FMT == MOFQ_FP4_E2M1) {
     carry = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(carry, t0, t1, 1.0f, 0);
     g = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(carry, 1.0f, 0);
+  } else if constexpr (FMT == MOFQ_FP4_E2M1_IEEE) {
+    // the same grid below 3: clamp, then the same convert
+    carry = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(carry, med3(t0, -3.0f, 3.0f), med3(t1, -3.0f, 3.0f), 1.0f, 0);
+    g = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(carry, 1.0f, 0);
   } else if constexpr (FMT == MOFQ_FP8_E4M3) {
     const int p = __builtin_amdgcn_cvt_pk_fp8_f32(med3(t0, -448.0f, 448.0f), med3(t1, -448.0f, 448.0f), 0, false);
     g = __builtin_amdgcn_cvt_pk_f32_fp8(p, false);
@@ -829,6 +833,8 @@ int launch_fmt(const SweepParams& p, const SweepArgs& a, hipStream_t st) {
   MOFQ_F(MOFQ_FP4_E2M1, -1)
   MOFQ_F(MOFQ_INT8, -1)
   MOFQ_F(MOFQ_FP8_E4M3, -1)
+  MOFQ_F(MOFQ_FP4_E2M1_IEEE, -1)
+  MOFQ_F(MOFQ_FP8_E5M2, -1)
   MOFQ_F(MOFQ_INT4, MOFQ_FP4_E2M1)   // pairs come in (INT, FP) order; the caller maps slots
   MOFQ_F(MOFQ_INT8, MOFQ_FP8_E4M3)
 #undef MOFQ_F

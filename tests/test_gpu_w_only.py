@@ -134,6 +134,30 @@ def test_group_wise_other_dtypes_and_formats(mq, dtype):
     check_tensor(mq, w, [orc.FP4_E2M1], orc.PER_GROUP, mi.clip_ratios(9), 128, True, label="group-single")
 
 
+@pytest.mark.parametrize("cands", [[orc.FP4_E2M1_IEEE], [orc.INT4, orc.FP4_E2M1_IEEE],
+                                   [orc.FP4_E2M1_IEEE, orc.FP4_E2M1], [orc.FP8_E5M2],
+                                   [orc.INT8, orc.FP8_E5M2], [orc.FP8_E5M2, orc.FP8_E4M3]])
+def test_ieee_fp4_and_e5m2_grids(mq, cands):
+    """The IEEE-aligned FP4 of Table 1 (saturating at 3) and FP8-E5M2: every granularity,
+    alone and against the other formats of their bit-width (such pairs are scored in
+    separate launches)."""
+    w = mi.llama_like_weight(9, 2048, seed=50, device=DEV, outlier_frac=2e-3)
+    check_tensor(mq, w, cands, orc.PER_CHANNEL, mi.clip_ratios(20), label="grids-channel")
+    check_tensor(mq, w, cands, orc.PER_CHANNEL, mi.clip_ratios(1), label="grids-absmax")
+    check_tensor(mq, w, cands, orc.PER_GROUP, mi.clip_ratios(10), 128, True, label="grids-group")
+    wb = mi.llama_like_weight(40, 512, seed=51, dtype=torch.bfloat16, device=DEV)
+    check_tensor(mq, wb, cands, orc.PER_TENSOR, mi.clip_ratios(3), label="grids-tensor")
+    # values far outside the grid, subnormals of the 8-bit format, signed zeros
+    e = torch.zeros(4, 256, dtype=torch.float32)
+    e[0] = torch.linspace(-70000, 70000, 256)
+    e[1] = torch.linspace(-4, 4, 256) * 2.0 ** -15
+    e[2, ::2] = -0.0
+    e[2, 1] = 1.0
+    e[3] = torch.linspace(-3.6, 3.6, 256)
+    check_tensor(mq, e.to(DEV), cands, orc.PER_TENSOR, mi.clip_ratios(1), label="grids-edge")
+    check_tensor(mq, e.to(DEV), cands, orc.PER_CHANNEL, mi.clip_ratios(2), label="grids-edge-channel")
+
+
 @pytest.mark.parametrize("fmt_pair", [(orc.INT8, orc.FP8_E4M3), (orc.INT4, orc.FP4_E2M1)])
 def test_per_tensor(mq, fmt_pair):
     x = mi.activations(300, 1024, seed=10, device=DEV)

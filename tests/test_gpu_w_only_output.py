@@ -97,6 +97,8 @@ def test_single_candidate_and_eight_bit_weights(mq):
     w = mi.llama_like_weight(256, 512, seed=87, dtype=torch.bfloat16, device=DEV)
     check_layer(mq, x, w, [FP4], orc.PER_CHANNEL, mi.clip_ratios(4), "single")
     check_layer(mq, x, w, [I8, FP8], orc.PER_CHANNEL, mi.clip_ratios(1), "w8a16")
+    check_layer(mq, x, w, [orc.FP4_E2M1_IEEE, FP4], orc.PER_CHANNEL, mi.clip_ratios(1), "ieee-vs-redesigned")
+    check_layer(mq, x, w, [orc.FP8_E5M2, FP8], orc.PER_TENSOR, mi.clip_ratios(1), "e5m2-vs-e4m3")
 
 
 def test_llama_shape_block(mq):
