@@ -339,3 +339,50 @@ def select_layer_w_only_output(x, w, candidates: Sequence[int], w_gran: int = PE
     best = select(errs)
     return Selected(best, errs, energy, qws[best], None, [(None, q) for q in qws])
 
+
+@dataclass
+class UnitSelected:
+    unit_format: np.ndarray  # [units] index into candidates, per scale unit
+    codes: np.ndarray        # [rows, cols] codes, each unit in its own format
+    scale: np.ndarray        # [units]
+    clip_idx: np.ndarray     # [units]
+    unit_err: np.ndarray     # [units] error of the chosen format
+    err: float               # sum over units, unit order
+    errs: list               # tensor error of each candidate used everywhere (layer-wise view)
+    per_candidate: list      # Quantized per candidate
+
+
+def select_units(w, candidates: Sequence[int], gran: int, clip, group: int = 0,
+                 scale_f16: bool = False, threads: int = 0) -> UnitSelected:
+    """Format select at the granularity of the scale unit (channel or group) instead of
+    the layer -- the extension Section 4.1 leaves open and the conclusion lists as future
+    work: every unit takes the candidate with its own smallest error, Algorithm 1's rule
+    applied per unit (candidates in list order, strictly smaller wins)."""
+    w = _f32c(w)
+    if gran == PER_TENSOR:
+        raise ValueError("a per-tensor unit is the layer itself")
+    qs = [quantize(w, f, gran, clip, group, scale_f16, threads=threads) for f in candidates]
+    units = qs[0].unit_err.shape[0]
+    pick = np.zeros(units, dtype=np.uint8)
+    best = qs[0].unit_err.copy()
+    for c in range(1, len(qs)):
+        better = qs[c].unit_err < best
+        pick[better] = c
+        best[better] = qs[c].unit_err[better]
+    rows, cols = w.shape
+    # unit index of every element
+    if gran == PER_CHANNEL:
+        unit_of = np.repeat(np.arange(rows)[:, None], cols, axis=1)
+    else:
+        unit_of = np.arange(rows)[:, None] * (cols // group) + (np.arange(cols) // group)[None, :]
+    codes = np.zeros((rows, cols), dtype=np.uint8)
+    scale = np.zeros(units, dtype=np.float32)
+    idx = np.zeros(units, dtype=np.int32)
+    for c, q in enumerate(qs):
+        m = pick == c
+        scale[m] = q.scale[m]
+        idx[m] = q.clip_idx[m]
+        em = m[unit_of]
+        codes[em] = q.codes[em]
+    return UnitSelected(pick, codes, scale, idx, best, tensor_err(best), [q.err for q in qs], qs)
+
