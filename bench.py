@@ -60,7 +60,7 @@ def parse():
     ap.add_argument("--model", default="7b", choices=["7b", "65b"],
                     help="65b = configs[4]: 560 linears, 129.5 GB of fp16 weights resident in HBM")
     ap.add_argument("--workload", default="w4_channel",
-                    choices=["w4_channel", "w4_group128", "w8a8", "w4a16_output", "k1_hbm", "fp4_variants"])
+                    choices=["w4_channel", "w4_group128", "w8a8", "w4a16_output", "k1_hbm", "fp4_variants", "w4_units"])
     ap.add_argument("--fp8-unit", action="store_true",
                     help="w8a8: E4M3 code product on the fp8 matrix cores (not within 1e-5 of the exact sum)")
     ap.add_argument("--blocks", type=int, default=0, help="debug: use only the first N blocks")
@@ -313,6 +313,62 @@ def run_fp4_variants(args, shapes, dev):
     }))
 
 
+def run_w4_units(args, shapes, dev):
+    """Per-unit format select (finer than the layer) on the 7B-shaped set, group 128 with
+    fp16 scales and 50 clip ratios: time, and the tensor error of the mixed assignment
+    against the layer-wise choice."""
+    import torch
+
+    import mofq_inputs as mi
+    from paper_2305_12356_amd import binding as mq
+
+    clip = mi.clip_ratios(N_CLIP_GROUP)
+    cfg = mq.Cfg(mq.PER_GROUP, clip, GROUP, True)
+    cands = [mq.INT4, mq.FP4_E2M1]
+    weights, outs, tags = [], [], []
+    results = mq.alloc_result(dev, len(shapes))
+    mixed = torch.zeros(len(shapes), dtype=torch.float64, device=dev)
+    ws_bytes = 0
+    for b, name, o, n in shapes:
+        w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, mi.LINEAR_NAMES.index(name)), device=dev)
+        weights.append(w)
+        outs.append(mq.alloc_qbuffers(o, n, 4, cfg, dev))
+        tags.append(torch.empty(o * (n // GROUP), dtype=torch.uint8, device=dev))
+        ws_bytes = max(ws_bytes, mq.select_units_workspace_bytes(w, 2, cfg))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for i, w in enumerate(weights):
+            mq.select_units(w, cands, cfg, outs[i], tags[i], results[i], mixed[i:i + 1], ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    res = mq.read_results(results)
+    layer = sum(min(r.err[0], r.err[1]) for r in res)
+    mix = float(mixed.sum().item())
+    fp_units = sum(int(t.sum().item()) for t in tags)
+    n_units = sum(t.numel() for t in tags)
+    n_elems = sum(o * n for _, _, o, n in shapes)
+    print(json.dumps({
+        "metric": "weight-elems x candidates scored/sec, per-unit format select (group 128)",
+        "value": n_elems * N_CLIP_GROUP * N_FMT / (elapsed / args.steps), "unit": "elem*cand/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 decisions, f64 errors", "data": "synthetic",
+        "config": {"workload": f"{len(shapes)} linears of the LLaMA-7B shape, fp16, group 128, fp16 scales, 50 clip "
+                               "ratios, INT4 vs FP4-E2M1 chosen per group",
+                   "mixed_error_relative_to_layer_wise": mix / layer,
+                   "fp4_units_percent": 100.0 * fp_units / n_units},
+    }))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -343,6 +399,9 @@ def main():
         return
     if args.workload == "fp4_variants":
         run_fp4_variants(args, shapes, dev)
+        return
+    if args.workload == "w4_units":
+        run_w4_units(args, shapes, dev)
         return
     group = args.workload == "w4_group128"
     n_clip = N_CLIP_GROUP if group else N_CLIP

@@ -194,6 +194,30 @@ int mofq_select_layer(const mofq_tensor_t* w, const mofq_tensor_t* x,
                       void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Format select at a finer granularity than the layer (Section 4.1 leaves it open, the
+ * conclusion lists channel-wise / block-wise selection as future work): weight-only,
+ * tensor error; every scale unit of w_cfg (a channel or a group; not per-tensor) takes
+ * the candidate with its own smallest error -- Algorithm 1's rule per unit, candidates
+ * in list order, strictly smaller wins.
+ *   unit_format : device, [units] bytes; receives the index into candidates[] per unit.
+ *   w_out       : codes (each unit in its own format; all candidates share the bit
+ *                 width, so the layout is that of mofq_quantize), scales, clip indices
+ *                 and unit errors of the chosen formats.
+ *   result      : device; err[c] = tensor error with candidate c used everywhere and
+ *                 best = the layer-wise choice, exactly as mofq_select_layer reports.
+ *   mixed_err   : device, one double; the tensor error of the mixed assignment (the sum
+ *                 of the per-unit minima, never above err[best]).
+ * Workspace: mofq_workspace_bytes(w, NULL, n_candidates, MOFQ_ERR_TENSOR, w_cfg) plus
+ * 8 bytes per unit, i.e. mofq_select_units_workspace_bytes().
+ */
+int mofq_select_units(const mofq_tensor_t* w, const int32_t* candidates, int32_t n_candidates,
+                      const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
+                      uint8_t* unit_format, mofq_result_t* result, double* mixed_err,
+                      void* ws, size_t ws_bytes, void* stream);
+size_t mofq_select_units_workspace_bytes(const mofq_tensor_t* w, int32_t n_candidates,
+                                         const mofq_scale_cfg_t* w_cfg);
+
+/*
  * mofq_select_layer with two caller-owned hipEvent_t (passed as void*, either may
  * be NULL) recorded on `stream` immediately before and after the error-scoring
  * kernels (the scale search for the tensor metric, the matrix products for the

@@ -76,6 +76,11 @@ def _load():
     L.mofq_workspace_bytes.restype = C.c_size_t
     L.mofq_workspace_bytes.argtypes = [C.POINTER(TensorDesc), C.POINTER(TensorDesc), C.c_int32,
                                        C.c_int32, C.POINTER(ScaleCfg)]
+    L.mofq_select_units.restype = C.c_int
+    L.mofq_select_units.argtypes = [C.POINTER(TensorDesc), C.POINTER(C.c_int32), C.c_int32,
+                                    C.POINTER(ScaleCfg), C.POINTER(QOut), vp, vp, vp, vp, C.c_size_t, vp]
+    L.mofq_select_units_workspace_bytes.restype = C.c_size_t
+    L.mofq_select_units_workspace_bytes.argtypes = [C.POINTER(TensorDesc), C.c_int32, C.POINTER(ScaleCfg)]
     L.mofq_num_units.restype = C.c_int64
     L.mofq_num_units.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32]
     L.mofq_status_string.restype = C.c_char_p
@@ -220,6 +225,26 @@ def select_layer(w: torch.Tensor, x: Optional[torch.Tensor], candidates: Sequenc
         rc = _lib.mofq_select_layer_timed(*args, _event_handle(ev_begin), _event_handle(ev_end))
     if rc != 0:
         raise MofqError(rc, "mofq_select_layer")
+
+
+def select_units_workspace_bytes(w: torch.Tensor, n_candidates: int, cfg: Cfg) -> int:
+    wd = tensor_desc(w)
+    return int(_lib.mofq_select_units_workspace_bytes(C.byref(wd), n_candidates, C.byref(cfg.c)))
+
+
+def select_units(w: torch.Tensor, candidates: Sequence[int], cfg: Cfg, w_out: QBuffers,
+                 unit_format: torch.Tensor, result: torch.Tensor, mixed_err: torch.Tensor,
+                 ws: torch.Tensor, stream=None) -> None:
+    """mofq_select_units: per-unit format select (weight-only, tensor error); enqueue.
+    `unit_format` is a device uint8 tensor [units], `mixed_err` a device float64 scalar."""
+    wd = tensor_desc(w)
+    cand = (C.c_int32 * len(candidates))(*candidates)
+    woc = w_out.c()
+    rc = _lib.mofq_select_units(C.byref(wd), cand, len(candidates), C.byref(cfg.c), C.byref(woc),
+                                _ptr(unit_format), _ptr(result), _ptr(mixed_err), _ptr(ws),
+                                ws.numel() * ws.element_size(), _stream_handle(stream))
+    if rc != 0:
+        raise MofqError(rc, "mofq_select_units")
 
 
 def alloc_result(device, n: int = 1) -> torch.Tensor:

@@ -494,6 +494,78 @@ int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, i
   return MOFQ_ERR_INVALID_ARG;
 }
 
+size_t mofq_select_units_workspace_bytes(const mofq_tensor_t* w, int32_t n_candidates,
+                                         const mofq_scale_cfg_t* w_cfg) {
+  const size_t base = mofq_workspace_bytes(w, nullptr, n_candidates, MOFQ_ERR_TENSOR, w_cfg);
+  if (!base || w_cfg->gran == MOFQ_PER_TENSOR) return 0;
+  const int64_t units = mofq_num_units(w->rows, w->cols, w_cfg->gran, w_cfg->group_size);
+  return base + (static_cast<size_t>(units) * sizeof(double) + kAlign - 1) / kAlign * kAlign;
+}
+
+int mofq_select_units(const mofq_tensor_t* w, const int32_t* candidates, int32_t n_candidates,
+                      const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out, uint8_t* unit_format,
+                      mofq_result_t* result, double* mixed_err, void* ws, size_t ws_bytes,
+                      void* stream) {
+  int rc = check_tensor(w);
+  if (rc) return rc;
+  if ((rc = check_cfg(w, w_cfg))) return rc;
+  if ((rc = check_candidates(candidates, n_candidates))) return rc;
+  if ((rc = check_out(w_out, true))) return rc;
+  if (!result || !unit_format || !mixed_err) return MOFQ_ERR_INVALID_ARG;
+  if (w_cfg->gran == MOFQ_PER_TENSOR) return MOFQ_ERR_UNSUPPORTED;   // that unit is the layer: mofq_select_layer
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t units = mofq_num_units(w->rows, w->cols, w_cfg->gran, w_cfg->group_size);
+  const WOnlyWs s = carve_w_only(ws, units, n_candidates, w_cfg->gran, w_cfg->n_clip);
+  const size_t need = mofq_select_units_workspace_bytes(w, n_candidates, w_cfg);
+  if (!ws || !need || ws_bytes < need || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+  double* picked = reinterpret_cast<double*>(static_cast<char*>(ws) + s.bytes);
+  if ((rc = sweep_candidates(w, candidates, n_candidates, w_cfg, s, st))) return rc;
+  // the layer-wise view, as mofq_select_layer reports it
+  DecideParams d{};
+  d.units = units;
+  d.n_cand = n_candidates;
+  for (int c = 0; c < n_candidates; ++c) d.err[c] = s.err[c];
+  d.energy = s.energy;
+  d.part = s.decide_part;
+  d.result = result;
+  if ((rc = launch_decide(d, st))) return rc;
+  // per unit
+  PickUnitsParams pk{};
+  pk.units = units;
+  pk.n_cand = n_candidates;
+  for (int c = 0; c < n_candidates; ++c) pk.err[c] = s.err[c];
+  pk.unit_fmt = unit_format;
+  pk.picked_err = picked;
+  if ((rc = launch_pick_units(pk, st))) return rc;
+  DecideParams m{};
+  m.units = units;
+  m.n_cand = 1;
+  m.err[0] = picked;
+  m.part = s.decide_part;
+  m.tensor_err_out = mixed_err;
+  if ((rc = launch_decide(m, st))) return rc;
+  EmitParams e{};
+  e.w = w->data;
+  e.dtype = w->dtype;
+  e.rows = w->rows;
+  e.cols = w->cols;
+  e.ld = w->ld;
+  e.gran = w_cfg->gran;
+  e.group = w_cfg->group_size;
+  e.scale_f16_out = w_cfg->scale_dtype == MOFQ_F16;
+  e.n_cand = n_candidates;
+  for (int c = 0; c < n_candidates; ++c) {
+    e.fmt[c] = candidates[c];
+    e.scale[c] = s.scale[c];
+    e.clip[c] = s.clip[c];
+    e.err[c] = s.err[c];
+  }
+  e.result = nullptr;
+  e.unit_fmt = unit_format;
+  e.out = *w_out;
+  return launch_emit(e, st);
+}
+
 int mofq_select_layer(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* candidates,
                       int32_t n_candidates, int32_t metric, const mofq_scale_cfg_t* w_cfg,
                       const mofq_qout_t* w_out, const mofq_qout_t* x_out, mofq_result_t* result,

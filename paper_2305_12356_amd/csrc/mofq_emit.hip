@@ -136,6 +136,7 @@ struct EmitArgs {
   const int32_t* clip[MOFQ_MAX_CANDIDATES];
   const double* err[MOFQ_MAX_CANDIDATES];
   const mofq_result_t* result;
+  const uint8_t* unit_fmt;  // per-unit candidate index, or nullptr (then the tensor-level choice)
   mofq_qout_t out;
   int32_t as_bf16_values;   // write dequantised grid values (bf16, unscaled) instead of codes
 };
@@ -148,12 +149,17 @@ MOFQ_DEV int chosen(const EmitArgs& a) {
 
 // One 8-element chunk: quantize with the unit's scale and store.
 template <typename In>
-MOFQ_DEV void emit_chunk(const EmitArgs& a, int fmt, const float* scale, int64_t cpr, int64_t c, const float (&v)[8]) {
+MOFQ_DEV void emit_chunk(const EmitArgs& a, int best, int64_t cpr, int64_t c, const float (&v)[8]) {
   const int64_t row = c / cpr, col = (c - row * cpr) * 8;
   int64_t unit = 0;
   if (a.gran == MOFQ_PER_CHANNEL) unit = row;
   else if (a.gran == MOFQ_PER_GROUP) unit = row * (a.cols / a.group) + col / a.group;
-  const float inv_s = 1.0f / scale[unit];
+  if (a.unit_fmt) {
+    best = a.unit_fmt[unit];
+    if (best >= a.n_cand) best = 0;
+  }
+  const int fmt = a.fmt[best];
+  const float inv_s = 1.0f / a.scale[best][unit];
   uint32_t words[2];
   switch (fmt) {
     case MOFQ_INT4: encode8<MOFQ_INT4>(v, inv_s, words); break;
@@ -198,8 +204,6 @@ template <typename In>
 __global__ __launch_bounds__(256) void emit_codes_kernel(const EmitArgs a) {
   using L = Load8<In>;
   const int best = chosen(a);
-  const int fmt = a.fmt[best];
-  const float* scale = a.scale[best];
   const int64_t cpr = a.cols / 8;
   const int64_t n_chunks = a.rows * cpr;
   const int64_t stride = static_cast<int64_t>(gridDim.x) * 256;
@@ -213,20 +217,24 @@ __global__ __launch_bounds__(256) void emit_codes_kernel(const EmitArgs a) {
       L::load(static_cast<const typename L::elem*>(a.w) + row * a.ld + col, v[u]);
     }
 #pragma unroll
-    for (int u = 0; u < kEmitUnroll; ++u) emit_chunk<In>(a, fmt, scale, cpr, c + u * stride, v[u]);
+    for (int u = 0; u < kEmitUnroll; ++u) emit_chunk<In>(a, best, cpr, c + u * stride, v[u]);
   }
   for (; c < n_chunks; c += stride) {
     float v[8];
     const int64_t row = c / cpr, col = (c - row * cpr) * 8;
     L::load(static_cast<const typename L::elem*>(a.w) + row * a.ld + col, v);
-    emit_chunk<In>(a, fmt, scale, cpr, c, v);
+    emit_chunk<In>(a, best, cpr, c, v);
   }
 }
 
 __global__ __launch_bounds__(256) void emit_units_kernel(const EmitArgs a) {
-  const int best = chosen(a);
+  int best = chosen(a);
   const int64_t u = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   if (u >= a.units) return;
+  if (a.unit_fmt) {
+    best = a.unit_fmt[u];
+    if (best >= a.n_cand) best = 0;
+  }
   const float s = a.scale[best][u];
   if (a.out.scales) {
     if (a.scale_f16_out)
@@ -238,7 +246,29 @@ __global__ __launch_bounds__(256) void emit_units_kernel(const EmitArgs a) {
   if (a.out.unit_err) a.out.unit_err[u] = a.err[best][u];
 }
 
+__global__ __launch_bounds__(256) void pick_units_kernel(const PickUnitsParams p) {
+  const int64_t u = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (u >= p.units) return;
+  // Algorithm 1's rule for one unit: start at infinity, list order, strictly smaller wins
+  double min_err = __builtin_inf();
+  int best = 0;
+#pragma unroll
+  for (int c = 0; c < MOFQ_MAX_CANDIDATES; ++c)
+    if (c < p.n_cand) {
+      const double e = p.err[c][u];
+      if (e < min_err) { min_err = e; best = c; }
+    }
+  p.unit_fmt[u] = static_cast<uint8_t>(best);
+  p.picked_err[u] = p.err[best][u];
+}
+
 }  // namespace
+
+int launch_pick_units(const PickUnitsParams& p, hipStream_t st) {
+  if (p.units <= 0 || p.n_cand < 1 || p.n_cand > MOFQ_MAX_CANDIDATES) return MOFQ_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(pick_units_kernel, dim3(static_cast<unsigned>((p.units + 255) / 256)), dim3(256), 0, st, p);
+  return hip_status(hipGetLastError());
+}
 
 int launch_decide(const DecideParams& p, hipStream_t st) {
   if (p.part && p.units > 16 * 1024) {
@@ -272,6 +302,7 @@ int launch_emit(const EmitParams& p, hipStream_t st) {
     a.err[c] = p.err[c];
   }
   a.result = p.result;
+  a.unit_fmt = p.unit_fmt;
   a.out = p.out;
   a.as_bf16_values = p.as_bf16_values;
   a.units = mofq_num_units(p.rows, p.cols, p.gran, p.group);

@@ -76,10 +76,22 @@ struct EmitParams {
   const int32_t* clip[MOFQ_MAX_CANDIDATES];
   const double* err[MOFQ_MAX_CANDIDATES];
   const mofq_result_t* result;   // device, may be nullptr (then candidate 0)
+  const uint8_t* unit_fmt;       // device [units] or nullptr: candidate index per unit (overrides result)
   mofq_qout_t out;
   int32_t as_bf16_values;        // 8-bit formats: out.codes receives the grid values as bf16
 };
 int launch_emit(const EmitParams& p, hipStream_t stream);
+
+// Per unit: the first candidate with the strictly smallest error; writes its index and
+// its error.
+struct PickUnitsParams {
+  int64_t units;
+  int32_t n_cand;
+  const double* err[MOFQ_MAX_CANDIDATES];
+  uint8_t* unit_fmt;     // [units]
+  double* picked_err;    // [units]
+};
+int launch_pick_units(const PickUnitsParams& p, hipStream_t stream);
 
 // Layer-output error of one linear layer: partial sums per 128x128 output tile.
 // A null xi/wi (or xf/wf) pair skips that format.
