@@ -218,6 +218,28 @@ size_t mofq_select_units_workspace_bytes(const mofq_tensor_t* w, int32_t n_candi
                                          const mofq_scale_cfg_t* w_cfg);
 
 /*
+ * Static calibration of a dynamic (activation) tensor (Section 3.2, dynamic tensor
+ * analysis): the scale is fixed from calibration batches -- the largest magnitude over
+ * all of them -- and then used for batches that were not seen.
+ *
+ * mofq_calibrate_absmax : *absmax = max(*absmax, max |x|).  `absmax` is one device float
+ *   that the caller sets to 0 before the first batch and passes to every further one.
+ * mofq_select_calibrated : Algorithm 1's loop body for one tensor whose scale comes from
+ *   the calibration: per-tensor scale s_f = fl32(absmax / qmax_f) per candidate (the same
+ *   expression as every other scale here, ratio 1; s = 1 if that is below 2^-126), tensor
+ *   error sum (x - Q_f(x))^2 with values beyond the calibrated range saturating, first
+ *   strictly smallest wins.  x_out (may be NULL) receives the codes and the one scale of
+ *   the winner; result as in mofq_select_layer (ref_energy = sum x^2).
+ * Workspace of both: mofq_workspace_bytes(x, NULL, n_candidates, MOFQ_ERR_TENSOR, cfg) for
+ * a per-tensor cfg with one clip ratio (n_candidates = 1 for the calibration call).
+ */
+int mofq_calibrate_absmax(const mofq_tensor_t* x, float* absmax, void* ws, size_t ws_bytes,
+                          void* stream);
+int mofq_select_calibrated(const mofq_tensor_t* x, const int32_t* candidates, int32_t n_candidates,
+                           const float* absmax, const mofq_qout_t* x_out, mofq_result_t* result,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/*
  * mofq_select_layer with two caller-owned hipEvent_t (passed as void*, either may
  * be NULL) recorded on `stream` immediately before and after the error-scoring
  * kernels (the scale search for the tensor metric, the matrix products for the

@@ -117,3 +117,19 @@ def activations(tokens: int, in_features: int, seed: int, dtype=torch.bfloat16,
 def to_f32_numpy(t: torch.Tensor) -> np.ndarray:
     """Exact widening of an fp32/fp16/bf16 tensor to a host fp32 array."""
     return t.detach().to("cpu").to(torch.float32).contiguous().numpy()
+
+
+def activation_batches(n_batches: int, tokens: int, in_features: int, seed: int,
+                       dtype=torch.bfloat16, device="cpu", spread: float = 0.35) -> List[torch.Tensor]:
+    """Batches of one layer's input for static calibration: activations() with a
+    per-batch gain drawn log-normally (sigma = `spread`), so the largest magnitude
+    differs from batch to batch and the calibrated scale is larger than most batches
+    need."""
+    g = _gen(seed, "cpu")
+    gains = torch.exp(torch.randn(n_batches, generator=g) * spread)
+    out = []
+    for b in range(n_batches):
+        x = activations(tokens, in_features, seed=seed * 1000 + b + 1, dtype=torch.float32, device=device)
+        out.append((x * float(gains[b])).to(dtype).contiguous())
+    return out
+

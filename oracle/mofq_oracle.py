@@ -386,3 +386,34 @@ def select_units(w, candidates: Sequence[int], gran: int, clip, group: int = 0,
         codes[em] = q.codes[em]
     return UnitSelected(pick, codes, scale, idx, best, tensor_err(best), [q.err for q in qs], qs)
 
+
+def calibrate_absmax(batches) -> np.float32:
+    """Static calibration (Section 3.2, dynamic tensor analysis): the largest magnitude
+    over all calibration batches."""
+    m = np.float32(0.0)
+    for b in batches:
+        m = np.maximum(m, np.max(np.abs(_f32c(b))))
+    return np.float32(m)
+
+
+def quantize_calibrated(x, fmt: int, absmax) -> Quantized:
+    """Per-tensor quantization of a batch that was not part of the calibration: the scale
+    comes from the calibrated magnitude (same scale expression as everywhere, ratio 1);
+    values beyond the calibrated range saturate at the format's extreme value."""
+    x = _f32c(x)
+    s = np.array([scale(np.float32(absmax), 1.0, fmt)], dtype=np.float32)
+    codes = emit(x, fmt, PER_TENSOR, s)
+    xh = decode_array(fmt, codes) * np.float64(s[0])
+    d = x.astype(np.float64) - xh
+    e = float(np.sum(d * d))
+    return Quantized(fmt, codes, s, np.zeros(1, dtype=np.int32), np.array([e]), e, None)
+
+
+def select_calibrated(x, candidates: Sequence[int], absmax) -> Selected:
+    """Algorithm 1's loop body for one dynamic tensor with calibrated scales."""
+    x = _f32c(x)
+    qs = [quantize_calibrated(x, f, absmax) for f in candidates]
+    errs = [q.err for q in qs]
+    best = select(errs)
+    return Selected(best, errs, float(np.sum(x.astype(np.float64) ** 2)), qs[best], None, qs)
+

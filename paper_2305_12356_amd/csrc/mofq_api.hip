@@ -104,7 +104,8 @@ WOnlyWs carve_w_only(void* ws, int64_t units, int n_cand, int gran, int n_clip) 
 
 // Scale search of all candidates (two formats per launch), results in the workspace.
 int sweep_candidates(const mofq_tensor_t* t, const int32_t* cand, int n_cand,
-                     const mofq_scale_cfg_t* cfg, const WOnlyWs& w, hipStream_t st) {
+                     const mofq_scale_cfg_t* cfg, const WOnlyWs& w, hipStream_t st,
+                     const float* ext_absmax = nullptr) {
   int c0 = 0;
   while (c0 < n_cand) {
     // two different formats share one launch (one read of the tensor); a repeated
@@ -135,6 +136,7 @@ int sweep_candidates(const mofq_tensor_t* t, const int32_t* cand, int n_cand,
     p.absmax_part = w.absmax_part;
     p.sse_part = w.sse_part;
     p.energy_part = w.energy_part;
+    p.ext_absmax = ext_absmax;
     const int rc = launch_sweep(p, st);
     if (rc != MOFQ_OK) return rc;
     c0 += n;
@@ -492,6 +494,68 @@ int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, i
     return launch_decide(d, st);
   }
   return MOFQ_ERR_INVALID_ARG;
+}
+
+int mofq_calibrate_absmax(const mofq_tensor_t* x, float* absmax, void* ws, size_t ws_bytes,
+                          void* stream) {
+  int rc = check_tensor(x);
+  if (rc) return rc;
+  if (!absmax) return MOFQ_ERR_INVALID_ARG;
+  const mofq_scale_cfg_t cfg = x_cfg();
+  if ((rc = check_cfg(x, &cfg))) return rc;
+  const WOnlyWs s = carve_w_only(ws, 1, 1, MOFQ_PER_TENSOR, 1);
+  if (!ws || ws_bytes < s.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+  SweepParams p{};
+  p.w = x->data;
+  p.dtype = x->dtype;
+  p.rows = x->rows;
+  p.cols = x->cols;
+  p.ld = x->ld;
+  p.absmax_part = s.absmax_part;
+  p.energy_part = s.energy_part;
+  return launch_running_absmax(p, absmax, static_cast<hipStream_t>(stream));
+}
+
+int mofq_select_calibrated(const mofq_tensor_t* x, const int32_t* candidates, int32_t n_candidates,
+                           const float* absmax, const mofq_qout_t* x_out, mofq_result_t* result,
+                           void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_tensor(x);
+  if (rc) return rc;
+  if ((rc = check_candidates(candidates, n_candidates))) return rc;
+  if (x_out && (rc = check_out(x_out, true))) return rc;
+  if (!absmax || !result) return MOFQ_ERR_INVALID_ARG;
+  const mofq_scale_cfg_t cfg = x_cfg();   // per-tensor, ratio 1, fp32 scale
+  if ((rc = check_cfg(x, &cfg))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const WOnlyWs s = carve_w_only(ws, 1, n_candidates, MOFQ_PER_TENSOR, 1);
+  if (!ws || ws_bytes < s.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+  if ((rc = sweep_candidates(x, candidates, n_candidates, &cfg, s, st, absmax))) return rc;
+  DecideParams d{};
+  d.units = 1;
+  d.n_cand = n_candidates;
+  for (int c = 0; c < n_candidates; ++c) d.err[c] = s.err[c];
+  d.energy = s.energy;
+  d.result = result;
+  if ((rc = launch_decide(d, st))) return rc;
+  if (!x_out) return MOFQ_OK;
+  EmitParams e{};
+  e.w = x->data;
+  e.dtype = x->dtype;
+  e.rows = x->rows;
+  e.cols = x->cols;
+  e.ld = x->ld;
+  e.gran = MOFQ_PER_TENSOR;
+  e.group = 0;
+  e.n_cand = n_candidates;
+  for (int c = 0; c < n_candidates; ++c) {
+    e.fmt[c] = candidates[c];
+    e.scale[c] = s.scale[c];
+    e.clip[c] = s.clip[c];
+    e.err[c] = s.err[c];
+  }
+  e.result = result;
+  e.out = *x_out;
+  return launch_emit(e, st);
 }
 
 size_t mofq_select_units_workspace_bytes(const mofq_tensor_t* w, int32_t n_candidates,

@@ -36,9 +36,14 @@ struct SweepParams {
   float* absmax_part;     // [kTensorBlocks]
   double* sse_part;       // [kTensorBlocks][n_fmt][n_clip]
   double* energy_part;    // [kTensorBlocks]
+  const float* ext_absmax;  // device, one value, or nullptr: use this magnitude instead of the tensor's own
 };
 
 constexpr int kTensorBlocks = 1024;  // partial results of per-tensor passes
+
+// max|x| of a tensor folded into a running maximum: *running = max(*running, max|x|).
+// `absmax_part` / `energy_part` are scratch of kTensorBlocks entries.
+int launch_running_absmax(const SweepParams& p, float* running, hipStream_t stream);
 
 // Enqueue the scale search.  Returns a mofq_status_t.
 int launch_sweep(const SweepParams& p, hipStream_t stream);

@@ -31,6 +31,7 @@ struct SweepArgs {
   double* sse_part;
   double* energy_part;
   int32_t n_blocks;  // per-tensor: blocks of the partial passes
+  const float* ext_absmax;   // per-tensor: calibrated magnitude replacing the tensor's own, or nullptr
   float clip[MOFQ_MAX_CLIP];
 };
 
@@ -637,6 +638,7 @@ __global__ __launch_bounds__(256) void tensor_absmax_kernel(const SweepArgs a) {
 constexpr int kTensorMaxClip = 8;
 
 MOFQ_DEV float tensor_absmax(const SweepArgs& a, float* s_tmp) {
+  if (a.ext_absmax) return *a.ext_absmax;   // uniform over the grid
   const int tid = threadIdx.x;
   float m = 0.0f;
   for (int i = tid; i < a.n_blocks; i += 256) m = __builtin_fmaxf(m, a.absmax_part[i]);
@@ -754,6 +756,21 @@ __global__ __launch_bounds__(256) void tensor_finalize_kernel(const SweepArgs a)
   }
 }
 
+// *dst = max(*dst, max of the partials): one workgroup.
+__global__ __launch_bounds__(256) void absmax_fold_kernel(const float* part, int n, float* dst) {
+  __shared__ float s_tmp[4];
+  const int tid = threadIdx.x;
+  float m = 0.0f;
+  for (int i = tid; i < n; i += 256) m = __builtin_fmaxf(m, part[i]);
+  m = wave_max(m);
+  if ((tid & 63) == 0) s_tmp[tid >> 6] = m;
+  __syncthreads();
+  if (tid == 0) {
+    m = __builtin_fmaxf(__builtin_fmaxf(s_tmp[0], s_tmp[1]), __builtin_fmaxf(s_tmp[2], s_tmp[3]));
+    *dst = __builtin_fmaxf(*dst, m);
+  }
+}
+
 // ---- dispatch ---------------------------------------------------------------------
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -860,6 +877,7 @@ int launch_sweep(const SweepParams& p, hipStream_t st) {
   a.absmax_part = p.absmax_part;
   a.sse_part = p.sse_part;
   a.energy_part = p.energy_part;
+  a.ext_absmax = (p.gran == MOFQ_PER_TENSOR) ? p.ext_absmax : nullptr;
   a.units = mofq_num_units(p.rows, p.cols, p.gran, p.group);
   for (int k = 0; k < p.n_clip; ++k) a.clip[k] = p.clip[k];
   if (a.units <= 0) return MOFQ_ERR_INVALID_ARG;
@@ -870,6 +888,27 @@ int launch_sweep(const SweepParams& p, hipStream_t st) {
     case MOFQ_BF16: return launch_fmt<BF16>(p, a, st);
   }
   return MOFQ_ERR_INVALID_ARG;
+}
+
+int launch_running_absmax(const SweepParams& p, float* running, hipStream_t st) {
+  if (!running || !p.absmax_part || !p.energy_part) return MOFQ_ERR_INVALID_ARG;
+  SweepArgs a{};
+  a.w = p.w;
+  a.rows = p.rows;
+  a.cols = p.cols;
+  a.ld = p.ld;
+  a.absmax_part = p.absmax_part;
+  a.energy_part = p.energy_part;
+  const int64_t n_chunks = a.rows * (a.cols / 8);
+  a.n_blocks = static_cast<int32_t>(std::min<int64_t>(kTensorBlocks, ceil_div(n_chunks, 256)));
+  switch (p.dtype) {
+    case MOFQ_F32: hipLaunchKernelGGL((tensor_absmax_kernel<F32>), dim3(a.n_blocks), dim3(256), 0, st, a); break;
+    case MOFQ_F16: hipLaunchKernelGGL((tensor_absmax_kernel<F16>), dim3(a.n_blocks), dim3(256), 0, st, a); break;
+    case MOFQ_BF16: hipLaunchKernelGGL((tensor_absmax_kernel<BF16>), dim3(a.n_blocks), dim3(256), 0, st, a); break;
+    default: return MOFQ_ERR_INVALID_ARG;
+  }
+  hipLaunchKernelGGL(absmax_fold_kernel, dim3(1), dim3(256), 0, st, a.absmax_part, a.n_blocks, running);
+  return hip_status(hipGetLastError());
 }
 
 }  // namespace mofq
