@@ -81,6 +81,11 @@ def _load():
                                     C.POINTER(ScaleCfg), C.POINTER(QOut), vp, vp, vp, vp, C.c_size_t, vp]
     L.mofq_select_units_workspace_bytes.restype = C.c_size_t
     L.mofq_select_units_workspace_bytes.argtypes = [C.POINTER(TensorDesc), C.c_int32, C.POINTER(ScaleCfg)]
+    L.mofq_calibrate_absmax.restype = C.c_int
+    L.mofq_calibrate_absmax.argtypes = [C.POINTER(TensorDesc), vp, vp, C.c_size_t, vp]
+    L.mofq_select_calibrated.restype = C.c_int
+    L.mofq_select_calibrated.argtypes = [C.POINTER(TensorDesc), C.POINTER(C.c_int32), C.c_int32, vp,
+                                         C.POINTER(QOut), vp, vp, C.c_size_t, vp]
     L.mofq_num_units.restype = C.c_int64
     L.mofq_num_units.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32]
     L.mofq_status_string.restype = C.c_char_p
@@ -245,6 +250,29 @@ def select_units(w: torch.Tensor, candidates: Sequence[int], cfg: Cfg, w_out: QB
                                 ws.numel() * ws.element_size(), _stream_handle(stream))
     if rc != 0:
         raise MofqError(rc, "mofq_select_units")
+
+
+def calibrate_absmax(x: torch.Tensor, absmax: torch.Tensor, ws: torch.Tensor, stream=None) -> None:
+    """mofq_calibrate_absmax: absmax (device float32 scalar) = max(absmax, max|x|); enqueue."""
+    xd = tensor_desc(x)
+    rc = _lib.mofq_calibrate_absmax(C.byref(xd), _ptr(absmax), _ptr(ws), ws.numel() * ws.element_size(),
+                                    _stream_handle(stream))
+    if rc != 0:
+        raise MofqError(rc, "mofq_calibrate_absmax")
+
+
+def select_calibrated(x: torch.Tensor, candidates: Sequence[int], absmax: torch.Tensor,
+                      x_out: Optional[QBuffers], result: torch.Tensor, ws: torch.Tensor,
+                      stream=None) -> None:
+    """mofq_select_calibrated: per-tensor select with the scale from a calibrated absmax."""
+    xd = tensor_desc(x)
+    cand = (C.c_int32 * len(candidates))(*candidates)
+    xoc = x_out.c() if x_out is not None else None
+    rc = _lib.mofq_select_calibrated(C.byref(xd), cand, len(candidates), _ptr(absmax),
+                                     C.byref(xoc) if xoc else None, _ptr(result), _ptr(ws),
+                                     ws.numel() * ws.element_size(), _stream_handle(stream))
+    if rc != 0:
+        raise MofqError(rc, "mofq_select_calibrated")
 
 
 def alloc_result(device, n: int = 1) -> torch.Tensor:
