@@ -157,11 +157,14 @@ def test_fp8_unit_metric_is_close_but_not_exact(mq):
     assert np.array_equal(unpack_codes(w_out.codes, 512, 1024, 8), ref.w.codes)
 
 
-def test_llama_shaped_linear(mq):
-    """One full-size linear of the 7B shape: 2048 tokens x 4096 -> 4096."""
-    x = mi.activations(2048, 4096, seed=mi.tensor_seed(3, 0, 0, 1), device=DEV)
-    w = mi.llama_like_weight(4096, 4096, seed=mi.tensor_seed(3, 0, 0), dtype=torch.bfloat16, device=DEV)
-    r = check_layer(mq, x, w, [I8, FP8], orc.PER_TENSOR, "llama-q")
+@pytest.mark.parametrize("name,o,n", [("q", 4096, 4096), ("gate", 11008, 4096), ("down", 4096, 11008)])
+def test_llama_shaped_linear(mq, name, o, n):
+    """The three distinct linear shapes of a 7B decoder block at full size (2048 tokens),
+    in the launch configuration bench.py times; the oracle's fp64 products take seconds."""
+    lin = mi.LINEAR_NAMES.index(name)
+    x = mi.activations(2048, n, seed=mi.tensor_seed(3, 0, lin, 1), device=DEV)
+    w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(3, 0, lin), dtype=torch.bfloat16, device=DEV)
+    r = check_layer(mq, x, w, [I8, FP8], orc.PER_TENSOR, "llama-" + name)
     assert r.best == 1        # FP8 wins with outlier channels (Section 3.2)
 
 
