@@ -36,7 +36,6 @@ int check_cfg(const mofq_tensor_t* t, const mofq_scale_cfg_t* c) {
     if (!(c->clip_ratios[k] > 0.0f) || !(c->clip_ratios[k] <= 1.0f)) return MOFQ_ERR_INVALID_ARG;
   switch (c->gran) {
     case MOFQ_PER_TENSOR:
-      if (c->n_clip > 8) return MOFQ_ERR_UNSUPPORTED;
       return MOFQ_OK;
     case MOFQ_PER_CHANNEL:
       if (t->cols > 32768) return MOFQ_ERR_UNSUPPORTED;

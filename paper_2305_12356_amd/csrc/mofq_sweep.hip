@@ -32,6 +32,7 @@ struct SweepArgs {
   double* energy_part;
   int32_t n_blocks;  // per-tensor: blocks of the partial passes
   const float* ext_absmax;   // per-tensor: calibrated magnitude replacing the tensor's own, or nullptr
+  int32_t k0;                // per-tensor: first clip candidate of this scoring pass
   float clip[MOFQ_MAX_CLIP];
 };
 
@@ -658,11 +659,12 @@ __global__ __launch_bounds__(256) void tensor_score_kernel(const SweepArgs a) {
   __shared__ float s_inv[NF][kTensorMaxClip];
   __shared__ double s_part[4][NF][kTensorMaxClip];
   const int tid = threadIdx.x;
-  const int K = a.n_clip;
+  // one pass scores up to kTensorMaxClip candidates, a.k0 onwards (more candidates: more passes)
+  const int K = (a.n_clip - a.k0) < kTensorMaxClip ? (a.n_clip - a.k0) : kTensorMaxClip;
   const float amax = tensor_absmax(a, s_tmp);
   if (tid < NF * K) {
     const int f = tid / K, k = tid - f * K;
-    const float s = unit_scale(amax, a.clip[k], f == 0 ? Codec<FA>::QMAX : Codec<FBX>::QMAX,
+    const float s = unit_scale(amax, a.clip[a.k0 + k], f == 0 ? Codec<FA>::QMAX : Codec<FBX>::QMAX,
                                a.scale_f16 != 0);
     s_scale[f][k] = s;
     s_inv[f][k] = 1.0f / s;
@@ -709,7 +711,7 @@ __global__ __launch_bounds__(256) void tensor_score_kernel(const SweepArgs a) {
   __syncthreads();
   if (tid < NF * K) {
     const int f = tid / K, k = tid - f * K;
-    a.sse_part[(static_cast<int64_t>(blockIdx.x) * NF + f) * K + k] =
+    a.sse_part[(static_cast<int64_t>(blockIdx.x) * NF + f) * a.n_clip + a.k0 + k] =
         (s_part[0][f][k] + s_part[1][f][k]) + (s_part[2][f][k] + s_part[3][f][k]);
   }
 }
@@ -720,21 +722,20 @@ __global__ __launch_bounds__(256) void tensor_finalize_kernel(const SweepArgs a)
   constexpr int FBX = (FB >= 0) ? FB : FA;
   __shared__ float s_tmp[4];
   __shared__ double s_red[4];
-  __shared__ double s_tot[NF][kTensorMaxClip];
+  __shared__ double s_tot[NF][MOFQ_MAX_CLIP];
   const int tid = threadIdx.x;
   const int K = a.n_clip;
   const float amax = tensor_absmax(a, s_tmp);
-  for (int f = 0; f < NF; ++f)
-    for (int k = 0; k < K; ++k) {
-      double t = 0.0;
-      for (int b = tid; b < a.n_blocks; b += 256)
-        t += a.sse_part[(static_cast<int64_t>(b) * NF + f) * K + k];
-      t = wave_sum(t);
-      __syncthreads();
-      if ((tid & 63) == 0) s_red[tid >> 6] = t;
-      __syncthreads();
-      if (tid == 0) s_tot[f][k] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
-    }
+  // one wave per (format, candidate): partials in block order (lane-strided, then the
+  // fixed cross-lane order of wave_sum)
+  for (int idx = tid >> 6; idx < NF * K; idx += 4) {
+    const int f = idx / K, k = idx - f * K;
+    double t = 0.0;
+    for (int b = tid & 63; b < a.n_blocks; b += 64)
+      t += a.sse_part[(static_cast<int64_t>(b) * NF + f) * K + k];
+    t = wave_sum(t);
+    if ((tid & 63) == 0) s_tot[f][k] = t;
+  }
   double en = 0.0;
   for (int b = tid; b < a.n_blocks; b += 256) en += a.energy_part[b];
   en = wave_sum(en);
@@ -822,11 +823,12 @@ int launch_group(const SweepArgs& a, hipStream_t st) {
 
 template <typename In, int FA, int FB>
 int launch_tensor(SweepArgs a, hipStream_t st) {
-  if (a.n_clip > kTensorMaxClip) return MOFQ_ERR_UNSUPPORTED;
   const int64_t n_chunks = a.rows * (a.cols / 8);
   a.n_blocks = static_cast<int32_t>(std::min<int64_t>(kTensorBlocks, ceil_div(n_chunks, 256)));
   hipLaunchKernelGGL((tensor_absmax_kernel<In>), dim3(a.n_blocks), dim3(256), 0, st, a);
-  hipLaunchKernelGGL((tensor_score_kernel<In, FA, FB>), dim3(a.n_blocks), dim3(256), 0, st, a);
+  for (a.k0 = 0; a.k0 < a.n_clip; a.k0 += kTensorMaxClip)
+    hipLaunchKernelGGL((tensor_score_kernel<In, FA, FB>), dim3(a.n_blocks), dim3(256), 0, st, a);
+  a.k0 = 0;
   hipLaunchKernelGGL((tensor_finalize_kernel<FA, FB>), dim3(1), dim3(256), 0, st, a);
   return hip_status(hipGetLastError());
 }

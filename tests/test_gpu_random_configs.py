@@ -48,7 +48,7 @@ def test_random_weight_only_config(mq, seed):  # noqa: F811
         n_clip = int([1, 3, 17, 50, 64][rng.integers(5)])
     elif gran == orc.PER_TENSOR:
         cols = 8 * int(rng.integers(1, 300))
-        n_clip = int(rng.integers(1, 9))
+        n_clip = int([1, 2, 5, 8, 9, 20, 64][rng.integers(7)])
     else:
         cols = 8 * int([rng.integers(1, 64), rng.integers(128, 700), rng.integers(1200, 3100)][rng.integers(3)])
         n_clip = int([1, 2, 7, 8, 31, 100, 128][rng.integers(7)])
