@@ -102,9 +102,16 @@ WOnlyWs carve_w_only(void* ws, int64_t units, int n_cand, int gran, int n_clip) 
 }
 
 // Scale search of all candidates (two formats per launch), results in the workspace.
+// Optional outputs of the scoring pass itself (per-tensor (INT8, FP8-E4M3) pair only).
+struct SweepEmit {
+  uint8_t* i8;
+  void* f8;
+  int f8_as_bf16;
+};
+
 int sweep_candidates(const mofq_tensor_t* t, const int32_t* cand, int n_cand,
                      const mofq_scale_cfg_t* cfg, const WOnlyWs& w, hipStream_t st,
-                     const float* ext_absmax = nullptr) {
+                     const float* ext_absmax = nullptr, const SweepEmit* em = nullptr) {
   int c0 = 0;
   while (c0 < n_cand) {
     // two different formats share one launch (one read of the tensor); a repeated
@@ -136,6 +143,12 @@ int sweep_candidates(const mofq_tensor_t* t, const int32_t* cand, int n_cand,
     p.sse_part = w.sse_part;
     p.energy_part = w.energy_part;
     p.ext_absmax = ext_absmax;
+    if (em) {
+      if (n != 2) return MOFQ_ERR_INVALID_ARG;
+      p.emit_i8 = em->i8;
+      p.emit_f8 = em->f8;
+      p.emit_f8_as_bf16 = em->f8_as_bf16;
+    }
     const int rc = launch_sweep(p, st);
     if (rc != MOFQ_OK) return rc;
     c0 += n;
@@ -299,8 +312,15 @@ int wa_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand
              hipEvent_t ev0, hipEvent_t ev1) {
   const mofq_scale_cfg_t xc = x_cfg();
   int rc;
-  if ((rc = sweep_candidates(x, cand, n_cand, &xc, a.xrec, st))) return rc;
-  if ((rc = sweep_candidates(w, cand, n_cand, w_cfg, a.wrec, st))) return rc;
+  // With both formats as candidates, a per-tensor scoring pass also writes both quantized
+  // copies of its tensor (one read instead of three).
+  bool both = false;
+  if (n_cand == 2)
+    both = (cand[0] == MOFQ_INT8 && cand[1] == MOFQ_FP8_E4M3) || (cand[0] == MOFQ_FP8_E4M3 && cand[1] == MOFQ_INT8);
+  const bool fused_x = both, fused_w = both && w_cfg->gran == MOFQ_PER_TENSOR;
+  const SweepEmit ex{a.xq[0], a.xq[1], fp8_unit ? 0 : 1}, ew{a.wq[0], a.wq[1], fp8_unit ? 0 : 1};
+  if ((rc = sweep_candidates(x, cand, n_cand, &xc, a.xrec, st, nullptr, fused_x ? &ex : nullptr))) return rc;
+  if ((rc = sweep_candidates(w, cand, n_cand, w_cfg, a.wrec, st, nullptr, fused_w ? &ew : nullptr))) return rc;
   WaGemmParams g{};
   int n_q = 0;
   for (int f = 0; f < 2; ++f) {
@@ -310,6 +330,7 @@ int wa_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand
       if (cand[c] == fmt) slot = c;
     if (slot < 0) continue;
     for (int which = 0; which < 2; ++which) {   // 0: X, 1: W
+      if (which ? fused_w : fused_x) continue;  // already written by the scoring pass
       const mofq_tensor_t* t = which ? w : x;
       const WOnlyWs& rec = which ? a.wrec : a.xrec;
       EmitParams e{};

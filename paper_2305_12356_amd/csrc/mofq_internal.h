@@ -37,6 +37,11 @@ struct SweepParams {
   double* sse_part;       // [kTensorBlocks][n_fmt][n_clip]
   double* energy_part;    // [kTensorBlocks]
   const float* ext_absmax;  // device, one value, or nullptr: use this magnitude instead of the tensor's own
+  // per-tensor (INT8, FP8-E4M3) pair with one clip ratio only: the scoring pass also writes
+  // the quantized tensor in both formats (dense rows), saving two further reads of the input
+  uint8_t* emit_i8;         // int8 codes, or nullptr
+  void* emit_f8;            // e4m3 codes (1 byte) or grid values as bf16 (2 bytes)
+  int32_t emit_f8_as_bf16;
 };
 
 constexpr int kTensorBlocks = 1024;  // partial results of per-tensor passes

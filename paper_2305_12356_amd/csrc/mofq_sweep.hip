@@ -33,6 +33,9 @@ struct SweepArgs {
   int32_t n_blocks;  // per-tensor: blocks of the partial passes
   const float* ext_absmax;   // per-tensor: calibrated magnitude replacing the tensor's own, or nullptr
   int32_t k0;                // per-tensor: first clip candidate of this scoring pass
+  uint8_t* emit_i8;          // per-tensor 8-bit pair: also write the codes (see SweepParams)
+  void* emit_f8;
+  int32_t emit_f8_as_bf16;
   float clip[MOFQ_MAX_CLIP];
 };
 
@@ -716,6 +719,76 @@ __global__ __launch_bounds__(256) void tensor_score_kernel(const SweepArgs a) {
   }
 }
 
+// Per-tensor (INT8, FP8-E4M3) pair at one clip ratio, as the weight-activation path uses
+// it: the same partial errors as tensor_score_kernel, and in the same pass the int8 codes
+// and the E4M3 codes (or their grid values as bf16) of every element, so that the operands
+// of the layer-output products cost one read of the tensor instead of three.
+template <typename In>
+__global__ __launch_bounds__(256) void tensor_score_emit8_kernel(const SweepArgs a) {
+  using L = Load8<In>;
+  __shared__ float s_tmp[4];
+  __shared__ double s_part[4][2];
+  const int tid = threadIdx.x;
+  const float amax = tensor_absmax(a, s_tmp);
+  const float sA = unit_scale(amax, a.clip[0], Codec<MOFQ_INT8>::QMAX, a.scale_f16 != 0);
+  const float sB = unit_scale(amax, a.clip[0], Codec<MOFQ_FP8_E4M3>::QMAX, a.scale_f16 != 0);
+  const float iA = 1.0f / sA, iB = 1.0f / sB;
+  const double sAd = static_cast<double>(sA), sBd = static_cast<double>(sB);
+  double accA = 0.0, accB = 0.0;
+  const int64_t cpr = a.cols / 8;
+  const int64_t n_chunks = a.rows * cpr;
+  for (int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + tid; c < n_chunks;
+       c += static_cast<int64_t>(gridDim.x) * 256) {
+    const int64_t row = c / cpr, col = (c - row * cpr) * 8;
+    float v[8];
+    L::load(static_cast<const typename L::elem*>(a.w) + row * a.ld + col, v);
+    uint32_t wi[2] = {0u, 0u};
+    int wf[2] = {0, 0};
+    u32x4 gb;
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+      // INT8
+      const float q0 = Codec<MOFQ_INT8>::grid(v[i] * iA), q1 = Codec<MOFQ_INT8>::grid(v[i + 1] * iA);
+      wi[i >> 2] |= (static_cast<uint32_t>(static_cast<int>(q0)) & 0xFFu) << (8 * (i & 3));
+      wi[i >> 2] |= (static_cast<uint32_t>(static_cast<int>(q1)) & 0xFFu) << (8 * ((i & 3) + 1));
+      const double d0 = __builtin_fma(-static_cast<double>(q0), sAd, static_cast<double>(v[i]));
+      const double d1 = __builtin_fma(-static_cast<double>(q1), sAd, static_cast<double>(v[i + 1]));
+      accA = __builtin_fma(d0, d0, accA);
+      accA = __builtin_fma(d1, d1, accA);
+      // E4M3: pack-convert (exact agreement with the codec, see grid2), decode for the error
+      const int p = __builtin_amdgcn_cvt_pk_fp8_f32(med3(v[i] * iB, -448.0f, 448.0f),
+                                                    med3(v[i + 1] * iB, -448.0f, 448.0f), 0, false);
+      const f32x2 g = __builtin_amdgcn_cvt_pk_f32_fp8(p, false);
+      wf[i >> 2] |= (p & 0xFFFF) << (16 * ((i >> 1) & 1));
+      gb[i >> 1] = (f2u(g[0]) >> 16) | (f2u(g[1]) & 0xFFFF0000u);
+      const double e0 = __builtin_fma(-static_cast<double>(g[0]), sBd, static_cast<double>(v[i]));
+      const double e1 = __builtin_fma(-static_cast<double>(g[1]), sBd, static_cast<double>(v[i + 1]));
+      accB = __builtin_fma(e0, e0, accB);
+      accB = __builtin_fma(e1, e1, accB);
+    }
+    const int64_t e8 = (row * a.cols + col) / 8;   // dense output rows
+    u32x2 oi;
+    oi[0] = wi[0];
+    oi[1] = wi[1];
+    reinterpret_cast<u32x2*>(a.emit_i8)[e8] = oi;
+    if (a.emit_f8_as_bf16) {
+      reinterpret_cast<u32x4*>(a.emit_f8)[e8] = gb;
+    } else {
+      u32x2 of;
+      of[0] = static_cast<uint32_t>(wf[0]);
+      of[1] = static_cast<uint32_t>(wf[1]);
+      reinterpret_cast<u32x2*>(a.emit_f8)[e8] = of;
+    }
+  }
+  accA = wave_sum(accA);
+  accB = wave_sum(accB);
+  if ((tid & 63) == 0) { s_part[tid >> 6][0] = accA; s_part[tid >> 6][1] = accB; }
+  __syncthreads();
+  if (tid < 2)
+    a.sse_part[static_cast<int64_t>(blockIdx.x) * 2 + tid] =
+        (s_part[0][tid] + s_part[1][tid]) + (s_part[2][tid] + s_part[3][tid]);
+}
+
 template <int FA, int FB>
 __global__ __launch_bounds__(256) void tensor_finalize_kernel(const SweepArgs a) {
   constexpr int NF = (FB >= 0) ? 2 : 1;
@@ -826,6 +899,14 @@ int launch_tensor(SweepArgs a, hipStream_t st) {
   const int64_t n_chunks = a.rows * (a.cols / 8);
   a.n_blocks = static_cast<int32_t>(std::min<int64_t>(kTensorBlocks, ceil_div(n_chunks, 256)));
   hipLaunchKernelGGL((tensor_absmax_kernel<In>), dim3(a.n_blocks), dim3(256), 0, st, a);
+  if constexpr (FA == MOFQ_INT8 && FB == MOFQ_FP8_E4M3) {
+    if (a.emit_i8 && a.emit_f8 && a.n_clip == 1) {
+      hipLaunchKernelGGL((tensor_score_emit8_kernel<In>), dim3(a.n_blocks), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((tensor_finalize_kernel<FA, FB>), dim3(1), dim3(256), 0, st, a);
+      return hip_status(hipGetLastError());
+    }
+  }
+  if (a.emit_i8 || a.emit_f8) return MOFQ_ERR_UNSUPPORTED;
   for (a.k0 = 0; a.k0 < a.n_clip; a.k0 += kTensorMaxClip)
     hipLaunchKernelGGL((tensor_score_kernel<In, FA, FB>), dim3(a.n_blocks), dim3(256), 0, st, a);
   a.k0 = 0;
@@ -880,6 +961,12 @@ int launch_sweep(const SweepParams& p, hipStream_t st) {
   a.sse_part = p.sse_part;
   a.energy_part = p.energy_part;
   a.ext_absmax = (p.gran == MOFQ_PER_TENSOR) ? p.ext_absmax : nullptr;
+  if (p.emit_i8 || p.emit_f8) {
+    if (p.gran != MOFQ_PER_TENSOR) return MOFQ_ERR_UNSUPPORTED;
+    a.emit_i8 = p.emit_i8;
+    a.emit_f8 = p.emit_f8;
+    a.emit_f8_as_bf16 = p.emit_f8_as_bf16;
+  }
   a.units = mofq_num_units(p.rows, p.cols, p.gran, p.group);
   for (int k = 0; k < p.n_clip; ++k) a.clip[k] = p.clip[k];
   if (a.units <= 0) return MOFQ_ERR_INVALID_ARG;
