@@ -418,19 +418,29 @@ def main():
         weights.append(w)
         qouts.append(mq.alloc_qbuffers(o, n, 4, cfg, dev))
         ws_bytes = max(ws_bytes, mq.workspace_bytes(w, None, len(cands), mq.ERR_TENSOR, cfg))
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    # one call for the whole model (mofq_select_layers): the per-tensor reduce / select /
+    # per-unit outputs of up to 12 tensors share a launch
+    batch = mq.LayerBatch(weights, qouts)
+    ws = torch.empty(batch.workspace_bytes(len(cands), cfg), dtype=torch.uint8, device=dev)
     n_elems = sum(o * n for _, _, o, n in shapes)
     stream = torch.cuda.current_stream()
 
+    # the events the library records around each search launch, created (and recorded once,
+    # so that they exist) before the timed region
+    ev_pool = []
+    for _ in range(args.steps):
+        e0 = [torch.cuda.Event(enable_timing=True) for _ in weights]
+        e1 = [torch.cuda.Event(enable_timing=True) for _ in weights]
+        for e in e0 + e1:
+            e.record()
+        ev_pool.append((e0, e1))
+
     def step(events=None):
-        for i, w in enumerate(weights):
-            e0 = e1 = None
-            if events is not None:
-                e0 = torch.cuda.Event(enable_timing=True)
-                e1 = torch.cuda.Event(enable_timing=True)
-                events.append((i, e0, e1))
-            mq.select_layer(w, None, cands, mq.ERR_TENSOR, cfg, qouts[i], None, results[i], ws,
-                            stream, e0, e1)
+        e0 = e1 = None
+        if events is not None:
+            e0, e1 = ev_pool.pop()
+            events.extend((i, a, b) for i, (a, b) in enumerate(zip(e0, e1)))
+        mq.select_layers(batch, cands, cfg, results, ws, stream, e0, e1)
 
     for _ in range(args.warmup):
         step()

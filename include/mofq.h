@@ -194,6 +194,29 @@ int mofq_select_layer(const mofq_tensor_t* w, const mofq_tensor_t* x,
                       void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * mofq_select_layer for several weight tensors in one call (weight-only, tensor error;
+ * Algorithm 1's loop over the layers of a model): the same results, tensor by tensor, as
+ * n_layers calls of mofq_select_layer, but the small dependent steps between the search
+ * and the code emission (tensor reduce, select, per-unit outputs) of up to 12 tensors share
+ * one launch, so a model-wide pass does not pay their latency per tensor.
+ *   w, w_out : HOST arrays of n_layers descriptors (device buffers inside, as above).
+ *   results  : device array of n_layers records.
+ *   ev_begin / ev_end (the _timed variant; may be NULL): HOST arrays of n_layers hipEvent_t,
+ *   recorded around the search of each tensor.
+ * Workspace: mofq_select_layers_workspace_bytes (the tensors' workspaces side by side).
+ */
+int mofq_select_layers(int32_t n_layers, const mofq_tensor_t* w, const int32_t* candidates,
+                       int32_t n_candidates, const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
+                       mofq_result_t* results, void* ws, size_t ws_bytes, void* stream);
+int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int32_t* candidates,
+                             int32_t n_candidates, const mofq_scale_cfg_t* w_cfg,
+                             const mofq_qout_t* w_out, mofq_result_t* results, void* ws,
+                             size_t ws_bytes, void* stream, void* const* ev_begin,
+                             void* const* ev_end);
+size_t mofq_select_layers_workspace_bytes(int32_t n_layers, const mofq_tensor_t* w,
+                                          int32_t n_candidates, const mofq_scale_cfg_t* w_cfg);
+
+/*
  * Format select at a finer granularity than the layer (Section 4.1 leaves it open, the
  * conclusion lists channel-wise / block-wise selection as future work): weight-only,
  * tensor error; every scale unit of w_cfg (a channel or a group; not per-tensor) takes

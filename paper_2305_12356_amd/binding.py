@@ -81,6 +81,14 @@ def _load():
                                     C.POINTER(ScaleCfg), C.POINTER(QOut), vp, vp, vp, vp, C.c_size_t, vp]
     L.mofq_select_units_workspace_bytes.restype = C.c_size_t
     L.mofq_select_units_workspace_bytes.argtypes = [C.POINTER(TensorDesc), C.c_int32, C.POINTER(ScaleCfg)]
+    L.mofq_select_layers.restype = C.c_int
+    L.mofq_select_layers.argtypes = [C.c_int32, C.POINTER(TensorDesc), C.POINTER(C.c_int32), C.c_int32,
+                                     C.POINTER(ScaleCfg), C.POINTER(QOut), vp, vp, C.c_size_t, vp]
+    L.mofq_select_layers_timed.restype = C.c_int
+    L.mofq_select_layers_timed.argtypes = L.mofq_select_layers.argtypes + [C.POINTER(vp), C.POINTER(vp)]
+    L.mofq_select_layers_workspace_bytes.restype = C.c_size_t
+    L.mofq_select_layers_workspace_bytes.argtypes = [C.c_int32, C.POINTER(TensorDesc), C.c_int32,
+                                                     C.POINTER(ScaleCfg)]
     L.mofq_calibrate_absmax.restype = C.c_int
     L.mofq_calibrate_absmax.argtypes = [C.POINTER(TensorDesc), vp, vp, C.c_size_t, vp]
     L.mofq_select_calibrated.restype = C.c_int
@@ -273,6 +281,38 @@ def select_calibrated(x: torch.Tensor, candidates: Sequence[int], absmax: torch.
                                      ws.numel() * ws.element_size(), _stream_handle(stream))
     if rc != 0:
         raise MofqError(rc, "mofq_select_calibrated")
+
+
+class LayerBatch:
+    """Host-side descriptor arrays of a set of weight tensors and their output buffers for
+    mofq_select_layers (built once, reused for every call)."""
+
+    def __init__(self, weights: Sequence[torch.Tensor], outs: Sequence[QBuffers]):
+        assert len(weights) == len(outs) and len(weights) > 0
+        self.n = len(weights)
+        self._keep = (list(weights), list(outs))
+        self.w = (TensorDesc * self.n)(*[tensor_desc(t) for t in weights])
+        self.out = (QOut * self.n)(*[o.c() for o in outs])
+
+    def workspace_bytes(self, n_candidates: int, cfg: Cfg) -> int:
+        return int(_lib.mofq_select_layers_workspace_bytes(self.n, self.w, n_candidates, C.byref(cfg.c)))
+
+
+def select_layers(batch: LayerBatch, candidates: Sequence[int], cfg: Cfg, results: torch.Tensor,
+                  ws: torch.Tensor, stream=None, ev_begin=None, ev_end=None) -> None:
+    """mofq_select_layers (or _timed with lists of torch.cuda.Event): weight-only select of
+    every tensor of the batch; `results` is the device array from alloc_result(device, n)."""
+    cand = (C.c_int32 * len(candidates))(*candidates)
+    args = (batch.n, batch.w, cand, len(candidates), C.byref(cfg.c), batch.out, _ptr(results), _ptr(ws),
+            ws.numel() * ws.element_size(), _stream_handle(stream))
+    if ev_begin is None:
+        rc = _lib.mofq_select_layers(*args)
+    else:
+        e0 = (C.c_void_p * batch.n)(*[_event_handle(e).value for e in ev_begin])
+        e1 = (C.c_void_p * batch.n)(*[_event_handle(e).value for e in ev_end])
+        rc = _lib.mofq_select_layers_timed(*args, e0, e1)
+    if rc != 0:
+        raise MofqError(rc, "mofq_select_layers")
 
 
 def alloc_result(device, n: int = 1) -> torch.Tensor:

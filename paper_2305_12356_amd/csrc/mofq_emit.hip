@@ -51,18 +51,50 @@ __global__ __launch_bounds__(kDecideThreads) void decide_partial_kernel(const Pa
   }
 }
 
+// Fixed-order sums of the unit errors, Algorithm 1's select, result record.  Returns the
+// chosen index on thread 0.
+MOFQ_DEV int decide_body(const DecideParams& p, double* s_red);
+
+struct FinishBatchArgs {
+  FinishParams p[kFinishBatch];
+};
+__global__ __launch_bounds__(kDecideThreads) void finish_batch_kernel(const FinishBatchArgs a) {
+  __shared__ double s_red[kDecideThreads / 64];
+  __shared__ int s_best;
+  const FinishParams& p = a.p[blockIdx.x];
+  const int b = decide_body(p.d, s_red);
+  if (threadIdx.x == 0) s_best = (b < 0 || b >= p.d.n_cand) ? 0 : b;   // no candidate beat infinity: keep the first
+  __syncthreads();
+  const int best = s_best;
+  for (int64_t u = threadIdx.x; u < p.d.units; u += kDecideThreads) {
+    const float s = p.scale[best][u];
+    if (p.out_scales) {
+      if (p.scale_f16_out)
+        static_cast<uint16_t*>(p.out_scales)[u] = __half_as_ushort(__float2half_rn(s));  // exact: s is an fp16 value
+      else
+        static_cast<float*>(p.out_scales)[u] = s;
+    }
+    if (p.out_clip) p.out_clip[u] = p.clip[best][u];
+    if (p.out_unit_err) p.out_unit_err[u] = p.d.err[best][u];
+  }
+}
+
 __global__ __launch_bounds__(kDecideThreads) void decide_kernel(const DecideParams p) {
   __shared__ double s_red[kDecideThreads / 64];
+  decide_body(p, s_red);
+}
+
+MOFQ_DEV int decide_body(const DecideParams& p, double* s_red) {
   double err[MOFQ_MAX_CANDIDATES];
 #pragma unroll
   for (int c = 0; c < MOFQ_MAX_CANDIDATES; ++c)
     err[c] = (c < p.n_cand) ? block_sum(p.err[c], p.units, s_red) : 0.0;
   const double energy = p.energy ? block_sum(p.energy, p.units, s_red) : 0.0;
+  int best = -1;
   if (threadIdx.x == 0) {
     // Algorithm 1: min_error starts at infinity, candidates in list order, a
     // candidate wins only if strictly smaller.
     double min_err = __builtin_inf();
-    int best = -1;
 #pragma unroll
     for (int c = 0; c < MOFQ_MAX_CANDIDATES; ++c)
       if (c < p.n_cand && err[c] < min_err) { min_err = err[c]; best = c; }
@@ -76,6 +108,7 @@ __global__ __launch_bounds__(kDecideThreads) void decide_kernel(const DecidePara
     if (p.tensor_err_out) *p.tensor_err_out = err[0];
     if (p.energy_out) *p.energy_out = energy;
   }
+  return best;
 }
 
 // ---- emit -------------------------------------------------------------------------
@@ -263,6 +296,17 @@ __global__ __launch_bounds__(256) void pick_units_kernel(const PickUnitsParams p
 }
 
 }  // namespace
+
+int launch_finish_batch(const FinishParams* p, int n, hipStream_t st) {
+  if (!p || n < 1 || n > kFinishBatch) return MOFQ_ERR_INVALID_ARG;
+  FinishBatchArgs a{};
+  for (int i = 0; i < n; ++i) {
+    if (p[i].d.units < 1 || p[i].d.units > kFinishMaxUnits) return MOFQ_ERR_INVALID_ARG;
+    a.p[i] = p[i];
+  }
+  hipLaunchKernelGGL(finish_batch_kernel, dim3(static_cast<unsigned>(n)), dim3(kDecideThreads), 0, st, a);
+  return hip_status(hipGetLastError());
+}
 
 int launch_pick_units(const PickUnitsParams& p, hipStream_t st) {
   if (p.units <= 0 || p.n_cand < 1 || p.n_cand > MOFQ_MAX_CANDIDATES) return MOFQ_ERR_INVALID_ARG;

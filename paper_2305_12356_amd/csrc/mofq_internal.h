@@ -92,6 +92,23 @@ struct EmitParams {
 };
 int launch_emit(const EmitParams& p, hipStream_t stream);
 
+// Tensor-level reduce + select + the per-unit outputs of the winner for several tensors in
+// one launch (one workgroup per tensor): the small dependent steps between the search and
+// the code emission, batched so that a model-wide pass does not pay their latency per
+// tensor.  Every tensor must have at most kFinishMaxUnits units.
+struct FinishParams {
+  DecideParams d;
+  int32_t scale_f16_out;
+  const float* scale[MOFQ_MAX_CANDIDATES];
+  const int32_t* clip[MOFQ_MAX_CANDIDATES];
+  void* out_scales;          // may be nullptr
+  int32_t* out_clip;         // may be nullptr
+  double* out_unit_err;      // may be nullptr
+};
+constexpr int kFinishBatch = 12;
+constexpr int64_t kFinishMaxUnits = 16 * 1024;
+int launch_finish_batch(const FinishParams* p, int n, hipStream_t stream);
+
 // Per unit: the first candidate with the strictly smallest error; writes its index and
 // its error.
 struct PickUnitsParams {

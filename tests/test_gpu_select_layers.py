@@ -1,0 +1,81 @@
+"""The batched weight-only select (mofq_select_layers) must give, tensor by tensor, exactly
+what mofq_select_layer gives (which the other tests hold to the oracle), and is also
+compared with the oracle directly on a few tensors."""
+import numpy as np
+import pytest
+import torch
+
+import mofq_inputs as mi
+from oracle import mofq_oracle as orc
+from tests.gpu_util import compare_quantized, scales_to_f32, unpack_codes
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def mq():
+    from paper_2305_12356_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def _single(mq, w, cands, cfg, bits):
+    out = mq.alloc_qbuffers(w.shape[0], w.shape[1], bits, cfg, DEV)
+    res = mq.alloc_result(DEV)
+    ws = torch.empty(mq.workspace_bytes(w, None, len(cands), mq.ERR_TENSOR, cfg), dtype=torch.uint8, device=DEV)
+    mq.select_layer(w, None, cands, mq.ERR_TENSOR, cfg, out, None, res, ws)
+    torch.cuda.synchronize()
+    return out, mq.read_result(res)
+
+
+@pytest.mark.parametrize("gran,group,f16,n_clip", [(orc.PER_CHANNEL, 0, False, 100), (orc.PER_CHANNEL, 0, True, 1),
+                                                   (orc.PER_GROUP, 128, True, 12), (orc.PER_TENSOR, 0, False, 3)])
+def test_batched_equals_single(mq, gran, group, f16, n_clip):
+    # 29 tensors: more than two batches, mixed shapes; group-wise ones above the per-launch unit limit too
+    shapes = [(7, 1024), (64, 4096), (3, 256), (300, 2048), (17, 11008)] * 5 + [(200, 12288), (5, 512), (1, 8 * 40), (130, 1536)]
+    shapes = [(r, c) for r, c in shapes if gran != orc.PER_GROUP or c % group == 0]
+    ws_ = [mi.llama_like_weight(r, c, seed=700 + i, device=DEV, outlier_frac=2e-3) for i, (r, c) in enumerate(shapes)]
+    cands = [mq.INT4, mq.FP4_E2M1]
+    cfg = mq.Cfg(gran, mi.clip_ratios(n_clip), group, f16)
+    outs = [mq.alloc_qbuffers(r, c, 4, cfg, DEV) for r, c in shapes]
+    batch = mq.LayerBatch(ws_, outs)
+    results = mq.alloc_result(DEV, len(shapes))
+    ws = torch.empty(batch.workspace_bytes(2, cfg), dtype=torch.uint8, device=DEV)
+    e0 = [torch.cuda.Event(enable_timing=True) for _ in shapes]
+    e1 = [torch.cuda.Event(enable_timing=True) for _ in shapes]
+    mq.select_layers(batch, cands, cfg, results, ws, None, e0, e1)
+    torch.cuda.synchronize()
+    assert all(a.elapsed_time(b) >= 0.0 for a, b in zip(e0, e1))
+    res = mq.read_results(results)
+    for i, w in enumerate(ws_):
+        ref_out, ref_res = _single(mq, w, cands, cfg, 4)
+        assert res[i].best == ref_res.best and list(res[i].err) == list(ref_res.err)
+        assert res[i].ref_energy == ref_res.ref_energy
+        assert torch.equal(outs[i].codes, ref_out.codes)
+        assert torch.equal(outs[i].scales, ref_out.scales)
+        assert torch.equal(outs[i].clip_idx, ref_out.clip_idx)
+        assert torch.equal(outs[i].unit_err, ref_out.unit_err)
+    # and against the oracle, directly
+    for i in (0, 3, len(shapes) - 1):
+        w32 = mi.to_f32_numpy(ws_[i])
+        clip = mi.clip_ratios(n_clip)
+        ref = orc.select_layer_w_only(w32, cands, gran, clip, group, f16, want_table=True)
+        assert res[i].best == ref.best
+        compare_quantized(w32, cands[ref.best], gran, group, f16, clip, ref.w,
+                          unpack_codes(outs[i].codes, *shapes[i], 4), scales_to_f32(outs[i].scales),
+                          outs[i].clip_idx.cpu().numpy(), outs[i].unit_err.cpu().numpy())
+
+
+def test_batched_rejects_before_enqueueing(mq):
+    w = [mi.llama_like_weight(8, 256, seed=1, device=DEV), mi.llama_like_weight(8, 252, seed=2, device=DEV)]
+    cfg = mq.Cfg(mq.PER_CHANNEL, mi.clip_ratios(2))
+    outs = [mq.alloc_qbuffers(8, 256, 4, cfg, DEV), mq.alloc_qbuffers(8, 256, 4, cfg, DEV)]
+    batch = mq.LayerBatch(w, outs)
+    assert batch.workspace_bytes(2, cfg) == 0 or True
+    results = mq.alloc_result(DEV, 2)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
+    with pytest.raises(mq.MofqError):        # second tensor: 252 columns is not a multiple of 8
+        mq.select_layers(batch, [mq.INT4, mq.FP4_E2M1], cfg, results, ws)
+    torch.cuda.synchronize()
