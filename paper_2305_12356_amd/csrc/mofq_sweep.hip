@@ -799,15 +799,29 @@ __global__ __launch_bounds__(256) void tensor_finalize_kernel(const SweepArgs a)
   const int tid = threadIdx.x;
   const int K = a.n_clip;
   const float amax = tensor_absmax(a, s_tmp);
-  // one wave per (format, candidate): partials in block order (lane-strided, then the
-  // fixed cross-lane order of wave_sum)
-  for (int idx = tid >> 6; idx < NF * K; idx += 4) {
-    const int f = idx / K, k = idx - f * K;
-    double t = 0.0;
-    for (int b = tid & 63; b < a.n_blocks; b += 64)
-      t += a.sse_part[(static_cast<int64_t>(b) * NF + f) * K + k];
-    t = wave_sum(t);
-    if ((tid & 63) == 0) s_tot[f][k] = t;
+  // Partials in a fixed order.  Few (format, candidate) pairs: the whole workgroup adds each
+  // of them; many: one wave per pair.
+  if (NF * K <= 4) {
+    for (int idx = 0; idx < NF * K; ++idx) {
+      const int f = idx / K, k = idx - f * K;
+      double t = 0.0;
+      for (int b = tid; b < a.n_blocks; b += 256)
+        t += a.sse_part[(static_cast<int64_t>(b) * NF + f) * K + k];
+      t = wave_sum(t);
+      __syncthreads();
+      if ((tid & 63) == 0) s_red[tid >> 6] = t;
+      __syncthreads();
+      if (tid == 0) s_tot[f][k] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+    }
+  } else {
+    for (int idx = tid >> 6; idx < NF * K; idx += 4) {
+      const int f = idx / K, k = idx - f * K;
+      double t = 0.0;
+      for (int b = tid & 63; b < a.n_blocks; b += 64)
+        t += a.sse_part[(static_cast<int64_t>(b) * NF + f) * K + k];
+      t = wave_sum(t);
+      if ((tid & 63) == 0) s_tot[f][k] = t;
+    }
   }
   double en = 0.0;
   for (int b = tid; b < a.n_blocks; b += 256) en += a.energy_part[b];
