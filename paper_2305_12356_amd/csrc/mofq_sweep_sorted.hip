@@ -23,6 +23,7 @@
 // Applies to 16-bit inputs (fp16 / bf16) and the 4-bit formats (16 levels); other
 // cases use the direct kernel in mofq_sweep.hip.
 #include <cmath>
+#include <type_traits>
 
 #include "mofq_device.h"
 #include "mofq_internal.h"
@@ -106,7 +107,8 @@ template <int FMT> MOFQ_DEV void rescore2(double& acc, float x0, float x1, float
 
 
 template <typename In, int FA, int FB, int THREADS, int CH>
-__global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs a) {
+// second bound: waves per SIMD that the LDS footprint of the instance allows
+__global__ __launch_bounds__(THREADS, (CH <= 2 ? 4 : 2)) void sweep_sorted_kernel(const SortedArgs a) {
   using L = Load8<In>;
   constexpr int NF = (FB >= 0) ? 2 : 1;
   constexpr int FBX = (FB >= 0) ? FB : FA;
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs 
   // The counters then hold the prefix sums (one exclusive prefix every BS positions).
   constexpr int KEYE = NP + NP / 32 + 16;                 // elements of one key buffer (padded layout + slack)
   constexpr int KEYB = KEYE * 2;
-  constexpr int CNTB = 16 * THREADS * 4;                  // bytes of the digit counters
+  constexpr int CNTB = 16 * THREADS * 4 + 16;             // bytes of the digit counters (+ the last prefix)
   constexpr int BS = (8 * (NP / 2 + 1) <= CNTB) ? 2 : ((8 * (NP / 4 + 1) <= CNTB) ? 4 : 8);
   constexpr int NBLK = NP / BS;
   static_assert(8 * (NBLK + 1) <= CNTB, "prefix sums do not fit");
@@ -143,10 +145,12 @@ __global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs 
   __shared__ float s_wmax[NW];
   __shared__ double s_wsum[3][NW];
   __shared__ double s_thr[NF];
-  __shared__ int s_list[MAXL];
+  __shared__ uint8_t s_list[MAXL];   // format * MOFQ_MAX_CLIP + candidate
   __shared__ int s_nlist;
   __shared__ double s_p2[NW];
   __shared__ double s_val[MAXL];
+  float* const s_cb = reinterpret_cast<float*>(s_val);   // level-square sums, before the re-score uses s_val
+  static_assert(MOFQ_MAX_CLIP * 2 <= 256, "shortlist entries are bytes");
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -202,11 +206,11 @@ __global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs 
   }
 
   // ---- LSD radix sort of the keys, 4 bits per pass; thread t owns positions [tE, tE+E) ---
-#pragma unroll 1
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = pass * 4;
-    const uint16_t* from = (pass & 1) ? s_keys1 : s_keys0;
-    uint16_t* to = (pass & 1) ? s_keys0 : s_keys1;
+  // LAST: the pass that writes the elements' bit patterns into the padded layout.
+  auto radix_pass = [&](auto last_tag, const int shift, const uint16_t* from, uint16_t* to) {
+    constexpr bool LAST = decltype(last_tag)::value;
+    constexpr int PER = THREADS / 64;   // counters of one digit per lane in the scan
+    constexpr int DPW = 16 / NW;        // digits scanned by one wave
 #pragma unroll
     for (int d = 0; d < 16; ++d) s_cnt[d][tid] = 0;
     uint32_t kreg[E / 2];
@@ -222,38 +226,54 @@ __global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs 
       atomicAdd(&s_cnt[(key >> shift) & 15u][tid], 1u);   // own column: plain LDS add
     }
     __syncthreads();
-    // per digit: exclusive scan of the counts across threads; digit totals aside
-    for (int d = wave; d < 16; d += NW) {
-      constexpr int PER = THREADS / 64;
-      uint32_t c[PER], sum = 0;
+    // per digit: exclusive scan of the counts across threads (kept in registers), digit totals aside
+    uint32_t c[DPW][PER], base[DPW];
 #pragma unroll
-      for (int i = 0; i < PER; ++i) { c[i] = s_cnt[d][lane * PER + i]; sum += c[i]; }
+    for (int m = 0; m < DPW; ++m) {
+      const int d = wave + m * NW;
+      uint32_t sum = 0;
+#pragma unroll
+      for (int i = 0; i < PER; ++i) { c[m][i] = s_cnt[d][lane * PER + i]; sum += c[m][i]; }
       uint32_t total;
-      uint32_t base = wave_excl_scan_u32(sum, total);
-#pragma unroll
-      for (int i = 0; i < PER; ++i) { s_cnt[d][lane * PER + i] = base; base += c[i]; }
+      base[m] = wave_excl_scan_u32(sum, total);
       if (lane == 0) s_dig_tot[d] = total;
     }
     __syncthreads();
-    // start of each digit's run, added to this thread's own counters
+    // start of each digit's run plus the scan: the first position of every (digit, thread)
     {
-      uint32_t run = 0;
+      uint32_t start[16], run = 0;
 #pragma unroll
-      for (int d = 0; d < 16; ++d) {
-        if (run) atomicAdd(&s_cnt[d][tid], run);
-        run += s_dig_tot[d];
+      for (int d = 0; d < 16; ++d) { start[d] = run; run += s_dig_tot[d]; }
+#pragma unroll
+      for (int m = 0; m < DPW; ++m) {
+        const int d = wave + m * NW;
+        uint32_t st = 0;
+#pragma unroll
+        for (int dd = 0; dd < 16; ++dd) st = (dd == d) ? start[dd] : st;   // wave-uniform pick
+        uint32_t bpos = base[m] + st;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) { s_cnt[d][lane * PER + i] = bpos; bpos += c[m][i]; }
       }
+    }
+    __syncthreads();
+    uint32_t pos[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const uint32_t key = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
+      pos[i] = atomicAdd(&s_cnt[(key >> shift) & 15u][tid], 1u);   // stable: thread order, then i
     }
 #pragma unroll
     for (int i = 0; i < E; ++i) {
       const uint32_t key = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
-      const uint32_t pos = atomicAdd(&s_cnt[(key >> shift) & 15u][tid], 1u);   // stable: thread order, then i
-      // last pass: back to bit patterns, into the padded layout
-      if (pass == 3) to[phys(static_cast<int>(pos))] = static_cast<uint16_t>(from_key(key));
-      else to[pos] = static_cast<uint16_t>(key);
+      if constexpr (LAST) to[phys(static_cast<int>(pos[i]))] = static_cast<uint16_t>(from_key(key));
+      else to[pos[i]] = static_cast<uint16_t>(key);
     }
     __syncthreads();
-  }
+  };
+#pragma unroll 1
+  for (int pass = 0; pass < 3; ++pass)
+    radix_pass(std::false_type{}, pass * 4, (pass & 1) ? s_keys1 : s_keys0, (pass & 1) ? s_keys0 : s_keys1);
+  radix_pass(std::true_type{}, 12, s_keys1, s_keys0);
   // Four passes: the result is back in the first buffer, as the elements' own bit
   // patterns in ascending order of value.  Padding became the pattern 0x7FFF (a NaN in
   // fp16 and bf16), which fails every "<= threshold" test; one more sits at [NP].
@@ -305,8 +325,9 @@ __global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs 
     const bool lane_live = (f < NF) && (b < a.nb[f]);
     const float thr = lane_live ? a.thr[f][b] : 0.0f;
     const double dg = lane_live ? static_cast<double>(a.dg[f][b]) : 0.0;
-    const double dg2 = lane_live ? static_cast<double>(a.dg2[f][b]) : 0.0;
-    const int steps = 32 - __builtin_clz(static_cast<unsigned>(n));   // 2^steps > n
+    const float dg2f = lane_live ? a.dg2[f][b] : 0.0f;
+    // 2^STEPS > row length: the probe offsets of the unrolled search are compile-time constants
+    constexpr int STEPS = 32 - __builtin_clz(static_cast<unsigned>(NP));
     const int fi = (f < NF) ? f : 0;
     for (int k0 = 0; k0 < K; k0 += HALVES * Q) {
       int kq[Q], ppos[Q];   // ppos: padded byte offset of the search position
@@ -319,11 +340,13 @@ __global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs 
       }
       // branch-free lower bound: position = number of elements on levels <= b.  Every
       // element before the position passes the test; the NaN padding stops it at n.
-      for (int stp = 1 << (steps - 1); stp > 0; stp >>= 1) {
-        const int probe = 2 * phys(stp - 1), inc = 2 * phys(stp);   // wave-uniform byte offsets
+#pragma unroll
+      for (int st = STEPS - 1; st >= 0; --st) {
+        const int stp = 1 << st;
+        const int probe = 2 * phys(stp - 1), inc = 2 * phys(stp);
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-          const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + (ppos[q] + probe));
+          const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + ppos[q] + probe);
           const float t = bits_to_float<In>(h) * inv[q];
           ppos[q] += (t <= thr) ? inc : 0;
         }
@@ -340,24 +363,31 @@ __global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs 
           const double val = static_cast<double>(bits_to_float<In>(sorted[in ? j0 + i : 0]));
           p += in ? val : 0.0;
         }
-        double ca = lane_live ? p * dg : 0.0;
+        // lanes without a boundary carry zero level differences
+        double ca = p * dg;
         // counts times level-square differences are small multiples of 1/4: exact in fp32
-        float cbf = lane_live ? static_cast<float>(j) * static_cast<float>(dg2) : 0.0f;
+        float cbf = static_cast<float>(j) * dg2f;
         ca = row16_sum(ca);
         cbf += dpp_f32<DPP_QUAD_XOR1>(cbf);
         cbf += dpp_f32<DPP_QUAD_XOR2>(cbf);
         cbf += dpp_f32<DPP_ROW_HALF_MIRROR>(cbf);
         cbf += dpp_f32<DPP_ROW_MIRROR>(cbf);
-        const double cb = static_cast<double>(cbf);
         if (b == 0 && f < NF && kq[q] < K) {
-          const double gl = static_cast<double>(a.g_last[f]);
-          const double A = ca + gl * s_total;
-          const double B = cb + gl * gl * static_cast<double>(n);
-          const double s = static_cast<double>(s_scale[f][kq[q]]);
-          s_fast[f][kq[q]] = (en - 2.0 * s * A) + s * s * B;
+          s_fast[f][kq[q]] = ca;
+          s_cb[f * MOFQ_MAX_CLIP + kq[q]] = cbf;
         }
       }
     }
+  }
+  __syncthreads();
+  // filtered error of every candidate from its two level sums
+  for (int idx = tid; idx < NF * K; idx += THREADS) {
+    const int f = idx / K, k = idx - f * K;
+    const double gl = static_cast<double>(a.g_last[f]);
+    const double A = s_fast[f][k] + gl * s_total;
+    const double B = static_cast<double>(s_cb[f * MOFQ_MAX_CLIP + k]) + gl * gl * static_cast<double>(n);
+    const double s = static_cast<double>(s_scale[f][k]);
+    s_fast[f][k] = (en - 2.0 * s * A) + s * s * B;
   }
   __syncthreads();
 
@@ -382,7 +412,7 @@ __global__ __launch_bounds__(THREADS) void sweep_sorted_kernel(const SortedArgs 
   __syncthreads();
   for (int idx = tid; idx < NF * K; idx += THREADS) {
     const int f = idx / K, k = idx - f * K;
-    if (!(s_fast[f][k] > s_thr[f])) s_list[atomicAdd(&s_nlist, 1)] = f * MOFQ_MAX_CLIP + k;   // any order
+    if (!(s_fast[f][k] > s_thr[f])) s_list[atomicAdd(&s_nlist, 1)] = static_cast<uint8_t>(f * MOFQ_MAX_CLIP + k);   // any order
   }
   __syncthreads();
   const int n_list = s_nlist;
