@@ -65,16 +65,22 @@ MOFQ_DEV constexpr int phys(int i) { return i + ((i >> 6) << 1); }
 // inverse on non-gap positions: 66 padded elements hold 64
 MOFQ_DEV int unphys(int p) { return p - 2 * static_cast<int>(__umulhi(static_cast<uint32_t>(p), 65075263u)); }
 
-// exclusive prefix over the wave (Hillis-Steele with shuffles), and the wave total
+// x plus the value the data-parallel-primitive control CTRL brings from another lane (0 where
+// the control has no source lane or ROW_MASK excludes the row)
+template <int CTRL, int ROW_MASK> MOFQ_DEV uint32_t dpp_add_u32(uint32_t x) {
+  return x + static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), CTRL, ROW_MASK, 0xf, false));
+}
+// exclusive prefix over the wave and the wave total: shifts by 1, 2, 4, 8 inside each row of
+// 16 lanes, then lane 15 of a row into the next row, then lane 31 into the upper half
 MOFQ_DEV uint32_t wave_excl_scan_u32(uint32_t v, uint32_t& total) {
-  const int lane = threadIdx.x & 63;
   uint32_t inc = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t o = __shfl_up(inc, off, 64);
-    if (lane >= off) inc += o;
-  }
-  total = __shfl(inc, 63, 64);
+  inc = dpp_add_u32<0x111, 0xf>(inc);   // row_shr:1
+  inc = dpp_add_u32<0x112, 0xf>(inc);   // row_shr:2
+  inc = dpp_add_u32<0x114, 0xf>(inc);   // row_shr:4
+  inc = dpp_add_u32<0x118, 0xf>(inc);   // row_shr:8
+  inc = dpp_add_u32<0x142, 0xa>(inc);   // row_bcast:15 into rows 1 and 3
+  inc = dpp_add_u32<0x143, 0xc>(inc);   // row_bcast:31 into rows 2 and 3
+  total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(inc), 63));
   return inc - v;
 }
 MOFQ_DEV double wave_excl_scan_f64(double v, double& total) {
@@ -241,16 +247,13 @@ __global__ __launch_bounds__(THREADS, (CH <= 2 ? 4 : 2)) void sweep_sorted_kerne
     __syncthreads();
     // start of each digit's run plus the scan: the first position of every (digit, thread)
     {
-      uint32_t start[16], run = 0;
-#pragma unroll
-      for (int d = 0; d < 16; ++d) { start[d] = run; run += s_dig_tot[d]; }
+      // lane d of every wave: first position of digit d
+      uint32_t unused;
+      const uint32_t start = wave_excl_scan_u32(lane < 16 ? s_dig_tot[lane & 15] : 0u, unused);
 #pragma unroll
       for (int m = 0; m < DPW; ++m) {
         const int d = wave + m * NW;
-        uint32_t st = 0;
-#pragma unroll
-        for (int dd = 0; dd < 16; ++dd) st = (dd == d) ? start[dd] : st;   // wave-uniform pick
-        uint32_t bpos = base[m] + st;
+        uint32_t bpos = base[m] + static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(start), d));
 #pragma unroll
         for (int i = 0; i < PER; ++i) { s_cnt[d][lane * PER + i] = bpos; bpos += c[m][i]; }
       }
