@@ -114,7 +114,7 @@ template <int FMT> MOFQ_DEV void rescore2(double& acc, float x0, float x1, float
 
 template <typename In, int FA, int FB, int THREADS, int CH>
 // second bound: waves per SIMD that the LDS footprint of the instance allows
-__global__ __launch_bounds__(THREADS, (CH <= 2 ? 4 : 2)) void sweep_sorted_kernel(const SortedArgs a) {
+__global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kernel(const SortedArgs a) {
   using L = Load8<In>;
   constexpr int NF = (FB >= 0) ? 2 : 1;
   constexpr int FBX = (FB >= 0) ? FB : FA;
@@ -127,23 +127,27 @@ __global__ __launch_bounds__(THREADS, (CH <= 2 ? 4 : 2)) void sweep_sorted_kerne
   // that 100 candidates fill whole rounds: 8 halves x 13 or 16 halves x 7
   constexpr int Q = (THREADS <= 256) ? 13 : 7;
 
-  // ---- LDS.  During the sort: two key buffers + digit counters.  The sorted row ends up
-  // in the first buffer in a padded layout (one 4-byte gap after every 64 elements, so that
-  // the power-of-two strides of a binary search do not all fall on one bank), followed by
-  // NaN sentinels up to twice the padded row length (the search may probe up to 2^steps - 2).
-  // The counters then hold the prefix sums (one exclusive prefix every BS positions).
-  constexpr int KEYE = NP + NP / 32 + 16;                 // elements of one key buffer (padded layout + slack)
+  // ---- LDS.  One key buffer, sorted in place (every pass holds all its keys in registers
+  // before the first one is written back), and the digit counters.  The sorted row ends up in
+  // a padded layout (one 4-byte gap after every 64 elements, so that the power-of-two strides
+  // of a binary search do not all fall on one bank).  The counters then hold the prefix sums
+  // (one exclusive prefix every BS positions).
+  constexpr bool NP_POW2 = (NP & (NP - 1)) == 0;
+  // first step of the boundary search; the padded row length is 2^k or 3 * 2^k
+  constexpr int FIRST = NP_POW2 ? NP / 2 : NP / 3;
+  static_assert((FIRST & (FIRST - 1)) == 0 && FIRST >= 64, "row length must be 2^k or 3 * 2^k");
+  constexpr int LSTEPS = 32 - __builtin_clz(static_cast<unsigned>(FIRST));   // steps FIRST, FIRST/2, .., 1
+  constexpr int KEYE = phys(NP) + 16;                      // elements of the key buffer (padded layout + slack)
   constexpr int KEYB = KEYE * 2;
   constexpr int CNTB = 16 * THREADS * 4 + 16;             // bytes of the digit counters (+ the last prefix)
   constexpr int BS = (8 * (NP / 2 + 1) <= CNTB) ? 2 : ((8 * (NP / 4 + 1) <= CNTB) ? 4 : 8);
   constexpr int NBLK = NP / BS;
   static_assert(8 * (NBLK + 1) <= CNTB, "prefix sums do not fit");
-  static_assert(KEYB % 16 == 0, "key buffers must stay 16-byte aligned");
-  __shared__ __attribute__((aligned(16))) unsigned char s_raw[2 * KEYB + CNTB];
-  uint16_t* const s_keys0 = reinterpret_cast<uint16_t*>(s_raw);
-  uint16_t* const s_keys1 = reinterpret_cast<uint16_t*>(s_raw + KEYB);
-  uint32_t (*const s_cnt)[THREADS] = reinterpret_cast<uint32_t (*)[THREADS]>(s_raw + 2 * KEYB);
-  double* const s_blk = reinterpret_cast<double*>(s_raw + 2 * KEYB);   // [NBLK + 1], valid after the sort
+  static_assert(KEYB % 16 == 0, "the counters must stay 16-byte aligned");
+  __shared__ __attribute__((aligned(16))) unsigned char s_raw[KEYB + CNTB];
+  uint16_t* const s_keys = reinterpret_cast<uint16_t*>(s_raw);
+  uint32_t (*const s_cnt)[THREADS] = reinterpret_cast<uint32_t (*)[THREADS]>(s_raw + KEYB);
+  double* const s_blk = reinterpret_cast<double*>(s_raw + KEYB);   // [NBLK + 1], valid after the sort
   __shared__ uint32_t s_dig_tot[16];
   __shared__ float s_scale[NF][MOFQ_MAX_CLIP];
   __shared__ float s_inv[NF][MOFQ_MAX_CLIP];
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 2 ? 4 : 2)) void sweep_sorted_kerne
       l1 += __builtin_fabs(d0) + __builtin_fabs(d1);
       keys[i] = ok ? (to_key(h0) | (to_key(h1) << 16)) : 0xFFFFFFFFu;   // padding sorts last
     }
-    *reinterpret_cast<u32x4*>(&s_keys0[tid * E + j * 8]) = keys;
+    *reinterpret_cast<u32x4*>(&s_keys[tid * E + j * 8]) = keys;
   }
   amax = wave_max(amax);
   en = wave_sum(en);
@@ -213,7 +217,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 2 ? 4 : 2)) void sweep_sorted_kerne
 
   // ---- LSD radix sort of the keys, 4 bits per pass; thread t owns positions [tE, tE+E) ---
   // LAST: the pass that writes the elements' bit patterns into the padded layout.
-  auto radix_pass = [&](auto last_tag, const int shift, const uint16_t* from, uint16_t* to) {
+  auto radix_pass = [&](auto last_tag, const int shift) {
     constexpr bool LAST = decltype(last_tag)::value;
     constexpr int PER = THREADS / 64;   // counters of one digit per lane in the scan
     constexpr int DPW = 16 / NW;        // digits scanned by one wave
@@ -222,7 +226,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 2 ? 4 : 2)) void sweep_sorted_kerne
     uint32_t kreg[E / 2];
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-      const u32x4 v = *reinterpret_cast<const u32x4*>(&from[tid * E + j * 8]);
+      const u32x4 v = *reinterpret_cast<const u32x4*>(&s_keys[tid * E + j * 8]);
 #pragma unroll
       for (int i = 0; i < 4; ++i) kreg[j * 4 + i] = v[i];
     }
@@ -268,20 +272,17 @@ __global__ __launch_bounds__(THREADS, (CH <= 2 ? 4 : 2)) void sweep_sorted_kerne
 #pragma unroll
     for (int i = 0; i < E; ++i) {
       const uint32_t key = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
-      if constexpr (LAST) to[phys(static_cast<int>(pos[i]))] = static_cast<uint16_t>(from_key(key));
-      else to[pos[i]] = static_cast<uint16_t>(key);
+      if constexpr (LAST) s_keys[phys(static_cast<int>(pos[i]))] = static_cast<uint16_t>(from_key(key));
+      else s_keys[pos[i]] = static_cast<uint16_t>(key);
     }
     __syncthreads();
   };
 #pragma unroll 1
-  for (int pass = 0; pass < 3; ++pass)
-    radix_pass(std::false_type{}, pass * 4, (pass & 1) ? s_keys1 : s_keys0, (pass & 1) ? s_keys0 : s_keys1);
-  radix_pass(std::true_type{}, 12, s_keys1, s_keys0);
-  // Four passes: the result is back in the first buffer, as the elements' own bit
-  // patterns in ascending order of value.  Padding became the pattern 0x7FFF (a NaN in
-  // fp16 and bf16), which fails every "<= threshold" test; one more sits at [NP].
-  const uint16_t* sorted = s_keys0;      // padded layout: element i at sorted[phys(i)]
-  for (int e = phys(NP) + tid; e < 2 * KEYE; e += THREADS) s_keys0[e] = 0x7FFFu;   // runs on into the second buffer
+  for (int pass = 0; pass < 3; ++pass) radix_pass(std::false_type{}, pass * 4);
+  radix_pass(std::true_type{}, 12);
+  // The buffer now holds the elements' own bit patterns in ascending order of value.  Padding
+  // became the pattern 0x7FFF (a NaN in fp16 and bf16), which fails every "<= threshold" test.
+  const uint16_t* sorted = s_keys;       // padded layout: element i at sorted[phys(i)]
 
   // ---- prefix sums of the sorted values: exclusive prefix at every BS-th position ----------
   {
@@ -329,34 +330,48 @@ __global__ __launch_bounds__(THREADS, (CH <= 2 ? 4 : 2)) void sweep_sorted_kerne
     const float thr = lane_live ? a.thr[f][b] : 0.0f;
     const double dg = lane_live ? static_cast<double>(a.dg[f][b]) : 0.0;
     const float dg2f = lane_live ? a.dg2[f][b] : 0.0f;
-    // 2^STEPS > row length: the probe offsets of the unrolled search are compile-time constants
-    constexpr int STEPS = 32 - __builtin_clz(static_cast<unsigned>(NP));
+    // Lower bound with the steps FIRST (twice when the row length is 3 * 2^k), FIRST/2, .., 1:
+    // they add up to NP - 1 and no probe leaves the row.  The last element is tested on its
+    // own afterwards.  Steps that are multiples of 64 or distinct smaller powers of two keep
+    // the padded offsets additive.
     const int fi = (f < NF) ? f : 0;
+    const float x_last = bits_to_float<In>(sorted[phys(NP - 1)]);
     for (int k0 = 0; k0 < K; k0 += HALVES * Q) {
-      int kq[Q], ppos[Q];   // ppos: padded byte offset of the search position
+      int kq[Q], ppos[Q];   // ppos: padded byte offset of the next probe; of the position at the end
       float inv[Q];
 #pragma unroll
       for (int q = 0; q < Q; ++q) {
         kq[q] = k0 + (tid >> 5) * Q + q;
         inv[q] = s_inv[fi][kq[q] < K ? kq[q] : K - 1];
-        ppos[q] = 0;
+        ppos[q] = 2 * phys(FIRST - 1);
       }
-      // branch-free lower bound: position = number of elements on levels <= b.  Every
-      // element before the position passes the test; the NaN padding stops it at n.
-#pragma unroll
-      for (int st = STEPS - 1; st >= 0; --st) {
-        const int stp = 1 << st;
-        const int probe = 2 * phys(stp - 1), inc = 2 * phys(stp);
+      // Branch-free: position = number of elements on levels <= b.  Every element before the
+      // position passes the test; the NaN padding stops it at n.  The offset of the next
+      // step's probe rides along in the position.
+      if constexpr (!NP_POW2) {
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-          const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + ppos[q] + probe);
+          const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + ppos[q]);
           const float t = bits_to_float<In>(h) * inv[q];
-          ppos[q] += (t <= thr) ? inc : 0;
+          ppos[q] += (t <= thr) ? 2 * phys(FIRST) : 0;
+        }
+      }
+#pragma unroll 1
+      for (int st = LSTEPS - 1; st >= 0; --st) {
+        const int stp = 1 << st;
+        const int next_probe = st > 0 ? 2 * phys((stp >> 1) - 1) : 0;
+        const int stay = next_probe - 2 * phys(stp - 1), go = stay + 2 * phys(stp);   // wave-uniform
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+          const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + ppos[q]);
+          const float t = bits_to_float<In>(h) * inv[q];
+          ppos[q] += (t <= thr) ? go : stay;
         }
       }
 #pragma unroll
       for (int q = 0; q < Q; ++q) {
-        const int j = unphys(ppos[q] >> 1);
+        int j = unphys(ppos[q] >> 1);
+        j += (j == NP - 1 && x_last * inv[q] <= thr) ? 1 : 0;
         constexpr int LB = (BS == 2) ? 1 : (BS == 4 ? 2 : 3);
         double p = s_blk[j >> LB];
         const int j0 = phys(j & ~(BS - 1));
