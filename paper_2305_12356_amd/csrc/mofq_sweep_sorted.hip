@@ -42,7 +42,7 @@ struct SortedArgs {
   float clip[MOFQ_MAX_CLIP];
   // per format slot: level(t) <= b  <=>  t <= thr[b];  levels ascending g_0 < g_1 < ...
   float thr[2][16];
-  float dg[2][16];    // g_b - g_{b+1}
+  double dgd[2][16];  // g_b - g_{b+1}
   float dg2[2][16];   // g_b^2 - g_{b+1}^2
   float g_last[2];    // largest level
   float g_absmax[2];  // largest |level|
@@ -122,10 +122,6 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   constexpr int E = CH * 8;            // keys per thread
   constexpr int NP = THREADS * E;      // padded row length
   constexpr int MAXL = NF * MOFQ_MAX_CLIP;
-  constexpr int HALVES = THREADS / 32; // candidates searched side by side (one per 32 lanes)
-  // candidates a lane searches at once (independent chains hide LDS latency); chosen so
-  // that 100 candidates fill whole rounds: 8 halves x 13 or 16 halves x 7
-  constexpr int Q = (THREADS <= 256) ? 13 : 7;
 
   // ---- LDS.  One key buffer, sorted in place (every pass holds all its keys in registers
   // before the first one is written back), and the digit counters.  The sorted row ends up in
@@ -159,7 +155,6 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   __shared__ int s_nlist;
   __shared__ double s_p2[NW];
   __shared__ double s_val[MAXL];
-  float* const s_cb = reinterpret_cast<float*>(s_val);   // level-square sums, before the re-score uses s_val
   static_assert(MOFQ_MAX_CLIP * 2 <= 256, "shortlist entries are bytes");
 
   const int tid = threadIdx.x;
@@ -323,37 +318,33 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   const double s_total = s_blk[NBLK];
 
   // ---- level boundaries of every candidate by binary search ------------------------------
+  // One lane per candidate, one wave per (format, 64 candidates); a lane walks the searches
+  // of all boundaries of its candidate side by side (independent chains hide the LDS latency)
+  // and adds up the two level sums itself.  Thresholds and level differences are wave-uniform.
   {
-    const int b = lane & 15;
-    const int f = (lane >> 4) & 1;
-    const bool lane_live = (f < NF) && (b < a.nb[f]);
-    const float thr = lane_live ? a.thr[f][b] : 0.0f;
-    const double dg = lane_live ? static_cast<double>(a.dg[f][b]) : 0.0;
-    const float dg2f = lane_live ? a.dg2[f][b] : 0.0f;
+    constexpr int NBD = 15;                 // boundaries of a 16-level format; unused ones carry zeros
     // Lower bound with the steps FIRST (twice when the row length is 3 * 2^k), FIRST/2, .., 1:
     // they add up to NP - 1 and no probe leaves the row.  The last element is tested on its
     // own afterwards.  Steps that are multiples of 64 or distinct smaller powers of two keep
     // the padded offsets additive.
-    const int fi = (f < NF) ? f : 0;
     const float x_last = bits_to_float<In>(sorted[phys(NP - 1)]);
-    for (int k0 = 0; k0 < K; k0 += HALVES * Q) {
-      int kq[Q], ppos[Q];   // ppos: padded byte offset of the next probe; of the position at the end
-      float inv[Q];
+    const int chunks = (K + 63) >> 6;
+    for (int u = wave; u < NF * chunks; u += NW) {
+      const int f = u / chunks;                       // wave-uniform
+      const int k = (u - f * chunks) * 64 + lane;
+      const float inv = s_inv[f][k < K ? k : K - 1];
+      int ppos[NBD];   // padded byte offset of the next probe; of the position at the end
 #pragma unroll
-      for (int q = 0; q < Q; ++q) {
-        kq[q] = k0 + (tid >> 5) * Q + q;
-        inv[q] = s_inv[fi][kq[q] < K ? kq[q] : K - 1];
-        ppos[q] = 2 * phys(FIRST - 1);
-      }
-      // Branch-free: position = number of elements on levels <= b.  Every element before the
+      for (int q = 0; q < NBD; ++q) ppos[q] = 2 * phys(FIRST - 1);
+      // Branch-free: position = number of elements on levels <= q.  Every element before the
       // position passes the test; the NaN padding stops it at n.  The offset of the next
       // step's probe rides along in the position.
       if constexpr (!NP_POW2) {
 #pragma unroll
-        for (int q = 0; q < Q; ++q) {
+        for (int q = 0; q < NBD; ++q) {
           const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + ppos[q]);
-          const float t = bits_to_float<In>(h) * inv[q];
-          ppos[q] += (t <= thr) ? 2 * phys(FIRST) : 0;
+          const float t = bits_to_float<In>(h) * inv;
+          ppos[q] += (t <= a.thr[f][q]) ? 2 * phys(FIRST) : 0;
         }
       }
 #pragma unroll 1
@@ -362,16 +353,19 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
         const int next_probe = st > 0 ? 2 * phys((stp >> 1) - 1) : 0;
         const int stay = next_probe - 2 * phys(stp - 1), go = stay + 2 * phys(stp);   // wave-uniform
 #pragma unroll
-        for (int q = 0; q < Q; ++q) {
+        for (int q = 0; q < NBD; ++q) {
           const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + ppos[q]);
-          const float t = bits_to_float<In>(h) * inv[q];
-          ppos[q] += (t <= thr) ? go : stay;
+          const float t = bits_to_float<In>(h) * inv;
+          ppos[q] += (t <= a.thr[f][q]) ? go : stay;
         }
       }
+      const float t_last = x_last * inv;
+      double ca = 0.0;
+      float cb = 0.0f;   // counts times level-square differences are small multiples of 1/4: exact in fp32
 #pragma unroll
-      for (int q = 0; q < Q; ++q) {
+      for (int q = 0; q < NBD; ++q) {
         int j = unphys(ppos[q] >> 1);
-        j += (j == NP - 1 && x_last * inv[q] <= thr) ? 1 : 0;
+        j += (j == NP - 1 && t_last <= a.thr[f][q]) ? 1 : 0;
         constexpr int LB = (BS == 2) ? 1 : (BS == 4 ? 2 : 3);
         double p = s_blk[j >> LB];
         const int j0 = phys(j & ~(BS - 1));
@@ -381,31 +375,17 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
           const double val = static_cast<double>(bits_to_float<In>(sorted[in ? j0 + i : 0]));
           p += in ? val : 0.0;
         }
-        // lanes without a boundary carry zero level differences
-        double ca = p * dg;
-        // counts times level-square differences are small multiples of 1/4: exact in fp32
-        float cbf = static_cast<float>(j) * dg2f;
-        ca = row16_sum(ca);
-        cbf += dpp_f32<DPP_QUAD_XOR1>(cbf);
-        cbf += dpp_f32<DPP_QUAD_XOR2>(cbf);
-        cbf += dpp_f32<DPP_ROW_HALF_MIRROR>(cbf);
-        cbf += dpp_f32<DPP_ROW_MIRROR>(cbf);
-        if (b == 0 && f < NF && kq[q] < K) {
-          s_fast[f][kq[q]] = ca;
-          s_cb[f * MOFQ_MAX_CLIP + kq[q]] = cbf;
-        }
+        ca += p * a.dgd[f][q];
+        cb += static_cast<float>(j) * a.dg2[f][q];
+      }
+      if (k < K) {
+        const double gl = static_cast<double>(a.g_last[f]);
+        const double A = ca + gl * s_total;
+        const double B = static_cast<double>(cb) + gl * gl * static_cast<double>(n);
+        const double sc = static_cast<double>(s_scale[f][k]);
+        s_fast[f][k] = (en - 2.0 * sc * A) + sc * sc * B;   // filtered error
       }
     }
-  }
-  __syncthreads();
-  // filtered error of every candidate from its two level sums
-  for (int idx = tid; idx < NF * K; idx += THREADS) {
-    const int f = idx / K, k = idx - f * K;
-    const double gl = static_cast<double>(a.g_last[f]);
-    const double A = s_fast[f][k] + gl * s_total;
-    const double B = static_cast<double>(s_cb[f * MOFQ_MAX_CLIP + k]) + gl * gl * static_cast<double>(n);
-    const double s = static_cast<double>(s_scale[f][k]);
-    s_fast[f][k] = (en - 2.0 * s * A) + s * s * B;
   }
   __syncthreads();
 
@@ -515,13 +495,13 @@ void fill_levels(int fmt, SortedArgs& a, int slot) {
   a.nb[slot] = nl - 1;
   a.g_last[slot] = static_cast<float>(lv[nl - 1]);
   a.g_absmax[slot] = static_cast<float>(std::fmax(std::fabs(lv[0]), std::fabs(lv[nl - 1])));
-  for (int b = 0; b < 16; ++b) { a.thr[slot][b] = 0.0f; a.dg[slot][b] = 0.0f; a.dg2[slot][b] = 0.0f; }
+  for (int b = 0; b < 16; ++b) { a.thr[slot][b] = 0.0f; a.dgd[slot][b] = 0.0; a.dg2[slot][b] = 0.0f; }
   for (int b = 0; b + 1 < nl; ++b) {
     const float mid = static_cast<float>(0.5 * (lv[b] + lv[b + 1]));   // exact in fp32
     // tie goes up  -> level <= b needs t <  mid -> t <= the float just below mid
     // tie goes down-> level <= b needs t <= mid
     a.thr[slot][b] = up_is_even[b] ? std::nextafterf(mid, -INFINITY) : mid;
-    a.dg[slot][b] = static_cast<float>(lv[b] - lv[b + 1]);
+    a.dgd[slot][b] = lv[b] - lv[b + 1];
     a.dg2[slot][b] = static_cast<float>(lv[b] * lv[b] - lv[b + 1] * lv[b + 1]);
   }
 }
