@@ -151,6 +151,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   __shared__ float s_wmax[NW];
   __shared__ double s_wsum[3][NW];
   __shared__ double s_thr[NF];
+  __shared__ int s_direct[NF];   // the winning candidate where no element-wise pass is needed, else -1
   __shared__ uint8_t s_list[MAXL];   // format * MOFQ_MAX_CLIP + candidate
   __shared__ int s_nlist;
   __shared__ double s_p2[NW];
@@ -390,27 +391,48 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   __syncthreads();
 
   // ---- shortlist: candidates the filter cannot separate from the best ---------------------
-  // |filtered - exact| <= ~3e4 * 2^-53 * (sum x^2 + 2 s g_max sum|x| + s^2 g_max^2 n); the
-  // margin below is 2^-34 of that magnitude (about 15 times the bound).
+  // Rounding of the filtered error, with u = 2^-53.  Every prefix sum comes from a summation
+  // tree of depth at most D = 2E + 32 (thread-sequential, wave scan, across waves) and is off
+  // by at most D u sum|x|; the level differences of one format add up to less than 16 and the
+  // largest level is at most 8, so the level sum A is off by less than 32 D u sum|x| including
+  // its own 15 additions.  The energy is off by (E + 14) u sum x^2; counts, level squares and
+  // s^2 are exact; the remaining products and additions round a handful of times on terms
+  // bounded by the three summands.  Hence
+  //   |filtered - exact| <= beta = u (40 D * 2 s sum|x| + (E + 32) sum x^2 + 8 s^2 g_max^2 n).
+  // The shortlist margin is far wider: 2^-33 of sum x^2 + 2 s g_max sum|x| + s^2 g_max^2 n.
+  // A format whose shortlist is a single candidate has its winner already; when beta is below
+  // 2^-34 of that candidate's filtered error, the filtered error is reported as it stands and
+  // the element-wise pass is skipped for the format.
   for (int f = wave; f < NF; f += NW) {
     double m = __builtin_inf();
+    int km = 0;
     float smax = 0.0f;
     for (int k = lane; k < K; k += 64) {
-      m = __builtin_fmin(m, s_fast[f][k]);
+      const double v = s_fast[f][k];
+      if (v < m) { m = v; km = k; }
       smax = __builtin_fmaxf(smax, s_scale[f][k]);
     }
-    int dummy = 0;
-    wave_argmin(m, dummy);
+    wave_argmin(m, km);
     smax = wave_max(smax);
     const double sm = static_cast<double>(smax), gm = static_cast<double>(a.g_absmax[f]);
-    const double mag = en + 2.0 * sm * gm * l1 + sm * sm * gm * gm * static_cast<double>(n);
-    if (lane == 0) s_thr[f] = m + 0x1p-33 * mag;   // twice the margin: both values carry the error
+    const double nd = static_cast<double>(n);
+    const double mag = en + 2.0 * sm * gm * l1 + sm * sm * gm * gm * nd;
+    const double thr = m + 0x1p-33 * mag;   // twice the margin: both values carry the error
+    int cnt = 0;
+    for (int k0 = 0; k0 < K; k0 += 64) {
+      const int k = k0 + lane;
+      cnt += __builtin_popcountll(__ballot(k < K && !(s_fast[f][k < K ? k : 0] > thr)));
+    }
+    const double beta = 0x1p-53 * (40.0 * (2 * E + 32) * 2.0 * sm * l1 + (E + 32) * en + 8.0 * sm * sm * gm * gm * nd);
+    const bool direct = cnt == 1 && beta <= 0x1p-34 * m;   // false for a zero or non-finite error
+    if (lane == 0) { s_thr[f] = thr; s_direct[f] = direct ? km : -1; }
   }
   if (tid == 0) s_nlist = 0;
   __syncthreads();
   for (int idx = tid; idx < NF * K; idx += THREADS) {
     const int f = idx / K, k = idx - f * K;
-    if (!(s_fast[f][k] > s_thr[f])) s_list[atomicAdd(&s_nlist, 1)] = static_cast<uint8_t>(f * MOFQ_MAX_CLIP + k);   // any order
+    if (s_direct[f] < 0 && !(s_fast[f][k] > s_thr[f]))
+      s_list[atomicAdd(&s_nlist, 1)] = static_cast<uint8_t>(f * MOFQ_MAX_CLIP + k);   // any order
   }
   __syncthreads();
   const int n_list = s_nlist;
@@ -454,7 +476,8 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   if (tid < NF) {
     const int f = tid;
     double best = __builtin_inf();
-    int bk = -1;
+    int bk = s_direct[f];
+    if (bk >= 0) best = s_fast[f][bk];
     for (int e = 0; e < n_list; ++e) {   // smallest error, then smallest index: the first smallest
       const int fk = s_list[e];
       if (fk / MOFQ_MAX_CLIP != f) continue;
