@@ -8,17 +8,19 @@
 //   sum (x - g s)^2 = sum x^2  -  2 s * sum_L g_L * S_L  +  s^2 * sum_L g_L^2 * n_L ,
 //
 // with S_L, n_L the sum and count of the elements on level L.  The kernel sorts the
-// row once (LDS radix sort of the 16-bit patterns), builds prefix sums of the sorted
-// values, and finds every level boundary of every candidate by binary search with
+// row once (in-place LDS radix sort of the 16-bit patterns), builds prefix sums of the
+// sorted values, and finds every level boundary of every candidate by binary search with
 // the exact fp32 decision arithmetic (t = fl32(x * fl32(1/s)) against the rounding
 // threshold of the boundary).  That is O(n log n + K * levels * log n) per row
 // instead of O(n * K).
 //
-// The formula cancels (the error is ~1 % of sum x^2) and is only used as a filter:
-// every candidate whose filtered error is within a rigorous bound of the smallest is
-// re-scored element by element in fp64, exactly like the direct kernel, and the
-// first smallest of those wins.  Exact ties (zero error on several candidates) and
-// the reported unit error therefore come from the element-wise arithmetic.
+// The formula cancels (the error is a few per cent of sum x^2), so it serves as a filter
+// with a rigorous rounding bound: every candidate whose filtered error is within a wide
+// margin of the smallest is shortlisted.  Where the shortlist of a format is one candidate
+// and the bound is below 2^-34 of its filtered error, that value is the reported error.
+// Otherwise (several candidates, exact ties, zero or tiny errors, non-finite input) the
+// shortlist is re-scored element by element in fp64, exactly like the direct kernel, and
+// the first smallest wins.
 //
 // Applies to 16-bit inputs (fp16 / bf16) and the 4-bit formats (16 levels); other
 // cases use the direct kernel in mofq_sweep.hip.

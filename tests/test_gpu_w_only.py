@@ -96,6 +96,22 @@ def test_per_channel_other_dtypes(mq, dtype):
     check_tensor(mq, w, [orc.INT4, orc.FP4_E2M1], orc.PER_CHANNEL, mi.clip_ratios(33), label="dtype")
 
 
+def test_repeated_and_dense_clip_ratios(mq):
+    """Clip tables whose candidates tie exactly (repeats) or differ by a few ulp: the winner of
+    each row has rivals within any rounding margin, so the sorted search has to settle them
+    element by element; rows of several tilings, wide (|x| >= 2) and narrow magnitudes."""
+    w = mi.llama_like_weight(11, 4096, seed=21, device=DEV)
+    w[3] *= 64.0
+    base = mi.clip_ratios(12)
+    rep = np.repeat(base, 2)[:20].astype(np.float32)
+    check_tensor(mq, w, [orc.INT4, orc.FP4_E2M1], orc.PER_CHANNEL, rep, label="repeats")
+    dense = np.array([np.nextafter(np.float32(0.8), np.float32(1.0 if i % 2 else 0.0)) for i in range(4)]
+                     + [0.8] * 4 + list(base), dtype=np.float32)
+    check_tensor(mq, w, [orc.INT4, orc.FP4_E2M1], orc.PER_CHANNEL, dense, label="dense")
+    w2 = mi.llama_like_weight(5, 11008, seed=22, device=DEV)
+    check_tensor(mq, w2, [orc.FP4_E2M1, orc.INT4], orc.PER_CHANNEL, rep, label="repeats-11008")
+
+
 def test_candidate_order_and_single_candidate(mq):
     w = mi.llama_like_weight(9, 1024, seed=8, device=DEV)
     clip = mi.clip_ratios(10)
