@@ -2,6 +2,7 @@
 // No device memory is allocated here and nothing synchronises.
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 
 #include "mofq_internal.h"
 
@@ -516,6 +517,45 @@ int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, i
   return MOFQ_ERR_INVALID_ARG;
 }
 
+namespace {
+
+// A second stream per device for mofq_select_layers: the memory-bound tail of a batch (select,
+// code emission) runs beside the ALU-bound searches of the next batch.  Default priority;
+// created on first use and kept until the process ends.
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+};
+constexpr int kMaxDevices = 64;
+SideStream g_side[kMaxDevices];
+std::mutex g_side_mu;       // creation
+std::mutex g_side_use_mu;   // the fork / join events are shared: one enqueueing call at a time
+
+int side_stream(SideStream** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOFQ_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_side_mu);
+  SideStream& s = g_side[dev];
+  if (!s.stream) {
+    hipStream_t st = nullptr;
+    hipEvent_t a = nullptr, b = nullptr;
+    if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return MOFQ_ERR_HIP;
+    if (hipEventCreateWithFlags(&a, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&b, hipEventDisableTiming) != hipSuccess) {
+      if (a) (void)hipEventDestroy(a);
+      (void)hipStreamDestroy(st);
+      return MOFQ_ERR_HIP;
+    }
+    s.stream = st;
+    s.fork = a;
+    s.join = b;
+  }
+  *out = &s;
+  return MOFQ_OK;
+}
+
+}  // namespace
+
 size_t mofq_select_layers_workspace_bytes(int32_t n_layers, const mofq_tensor_t* w,
                                           int32_t n_candidates, const mofq_scale_cfg_t* w_cfg) {
   if (n_layers < 1 || !w) return 0;
@@ -552,6 +592,18 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
   const size_t need = mofq_select_layers_workspace_bytes(n_layers, w, n_candidates, w_cfg);
   if (!ws || !need || ws_bytes < need || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  SideStream* side = nullptr;
+  if ((rc = side_stream(&side))) return rc;
+  hipStream_t st2 = side->stream;
+  std::lock_guard<std::mutex> enqueue_lock(g_side_use_mu);
+  bool forked = false;
+  // whatever happens after the first fork, the caller's stream waits for the side stream
+  auto join = [&](int status) {
+    if (!forked) return status;
+    if (hipEventRecord(side->join, st2) != hipSuccess || hipStreamWaitEvent(st, side->join, 0) != hipSuccess)
+      return status ? status : static_cast<int>(MOFQ_ERR_HIP);
+    return status;
+  };
 
   auto emit_params = [&](int i, const WOnlyWs& s) {
     EmitParams e{};
@@ -597,9 +649,9 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
       const int64_t units = mofq_num_units(w[i].rows, w[i].cols, w_cfg->gran, w_cfg->group_size);
       slot[j] = carve_w_only(base, units, n_candidates, w_cfg->gran, w_cfg->n_clip);
       base += slot[j].bytes;
-      if (ev_begin && hipEventRecord(static_cast<hipEvent_t>(ev_begin[i]), st) != hipSuccess) return MOFQ_ERR_HIP;
-      if ((rc = sweep_candidates(&w[i], candidates, n_candidates, w_cfg, slot[j], st))) return rc;
-      if (ev_end && hipEventRecord(static_cast<hipEvent_t>(ev_end[i]), st) != hipSuccess) return MOFQ_ERR_HIP;
+      if (ev_begin && hipEventRecord(static_cast<hipEvent_t>(ev_begin[i]), st) != hipSuccess) return join(MOFQ_ERR_HIP);
+      if ((rc = sweep_candidates(&w[i], candidates, n_candidates, w_cfg, slot[j], st))) return join(rc);
+      if (ev_end && hipEventRecord(static_cast<hipEvent_t>(ev_end[i]), st) != hipSuccess) return join(MOFQ_ERR_HIP);
       DecideParams d{};
       d.units = units;
       d.n_cand = n_candidates;
@@ -619,23 +671,29 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
         fin_of[n_fin++] = j;
       } else {
         // many units (group-wise scales): the two-stage reduce and the per-unit kernel of the single-tensor path
-        if ((rc = launch_decide(d, st))) return rc;
-        if ((rc = launch_emit(emit_params(i, slot[j]), st))) return rc;
+        if ((rc = launch_decide(d, st))) return join(rc);
+        if ((rc = launch_emit(emit_params(i, slot[j]), st))) return join(rc);
       }
     }
-    // 2. reduce + select + per-unit outputs of the batch, one launch
-    if (n_fin && (rc = launch_finish_batch(fin, n_fin, st))) return rc;
-    // 3. the codes of the winners
-    for (int q = 0; q < n_fin; ++q) {
-      const int j = fin_of[q];
-      EmitParams e = emit_params(i0 + j, slot[j]);
-      e.out.scales = nullptr;
-      e.out.clip_idx = nullptr;
-      e.out.unit_err = nullptr;
-      if ((rc = launch_emit(e, st))) return rc;
+    // 2. on the side stream, once the batch's searches are done: reduce + select + per-unit
+    //    outputs of the batch in one launch, then the codes of the winners.  The next batch's
+    //    searches follow on the caller's stream meanwhile; every tensor has its own workspace.
+    if (n_fin) {
+      if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(st2, side->fork, 0) != hipSuccess)
+        return join(MOFQ_ERR_HIP);
+      forked = true;
+      if ((rc = launch_finish_batch(fin, n_fin, st2))) return join(rc);
+      for (int q = 0; q < n_fin; ++q) {
+        const int j = fin_of[q];
+        EmitParams e = emit_params(i0 + j, slot[j]);
+        e.out.scales = nullptr;
+        e.out.clip_idx = nullptr;
+        e.out.unit_err = nullptr;
+        if ((rc = launch_emit(e, st2))) return join(rc);
+      }
     }
   }
-  return MOFQ_OK;
+  return join(MOFQ_OK);
 }
 
 int mofq_calibrate_absmax(const mofq_tensor_t* x, float* absmax, void* ws, size_t ws_bytes,
