@@ -424,6 +424,7 @@ def main():
     ws = torch.empty(batch.workspace_bytes(len(cands), cfg), dtype=torch.uint8, device=dev)
     n_elems = sum(o * n for _, _, o, n in shapes)
     stream = torch.cuda.current_stream()
+    side = torch.cuda.Stream()   # default priority: select + code emission beside the next batch's searches
 
     # the events the library records around each search launch, created (and recorded once,
     # so that they exist) before the timed region
@@ -440,7 +441,7 @@ def main():
         if events is not None:
             e0, e1 = ev_pool.pop()
             events.extend((i, a, b) for i, (a, b) in enumerate(zip(e0, e1)))
-        mq.select_layers(batch, cands, cfg, results, ws, stream, e0, e1)
+        mq.select_layers(batch, cands, cfg, results, ws, stream, e0, e1, side_stream=side)
 
     for _ in range(args.warmup):
         step()

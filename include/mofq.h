@@ -204,20 +204,22 @@ int mofq_select_layer(const mofq_tensor_t* w, const mofq_tensor_t* x,
  *   ev_begin / ev_end (the _timed variant; may be NULL): HOST arrays of n_layers hipEvent_t,
  *   recorded around the search of each tensor.
  * Workspace: mofq_select_layers_workspace_bytes (the tensors' workspaces side by side).
- * Streams: the searches are enqueued on `stream`; the select and the code emission of a
- * batch run on a second stream that the library keeps per device (default priority, created
- * on first use), beside the searches of the next batch.  Both are ordered after the work
- * already on `stream`, and `stream` waits for the second stream before the call returns, so
- * the caller sees single-stream semantics.
+ * Streams: `side_stream` (a hipStream_t of the caller, default priority; may be NULL or equal
+ * to `stream`) lets the select and the code emission of a batch run beside the searches of
+ * the next batch, which stay on `stream`.  The side work is ordered after the work already
+ * on `stream`, and `stream` waits for it before the call returns, so the caller sees
+ * single-stream semantics on `stream`; `side_stream` must not be used by another call at the
+ * same time.  The library creates two events for the duration of the call and nothing else.
  */
 int mofq_select_layers(int32_t n_layers, const mofq_tensor_t* w, const int32_t* candidates,
                        int32_t n_candidates, const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
-                       mofq_result_t* results, void* ws, size_t ws_bytes, void* stream);
+                       mofq_result_t* results, void* ws, size_t ws_bytes, void* stream,
+                       void* side_stream);
 int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int32_t* candidates,
                              int32_t n_candidates, const mofq_scale_cfg_t* w_cfg,
                              const mofq_qout_t* w_out, mofq_result_t* results, void* ws,
-                             size_t ws_bytes, void* stream, void* const* ev_begin,
-                             void* const* ev_end);
+                             size_t ws_bytes, void* stream, void* side_stream,
+                             void* const* ev_begin, void* const* ev_end);
 size_t mofq_select_layers_workspace_bytes(int32_t n_layers, const mofq_tensor_t* w,
                                           int32_t n_candidates, const mofq_scale_cfg_t* w_cfg);
 

@@ -83,7 +83,7 @@ def _load():
     L.mofq_select_units_workspace_bytes.argtypes = [C.POINTER(TensorDesc), C.c_int32, C.POINTER(ScaleCfg)]
     L.mofq_select_layers.restype = C.c_int
     L.mofq_select_layers.argtypes = [C.c_int32, C.POINTER(TensorDesc), C.POINTER(C.c_int32), C.c_int32,
-                                     C.POINTER(ScaleCfg), C.POINTER(QOut), vp, vp, C.c_size_t, vp]
+                                     C.POINTER(ScaleCfg), C.POINTER(QOut), vp, vp, C.c_size_t, vp, vp]
     L.mofq_select_layers_timed.restype = C.c_int
     L.mofq_select_layers_timed.argtypes = L.mofq_select_layers.argtypes + [C.POINTER(vp), C.POINTER(vp)]
     L.mofq_select_layers_workspace_bytes.restype = C.c_size_t
@@ -299,12 +299,15 @@ class LayerBatch:
 
 
 def select_layers(batch: LayerBatch, candidates: Sequence[int], cfg: Cfg, results: torch.Tensor,
-                  ws: torch.Tensor, stream=None, ev_begin=None, ev_end=None) -> None:
+                  ws: torch.Tensor, stream=None, ev_begin=None, ev_end=None, side_stream=None) -> None:
     """mofq_select_layers (or _timed with lists of torch.cuda.Event): weight-only select of
-    every tensor of the batch; `results` is the device array from alloc_result(device, n)."""
+    every tensor of the batch; `results` is the device array from alloc_result(device, n).
+    `side_stream`: a torch.cuda.Stream for the select + emission of each batch (None: all on
+    `stream`)."""
     cand = (C.c_int32 * len(candidates))(*candidates)
+    side = C.c_void_p(side_stream.cuda_stream) if side_stream is not None else C.c_void_p(0)
     args = (batch.n, batch.w, cand, len(candidates), C.byref(cfg.c), batch.out, _ptr(results), _ptr(ws),
-            ws.numel() * ws.element_size(), _stream_handle(stream))
+            ws.numel() * ws.element_size(), _stream_handle(stream), side)
     if ev_begin is None:
         rc = _lib.mofq_select_layers(*args)
     else:

@@ -2,7 +2,6 @@
 // No device memory is allocated here and nothing synchronises.
 #include <algorithm>
 #include <cstring>
-#include <mutex>
 
 #include "mofq_internal.h"
 
@@ -517,45 +516,6 @@ int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, i
   return MOFQ_ERR_INVALID_ARG;
 }
 
-namespace {
-
-// A second stream per device for mofq_select_layers: the memory-bound tail of a batch (select,
-// code emission) runs beside the ALU-bound searches of the next batch.  Default priority;
-// created on first use and kept until the process ends.
-struct SideStream {
-  hipStream_t stream = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr;
-};
-constexpr int kMaxDevices = 64;
-SideStream g_side[kMaxDevices];
-std::mutex g_side_mu;       // creation
-std::mutex g_side_use_mu;   // the fork / join events are shared: one enqueueing call at a time
-
-int side_stream(SideStream** out) {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOFQ_ERR_HIP;
-  std::lock_guard<std::mutex> lock(g_side_mu);
-  SideStream& s = g_side[dev];
-  if (!s.stream) {
-    hipStream_t st = nullptr;
-    hipEvent_t a = nullptr, b = nullptr;
-    if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return MOFQ_ERR_HIP;
-    if (hipEventCreateWithFlags(&a, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&b, hipEventDisableTiming) != hipSuccess) {
-      if (a) (void)hipEventDestroy(a);
-      (void)hipStreamDestroy(st);
-      return MOFQ_ERR_HIP;
-    }
-    s.stream = st;
-    s.fork = a;
-    s.join = b;
-  }
-  *out = &s;
-  return MOFQ_OK;
-}
-
-}  // namespace
-
 size_t mofq_select_layers_workspace_bytes(int32_t n_layers, const mofq_tensor_t* w,
                                           int32_t n_candidates, const mofq_scale_cfg_t* w_cfg) {
   if (n_layers < 1 || !w) return 0;
@@ -570,16 +530,17 @@ size_t mofq_select_layers_workspace_bytes(int32_t n_layers, const mofq_tensor_t*
 
 int mofq_select_layers(int32_t n_layers, const mofq_tensor_t* w, const int32_t* candidates,
                        int32_t n_candidates, const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
-                       mofq_result_t* results, void* ws, size_t ws_bytes, void* stream) {
+                       mofq_result_t* results, void* ws, size_t ws_bytes, void* stream,
+                       void* side_stream) {
   return mofq_select_layers_timed(n_layers, w, candidates, n_candidates, w_cfg, w_out, results, ws,
-                                  ws_bytes, stream, nullptr, nullptr);
+                                  ws_bytes, stream, side_stream, nullptr, nullptr);
 }
 
 int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int32_t* candidates,
                              int32_t n_candidates, const mofq_scale_cfg_t* w_cfg,
                              const mofq_qout_t* w_out, mofq_result_t* results, void* ws,
-                             size_t ws_bytes, void* stream, void* const* ev_begin,
-                             void* const* ev_end) {
+                             size_t ws_bytes, void* stream, void* side_stream,
+                             void* const* ev_begin, void* const* ev_end) {
   if (n_layers < 1 || !w || !w_out || !results) return MOFQ_ERR_INVALID_ARG;
   int rc = check_candidates(candidates, n_candidates);
   if (rc) return rc;
@@ -592,16 +553,29 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
   const size_t need = mofq_select_layers_workspace_bytes(n_layers, w, n_candidates, w_cfg);
   if (!ws || !need || ws_bytes < need || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  SideStream* side = nullptr;
-  if ((rc = side_stream(&side))) return rc;
-  hipStream_t st2 = side->stream;
-  std::lock_guard<std::mutex> enqueue_lock(g_side_use_mu);
+  // With a second stream the memory-bound tail of a batch (select, code emission) runs beside
+  // the ALU-bound searches of the next batch.  The two events live for this call only;
+  // destroying them while waits are pending is deferred by the runtime.
+  hipStream_t st2 = static_cast<hipStream_t>(side_stream);
+  const bool two = side_stream != nullptr && side_stream != stream;
+  if (!two) st2 = st;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  if (two) {
+    if (hipEventCreateWithFlags(&ev_fork, hipEventDisableTiming) != hipSuccess) return MOFQ_ERR_HIP;
+    if (hipEventCreateWithFlags(&ev_join, hipEventDisableTiming) != hipSuccess) {
+      (void)hipEventDestroy(ev_fork);
+      return MOFQ_ERR_HIP;
+    }
+  }
   bool forked = false;
-  // whatever happens after the first fork, the caller's stream waits for the side stream
+  // whatever happens after the first fork, the caller's stream waits for the second stream
   auto join = [&](int status) {
-    if (!forked) return status;
-    if (hipEventRecord(side->join, st2) != hipSuccess || hipStreamWaitEvent(st, side->join, 0) != hipSuccess)
-      return status ? status : static_cast<int>(MOFQ_ERR_HIP);
+    if (forked && (hipEventRecord(ev_join, st2) != hipSuccess || hipStreamWaitEvent(st, ev_join, 0) != hipSuccess))
+      status = status ? status : static_cast<int>(MOFQ_ERR_HIP);
+    if (two) {
+      (void)hipEventDestroy(ev_fork);
+      (void)hipEventDestroy(ev_join);
+    }
     return status;
   };
 
@@ -675,13 +649,15 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
         if ((rc = launch_emit(emit_params(i, slot[j]), st))) return join(rc);
       }
     }
-    // 2. on the side stream, once the batch's searches are done: reduce + select + per-unit
+    // 2. on the second stream, once the batch's searches are done: reduce + select + per-unit
     //    outputs of the batch in one launch, then the codes of the winners.  The next batch's
     //    searches follow on the caller's stream meanwhile; every tensor has its own workspace.
     if (n_fin) {
-      if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(st2, side->fork, 0) != hipSuccess)
-        return join(MOFQ_ERR_HIP);
-      forked = true;
+      if (two) {
+        if (hipEventRecord(ev_fork, st) != hipSuccess || hipStreamWaitEvent(st2, ev_fork, 0) != hipSuccess)
+          return join(MOFQ_ERR_HIP);
+        forked = true;
+      }
       if ((rc = launch_finish_batch(fin, n_fin, st2))) return join(rc);
       for (int q = 0; q < n_fin; ++q) {
         const int j = fin_of[q];

@@ -32,7 +32,8 @@ def _single(mq, w, cands, cfg, bits):
 
 @pytest.mark.parametrize("gran,group,f16,n_clip", [(orc.PER_CHANNEL, 0, False, 100), (orc.PER_CHANNEL, 0, True, 1),
                                                    (orc.PER_GROUP, 128, True, 12), (orc.PER_TENSOR, 0, False, 3)])
-def test_batched_equals_single(mq, gran, group, f16, n_clip):
+@pytest.mark.parametrize("two_streams", [False, True])
+def test_batched_equals_single(mq, gran, group, f16, n_clip, two_streams):
     # 29 tensors: more than two batches, mixed shapes; group-wise ones above the per-launch unit limit too
     shapes = [(7, 1024), (64, 4096), (3, 256), (300, 2048), (17, 11008)] * 5 + [(200, 12288), (5, 512), (1, 8 * 40), (130, 1536)]
     shapes = [(r, c) for r, c in shapes if gran != orc.PER_GROUP or c % group == 0]
@@ -45,18 +46,23 @@ def test_batched_equals_single(mq, gran, group, f16, n_clip):
     ws = torch.empty(batch.workspace_bytes(2, cfg), dtype=torch.uint8, device=DEV)
     e0 = [torch.cuda.Event(enable_timing=True) for _ in shapes]
     e1 = [torch.cuda.Event(enable_timing=True) for _ in shapes]
-    mq.select_layers(batch, cands, cfg, results, ws, None, e0, e1)
+    side = torch.cuda.Stream() if two_streams else None
+    mq.select_layers(batch, cands, cfg, results, ws, None, e0, e1, side_stream=side)
+    # the caller's stream alone orders what follows: copies enqueued on it right away must see
+    # the finished outputs, whichever stream wrote them
+    snap = [(o.codes.clone(), o.scales.clone(), o.clip_idx.clone(), o.unit_err.clone()) for o in outs]
+    results_snap = results.clone()
     torch.cuda.synchronize()
     assert all(a.elapsed_time(b) >= 0.0 for a, b in zip(e0, e1))
-    res = mq.read_results(results)
+    res = mq.read_results(results_snap)
     for i, w in enumerate(ws_):
         ref_out, ref_res = _single(mq, w, cands, cfg, 4)
         assert res[i].best == ref_res.best and list(res[i].err) == list(ref_res.err)
         assert res[i].ref_energy == ref_res.ref_energy
-        assert torch.equal(outs[i].codes, ref_out.codes)
-        assert torch.equal(outs[i].scales, ref_out.scales)
-        assert torch.equal(outs[i].clip_idx, ref_out.clip_idx)
-        assert torch.equal(outs[i].unit_err, ref_out.unit_err)
+        assert torch.equal(snap[i][0], ref_out.codes)
+        assert torch.equal(snap[i][1], ref_out.scales)
+        assert torch.equal(snap[i][2], ref_out.clip_idx)
+        assert torch.equal(snap[i][3], ref_out.unit_err)
     # and against the oracle, directly
     for i in (0, 3, len(shapes) - 1):
         w32 = mi.to_f32_numpy(ws_[i])
