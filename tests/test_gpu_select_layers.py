@@ -32,7 +32,7 @@ def _single(mq, w, cands, cfg, bits):
 
 @pytest.mark.parametrize("gran,group,f16,n_clip", [(orc.PER_CHANNEL, 0, False, 100), (orc.PER_CHANNEL, 0, True, 1),
                                                    (orc.PER_GROUP, 128, True, 12), (orc.PER_TENSOR, 0, False, 3)])
-@pytest.mark.parametrize("two_streams", [False, True])
+@pytest.mark.parametrize("two_streams", [False, True, "same"])
 def test_batched_equals_single(mq, gran, group, f16, n_clip, two_streams):
     # 29 tensors: more than two batches, mixed shapes; group-wise ones above the per-launch unit limit too
     shapes = [(7, 1024), (64, 4096), (3, 256), (300, 2048), (17, 11008)] * 5 + [(200, 12288), (5, 512), (1, 8 * 40), (130, 1536)]
@@ -46,7 +46,7 @@ def test_batched_equals_single(mq, gran, group, f16, n_clip, two_streams):
     ws = torch.empty(batch.workspace_bytes(2, cfg), dtype=torch.uint8, device=DEV)
     e0 = [torch.cuda.Event(enable_timing=True) for _ in shapes]
     e1 = [torch.cuda.Event(enable_timing=True) for _ in shapes]
-    side = torch.cuda.Stream() if two_streams else None
+    side = {False: None, True: torch.cuda.Stream(), "same": torch.cuda.current_stream()}[two_streams]
     mq.select_layers(batch, cands, cfg, results, ws, None, e0, e1, side_stream=side)
     # the caller's stream alone orders what follows: copies enqueued on it right away must see
     # the finished outputs, whichever stream wrote them
