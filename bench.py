@@ -65,6 +65,8 @@ def parse():
                     help="w8a8: E4M3 code product on the fp8 matrix cores (not within 1e-5 of the exact sum)")
     ap.add_argument("--blocks", type=int, default=0, help="debug: use only the first N blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="w4_channel: no second stream (kernels run one at a time; for counter runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -424,7 +426,8 @@ def main():
     ws = torch.empty(batch.workspace_bytes(len(cands), cfg), dtype=torch.uint8, device=dev)
     n_elems = sum(o * n for _, _, o, n in shapes)
     stream = torch.cuda.current_stream()
-    side = torch.cuda.Stream()   # default priority: select + code emission beside the next batch's searches
+    # default priority: select + code emission beside the next batch's searches
+    side = None if args.single_stream else torch.cuda.Stream()
 
     # the events the library records around each search launch, created (and recorded once,
     # so that they exist) before the timed region
