@@ -326,10 +326,10 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   // and adds up the two level sums itself.  Thresholds and level differences are wave-uniform.
   {
     constexpr int NBD = 15;                 // boundaries of a 16-level format; unused ones carry zeros
-    // Lower bound with the steps FIRST (twice when the row length is 3 * 2^k), FIRST/2, .., 1:
-    // they add up to NP - 1 and no probe leaves the row.  The last element is tested on its
-    // own afterwards.  Steps that are multiples of 64 or distinct smaller powers of two keep
-    // the padded offsets additive.
+    // Lower bound over the first NP - 1 elements with the steps FIRST (twice when the row
+    // length is 3 * 2^k), FIRST/2, .., 1: they add up to NP - 1 and no probe leaves that
+    // range.  The last element is tested on its own afterwards.  Steps that are multiples of
+    // 64 or distinct smaller powers of two keep the padded offsets additive.
     const float x_last = bits_to_float<In>(sorted[phys(NP - 1)]);
     const int chunks = (K + 63) >> 6;
     for (int u = wave; u < NF * chunks; u += NW) {
@@ -367,8 +367,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
       float cb = 0.0f;   // counts times level-square differences are small multiples of 1/4: exact in fp32
 #pragma unroll
       for (int q = 0; q < NBD; ++q) {
-        int j = unphys(ppos[q] >> 1);
-        j += (j == NP - 1 && t_last <= a.thr[f][q]) ? 1 : 0;
+        const int j = unphys(ppos[q] >> 1) + (t_last <= a.thr[f][q] ? 1 : 0);
         constexpr int LB = (BS == 2) ? 1 : (BS == 4 ? 2 : 3);
         double p = s_blk[j >> LB];
         const int j0 = phys(j & ~(BS - 1));
