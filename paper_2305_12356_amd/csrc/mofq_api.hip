@@ -616,7 +616,8 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
     }
     WOnlyWs slot[kFinishBatch];
     FinishParams fin[kFinishBatch];
-    int n_fin = 0, fin_of[kFinishBatch];
+    DecideParams big[kFinishBatch];
+    int n_fin = 0, fin_of[kFinishBatch], n_big = 0, big_of[kFinishBatch];
     // 1. the searches, back to back
     for (int j = 0; j < nb; ++j) {
       const int i = i0 + j;
@@ -644,29 +645,32 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
         f.out_unit_err = w_out[i].unit_err;
         fin_of[n_fin++] = j;
       } else {
-        // many units (group-wise scales): the two-stage reduce and the per-unit kernel of the single-tensor path
-        if ((rc = launch_decide(d, st))) return join(rc);
-        if ((rc = launch_emit(emit_params(i, slot[j]), st))) return join(rc);
+        // many units (group-wise scales): the two-stage reduce and the per-unit kernel of the
+        // single-tensor path, after the batch's searches
+        big[n_big] = d;
+        big_of[n_big++] = j;
       }
     }
     // 2. on the second stream, once the batch's searches are done: reduce + select + per-unit
     //    outputs of the batch in one launch, then the codes of the winners.  The next batch's
     //    searches follow on the caller's stream meanwhile; every tensor has its own workspace.
-    if (n_fin) {
-      if (two) {
-        if (hipEventRecord(ev_fork, st) != hipSuccess || hipStreamWaitEvent(st2, ev_fork, 0) != hipSuccess)
-          return join(MOFQ_ERR_HIP);
-        forked = true;
-      }
-      if ((rc = launch_finish_batch(fin, n_fin, st2))) return join(rc);
-      for (int q = 0; q < n_fin; ++q) {
-        const int j = fin_of[q];
-        EmitParams e = emit_params(i0 + j, slot[j]);
-        e.out.scales = nullptr;
-        e.out.clip_idx = nullptr;
-        e.out.unit_err = nullptr;
-        if ((rc = launch_emit(e, st2))) return join(rc);
-      }
+    if (two) {
+      if (hipEventRecord(ev_fork, st) != hipSuccess || hipStreamWaitEvent(st2, ev_fork, 0) != hipSuccess)
+        return join(MOFQ_ERR_HIP);
+      forked = true;
+    }
+    if (n_fin && (rc = launch_finish_batch(fin, n_fin, st2))) return join(rc);
+    for (int q = 0; q < n_fin; ++q) {
+      const int j = fin_of[q];
+      EmitParams e = emit_params(i0 + j, slot[j]);
+      e.out.scales = nullptr;
+      e.out.clip_idx = nullptr;
+      e.out.unit_err = nullptr;
+      if ((rc = launch_emit(e, st2))) return join(rc);
+    }
+    for (int q = 0; q < n_big; ++q) {
+      if ((rc = launch_decide(big[q], st2))) return join(rc);
+      if ((rc = launch_emit(emit_params(i0 + big_of[q], slot[big_of[q]]), st2))) return join(rc);
     }
   }
   return join(MOFQ_OK);
