@@ -52,8 +52,14 @@ struct SortedArgs {
 };
 
 // ---- order-preserving 16-bit keys ----------------------------------------------------
-MOFQ_DEV uint32_t to_key(uint32_t h) { return (h & 0x8000u) ? (~h & 0xFFFFu) : (h | 0x8000u); }
-MOFQ_DEV uint32_t from_key(uint32_t k) { return (k & 0x8000u) ? (k ^ 0x8000u) : (~k & 0xFFFFu); }
+// Two 16-bit patterns per register.  Key of a pattern h: its complement when the sign bit is
+// set, h with the sign bit set otherwise; the halves never interact.
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+MOFQ_DEV uint32_t sign_fill2(uint32_t w) {   // each half: 0xFFFF where its top bit is set, else 0
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(i16x2, w) >> 15);
+}
+MOFQ_DEV uint32_t to_key2(uint32_t w) { return w ^ (sign_fill2(w) | 0x80008000u); }
+MOFQ_DEV uint32_t from_key2(uint32_t k) { return ~(k ^ (sign_fill2(k) & 0x7FFF7FFFu)); }
 
 template <typename In> MOFQ_DEV float bits_to_float(uint32_t h);
 template <> MOFQ_DEV float bits_to_float<F16>(uint32_t h) {
@@ -85,14 +91,21 @@ MOFQ_DEV uint32_t wave_excl_scan_u32(uint32_t v, uint32_t& total) {
   total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(inc), 63));
   return inc - v;
 }
+// the same for doubles: each step moves the two halves of the running sum separately
+template <int CTRL, int ROW_MASK> MOFQ_DEV double dpp_add_f64(double x) {
+  const uint64_t u = __builtin_bit_cast(uint64_t, x);
+  const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(static_cast<uint32_t>(u)), CTRL, ROW_MASK, 0xf, false));
+  const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(static_cast<uint32_t>(u >> 32)), CTRL, ROW_MASK, 0xf, false));
+  return x + __builtin_bit_cast(double, (static_cast<uint64_t>(hi) << 32) | lo);   // +0.0 where nothing arrives
+}
 MOFQ_DEV double wave_excl_scan_f64(double v, double& total) {
-  const int lane = threadIdx.x & 63;
   double inc = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const double o = __shfl_up(inc, off, 64);
-    if (lane >= off) inc += o;
-  }
+  inc = dpp_add_f64<0x111, 0xf>(inc);   // row_shr:1
+  inc = dpp_add_f64<0x112, 0xf>(inc);   // row_shr:2
+  inc = dpp_add_f64<0x114, 0xf>(inc);   // row_shr:4
+  inc = dpp_add_f64<0x118, 0xf>(inc);   // row_shr:8
+  inc = dpp_add_f64<0x142, 0xa>(inc);   // row_bcast:15 into rows 1 and 3
+  inc = dpp_add_f64<0x143, 0xc>(inc);   // row_bcast:31 into rows 2 and 3
   total = __shfl(inc, 63, 64);
   return inc - v;
 }
@@ -187,7 +200,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
       en = __builtin_fma(d0, d0, en);
       en = __builtin_fma(d1, d1, en);
       l1 += __builtin_fabs(d0) + __builtin_fabs(d1);
-      keys[i] = ok ? (to_key(h0) | (to_key(h1) << 16)) : 0xFFFFFFFFu;   // padding sorts last
+      keys[i] = ok ? to_key2(raw[i]) : 0xFFFFFFFFu;   // padding sorts last
     }
     *reinterpret_cast<u32x4*>(&s_keys[tid * E + j * 8]) = keys;
   }
@@ -267,11 +280,15 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
       const uint32_t key = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
       pos[i] = atomicAdd(&s_cnt[(key >> shift) & 15u][tid], 1u);   // stable: thread order, then i
     }
+    if constexpr (LAST) {   // back to the elements' own patterns
+#pragma unroll
+      for (int i = 0; i < E / 2; ++i) kreg[i] = from_key2(kreg[i]);
+    }
 #pragma unroll
     for (int i = 0; i < E; ++i) {
-      const uint32_t key = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
-      if constexpr (LAST) s_keys[phys(static_cast<int>(pos[i]))] = static_cast<uint16_t>(from_key(key));
-      else s_keys[pos[i]] = static_cast<uint16_t>(key);
+      const uint32_t v = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
+      if constexpr (LAST) s_keys[phys(static_cast<int>(pos[i]))] = static_cast<uint16_t>(v);
+      else s_keys[pos[i]] = static_cast<uint16_t>(v);
     }
     __syncthreads();
   };
