@@ -70,8 +70,6 @@ template <> MOFQ_DEV float bits_to_float<BF16>(uint32_t h) { return u2f(h << 16)
 // Padded position of sorted element i (in elements): a 2-element gap after every 64.
 // Additive over sums of distinct powers of two, which the search below relies on.
 MOFQ_DEV constexpr int phys(int i) { return i + ((i >> 6) << 1); }
-// inverse on non-gap positions: 66 padded elements hold 64
-MOFQ_DEV int unphys(int p) { return p - 2 * static_cast<int>(__umulhi(static_cast<uint32_t>(p), 65075263u)); }
 
 // x plus the value the data-parallel-primitive control CTRL brings from another lane (0 where
 // the control has no source lane or ROW_MASK excludes the row)
@@ -384,18 +382,27 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
       float cb = 0.0f;   // counts times level-square differences are small multiples of 1/4: exact in fp32
 #pragma unroll
       for (int q = 0; q < NBD; ++q) {
-        const int j = unphys(ppos[q] >> 1) + (t_last <= a.thr[f][q] ? 1 : 0);
+        // position in elements: the padded byte offset holds 132 bytes per 64 elements
+        const int j0 = (ppos[q] >> 1) - 2 * static_cast<int>(__umulhi(static_cast<uint32_t>(ppos[q]), 32537632u));
+        const int j = j0 + (t_last <= a.thr[f][q] ? 1 : 0);
         constexpr int LB = (BS == 2) ? 1 : (BS == 4 ? 2 : 3);
         double p = s_blk[j >> LB];
-        const int j0 = phys(j & ~(BS - 1));
+        if constexpr (BS == 2) {
+          // an odd position adds the element before it, which sits at the offset rounded down
+          // to 4 bytes (an even position reads its own element there and drops it; j = NP is even)
+          const float xv = bits_to_float<In>(*reinterpret_cast<const uint16_t*>(s_raw + (ppos[q] & ~3)));
+          p += static_cast<double>((j & 1) ? xv : 0.0f);
+        } else {
+          const int jb = phys(j & ~(BS - 1));
 #pragma unroll
-        for (int i = 0; i < BS - 1; ++i) {
-          const bool in = i < (j & (BS - 1));
-          const double val = static_cast<double>(bits_to_float<In>(sorted[in ? j0 + i : 0]));
-          p += in ? val : 0.0;
+          for (int i = 0; i < BS - 1; ++i) {
+            const bool in = i < (j & (BS - 1));
+            const double val = static_cast<double>(bits_to_float<In>(sorted[in ? jb + i : 0]));
+            p += in ? val : 0.0;
+          }
         }
         ca += p * a.dgd[f][q];
-        cb += static_cast<float>(j) * a.dg2[f][q];
+        cb = __builtin_fmaf(static_cast<float>(j), a.dg2[f][q], cb);
       }
       if (k < K) {
         const double gl = static_cast<double>(a.g_last[f]);
