@@ -567,7 +567,7 @@ int launch_shape(const SortedArgs& a, hipStream_t st) {
   MOFQ_SORTED(256, 2)   //  4096
   MOFQ_SORTED(256, 4)   //  8192
   MOFQ_SORTED(256, 6)   // 12288
-  MOFQ_SORTED(512, 6)   // 24576
+  MOFQ_SORTED(1024, 3)  // 24576
 #undef MOFQ_SORTED
   return MOFQ_ERR_UNSUPPORTED;
 }
