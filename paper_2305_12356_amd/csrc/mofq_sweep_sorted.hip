@@ -346,27 +346,26 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
     // range.  The last element is tested on its own afterwards.  Steps that are multiples of
     // 64 or distinct smaller powers of two keep the padded offsets additive.
     const float x_last = bits_to_float<In>(sorted[phys(NP - 1)]);
+    const float x_first = bits_to_float<In>(sorted[phys(FIRST - 1)]);   // the first step's probe
     const int chunks = (K + 63) >> 6;
     for (int u = wave; u < NF * chunks; u += NW) {
       const int f = u / chunks;                       // wave-uniform
       const int k = (u - f * chunks) * 64 + lane;
       const float inv = s_inv[f][k < K ? k : K - 1];
       int ppos[NBD];   // padded byte offset of the next probe; of the position at the end
-#pragma unroll
-      for (int q = 0; q < NBD; ++q) ppos[q] = 2 * phys(FIRST - 1);
       // Branch-free: position = number of elements on levels <= q.  Every element before the
       // position passes the test; the NaN padding stops it at n.  The offset of the next
-      // step's probe rides along in the position.
-      if constexpr (!NP_POW2) {
+      // step's probe rides along in the position.  The first step probes the same element
+      // for every boundary: one product serves them all.
+      {
+        constexpr int NEXT = NP_POW2 ? FIRST / 2 : FIRST;     // size of the step after the first
+        const float t0 = x_first * inv;
 #pragma unroll
-        for (int q = 0; q < NBD; ++q) {
-          const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + ppos[q]);
-          const float t = bits_to_float<In>(h) * inv;
-          ppos[q] += (t <= a.thr[f][q]) ? 2 * phys(FIRST) : 0;
-        }
+        for (int q = 0; q < NBD; ++q)
+          ppos[q] = 2 * phys(NEXT - 1) + ((t0 <= a.thr[f][q]) ? 2 * phys(FIRST) : 0);
       }
 #pragma unroll 1
-      for (int st = LSTEPS - 1; st >= 0; --st) {
+      for (int st = (NP_POW2 ? LSTEPS - 2 : LSTEPS - 1); st >= 0; --st) {
         const int stp = 1 << st;
         const int next_probe = st > 0 ? 2 * phys((stp >> 1) - 1) : 0;
         const int stay = next_probe - 2 * phys(stp - 1), go = stay + 2 * phys(stp);   // wave-uniform
