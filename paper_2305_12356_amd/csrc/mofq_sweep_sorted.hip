@@ -67,6 +67,15 @@ template <> MOFQ_DEV float bits_to_float<F16>(uint32_t h) {
 }
 template <> MOFQ_DEV float bits_to_float<BF16>(uint32_t h) { return u2f(h << 16); }
 
+// fl32(x * inv) for the element with bit pattern h.  For fp16 the widening and the product are
+// one mixed-precision fused multiply-add with a zero addend: the same single rounding of the
+// exact product (only the sign of a zero result can differ, which no comparison sees).
+template <typename In> MOFQ_DEV float scaled(uint32_t h, float inv);
+template <> MOFQ_DEV float scaled<F16>(uint32_t h, float inv) {
+  return __builtin_fmaf(static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h))), inv, 0.0f);
+}
+template <> MOFQ_DEV float scaled<BF16>(uint32_t h, float inv) { return u2f(h << 16) * inv; }
+
 // Padded position of sorted element i (in elements): a 2-element gap after every 64.
 // Additive over sums of distinct powers of two, which the search below relies on.
 MOFQ_DEV constexpr int phys(int i) { return i + ((i >> 6) << 1); }
@@ -372,7 +381,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
 #pragma unroll
         for (int q = 0; q < NBD; ++q) {
           const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + ppos[q]);
-          const float t = bits_to_float<In>(h) * inv;
+          const float t = scaled<In>(h, inv);
           ppos[q] += (t <= a.thr[f][q]) ? go : stay;
         }
       }
