@@ -307,6 +307,46 @@ int wo_output_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_
 
 // Quantize X and W in every candidate format, then one pass over the matrix cores
 // that leaves per-tile partial errors in the workspace.
+// Work on a second stream of the caller beside `main`: fork() orders the side stream after
+// what is on `main` so far, join() makes `main` wait for the side stream.  The two events live
+// for one call (destroying an event with waits pending is deferred by the runtime).  Without a
+// second stream (null, or the same as `main`) everything stays on `main`.
+struct SideWork {
+  hipStream_t main, side;
+  bool two, forked = false;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  SideWork(hipStream_t m, void* s) : main(m), side(static_cast<hipStream_t>(s)), two(s != nullptr && s != m) {
+    if (!two) side = main;
+  }
+  SideWork(const SideWork&) = delete;
+  SideWork& operator=(const SideWork&) = delete;
+  ~SideWork() {
+    if (ev_fork) (void)hipEventDestroy(ev_fork);
+    if (ev_join) (void)hipEventDestroy(ev_join);
+  }
+  int init() {
+    if (!two) return MOFQ_OK;
+    if (hipEventCreateWithFlags(&ev_fork, hipEventDisableTiming) != hipSuccess) return MOFQ_ERR_HIP;
+    if (hipEventCreateWithFlags(&ev_join, hipEventDisableTiming) != hipSuccess) return MOFQ_ERR_HIP;
+    return MOFQ_OK;
+  }
+  int fork() {
+    if (!two) return MOFQ_OK;
+    if (hipEventRecord(ev_fork, main) != hipSuccess || hipStreamWaitEvent(side, ev_fork, 0) != hipSuccess)
+      return MOFQ_ERR_HIP;
+    forked = true;
+    return MOFQ_OK;
+  }
+  // returns `status`, or the join's own failure if `status` was fine
+  int join(int status) {
+    if (!forked) return status;
+    forked = false;
+    if (hipEventRecord(ev_join, side) != hipSuccess || hipStreamWaitEvent(main, ev_join, 0) != hipSuccess)
+      return status ? status : static_cast<int>(MOFQ_ERR_HIP);
+    return status;
+  }
+};
+
 int wa_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand, int n_cand,
              const mofq_scale_cfg_t* w_cfg, bool fp8_unit, const WaWs& a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
@@ -554,30 +594,11 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
   if (!ws || !need || ws_bytes < need || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   // With a second stream the memory-bound tail of a batch (select, code emission) runs beside
-  // the ALU-bound searches of the next batch.  The two events live for this call only;
-  // destroying them while waits are pending is deferred by the runtime.
-  hipStream_t st2 = static_cast<hipStream_t>(side_stream);
-  const bool two = side_stream != nullptr && side_stream != stream;
-  if (!two) st2 = st;
-  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-  if (two) {
-    if (hipEventCreateWithFlags(&ev_fork, hipEventDisableTiming) != hipSuccess) return MOFQ_ERR_HIP;
-    if (hipEventCreateWithFlags(&ev_join, hipEventDisableTiming) != hipSuccess) {
-      (void)hipEventDestroy(ev_fork);
-      return MOFQ_ERR_HIP;
-    }
-  }
-  bool forked = false;
-  // whatever happens after the first fork, the caller's stream waits for the second stream
-  auto join = [&](int status) {
-    if (forked && (hipEventRecord(ev_join, st2) != hipSuccess || hipStreamWaitEvent(st, ev_join, 0) != hipSuccess))
-      status = status ? status : static_cast<int>(MOFQ_ERR_HIP);
-    if (two) {
-      (void)hipEventDestroy(ev_fork);
-      (void)hipEventDestroy(ev_join);
-    }
-    return status;
-  };
+  // the ALU-bound searches of the next batch.
+  SideWork sw(st, side_stream);
+  if ((rc = sw.init())) return rc;
+  hipStream_t st2 = sw.side;
+  auto join = [&](int status) { return sw.join(status); };
 
   auto emit_params = [&](int i, const WOnlyWs& s) {
     EmitParams e{};
@@ -654,11 +675,7 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
     // 2. on the second stream, once the batch's searches are done: reduce + select + per-unit
     //    outputs of the batch in one launch, then the codes of the winners.  The next batch's
     //    searches follow on the caller's stream meanwhile; every tensor has its own workspace.
-    if (two) {
-      if (hipEventRecord(ev_fork, st) != hipSuccess || hipStreamWaitEvent(st2, ev_fork, 0) != hipSuccess)
-        return join(MOFQ_ERR_HIP);
-      forked = true;
-    }
+    if ((rc = sw.fork())) return join(rc);
     if (n_fin && (rc = launch_finish_batch(fin, n_fin, st2))) return join(rc);
     for (int q = 0; q < n_fin; ++q) {
       const int j = fin_of[q];
