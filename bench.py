@@ -151,6 +151,7 @@ def run_w8a8(args, shapes, dev, w_only=False):
             xouts[(o, n)] = mq.alloc_qbuffers(o, n, bits, cfg, dev)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
+
     def step(events=None):
         for i, w in enumerate(weights):
             _, _, o, n = shapes[i]
