@@ -310,6 +310,9 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   {
     constexpr int NB8 = 8 / BS;             // prefix entries per 8 elements
     double bs[CH][NB8], tsum = 0.0;
+    // no padding among this wave's positions: the common case needs no per-element test (the
+    // second copy of the loop only pays where it is short)
+    const bool wave_full = CH <= 4 && __builtin_amdgcn_readfirstlane((wave + 1) * 64 * E) <= n;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
       const uint32_t* cp = reinterpret_cast<const uint32_t*>(&sorted[phys(tid * E + j * 8)]);
@@ -322,7 +325,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
           const uint32_t h = (v[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
           const int pos = tid * E + j * 8 + i;
           const double val = static_cast<double>(bits_to_float<In>(h));
-          b += (pos < n) ? val : 0.0;
+          b += (wave_full || pos < n) ? val : 0.0;
         }
         bs[j][g] = b;
         tsum += b;
@@ -409,7 +412,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
             p += in ? val : 0.0;
           }
         }
-        ca += p * a.dgd[f][q];
+        ca = __builtin_fma(p, a.dgd[f][q], ca);
         cb = __builtin_fmaf(static_cast<float>(j), a.dg2[f][q], cb);
       }
       if (k < K) {
