@@ -353,8 +353,9 @@ int launch_emit(const EmitParams& p, hipStream_t st) {
   if (a.units <= 0) return MOFQ_ERR_INVALID_ARG;
   const int64_t n_chunks = p.rows * (p.cols / 8);
   // full occupancy (8 workgroups of 256 on each of 256 compute units), several chunks per thread
+  const int64_t cap = p.max_blocks > 0 ? p.max_blocks : 256 * 8;
   const unsigned blocks = static_cast<unsigned>(
-      std::max<int64_t>(1, std::min<int64_t>((n_chunks + 256 * kEmitUnroll - 1) / (256 * kEmitUnroll), 256 * 8)));
+      std::max<int64_t>(1, std::min<int64_t>((n_chunks + 256 * kEmitUnroll - 1) / (256 * kEmitUnroll), cap)));
   if (p.out.codes) {
     switch (p.dtype) {
       case MOFQ_F32: hipLaunchKernelGGL(emit_codes_kernel<F32>, dim3(blocks), dim3(256), 0, st, a); break;

@@ -89,6 +89,7 @@ struct EmitParams {
   const uint8_t* unit_fmt;       // device [units] or nullptr: candidate index per unit (overrides result)
   mofq_qout_t out;
   int32_t as_bf16_values;        // 8-bit formats: out.codes receives the grid values as bf16
+  int32_t max_blocks;            // 0: fill the device; else a cap for emission that runs beside other kernels
 };
 int launch_emit(const EmitParams& p, hipStream_t stream);
 
