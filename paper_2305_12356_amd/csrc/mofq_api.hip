@@ -604,7 +604,7 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
   // set: 33.9 ms per pass against 35.1 ms with the device-filling grid; 128 and 512 workgroups
   // are both slower).
   constexpr int kBackgroundEmitBlocks = 256;
-  const int emit_cap = sw.two ? kBackgroundEmitBlocks : 0;
+  int emit_cap = sw.two ? kBackgroundEmitBlocks : 0;
 
   auto emit_params = [&](int i, const WOnlyWs& s) {
     EmitParams e{};
@@ -679,6 +679,7 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
         big_of[n_big++] = j;
       }
     }
+    if (i0 + nb >= n_layers) emit_cap = 0;   // nothing runs beside the last batch's emission
     // 2. on the second stream, once the batch's searches are done: reduce + select + per-unit
     //    outputs of the batch in one launch, then the codes of the winners.  The next batch's
     //    searches follow on the caller's stream meanwhile; every tensor has its own workspace.
