@@ -48,8 +48,11 @@ FLOPS_PER_ELEM_CAND_FMT = 7
 ALU_PEAK_TFLOPS = 7.0 / (3.0 / 157.3 + 4.0 / 78.6)
 # HBM bytes per launch of the search kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command,
 # scaled by what the same counters read for a plain 1 GiB copy (profiles/w_only_7b_k100_hbm_traffic.txt):
-# KiB read and written per launch, by tensor shape.  Only the 7B per-channel workload has been measured.
-MEASURED_TRAFFIC_KIB = {(4096, 4096): (33124, 896), (11008, 4096): (88420, 2408), (4096, 11008): (88662, 896)}
+# a launch over 46592 rows of 4096 fp16 columns reads 373 230 KiB (1.0013 x its 2 bytes per element) and
+# writes 10 192 KiB (224 bytes of per-channel records per row).  Only the 7B per-channel workload has
+# been measured.
+MEASURED_READ_PER_INPUT_BYTE = 373230.0 / (46592 * 4096 * 2 / 1024)
+MEASURED_WRITE_BYTES_PER_ROW = 10192.0 * 1024 / 46592
 
 
 def parse():
@@ -421,7 +424,8 @@ def main():
         qouts.append(mq.alloc_qbuffers(o, n, 4, cfg, dev))
         ws_bytes = max(ws_bytes, mq.workspace_bytes(w, None, len(cands), mq.ERR_TENSOR, cfg))
     # one call for the whole model (mofq_select_layers): the per-tensor reduce / select /
-    # per-unit outputs of up to 12 tensors share a launch
+    # per-unit outputs of up to 12 tensors share a launch, and so do the searches of those of
+    # them that have one row length
     batch = mq.LayerBatch(weights, qouts)
     ws = torch.empty(batch.workspace_bytes(len(cands), cfg), dtype=torch.uint8, device=dev)
     n_elems = sum(o * n for _, _, o, n in shapes)
@@ -462,12 +466,17 @@ def main():
     value = elem_cand / (elapsed / args.steps)
 
     # ---- dominant kernel: the scale-search instance for 4096-column rows ------------
-    # (q, k, v, o, gate, up: 78 % of all elements; one launch per tensor).  Duration
-    # from the HIP events the library recorded around each launch.
+    # (q, k, v, o, gate, up: 78 % of all elements; the tensors of a batch with one row length
+    # share a launch).  Duration from the HIP events the library recorded around each launch: the
+    # begin event of a launch's first tensor, the end event of its last.
+    first = batch.search_groups(cands)
+    last = {f: i for i, f in enumerate(first)}
     by_cols = {}
-    for i, e0, e1 in events:
-        _, _, o, n = shapes[i]
-        by_cols.setdefault(n, []).append((o * n, e0.elapsed_time(e1) * 1e-3))
+    for step_i in range(args.steps):
+        ev = events[step_i * len(shapes):(step_i + 1) * len(shapes)]
+        for f, l in last.items():
+            elems = sum(shapes[i][2] * shapes[i][3] for i in range(f, l + 1) if first[i] == f)
+            by_cols.setdefault(shapes[f][3], []).append((elems, ev[f][1].elapsed_time(ev[l][2]) * 1e-3))
     dom_cols = max(by_cols, key=lambda c: sum(e for e, _ in by_cols[c]))
     dom = by_cols[dom_cols]
     dom_flops = sum(e for e, _ in dom) * n_clip * N_FMT * FLOPS_PER_ELEM_CAND_FMT
@@ -475,8 +484,9 @@ def main():
     achieved = dom_flops / dom_time / 1e12
     traffic = None
     if not group and args.model == "7b":
-        per = [sum(MEASURED_TRAFFIC_KIB[(o, n)]) * 1024.0 for _, _, o, n in shapes if n == dom_cols]
-        traffic = sum(per) / len(per)
+        per = [o * n * 2 * MEASURED_READ_PER_INPUT_BYTE + o * MEASURED_WRITE_BYTES_PER_ROW
+               for _, _, o, n in shapes if n == dom_cols]
+        traffic = sum(per) * args.steps / len(by_cols[dom_cols])   # per launch (a launch covers several tensors)
     search_time = sum(t for v in by_cols.values() for _, t in v) / args.steps
     roofline = {
         "bound": "alu", "achieved": achieved, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -198,11 +198,12 @@ int mofq_select_layer(const mofq_tensor_t* w, const mofq_tensor_t* x,
  * Algorithm 1's loop over the layers of a model): the same results, tensor by tensor, as
  * n_layers calls of mofq_select_layer, but the small dependent steps between the search
  * and the code emission (tensor reduce, select, per-unit outputs) of up to 12 tensors share
- * one launch, so a model-wide pass does not pay their latency per tensor.
+ * one launch, so a model-wide pass does not pay their latency per tensor, and the tensors
+ * of such a batch that have one row length are searched in one launch.
  *   w, w_out : HOST arrays of n_layers descriptors (device buffers inside, as above).
  *   results  : device array of n_layers records.
  *   ev_begin / ev_end (the _timed variant; may be NULL): HOST arrays of n_layers hipEvent_t,
- *   recorded around the search of each tensor.
+ *   recorded around the search launches (see mofq_select_layers_search_groups).
  * Workspace: mofq_select_layers_workspace_bytes (the tensors' workspaces side by side).
  * Streams: `side_stream` (a hipStream_t of the caller, default priority; may be NULL or equal
  * to `stream`) lets the select and the code emission of a batch run beside the searches of
@@ -222,6 +223,17 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
                              void* const* ev_begin, void* const* ev_end);
 size_t mofq_select_layers_workspace_bytes(int32_t n_layers, const mofq_tensor_t* w,
                                           int32_t n_candidates, const mofq_scale_cfg_t* w_cfg);
+/*
+ * How mofq_select_layers groups the searches (host only, enqueues nothing): tensors of one
+ * row length (cols) and dtype inside a batch, adjacent or not, are searched together (in one
+ * launch where the sort-based per-channel search applies, else in consecutive launches).
+ * group_first (HOST, n_layers entries) receives, for every tensor, the index of the first
+ * tensor of its group.  The _timed variant records ev_begin[] of that first tensor before the
+ * group's launch and ev_end[] of the group's last tensor (the largest index) after it, and
+ * leaves the other events of the group alone.
+ */
+int mofq_select_layers_search_groups(int32_t n_layers, const mofq_tensor_t* w, const int32_t* candidates,
+                                     int32_t n_candidates, int32_t* group_first);
 
 /*
  * Format select at a finer granularity than the layer (Section 4.1 leaves it open, the

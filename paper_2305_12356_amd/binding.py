@@ -86,6 +86,9 @@ def _load():
                                      C.POINTER(ScaleCfg), C.POINTER(QOut), vp, vp, C.c_size_t, vp, vp]
     L.mofq_select_layers_timed.restype = C.c_int
     L.mofq_select_layers_timed.argtypes = L.mofq_select_layers.argtypes + [C.POINTER(vp), C.POINTER(vp)]
+    L.mofq_select_layers_search_groups.restype = C.c_int
+    L.mofq_select_layers_search_groups.argtypes = [C.c_int32, C.POINTER(TensorDesc), C.POINTER(C.c_int32),
+                                                   C.c_int32, C.POINTER(C.c_int32)]
     L.mofq_select_layers_workspace_bytes.restype = C.c_size_t
     L.mofq_select_layers_workspace_bytes.argtypes = [C.c_int32, C.POINTER(TensorDesc), C.c_int32,
                                                      C.POINTER(ScaleCfg)]
@@ -296,6 +299,16 @@ class LayerBatch:
 
     def workspace_bytes(self, n_candidates: int, cfg: Cfg) -> int:
         return int(_lib.mofq_select_layers_workspace_bytes(self.n, self.w, n_candidates, C.byref(cfg.c)))
+
+    def search_groups(self, candidates: Sequence[int]):
+        """mofq_select_layers_search_groups: for every tensor, the index of the first tensor of
+        the search launch it belongs to."""
+        cand = (C.c_int32 * len(candidates))(*candidates)
+        first = (C.c_int32 * self.n)()
+        rc = _lib.mofq_select_layers_search_groups(self.n, self.w, cand, len(candidates), first)
+        if rc != 0:
+            raise MofqError(rc, "mofq_select_layers_search_groups")
+        return list(first)
 
 
 def select_layers(batch: LayerBatch, candidates: Sequence[int], cfg: Cfg, results: torch.Tensor,

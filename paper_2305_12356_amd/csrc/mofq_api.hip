@@ -109,6 +109,43 @@ struct SweepEmit {
   int f8_as_bf16;
 };
 
+// Parameters of the launch that scores candidates c0 .. c0 + n - 1 (n = 2: a pair of different
+// formats that share one read of the tensor).
+SweepParams sweep_params(const mofq_tensor_t* t, const int32_t* cand, int c0, int n,
+                         const mofq_scale_cfg_t* cfg, const WOnlyWs& w) {
+  SweepParams p{};
+  p.w = t->data;
+  p.dtype = t->dtype;
+  p.rows = t->rows;
+  p.cols = t->cols;
+  p.ld = t->ld;
+  p.gran = cfg->gran;
+  p.group = cfg->group_size;
+  p.scale_f16 = cfg->scale_dtype == MOFQ_F16;
+  p.n_clip = cfg->n_clip;
+  std::memcpy(p.clip, cfg->clip_ratios, sizeof(float) * cfg->n_clip);
+  p.n_fmt = n;
+  // kernels exist for the (INT, FP) order; a reversed pair swaps its record slots
+  int slot[2] = {c0, c0 + 1};
+  if (n == 2 && !(cand[c0] == MOFQ_INT4 || cand[c0] == MOFQ_INT8)) std::swap(slot[0], slot[1]);
+  for (int f = 0; f < n; ++f) {
+    p.fmt[f] = cand[slot[f]];
+    p.rec.scale[f] = w.scale[slot[f]];
+    p.rec.clip[f] = w.clip[slot[f]];
+    p.rec.err[f] = w.err[slot[f]];
+  }
+  p.rec.energy = (c0 == 0) ? w.energy : nullptr;
+  p.absmax_part = w.absmax_part;
+  p.sse_part = w.sse_part;
+  p.energy_part = w.energy_part;
+  return p;
+}
+
+// The whole candidate list is one launch: a single format or a pair of different ones.
+bool one_sweep_launch(const int32_t* cand, int n_cand) {
+  return n_cand == 1 || (n_cand == 2 && paired(cand[0], cand[1]));
+}
+
 int sweep_candidates(const mofq_tensor_t* t, const int32_t* cand, int n_cand,
                      const mofq_scale_cfg_t* cfg, const WOnlyWs& w, hipStream_t st,
                      const float* ext_absmax = nullptr, const SweepEmit* em = nullptr) {
@@ -117,31 +154,7 @@ int sweep_candidates(const mofq_tensor_t* t, const int32_t* cand, int n_cand,
     // two different formats share one launch (one read of the tensor); a repeated
     // format is scored on its own
     const int n = (c0 + 1 < n_cand && paired(cand[c0], cand[c0 + 1])) ? 2 : 1;
-    SweepParams p{};
-    p.w = t->data;
-    p.dtype = t->dtype;
-    p.rows = t->rows;
-    p.cols = t->cols;
-    p.ld = t->ld;
-    p.gran = cfg->gran;
-    p.group = cfg->group_size;
-    p.scale_f16 = cfg->scale_dtype == MOFQ_F16;
-    p.n_clip = cfg->n_clip;
-    std::memcpy(p.clip, cfg->clip_ratios, sizeof(float) * cfg->n_clip);
-    p.n_fmt = n;
-    // kernels exist for the (INT, FP) order; a reversed pair swaps its record slots
-    int slot[2] = {c0, c0 + 1};
-    if (n == 2 && !(cand[c0] == MOFQ_INT4 || cand[c0] == MOFQ_INT8)) std::swap(slot[0], slot[1]);
-    for (int f = 0; f < n; ++f) {
-      p.fmt[f] = cand[slot[f]];
-      p.rec.scale[f] = w.scale[slot[f]];
-      p.rec.clip[f] = w.clip[slot[f]];
-      p.rec.err[f] = w.err[slot[f]];
-    }
-    p.rec.energy = (c0 == 0) ? w.energy : nullptr;
-    p.absmax_part = w.absmax_part;
-    p.sse_part = w.sse_part;
-    p.energy_part = w.energy_part;
+    SweepParams p = sweep_params(t, cand, c0, n, cfg, w);
     p.ext_absmax = ext_absmax;
     if (em) {
       if (n != 2) return MOFQ_ERR_INVALID_ARG;
@@ -556,6 +569,66 @@ int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, i
   return MOFQ_ERR_INVALID_ARG;
 }
 
+}  // extern "C"
+
+namespace {
+
+// A batch of mofq_select_layers ends at kFinishBatch tensors or once it holds kBatchBytes of
+// input.  The batch is the unit of overlap (its select and emission run beside the next
+// batch's searches) and of search grouping (its tensors of one row length share a launch), so
+// it should span the same-length tensors of a transformer block; past that, larger batches
+// only lengthen the exposed emission of the last one.  Measured on the 7B-shaped set, whole
+// pass: 31.4 ms at 256 MB, 30.6 ms at 400 MB, 30.3 ms at 520 MB.  Returns the number of
+// tensors in the batch that starts at i0.
+int batch_length(int n_layers, const mofq_tensor_t* w, int i0) {
+  constexpr int64_t kBatchBytes = int64_t{512} << 20;
+  int64_t bytes = 0;
+  int nb = 0;
+  for (; i0 + nb < n_layers && nb < kFinishBatch; ++nb) {
+    const int64_t b = w[i0 + nb].rows * w[i0 + nb].cols * (w[i0 + nb].dtype == MOFQ_F32 ? 4 : 2);
+    if (nb > 0 && bytes + b > kBatchBytes) break;
+    bytes += b;
+  }
+  return nb;
+}
+
+// Tensors of a batch with one row length and dtype share a search launch (up to
+// kSweepGroupMax of them, adjacent or not: a larger launch fills the device better than
+// several small ones, and nothing orders the searches inside a batch).  first[j] (j < nb)
+// receives the batch-relative index of the first member of tensor j's launch.
+void plan_search_groups(const mofq_tensor_t* w, int nb, const int32_t* cand, int n_cand, int* first) {
+  const bool joinable = one_sweep_launch(cand, n_cand);
+  for (int j = 0; j < nb; ++j) first[j] = -1;
+  for (int j = 0; j < nb; ++j) {
+    if (first[j] >= 0) continue;
+    first[j] = j;
+    int n = 1;
+    for (int k = j + 1; joinable && k < nb && n < kSweepGroupMax; ++k)
+      if (first[k] < 0 && w[k].cols == w[j].cols && w[k].dtype == w[j].dtype) {
+        first[k] = j;
+        ++n;
+      }
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int mofq_select_layers_search_groups(int32_t n_layers, const mofq_tensor_t* w, const int32_t* candidates,
+                                     int32_t n_candidates, int32_t* group_first) {
+  if (n_layers < 1 || !w || !group_first) return MOFQ_ERR_INVALID_ARG;
+  const int rc = check_candidates(candidates, n_candidates);
+  if (rc) return rc;
+  for (int i0 = 0, nb = 0; i0 < n_layers; i0 += nb) {
+    nb = batch_length(n_layers, w, i0);
+    int first[kFinishBatch];
+    plan_search_groups(w + i0, nb, candidates, n_candidates, first);
+    for (int j = 0; j < nb; ++j) group_first[i0 + j] = i0 + first[j];
+  }
+  return MOFQ_OK;
+}
+
 size_t mofq_select_layers_workspace_bytes(int32_t n_layers, const mofq_tensor_t* w,
                                           int32_t n_candidates, const mofq_scale_cfg_t* w_cfg) {
   if (n_layers < 1 || !w) return 0;
@@ -630,31 +703,40 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
   };
 
   char* base = static_cast<char*>(ws);
-  // A batch ends at kFinishBatch tensors or once it holds kBatchBytes of input (the size of
-  // the last-level cache: the code emission re-reads each tensor after its batch's searches;
-  // measured on the 7B-shaped set, 256 MB is at the optimum, 61.4 ms against 63.2 ms for
-  // one tensor per batch).
-  constexpr int64_t kBatchBytes = int64_t{256} << 20;
   for (int i0 = 0, nb = 0; i0 < n_layers; i0 += nb) {
-    int64_t bytes = 0;
-    for (nb = 0; i0 + nb < n_layers && nb < kFinishBatch; ++nb) {
-      const int64_t b = w[i0 + nb].rows * w[i0 + nb].cols * (w[i0 + nb].dtype == MOFQ_F32 ? 4 : 2);
-      if (nb > 0 && bytes + b > kBatchBytes) break;
-      bytes += b;
-    }
+    nb = batch_length(n_layers, w, i0);
     WOnlyWs slot[kFinishBatch];
     FinishParams fin[kFinishBatch];
     DecideParams big[kFinishBatch];
     int n_fin = 0, fin_of[kFinishBatch], n_big = 0, big_of[kFinishBatch];
-    // 1. the searches, back to back
+    // 1. the searches, back to back; consecutive tensors of one shape share a launch
+    for (int j = 0; j < nb; ++j) {
+      const int64_t units = mofq_num_units(w[i0 + j].rows, w[i0 + j].cols, w_cfg->gran, w_cfg->group_size);
+      slot[j] = carve_w_only(base, units, n_candidates, w_cfg->gran, w_cfg->n_clip);
+      base += slot[j].bytes;
+    }
+    int first[kFinishBatch];
+    plan_search_groups(w + i0, nb, candidates, n_candidates, first);
+    for (int j = 0; j < nb; ++j) {
+      if (first[j] != j) continue;
+      SweepParams sp[kSweepGroupMax];
+      int g = 0, last = j;
+      for (int k = j; k < nb; ++k)
+        if (first[k] == j) {
+          sp[g++] = sweep_params(&w[i0 + k], candidates, 0, n_candidates, w_cfg, slot[k]);
+          last = k;
+        }
+      if (ev_begin && hipEventRecord(static_cast<hipEvent_t>(ev_begin[i0 + j]), st) != hipSuccess) return join(MOFQ_ERR_HIP);
+      if (g > 1) {
+        if ((rc = launch_sweep_group(sp, g, st))) return join(rc);
+      } else {
+        if ((rc = sweep_candidates(&w[i0 + j], candidates, n_candidates, w_cfg, slot[j], st))) return join(rc);
+      }
+      if (ev_end && hipEventRecord(static_cast<hipEvent_t>(ev_end[i0 + last]), st) != hipSuccess) return join(MOFQ_ERR_HIP);
+    }
     for (int j = 0; j < nb; ++j) {
       const int i = i0 + j;
       const int64_t units = mofq_num_units(w[i].rows, w[i].cols, w_cfg->gran, w_cfg->group_size);
-      slot[j] = carve_w_only(base, units, n_candidates, w_cfg->gran, w_cfg->n_clip);
-      base += slot[j].bytes;
-      if (ev_begin && hipEventRecord(static_cast<hipEvent_t>(ev_begin[i]), st) != hipSuccess) return join(MOFQ_ERR_HIP);
-      if ((rc = sweep_candidates(&w[i], candidates, n_candidates, w_cfg, slot[j], st))) return join(rc);
-      if (ev_end && hipEventRecord(static_cast<hipEvent_t>(ev_end[i]), st) != hipSuccess) return join(MOFQ_ERR_HIP);
       DecideParams d{};
       d.units = units;
       d.n_cand = n_candidates;

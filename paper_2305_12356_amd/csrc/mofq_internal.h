@@ -55,6 +55,13 @@ int launch_sweep(const SweepParams& p, hipStream_t stream);
 // Sort-based search for per-channel 4-bit searches on 16-bit inputs; returns
 // MOFQ_ERR_UNSUPPORTED (nothing enqueued) outside that domain.
 int launch_sweep_sorted(const SweepParams& p, hipStream_t stream);
+// The same for up to kSweepGroupMax tensors of one row length, dtype and configuration in one
+// launch (MOFQ_ERR_UNSUPPORTED, nothing enqueued, if they differ or are outside the domain).
+constexpr int kSweepGroupMax = 8;
+int launch_sweep_sorted_group(const SweepParams* p, int n, hipStream_t stream);
+// Scale search of n tensors: one launch where launch_sweep_sorted_group takes them, else one
+// launch_sweep per tensor.
+int launch_sweep_group(const SweepParams* p, int n, hipStream_t stream);
 
 // Tensor-level reduce + Algorithm 1's strict-less select over n_cand formats
 // whose unit errors live in `err[c]` (units entries each).

@@ -993,6 +993,18 @@ int launch_sweep(const SweepParams& p, hipStream_t st) {
   return MOFQ_ERR_INVALID_ARG;
 }
 
+int launch_sweep_group(const SweepParams* p, int n, hipStream_t st) {
+  if (n > 1) {
+    const int rc = launch_sweep_sorted_group(p, n, st);
+    if (rc != MOFQ_ERR_UNSUPPORTED) return rc;
+  }
+  for (int i = 0; i < n; ++i) {
+    const int rc = launch_sweep(p[i], st);
+    if (rc != MOFQ_OK) return rc;
+  }
+  return MOFQ_OK;
+}
+
 int launch_running_absmax(const SweepParams& p, float* running, hipStream_t st) {
   if (!running || !p.absmax_part || !p.energy_part) return MOFQ_ERR_INVALID_ARG;
   SweepArgs a{};

@@ -36,11 +36,18 @@ namespace {
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-struct SortedArgs {
+// One launch searches up to kSweepGroupMax tensors of one row length, dtype and configuration:
+// the rows of all tensors are numbered through, one workgroup per row.
+struct SortedTensor {
   const void* w;
-  int64_t rows, cols, ld;
-  int32_t scale_f16, n_clip;
+  int64_t ld;
   UnitRecords rec;
+};
+struct SortedArgs {
+  SortedTensor t[kSweepGroupMax];
+  uint32_t row0[kSweepGroupMax];   // number of the first row of tensor i (unused entries: 0xFFFFFFFF)
+  int64_t cols;                    // of every tensor
+  int32_t scale_f16, n_clip;
   float clip[MOFQ_MAX_CLIP];
   // per format slot: level(t) <= b  <=>  t <= thr[b];  levels ascending g_0 < g_1 < ...
   float thr[2][16];
@@ -183,8 +190,12 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int64_t row = blockIdx.x;
-  const typename L::elem* src = static_cast<const typename L::elem*>(a.w) + row * a.ld;
+  uint32_t tensor = 0;                                                    // wave-uniform
+#pragma unroll
+  for (int i = 1; i < kSweepGroupMax; ++i) tensor += (blockIdx.x >= a.row0[i]);
+  const int64_t row = blockIdx.x - a.row0[tensor];
+  const SortedTensor& T = a.t[tensor];
+  const typename L::elem* src = static_cast<const typename L::elem*>(T.w) + row * T.ld;
   const int K = a.n_clip;
   const int n = static_cast<int>(a.cols);
 
@@ -521,10 +532,10 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
       if (s_val[e] < best || (s_val[e] == best && k < bk)) { best = s_val[e]; bk = k; }
     }
     if (bk < 0) { bk = 0; best = __builtin_nan(""); }   // only on non-finite input
-    a.rec.scale[f][row] = s_scale[f][bk];
-    a.rec.clip[f][row] = bk;
-    a.rec.err[f][row] = best;
-    if (f == 0 && a.rec.energy) a.rec.energy[row] = en;
+    T.rec.scale[f][row] = s_scale[f][bk];
+    T.rec.clip[f][row] = bk;
+    T.rec.err[f][row] = best;
+    if (f == 0 && T.rec.energy) T.rec.energy[row] = en;
   }
 }
 
@@ -566,8 +577,8 @@ void fill_levels(int fmt, SortedArgs& a, int slot) {
 }
 
 template <typename In, int FA, int FB>
-int launch_shape(const SortedArgs& a, hipStream_t st) {
-  const dim3 grid(static_cast<unsigned>(a.rows));
+int launch_shape(const SortedArgs& a, int64_t total_rows, hipStream_t st) {
+  const dim3 grid(static_cast<unsigned>(total_rows));
   const int64_t chunks = a.cols / 8;
 #define MOFQ_SORTED(THREADS, CH)                                                          \
   if (chunks <= static_cast<int64_t>(THREADS) * (CH)) {                                    \
@@ -584,35 +595,62 @@ int launch_shape(const SortedArgs& a, hipStream_t st) {
 }
 
 template <typename In>
-int launch_fmt(const SweepParams& p, const SortedArgs& a, hipStream_t st) {
+int launch_fmt(const SweepParams& p, const SortedArgs& a, int64_t total_rows, hipStream_t st) {
   const int fa = p.fmt[0], fb = p.n_fmt == 2 ? p.fmt[1] : -1;
-  if (fa == MOFQ_INT4 && fb == MOFQ_FP4_E2M1) return launch_shape<In, MOFQ_INT4, MOFQ_FP4_E2M1>(a, st);
-  if (fa == MOFQ_INT4 && fb == -1) return launch_shape<In, MOFQ_INT4, -1>(a, st);
-  if (fa == MOFQ_FP4_E2M1 && fb == -1) return launch_shape<In, MOFQ_FP4_E2M1, -1>(a, st);
+  if (fa == MOFQ_INT4 && fb == MOFQ_FP4_E2M1) return launch_shape<In, MOFQ_INT4, MOFQ_FP4_E2M1>(a, total_rows, st);
+  if (fa == MOFQ_INT4 && fb == -1) return launch_shape<In, MOFQ_INT4, -1>(a, total_rows, st);
+  if (fa == MOFQ_FP4_E2M1 && fb == -1) return launch_shape<In, MOFQ_FP4_E2M1, -1>(a, total_rows, st);
   return MOFQ_ERR_UNSUPPORTED;
 }
 
 }  // namespace
 
 // Returns MOFQ_ERR_UNSUPPORTED when the configuration is outside this kernel's domain
-// (the caller then uses the direct kernel); nothing has been enqueued in that case.
-int launch_sweep_sorted(const SweepParams& p, hipStream_t st) {
+// (the caller then uses the direct kernel) or the tensors do not share row length, dtype and
+// configuration; nothing has been enqueued in that case.
+int launch_sweep_sorted_group(const SweepParams* ps, int n, hipStream_t st) {
+  if (!ps || n < 1 || n > kSweepGroupMax) return MOFQ_ERR_UNSUPPORTED;
+  const SweepParams& p = ps[0];
   if (p.gran != MOFQ_PER_CHANNEL) return MOFQ_ERR_UNSUPPORTED;
   if (p.dtype != MOFQ_F16 && p.dtype != MOFQ_BF16) return MOFQ_ERR_UNSUPPORTED;
   if (p.n_clip < 8 || p.cols < 1024 || p.cols > 24576) return MOFQ_ERR_UNSUPPORTED;
   for (int f = 0; f < p.n_fmt; ++f)
     if (p.fmt[f] != MOFQ_INT4 && p.fmt[f] != MOFQ_FP4_E2M1) return MOFQ_ERR_UNSUPPORTED;
+  int64_t total_rows = 0;
+  for (int i = 0; i < n; ++i) {
+    if (ps[i].rows < 1) return MOFQ_ERR_UNSUPPORTED;
+    total_rows += ps[i].rows;
+  }
+  if (total_rows >= (int64_t{1} << 31)) return MOFQ_ERR_UNSUPPORTED;
+  for (int i = 1; i < n; ++i) {
+    const SweepParams& q = ps[i];
+    if (q.gran != p.gran || q.dtype != p.dtype || q.cols != p.cols ||
+        q.scale_f16 != p.scale_f16 || q.n_clip != p.n_clip || q.n_fmt != p.n_fmt)
+      return MOFQ_ERR_UNSUPPORTED;
+    for (int f = 0; f < p.n_fmt; ++f)
+      if (q.fmt[f] != p.fmt[f]) return MOFQ_ERR_UNSUPPORTED;
+    for (int k = 0; k < p.n_clip; ++k)
+      if (q.clip[k] != p.clip[k]) return MOFQ_ERR_UNSUPPORTED;
+  }
   SortedArgs a{};
-  a.w = p.w;
-  a.rows = p.rows;
+  uint32_t row0 = 0;
+  for (int i = 0; i < kSweepGroupMax; ++i) {
+    a.row0[i] = 0xFFFFFFFFu;
+    if (i >= n) continue;
+    a.t[i].w = ps[i].w;
+    a.t[i].ld = ps[i].ld;
+    a.t[i].rec = ps[i].rec;
+    a.row0[i] = row0;
+    row0 += static_cast<uint32_t>(ps[i].rows);
+  }
   a.cols = p.cols;
-  a.ld = p.ld;
   a.scale_f16 = p.scale_f16;
   a.n_clip = p.n_clip;
-  a.rec = p.rec;
   for (int k = 0; k < p.n_clip; ++k) a.clip[k] = p.clip[k];
   for (int f = 0; f < p.n_fmt; ++f) fill_levels(p.fmt[f], a, f);
-  return p.dtype == MOFQ_F16 ? launch_fmt<F16>(p, a, st) : launch_fmt<BF16>(p, a, st);
+  return p.dtype == MOFQ_F16 ? launch_fmt<F16>(p, a, total_rows, st) : launch_fmt<BF16>(p, a, total_rows, st);
 }
+
+int launch_sweep_sorted(const SweepParams& p, hipStream_t st) { return launch_sweep_sorted_group(&p, 1, st); }
 
 }  // namespace mofq

@@ -34,10 +34,19 @@ def _single(mq, w, cands, cfg, bits):
                                                    (orc.PER_GROUP, 128, True, 12), (orc.PER_TENSOR, 0, False, 3)])
 @pytest.mark.parametrize("two_streams", [False, True, "same"])
 def test_batched_equals_single(mq, gran, group, f16, n_clip, two_streams):
-    # 29 tensors: more than two batches, mixed shapes; group-wise ones above the per-launch unit limit too
+    # more than four batches, mixed shapes; group-wise ones above the per-launch unit limit too;
+    # runs of one shape (tensors of one row length in a batch are searched in one launch: 4, 2,
+    # and 11 = more than a launch takes), one of
+    # them with a member of another dtype and one with a member whose rows are strided
     shapes = [(7, 1024), (64, 4096), (3, 256), (300, 2048), (17, 11008)] * 5 + [(200, 12288), (5, 512), (1, 8 * 40), (130, 1536)]
+    shapes += [(64, 4096)] * 4 + [(17, 11008)] * 2 + [(3, 256)] * 11 + [(33, 2048)] * 3 + [(9, 1024)] * 3
     shapes = [(r, c) for r, c in shapes if gran != orc.PER_GROUP or c % group == 0]
     ws_ = [mi.llama_like_weight(r, c, seed=700 + i, device=DEV, outlier_frac=2e-3) for i, (r, c) in enumerate(shapes)]
+    mid33 = [i for i, sh in enumerate(shapes) if sh == (33, 2048)][1]
+    ws_[mid33] = ws_[mid33].to(torch.bfloat16)
+    mid9 = [i for i, sh in enumerate(shapes) if sh == (9, 1024)][1]
+    ws_[mid9] = torch.cat([ws_[mid9], ws_[mid9]], dim=1)[:, :1024]      # row stride 2048
+    assert ws_[mid9].stride(0) == 2048
     cands = [mq.INT4, mq.FP4_E2M1]
     cfg = mq.Cfg(gran, mi.clip_ratios(n_clip), group, f16)
     outs = [mq.alloc_qbuffers(r, c, 4, cfg, DEV) for r, c in shapes]
@@ -53,7 +62,14 @@ def test_batched_equals_single(mq, gran, group, f16, n_clip, two_streams):
     snap = [(o.codes.clone(), o.scales.clone(), o.clip_idx.clone(), o.unit_err.clone()) for o in outs]
     results_snap = results.clone()
     torch.cuda.synchronize()
-    assert all(a.elapsed_time(b) >= 0.0 for a, b in zip(e0, e1))
+    # events bracket each search launch: begin of its first tensor, end of its last
+    first = batch.search_groups(cands)
+    assert all(f <= i and first[f] == f and i - f < 12 for i, f in enumerate(first))
+    assert all(ws_[i].shape[1] == ws_[f].shape[1] and ws_[i].dtype == ws_[f].dtype for i, f in enumerate(first))
+    last = {f: i for i, f in enumerate(first)}
+    assert all(first.count(f) <= 8 for f in last)
+    assert max(first.count(f) for f in last) >= 4
+    assert all(e0[f].elapsed_time(e1[l]) >= 0.0 for f, l in last.items())
     res = mq.read_results(results_snap)
     for i, w in enumerate(ws_):
         ref_out, ref_res = _single(mq, w, cands, cfg, 4)
