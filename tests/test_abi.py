@@ -104,3 +104,43 @@ def test_workspace_bytes_host_only(lib):
     units = 4096 * 86
     assert n1 >= units * (4 + 4 + 8 + 8) and n2 >= units * (2 * 16 + 8) and n2 > n1
     assert L.mofq_workspace_bytes(C.byref(t), None, 0, lib.ERR_TENSOR, C.byref(cfg)) == 0
+
+
+def test_search_groups_host_only(lib):
+    """mofq_select_layers_search_groups: tensors of one row length and dtype inside a batch
+    (at most 12 tensors / 512 MB) share a launch, at most 8 per launch."""
+    L = lib._lib
+
+    def groups(descs, cands):
+        n = len(descs)
+        w = (lib.TensorDesc * n)(*descs)
+        c = (C.c_int32 * len(cands))(*cands)
+        first = (C.c_int32 * n)()
+        assert L.mofq_select_layers_search_groups(n, w, c, len(cands), first) == 0
+        return list(first)
+
+    def t(rows, cols, dtype=None):
+        return lib.TensorDesc(0x1000, lib.F16 if dtype is None else dtype, rows, cols, cols)
+
+    pair = [lib.INT4, lib.FP4_E2M1]
+    # one 7B-shaped block (386 MB): every 4096-column tensor in one group, the down projection alone
+    block = [t(4096, 4096)] * 4 + [t(11008, 4096)] * 2 + [t(4096, 11008)]
+    assert groups(block, pair) == [0, 0, 0, 0, 0, 0, 6]
+    # not adjacent, other dtype in between, more than 8 members
+    mixed = [t(8, 1024), t(8, 2048), t(16, 1024), t(8, 1024, lib.BF16)] + [t(8, 1024)] * 8
+    assert groups(mixed, pair) == [0, 1, 0, 3] + [0] * 6 + [10, 10]
+    # a batch ends after 12 tensors ...
+    assert groups([t(8, 1024)] * 14, pair) == [0] * 8 + [8] * 4 + [12] * 2
+    # ... or before it would exceed 512 MB (the first tensor of a batch may be larger than that)
+    big = [t(16384, 8192)] * 3                                # 256 MB each
+    assert groups(big, pair) == [0, 0, 2]
+    assert groups([t(32768, 16384), t(8, 16384)], pair) == [0, 1]
+    # three candidates need two launches per tensor: nothing is joined
+    assert groups(block, [lib.INT4, lib.FP4_E2M1, lib.FP4_E2M1_IEEE]) == list(range(7))
+    # invalid arguments
+    c = (C.c_int32 * 2)(*pair)
+    w = (lib.TensorDesc * 1)(t(8, 1024))
+    first = (C.c_int32 * 1)()
+    assert L.mofq_select_layers_search_groups(0, w, c, 2, first) != 0
+    assert L.mofq_select_layers_search_groups(1, w, c, 2, None) != 0
+    assert L.mofq_select_layers_search_groups(1, w, c, 0, first) != 0
