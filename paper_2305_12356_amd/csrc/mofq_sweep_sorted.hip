@@ -35,6 +35,7 @@ namespace mofq {
 namespace {
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 // One launch searches up to kSweepGroupMax tensors of one row length, dtype and configuration:
 // the rows of all tensors are numbered through, one workgroup per row.
@@ -124,6 +125,19 @@ MOFQ_DEV double wave_excl_scan_f64(double v, double& total) {
   return inc - v;
 }
 
+// sum over the wave in fp32 (uniform result)
+MOFQ_DEV float wave_sum_f32(float v) {
+  v += dpp_f32<DPP_QUAD_XOR1>(v);
+  v += dpp_f32<DPP_QUAD_XOR2>(v);
+  v += dpp_f32<DPP_ROW_HALF_MIRROR>(v);
+  v += dpp_f32<DPP_ROW_MIRROR>(v);
+  const float a = u2f(__builtin_amdgcn_readlane(static_cast<int>(f2u(v)), 0));
+  const float b = u2f(__builtin_amdgcn_readlane(static_cast<int>(f2u(v)), 16));
+  const float c = u2f(__builtin_amdgcn_readlane(static_cast<int>(f2u(v)), 32));
+  const float d = u2f(__builtin_amdgcn_readlane(static_cast<int>(f2u(v)), 48));
+  return (a + b) + (c + d);
+}
+
 // exact re-score of two elements (same arithmetic as the direct kernel's second phase)
 template <int FMT> MOFQ_DEV void rescore2(double& acc, float x0, float x1, float inv_s, double sd, uint32_t& carry) {
   f32x2 g;
@@ -200,8 +214,9 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   const int n = static_cast<int>(a.cols);
 
   // ---- load the row: absmax, energy, and the sort keys ------------------------------
-  float amax = 0.0f;
-  double en = 0.0, l1 = 0.0;
+  float amax = 0.0f, l1f = 0.0f;
+  uint32_t amax2 = 0;   // fp16 rows: running maximum of |x| in both halves of a register
+  double en = 0.0;
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
     const int64_t c0 = (static_cast<int64_t>(j) * THREADS + tid) * 8;
@@ -213,18 +228,28 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
     for (int i = 0; i < 4; ++i) {
       const uint32_t h0 = raw[i] & 0xFFFFu, h1 = raw[i] >> 16;
       const float v0 = bits_to_float<In>(h0), v1 = bits_to_float<In>(h1);
-      amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fabsf(v0), __builtin_fabsf(v1)));
+      if constexpr (std::is_same<In, F16>::value) {
+        amax2 = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(f16x2, amax2),
+                                                                       __builtin_bit_cast(f16x2, raw[i] & 0x7FFF7FFFu)));
+      } else {
+        amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fabsf(v0), __builtin_fabsf(v1)));
+      }
       const double d0 = static_cast<double>(v0), d1 = static_cast<double>(v1);
       en = __builtin_fma(d0, d0, en);
       en = __builtin_fma(d1, d1, en);
-      l1 += __builtin_fabs(d0) + __builtin_fabs(d1);
+      l1f += __builtin_fabsf(v0) + __builtin_fabsf(v1);
       keys[i] = ok ? to_key2(raw[i]) : 0xFFFFFFFFu;   // padding sorts last
     }
     *reinterpret_cast<u32x4*>(&s_keys[tid * E + j * 8]) = keys;
   }
+  if constexpr (std::is_same<In, F16>::value)
+    amax = __builtin_fmaxf(bits_to_float<In>(amax2 & 0xFFFFu), bits_to_float<In>(amax2 >> 16));
   amax = wave_max(amax);
   en = wave_sum(en);
-  l1 = wave_sum(l1);
+  // sum |x| only enters the rounding bounds below: summed in fp32 (E + 7 additions of non-negative
+  // terms, each off by at most 2^-24 relative; E <= 48) and raised by 2^-17 so that it stays an
+  // upper bound
+  double l1 = static_cast<double>(wave_sum_f32(l1f)) * (1.0 + 0x1p-17);
   if (lane == 0) { s_wmax[wave] = amax; s_wsum[0][wave] = en; s_wsum[1][wave] = l1; }
   __syncthreads();
   amax = s_wmax[0];
@@ -260,10 +285,8 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
       for (int i = 0; i < 4; ++i) kreg[j * 4 + i] = v[i];
     }
 #pragma unroll
-    for (int i = 0; i < E; ++i) {
-      const uint32_t key = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
-      atomicAdd(&s_cnt[(key >> shift) & 15u][tid], 1u);   // own column: plain LDS add
-    }
+    for (int i = 0; i < E; ++i)   // own column: plain LDS add; positions are counted in bytes
+      atomicAdd(&s_cnt[__builtin_amdgcn_ubfe(kreg[i >> 1], shift + (i & 1) * 16, 4)][tid], 2u);
     __syncthreads();
     // per digit: exclusive scan of the counts across threads (kept in registers), digit totals aside
     uint32_t c[DPW][PER], base[DPW];
@@ -294,10 +317,8 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
     __syncthreads();
     uint32_t pos[E];
 #pragma unroll
-    for (int i = 0; i < E; ++i) {
-      const uint32_t key = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
-      pos[i] = atomicAdd(&s_cnt[(key >> shift) & 15u][tid], 1u);   // stable: thread order, then i
-    }
+    for (int i = 0; i < E; ++i)   // stable: thread order, then i
+      pos[i] = atomicAdd(&s_cnt[__builtin_amdgcn_ubfe(kreg[i >> 1], shift + (i & 1) * 16, 4)][tid], 2u);
     if constexpr (LAST) {   // back to the elements' own patterns
 #pragma unroll
       for (int i = 0; i < E / 2; ++i) kreg[i] = from_key2(kreg[i]);
@@ -305,8 +326,9 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
 #pragma unroll
     for (int i = 0; i < E; ++i) {
       const uint32_t v = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
-      if constexpr (LAST) s_keys[phys(static_cast<int>(pos[i]))] = static_cast<uint16_t>(v);
-      else s_keys[pos[i]] = static_cast<uint16_t>(v);
+      // byte offset; the padded layout adds 4 bytes per 128
+      const uint32_t off = LAST ? pos[i] + ((pos[i] >> 7) << 2) : pos[i];
+      *reinterpret_cast<uint16_t*>(s_raw + off) = static_cast<uint16_t>(v);
     }
     __syncthreads();
   };
