@@ -53,7 +53,7 @@ struct SortedArgs {
   // per format slot: level(t) <= b  <=>  t <= thr[b];  levels ascending g_0 < g_1 < ...
   float thr[2][16];
   double dgd[2][16];  // g_b - g_{b+1}
-  float dg2[2][16];   // g_b^2 - g_{b+1}^2
+  int32_t dg2q[2][16];  // 4 (g_b^2 - g_{b+1}^2): an integer for every 4-bit format
   float g_last[2];    // largest level
   float g_absmax[2];  // largest |level|
   int32_t nb[2];      // number of boundaries (levels - 1)
@@ -423,19 +423,23 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
       }
       const float t_last = x_last * inv;
       double ca = 0.0;
-      float cb = 0.0f;   // counts times level-square differences are small multiples of 1/4: exact in fp32
+      int cb4 = 0;       // 4 sum_b (count below boundary b) (g_b^2 - g_{b+1}^2): an integer below 2^31
 #pragma unroll
       for (int q = 0; q < NBD; ++q) {
         // position in elements: the padded byte offset holds 132 bytes per 64 elements
-        const int j0 = (ppos[q] >> 1) - 2 * static_cast<int>(__umulhi(static_cast<uint32_t>(ppos[q]), 32537632u));
+        // (slot / 66 = slot * 993 >> 16 for every slot of a row of up to 24576 elements: the slot of
+        // an element leaves a remainder of at most 63, so the quotient's fraction stays below 1 - 2/66
+        // and the factor's excess of 5e-7 per slot cannot carry)
+        const int slot = ppos[q] >> 1;
+        const int j0 = slot - 2 * static_cast<int>(__umul24(static_cast<uint32_t>(slot), 993u) >> 16);
         const int j = j0 + (t_last <= a.thr[f][q] ? 1 : 0);
         constexpr int LB = (BS == 2) ? 1 : (BS == 4 ? 2 : 3);
         double p = s_blk[j >> LB];
         if constexpr (BS == 2) {
           // an odd position adds the element before it, which sits at the offset rounded down
           // to 4 bytes (an even position reads its own element there and drops it; j = NP is even)
-          const float xv = bits_to_float<In>(*reinterpret_cast<const uint16_t*>(s_raw + (ppos[q] & ~3)));
-          p += static_cast<double>((j & 1) ? xv : 0.0f);
+          const uint32_t hv = *reinterpret_cast<const uint16_t*>(s_raw + (ppos[q] & ~3));
+          p += static_cast<double>(bits_to_float<In>(hv & static_cast<uint32_t>(-(j & 1))));
         } else {
           const int jb = phys(j & ~(BS - 1));
 #pragma unroll
@@ -446,12 +450,12 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
           }
         }
         ca = __builtin_fma(p, a.dgd[f][q], ca);
-        cb = __builtin_fmaf(static_cast<float>(j), a.dg2[f][q], cb);
+        cb4 = __mul24(j, a.dg2q[f][q]) + cb4;
       }
       if (k < K) {
         const double gl = static_cast<double>(a.g_last[f]);
         const double A = ca + gl * s_total;
-        const double B = static_cast<double>(cb) + gl * gl * static_cast<double>(n);
+        const double B = 0.25 * static_cast<double>(cb4) + gl * gl * static_cast<double>(n);
         const double sc = static_cast<double>(s_scale[f][k]);
         s_fast[f][k] = (en - 2.0 * sc * A) + sc * sc * B;   // filtered error
       }
@@ -587,14 +591,14 @@ void fill_levels(int fmt, SortedArgs& a, int slot) {
   a.nb[slot] = nl - 1;
   a.g_last[slot] = static_cast<float>(lv[nl - 1]);
   a.g_absmax[slot] = static_cast<float>(std::fmax(std::fabs(lv[0]), std::fabs(lv[nl - 1])));
-  for (int b = 0; b < 16; ++b) { a.thr[slot][b] = 0.0f; a.dgd[slot][b] = 0.0; a.dg2[slot][b] = 0.0f; }
+  for (int b = 0; b < 16; ++b) { a.thr[slot][b] = 0.0f; a.dgd[slot][b] = 0.0; a.dg2q[slot][b] = 0; }
   for (int b = 0; b + 1 < nl; ++b) {
     const float mid = static_cast<float>(0.5 * (lv[b] + lv[b + 1]));   // exact in fp32
     // tie goes up  -> level <= b needs t <  mid -> t <= the float just below mid
     // tie goes down-> level <= b needs t <= mid
     a.thr[slot][b] = up_is_even[b] ? std::nextafterf(mid, -INFINITY) : mid;
     a.dgd[slot][b] = lv[b] - lv[b + 1];
-    a.dg2[slot][b] = static_cast<float>(lv[b] * lv[b] - lv[b + 1] * lv[b + 1]);
+    a.dg2q[slot][b] = static_cast<int32_t>(4.0 * (lv[b] * lv[b] - lv[b + 1] * lv[b + 1]));   // exact
   }
 }
 
