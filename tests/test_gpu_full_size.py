@@ -105,3 +105,38 @@ def test_whole_block_every_linear_decision(mq):
     # Table 2 reports 88.9-97.9 % of layers choosing FP4 on real weights; Gaussian rows with
     # heavy-tailed outliers behave the same way
     assert sum(picks) >= 6
+
+
+def test_7b_first_batch_through_select_layers(mq):
+    """bench.py's launch configuration: one mofq_select_layers call with a second stream, whose
+    first batch is the seven linears of block 0 and q, k, v of block 1 -- the eight 4096-column
+    tensors that come first (46592 rows) in one search launch.  Every tensor against the oracle
+    on sampled rows and, whole, against the single-tensor call."""
+    clip = mi.clip_ratios(100)
+    cfg = mq.Cfg(orc.PER_CHANNEL, clip)
+    shapes = [(b, li, o, n) for b in range(2) for li, (_, o, n) in enumerate(mi.block_linear_shapes("7b"))][:10]
+    ws_ = [mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, li), device=DEV) for b, li, o, n in shapes]
+    outs = [mq.alloc_qbuffers(o, n, 4, cfg, DEV) for _, _, o, n in shapes]
+    batch = mq.LayerBatch(ws_, outs)
+    first = batch.search_groups(CANDS)
+    assert first == [0, 0, 0, 0, 0, 0, 6, 0, 0, 9]
+    results = mq.alloc_result(DEV, len(shapes))
+    ws = torch.empty(batch.workspace_bytes(2, cfg), dtype=torch.uint8, device=DEV)
+    print("[case] 7b first batch through mofq_select_layers", flush=True)
+    mq.select_layers(batch, CANDS, cfg, results, ws, side_stream=torch.cuda.Stream())
+    torch.cuda.synchronize()
+    res = mq.read_results(results)
+    rng = np.random.default_rng(11)
+    for i, (b, li, o, n) in enumerate(shapes):
+        rows = np.sort(rng.choice(o, size=12, replace=False))
+        rows[0], rows[-1] = 0, o - 1
+        w32 = mi.to_f32_numpy(ws_[i][torch.as_tensor(rows, device=DEV)])
+        rt = torch.as_tensor(rows, device=DEV)
+        ref = orc.quantize(w32, CANDS[res[i].best], orc.PER_CHANNEL, clip, 0, False, want_table=True)
+        compare_quantized(w32, CANDS[res[i].best], orc.PER_CHANNEL, 0, False, np.asarray(clip, dtype=np.float32), ref,
+                          _rows_codes(outs[i], rows, n), scales_to_f32(outs[i].scales[rt]),
+                          outs[i].clip_idx[rt].cpu().numpy(), outs[i].unit_err[rt].cpu().numpy())
+        one, r1, _ = _select(mq, ws_[i], cfg)
+        assert res[i].best == r1.best and list(res[i].err) == list(r1.err) and res[i].ref_energy == r1.ref_energy
+        assert torch.equal(outs[i].codes, one.codes) and torch.equal(outs[i].scales, one.scales)
+        assert torch.equal(outs[i].clip_idx, one.clip_idx) and torch.equal(outs[i].unit_err, one.unit_err)
