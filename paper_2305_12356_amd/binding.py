@@ -316,7 +316,9 @@ def select_layers(batch: LayerBatch, candidates: Sequence[int], cfg: Cfg, result
     """mofq_select_layers (or _timed with lists of torch.cuda.Event): weight-only select of
     every tensor of the batch; `results` is the device array from alloc_result(device, n).
     `side_stream`: a torch.cuda.Stream for the select + emission of each batch (None: all on
-    `stream`)."""
+    `stream`).  The events bracket search launches, which cover several tensors each:
+    ev_begin of a launch's first tensor and ev_end of its last are recorded, the others are
+    left alone (LayerBatch.search_groups tells which)."""
     cand = (C.c_int32 * len(candidates))(*candidates)
     side = C.c_void_p(side_stream.cuda_stream) if side_stream is not None else C.c_void_p(0)
     args = (batch.n, batch.w, cand, len(candidates), C.byref(cfg.c), batch.out, _ptr(results), _ptr(ws),

@@ -709,7 +709,7 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
     FinishParams fin[kFinishBatch];
     DecideParams big[kFinishBatch];
     int n_fin = 0, fin_of[kFinishBatch], n_big = 0, big_of[kFinishBatch];
-    // 1. the searches, back to back; consecutive tensors of one shape share a launch
+    // 1. the searches, back to back; the tensors of one row length share a launch
     for (int j = 0; j < nb; ++j) {
       const int64_t units = mofq_num_units(w[i0 + j].rows, w[i0 + j].cols, w_cfg->gran, w_cfg->group_size);
       slot[j] = carve_w_only(base, units, n_candidates, w_cfg->gran, w_cfg->n_clip);
