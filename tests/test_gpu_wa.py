@@ -184,3 +184,37 @@ def test_wa_argument_errors(mq):
     with pytest.raises(mq.MofqError) as e:      # inner dimensions differ
         mq.score(wb[:, :64].contiguous(), x, I8, mq.ERR_LAYER_OUTPUT, cfg, err, None, ws)
     assert e.value.status == -1
+
+
+def test_calls_on_two_caller_streams_equal_serial_calls(mq):
+    """The library keeps no state: calls for different linears may run concurrently on two
+    streams of the caller (own workspace and outputs per stream) and give, bit for bit, what
+    the same calls give one after the other."""
+    shapes = [(512, 1024), (300, 1024), (1024, 512), (129, 2048), (512, 1024), (640, 512)]
+    xs = {k: mi.activations(384, k, seed=900 + k, device=DEV) for k in {n for _, n in shapes}}
+    ws_ = [mi.llama_like_weight(o, n, seed=910 + i, dtype=torch.bfloat16, device=DEV) for i, (o, n) in enumerate(shapes)]
+    cands = [I8, FP8]
+    cfg = mq.Cfg(orc.PER_TENSOR, mi.clip_ratios(1))
+    xcfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
+    nbytes = max(mq.workspace_bytes(w, xs[w.shape[1]], 2, mq.ERR_LAYER_OUTPUT, cfg) for w in ws_)
+
+    def run(streams):
+        res = mq.alloc_result(DEV, len(shapes))
+        wsp = [torch.empty(nbytes, dtype=torch.uint8, device=DEV) for _ in streams]
+        w_out = [mq.alloc_qbuffers(o, n, 8, cfg, DEV) for o, n in shapes]
+        x_out = [mq.alloc_qbuffers(384, n, 8, xcfg, DEV) for _, n in shapes]
+        torch.cuda.synchronize()
+        for rep in range(3):                      # several rounds, so that the calls really overlap
+            for i, w in enumerate(ws_):
+                s = i % len(streams)
+                mq.select_layer(w, xs[w.shape[1]], cands, mq.ERR_LAYER_OUTPUT, cfg, w_out[i], x_out[i], res[i],
+                                wsp[s], streams[s])
+        torch.cuda.synchronize()
+        return mq.read_results(res), w_out, x_out
+
+    r1, w1, x1 = run([torch.cuda.current_stream()])
+    r2, w2, x2 = run([torch.cuda.Stream(), torch.cuda.Stream()])
+    for i in range(len(shapes)):
+        assert r1[i].best == r2[i].best and list(r1[i].err) == list(r2[i].err) and r1[i].ref_energy == r2[i].ref_energy
+        assert torch.equal(w1[i].codes, w2[i].codes) and torch.equal(w1[i].scales, w2[i].scales)
+        assert torch.equal(x1[i].codes, x2[i].codes) and torch.equal(x1[i].scales, x2[i].scales)
