@@ -134,7 +134,8 @@ typedef struct {
 
 /* Outcome of Algorithm 1 for one layer; device memory. */
 typedef struct {
-  int32_t best;       /* index into candidates[] of the chosen format */
+  int32_t best;       /* index into candidates[] of the chosen format; always in range: 0 when no
+                         candidate's error is below +inf (non-finite input) */
   int32_t n;          /* number of candidates */
   double err[MOFQ_MAX_CANDIDATES]; /* error sum of squares per candidate */
   double ref_energy;  /* sum x^2 (tensor metric) or sum (X W^T)^2 (layer-output metric):

@@ -110,9 +110,10 @@ struct SweepEmit {
 };
 
 // Parameters of the launch that scores candidates c0 .. c0 + n - 1 (n = 2: a pair of different
-// formats that share one read of the tensor).
-SweepParams sweep_params(const mofq_tensor_t* t, const int32_t* cand, int c0, int n,
-                         const mofq_scale_cfg_t* cfg, const WOnlyWs& w) {
+// formats that share one read of the tensor).  A launch takes at most kMaxFmt formats.
+int sweep_params(const mofq_tensor_t* t, const int32_t* cand, int c0, int n,
+                 const mofq_scale_cfg_t* cfg, const WOnlyWs& w, SweepParams* out) {
+  if (n < 1 || n > kMaxFmt || c0 < 0 || c0 + n > MOFQ_MAX_CANDIDATES) return MOFQ_ERR_INVALID_ARG;
   SweepParams p{};
   p.w = t->data;
   p.dtype = t->dtype;
@@ -138,7 +139,8 @@ SweepParams sweep_params(const mofq_tensor_t* t, const int32_t* cand, int c0, in
   p.absmax_part = w.absmax_part;
   p.sse_part = w.sse_part;
   p.energy_part = w.energy_part;
-  return p;
+  *out = p;
+  return MOFQ_OK;
 }
 
 // The whole candidate list is one launch: a single format or a pair of different ones.
@@ -154,7 +156,9 @@ int sweep_candidates(const mofq_tensor_t* t, const int32_t* cand, int n_cand,
     // two different formats share one launch (one read of the tensor); a repeated
     // format is scored on its own
     const int n = (c0 + 1 < n_cand && paired(cand[c0], cand[c0 + 1])) ? 2 : 1;
-    SweepParams p = sweep_params(t, cand, c0, n, cfg, w);
+    SweepParams p{};
+    int rc = sweep_params(t, cand, c0, n, cfg, w, &p);
+    if (rc != MOFQ_OK) return rc;
     p.ext_absmax = ext_absmax;
     if (em) {
       if (n != 2) return MOFQ_ERR_INVALID_ARG;
@@ -162,7 +166,7 @@ int sweep_candidates(const mofq_tensor_t* t, const int32_t* cand, int n_cand,
       p.emit_f8 = em->f8;
       p.emit_f8_as_bf16 = em->f8_as_bf16;
     }
-    const int rc = launch_sweep(p, st);
+    rc = launch_sweep(p, st);
     if (rc != MOFQ_OK) return rc;
     c0 += n;
   }
@@ -573,20 +577,34 @@ int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, i
 
 namespace {
 
-// A batch of mofq_select_layers ends at kFinishBatch tensors or once it holds kBatchBytes of
-// input.  The batch is the unit of overlap (its select and emission run beside the next
+// Compute units of the current device (256 on an MI355X); 256 when no device answers, so that
+// the host-only planning calls work anywhere.
+int compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+    (void)hipGetLastError();
+    return 256;
+  }
+  return n;
+}
+
+// A batch of mofq_select_layers ends at kFinishBatch tensors or once it holds 2 MB of input per
+// compute unit.  The batch is the unit of overlap (its select and emission run beside the next
 // batch's searches) and of search grouping (its tensors of one row length share a launch), so
 // it should span the same-length tensors of a transformer block; past that, larger batches
-// only lengthen the exposed emission of the last one.  Measured on the 7B-shaped set, whole
-// pass: 31.4 ms at 256 MB, 30.6 ms at 400 MB, 30.3 ms at 520 MB.  Returns the number of
-// tensors in the batch that starts at i0.
-int batch_length(int n_layers, const mofq_tensor_t* w, int i0) {
-  constexpr int64_t kBatchBytes = int64_t{512} << 20;
+// only lengthen the exposed emission of the last one.  Measured on 256 compute units with the
+// 7B-shaped set, whole pass: 31.4 ms at 256 MB, 30.6 ms at 400 MB, 30.3 ms at 520 MB.  The budget is
+// per compute unit because what it balances, a launch that fills the device against the
+// exposed tail, scales with the device.  Returns the number of tensors in the batch that
+// starts at i0.
+int batch_length(int n_layers, const mofq_tensor_t* w, int i0, int cus) {
+  const int64_t batch_bytes = static_cast<int64_t>(cus) * (int64_t{2} << 20);
   int64_t bytes = 0;
   int nb = 0;
   for (; i0 + nb < n_layers && nb < kFinishBatch; ++nb) {
     const int64_t b = w[i0 + nb].rows * w[i0 + nb].cols * (w[i0 + nb].dtype == MOFQ_F32 ? 4 : 2);
-    if (nb > 0 && bytes + b > kBatchBytes) break;
+    if (nb > 0 && bytes + b > batch_bytes) break;
     bytes += b;
   }
   return nb;
@@ -620,8 +638,9 @@ int mofq_select_layers_search_groups(int32_t n_layers, const mofq_tensor_t* w, c
   if (n_layers < 1 || !w || !group_first) return MOFQ_ERR_INVALID_ARG;
   const int rc = check_candidates(candidates, n_candidates);
   if (rc) return rc;
+  const int cus = compute_units();
   for (int i0 = 0, nb = 0; i0 < n_layers; i0 += nb) {
-    nb = batch_length(n_layers, w, i0);
+    nb = batch_length(n_layers, w, i0, cus);
     int first[kFinishBatch];
     plan_search_groups(w + i0, nb, candidates, n_candidates, first);
     for (int j = 0; j < nb; ++j) group_first[i0 + j] = i0 + first[j];
@@ -673,11 +692,11 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
   hipStream_t st2 = sw.side;
   auto join = [&](int status) { return sw.join(status); };
   // Beside the searches the emission has their whole duration to move its bytes: one
-  // workgroup per compute unit leaves the wave slots to the searches (measured on the 7B-shaped
-  // set: 33.9 ms per pass against 35.1 ms with the device-filling grid; 128 and 512 workgroups
-  // are both slower).
-  constexpr int kBackgroundEmitBlocks = 256;
-  int emit_cap = sw.two ? kBackgroundEmitBlocks : 0;
+  // workgroup per compute unit leaves the wave slots to the searches (measured on 256 compute
+  // units with the 7B-shaped set: 33.9 ms per pass against 35.1 ms with the device-filling grid;
+  // half and twice as many workgroups are both slower).
+  const int cus = compute_units();
+  int emit_cap = sw.two ? cus : 0;
 
   auto emit_params = [&](int i, const WOnlyWs& s) {
     EmitParams e{};
@@ -704,7 +723,7 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
 
   char* base = static_cast<char*>(ws);
   for (int i0 = 0, nb = 0; i0 < n_layers; i0 += nb) {
-    nb = batch_length(n_layers, w, i0);
+    nb = batch_length(n_layers, w, i0, cus);
     WOnlyWs slot[kFinishBatch];
     FinishParams fin[kFinishBatch];
     DecideParams big[kFinishBatch];
@@ -717,17 +736,24 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
     }
     int first[kFinishBatch];
     plan_search_groups(w + i0, nb, candidates, n_candidates, first);
+    const bool one_launch = one_sweep_launch(candidates, n_candidates);
     for (int j = 0; j < nb; ++j) {
       if (first[j] != j) continue;
+      // A launch over several tensors exists only where the whole candidate list is one
+      // launch (plan_search_groups joins nothing otherwise); longer lists go tensor by tensor
+      // through sweep_candidates, which splits them into launches of at most two formats.
       SweepParams sp[kSweepGroupMax];
       int g = 0, last = j;
       for (int k = j; k < nb; ++k)
         if (first[k] == j) {
-          sp[g++] = sweep_params(&w[i0 + k], candidates, 0, n_candidates, w_cfg, slot[k]);
+          if (one_launch && (rc = sweep_params(&w[i0 + k], candidates, 0, n_candidates, w_cfg, slot[k], &sp[g])))
+            return join(rc);
+          ++g;
           last = k;
         }
       if (ev_begin && hipEventRecord(static_cast<hipEvent_t>(ev_begin[i0 + j]), st) != hipSuccess) return join(MOFQ_ERR_HIP);
       if (g > 1) {
+        if (!one_launch) return join(MOFQ_ERR_INVALID_ARG);   // cannot happen: see plan_search_groups
         if ((rc = launch_sweep_group(sp, g, st))) return join(rc);
       } else {
         if ((rc = sweep_candidates(&w[i0 + j], candidates, n_candidates, w_cfg, slot[j], st))) return join(rc);

@@ -99,7 +99,9 @@ MOFQ_DEV int decide_body(const DecideParams& p, double* s_red) {
     for (int c = 0; c < MOFQ_MAX_CANDIDATES; ++c)
       if (c < p.n_cand && err[c] < min_err) { min_err = err[c]; best = c; }
     if (p.result) {
-      p.result->best = best;
+      // no candidate below infinity (non-finite input): the first candidate, which is also what
+      // the emission falls back to, so record and codes agree
+      p.result->best = best < 0 ? 0 : best;
       p.result->n = p.n_cand;
 #pragma unroll
       for (int c = 0; c < MOFQ_MAX_CANDIDATES; ++c) p.result->err[c] = (c < p.n_cand) ? err[c] : 0.0;

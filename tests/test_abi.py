@@ -144,3 +144,31 @@ def test_search_groups_host_only(lib):
     assert L.mofq_select_layers_search_groups(0, w, c, 2, first) != 0
     assert L.mofq_select_layers_search_groups(1, w, c, 2, None) != 0
     assert L.mofq_select_layers_search_groups(1, w, c, 0, first) != 0
+
+
+def test_select_layers_long_candidate_lists_host_only(lib):
+    """Candidate lists of three and four formats are legal (MOFQ_MAX_CANDIDATES = 4): the batched
+    call must take them through launches of at most two formats each and never index past its
+    per-launch tables.  Without a GPU the first launch fails, so the call returns the launch
+    status (a crash here is the bug this guards against); five candidates are rejected on the
+    host."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("uses made-up device pointers: only where nothing can be launched")
+    L = lib._lib
+    clip = np.array([1.0, 0.9], dtype=np.float32)
+    cfg = lib.ScaleCfg(lib.PER_CHANNEL, 0, lib.F32, 2, clip.ctypes.data_as(C.POINTER(C.c_float)))
+    n = 3
+    w = (lib.TensorDesc * n)(*[lib.TensorDesc(0x10000, lib.F16, 16, 4096, 4096)] * n)
+    out = (lib.QOut * n)(*[lib.QOut(0x20000, 0x30000, None, None)] * n)
+    res, ws = C.c_void_p(0x50000), C.c_void_p(0x100000)
+    for cands in ([lib.INT4, lib.FP4_E2M1, lib.FP4_E2M1_IEEE],
+                  [lib.INT4, lib.FP4_E2M1, lib.FP4_E2M1_IEEE, lib.INT4],
+                  [lib.FP4_E2M1, lib.FP4_E2M1, lib.INT4]):
+        c = (C.c_int32 * len(cands))(*cands)
+        need = L.mofq_select_layers_workspace_bytes(n, w, len(cands), C.byref(cfg))
+        assert need > 0
+        rc = L.mofq_select_layers(n, w, c, len(cands), C.byref(cfg), out, res, ws, need, None, None)
+        assert rc in (0, -5), rc
+    c5 = (C.c_int32 * 5)(lib.INT4, lib.FP4_E2M1, lib.INT4, lib.FP4_E2M1, lib.INT4)
+    assert L.mofq_select_layers(n, w, c5, 5, C.byref(cfg), out, res, ws, 1 << 20, None, None) == -1

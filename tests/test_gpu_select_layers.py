@@ -95,9 +95,46 @@ def test_batched_rejects_before_enqueueing(mq):
     cfg = mq.Cfg(mq.PER_CHANNEL, mi.clip_ratios(2))
     outs = [mq.alloc_qbuffers(8, 256, 4, cfg, DEV), mq.alloc_qbuffers(8, 256, 4, cfg, DEV)]
     batch = mq.LayerBatch(w, outs)
-    assert batch.workspace_bytes(2, cfg) == 0 or True
+    assert batch.workspace_bytes(2, cfg) > 0       # sizes alone are fine; the 252 columns are not
     results = mq.alloc_result(DEV, 2)
     ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
     with pytest.raises(mq.MofqError):        # second tensor: 252 columns is not a multiple of 8
         mq.select_layers(batch, [mq.INT4, mq.FP4_E2M1], cfg, results, ws)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("cands_name", ["int4,fp4,ieee", "int4,fp4,ieee,int4", "fp4,fp4,int4", "int8,e4m3,e5m2"])
+def test_batched_three_and_four_candidates(mq, cands_name):
+    """Candidate lists longer than one search launch takes (two formats): every tensor goes
+    through launches of at most two formats; results equal the single-tensor call and the
+    oracle, tensor by tensor."""
+    fmt = {"int4": mq.INT4, "fp4": mq.FP4_E2M1, "ieee": mq.FP4_E2M1_IEEE, "int8": mq.INT8,
+           "e4m3": mq.FP8_E4M3, "e5m2": mq.FP8_E5M2}
+    cands = [fmt[c] for c in cands_name.split(",")]
+    bits = 8 if cands[0] in (mq.INT8, mq.FP8_E4M3, mq.FP8_E5M2) else 4
+    shapes = [(40, 4096), (12, 1024), (40, 4096), (9, 11008), (40, 4096)]
+    ws_ = [mi.llama_like_weight(r, c, seed=900 + i, device=DEV, outlier_frac=2e-3) for i, (r, c) in enumerate(shapes)]
+    clip = mi.clip_ratios(10)
+    cfg = mq.Cfg(mq.PER_CHANNEL, clip)
+    outs = [mq.alloc_qbuffers(r, c, bits, cfg, DEV) for r, c in shapes]
+    batch = mq.LayerBatch(ws_, outs)
+    assert batch.search_groups(cands) == list(range(len(shapes)))     # nothing is joined
+    results = mq.alloc_result(DEV, len(shapes))
+    ws = torch.empty(batch.workspace_bytes(len(cands), cfg), dtype=torch.uint8, device=DEV)
+    print(f"[case] select_layers with candidates {cands_name}", flush=True)
+    mq.select_layers(batch, cands, cfg, results, ws, side_stream=torch.cuda.Stream())
+    torch.cuda.synchronize()
+    res = mq.read_results(results)
+    for i, w in enumerate(ws_):
+        ref_out, ref_res = _single(mq, w, cands, cfg, bits)
+        assert res[i].n == len(cands)
+        assert res[i].best == ref_res.best and list(res[i].err) == list(ref_res.err)
+        assert torch.equal(outs[i].codes, ref_out.codes) and torch.equal(outs[i].scales, ref_out.scales)
+        assert torch.equal(outs[i].clip_idx, ref_out.clip_idx) and torch.equal(outs[i].unit_err, ref_out.unit_err)
+        w32 = mi.to_f32_numpy(w)
+        ref = orc.select_layer_w_only(w32, cands, orc.PER_CHANNEL, clip, want_table=True)
+        assert res[i].best == ref.best
+        assert np.allclose(list(res[i].err)[:len(cands)], ref.errs, rtol=1e-9)
+        compare_quantized(w32, cands[ref.best], orc.PER_CHANNEL, 0, False, clip, ref.w,
+                          unpack_codes(outs[i].codes, *shapes[i], bits), scales_to_f32(outs[i].scales),
+                          outs[i].clip_idx.cpu().numpy(), outs[i].unit_err.cpu().numpy())
