@@ -10,7 +10,8 @@
  *     (the linear layer A_out = W * A_in of Section 3.2).
  *   - Every pointer is a DEVICE pointer unless the comment says HOST.  The
  *     caller owns all memory; the library allocates none, keeps no pointer
- *     after the call and has no global state.
+ *     after the call and has no global state (one exception, stated there:
+ *     mofq_select_layer_static and its built-in workspace).
  *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*;
  *     NULL = the default stream) and never synchronise: results, including the
  *     chosen format, land in device memory.
@@ -193,6 +194,29 @@ int mofq_select_layer(const mofq_tensor_t* w, const mofq_tensor_t* x,
                       const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
                       const mofq_qout_t* x_out, mofq_result_t* result,
                       void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * mofq_select_layer for callers that cannot allocate or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Weight-only,
+ * tensor error (x = NULL, metric = MOFQ_ERR_TENSOR of mofq_select_layer); same arguments
+ * otherwise, same kernels, same results bit for bit.  The workspace is an array of
+ * MOFQ_STATIC_WORKSPACE_BYTES inside the library's device image (one copy per GPU, held until
+ * the process ends); its address is looked up on the first call on a device.  The call
+ * allocates nothing (no hipMalloc / hipFree, no allocating library routine) and enqueues no
+ * memset.
+ *   - Returns MOFQ_ERR_WORKSPACE, with nothing enqueued, when
+ *     mofq_workspace_bytes(w, NULL, n_candidates, MOFQ_ERR_TENSOR, w_cfg) exceeds
+ *     MOFQ_STATIC_WORKSPACE_BYTES (per-channel scales: up to about 200 000 rows with two
+ *     candidates; groups of 128: up to about 26 M elements).
+ *   - Every call on a GPU uses that GPU's one array, which keeps the previous call's
+ *     contents; nothing in it has to start at zero (every entry is written before it is
+ *     read).  Calls that overlap on one GPU (different streams, or different threads without
+ *     ordering) race on it: order them on one stream.
+ */
+#define MOFQ_STATIC_WORKSPACE_BYTES (8u << 20)
+int mofq_select_layer_static(const mofq_tensor_t* w, const int32_t* candidates, int32_t n_candidates,
+                             const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
+                             mofq_result_t* result, void* stream);
 
 /*
  * mofq_select_layer for several weight tensors in one call (weight-only, tensor error;

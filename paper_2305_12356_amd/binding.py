@@ -71,6 +71,9 @@ def _load():
                                     C.POINTER(C.c_int32), C.c_int32, C.c_int32,
                                     C.POINTER(ScaleCfg), C.POINTER(QOut), C.POINTER(QOut),
                                     vp, vp, C.c_size_t, vp]
+    L.mofq_select_layer_static.restype = C.c_int
+    L.mofq_select_layer_static.argtypes = [C.POINTER(TensorDesc), C.POINTER(C.c_int32), C.c_int32,
+                                           C.POINTER(ScaleCfg), C.POINTER(QOut), vp, vp]
     L.mofq_select_layer_timed.restype = C.c_int
     L.mofq_select_layer_timed.argtypes = L.mofq_select_layer.argtypes + [vp, vp]
     L.mofq_workspace_bytes.restype = C.c_size_t
@@ -241,6 +244,22 @@ def select_layer(w: torch.Tensor, x: Optional[torch.Tensor], candidates: Sequenc
         rc = _lib.mofq_select_layer_timed(*args, _event_handle(ev_begin), _event_handle(ev_end))
     if rc != 0:
         raise MofqError(rc, "mofq_select_layer")
+
+
+STATIC_WORKSPACE_BYTES = 8 << 20
+
+
+def select_layer_static(w: torch.Tensor, candidates: Sequence[int], cfg: Cfg, w_out: QBuffers,
+                        result: torch.Tensor, stream=None) -> None:
+    """mofq_select_layer_static: the weight-only, tensor-error select of one layer with the
+    library's built-in workspace (no workspace argument, nothing allocated); enqueue."""
+    wd = tensor_desc(w)
+    cand = (C.c_int32 * len(candidates))(*candidates)
+    woc = w_out.c()
+    rc = _lib.mofq_select_layer_static(C.byref(wd), cand, len(candidates), C.byref(cfg.c), C.byref(woc),
+                                       _ptr(result), _stream_handle(stream))
+    if rc != 0:
+        raise MofqError(rc, "mofq_select_layer_static")
 
 
 def select_units_workspace_bytes(w: torch.Tensor, n_candidates: int, cfg: Cfg) -> int:

@@ -2,6 +2,7 @@
 // No device memory is allocated here and nothing synchronises.
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 
 #include "mofq_internal.h"
 
@@ -424,6 +425,80 @@ int wa_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand
   if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return MOFQ_ERR_HIP;
   if ((rc = launch_wa_gemm(g, st))) return rc;
   if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return MOFQ_ERR_HIP;
+  return MOFQ_OK;
+}
+
+// Algorithm 1's loop body for one weight tensor with the tensor-error metric: search every
+// candidate, reduce + select on the device, emit the winner.  Arguments are already validated
+// except for the workspace.
+int select_w_only(const mofq_tensor_t* w, const int32_t* candidates, int n_candidates,
+                  const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out, mofq_result_t* result,
+                  void* ws, size_t ws_bytes, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  int rc;
+  const int64_t units = mofq_num_units(w->rows, w->cols, w_cfg->gran, w_cfg->group_size);
+  const WOnlyWs s = carve_w_only(ws, units, n_candidates, w_cfg->gran, w_cfg->n_clip);
+  if (!ws || ws_bytes < s.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+  if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return MOFQ_ERR_HIP;
+  if ((rc = sweep_candidates(w, candidates, n_candidates, w_cfg, s, st))) return rc;
+  if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return MOFQ_ERR_HIP;
+  DecideParams d{};
+  d.units = units;
+  d.n_cand = n_candidates;
+  for (int c = 0; c < n_candidates; ++c) d.err[c] = s.err[c];
+  d.energy = s.energy;
+  d.part = s.decide_part;
+  d.result = result;
+  if ((rc = launch_decide(d, st))) return rc;
+  EmitParams e{};
+  e.w = w->data;
+  e.dtype = w->dtype;
+  e.rows = w->rows;
+  e.cols = w->cols;
+  e.ld = w->ld;
+  e.gran = w_cfg->gran;
+  e.group = w_cfg->group_size;
+  e.scale_f16_out = w_cfg->scale_dtype == MOFQ_F16;
+  e.n_cand = n_candidates;
+  for (int c = 0; c < n_candidates; ++c) {
+    e.fmt[c] = candidates[c];
+    e.scale[c] = s.scale[c];
+    e.clip[c] = s.clip[c];
+    e.err[c] = s.err[c];
+  }
+  e.result = result;
+  e.out = *w_out;
+  return launch_emit(e, st);
+}
+
+}  // namespace
+
+// ---- the workspace of mofq_select_layer_static ------------------------------------------
+// One array per GPU, in the library's own device image, so that the call needs no allocation
+// and no workspace argument.  In host code the array's name is only a handle for the symbol
+// lookup, never a device address: the address is asked for once per device (with that device
+// current) and kept, and kernels, like everything else on the host side, get that pointer.
+static __device__ __align__(256) unsigned char scratch[MOFQ_STATIC_WORKSPACE_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return MOFQ_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return MOFQ_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return MOFQ_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
   return MOFQ_OK;
 }
 
@@ -951,6 +1026,23 @@ int mofq_select_layer(const mofq_tensor_t* w, const mofq_tensor_t* x, const int3
                                  result, ws, ws_bytes, stream, nullptr, nullptr);
 }
 
+int mofq_select_layer_static(const mofq_tensor_t* w, const int32_t* candidates, int32_t n_candidates,
+                             const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
+                             mofq_result_t* result, void* stream) {
+  int rc = check_tensor(w);
+  if (rc) return rc;
+  if ((rc = check_cfg(w, w_cfg))) return rc;
+  if ((rc = check_candidates(candidates, n_candidates))) return rc;
+  if ((rc = check_out(w_out, true))) return rc;
+  if (!result) return MOFQ_ERR_INVALID_ARG;
+  const size_t need = mofq_workspace_bytes(w, nullptr, n_candidates, MOFQ_ERR_TENSOR, w_cfg);
+  if (!need || need > MOFQ_STATIC_WORKSPACE_BYTES) return MOFQ_ERR_WORKSPACE;   // beyond the built-in array
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws))) return rc;
+  return select_w_only(w, candidates, n_candidates, w_cfg, w_out, result, ws, MOFQ_STATIC_WORKSPACE_BYTES,
+                       static_cast<hipStream_t>(stream), nullptr, nullptr);
+}
+
 int mofq_select_layer_timed(const mofq_tensor_t* w, const mofq_tensor_t* x,
                             const int32_t* candidates, int32_t n_candidates, int32_t metric,
                             const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
@@ -969,39 +1061,7 @@ int mofq_select_layer_timed(const mofq_tensor_t* w, const mofq_tensor_t* x,
   if (!x) {
     if (metric != MOFQ_ERR_TENSOR) return MOFQ_ERR_INVALID_ARG;
     (void)x_out;
-    const int64_t units = mofq_num_units(w->rows, w->cols, w_cfg->gran, w_cfg->group_size);
-    const WOnlyWs s = carve_w_only(ws, units, n_candidates, w_cfg->gran, w_cfg->n_clip);
-    if (!ws || ws_bytes < s.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
-    if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return MOFQ_ERR_HIP;
-    if ((rc = sweep_candidates(w, candidates, n_candidates, w_cfg, s, st))) return rc;
-    if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return MOFQ_ERR_HIP;
-    DecideParams d{};
-    d.units = units;
-    d.n_cand = n_candidates;
-    for (int c = 0; c < n_candidates; ++c) d.err[c] = s.err[c];
-    d.energy = s.energy;
-    d.part = s.decide_part;
-    d.result = result;
-    if ((rc = launch_decide(d, st))) return rc;
-    EmitParams e{};
-    e.w = w->data;
-    e.dtype = w->dtype;
-    e.rows = w->rows;
-    e.cols = w->cols;
-    e.ld = w->ld;
-    e.gran = w_cfg->gran;
-    e.group = w_cfg->group_size;
-    e.scale_f16_out = w_cfg->scale_dtype == MOFQ_F16;
-    e.n_cand = n_candidates;
-    for (int c = 0; c < n_candidates; ++c) {
-      e.fmt[c] = candidates[c];
-      e.scale[c] = s.scale[c];
-      e.clip[c] = s.clip[c];
-      e.err[c] = s.err[c];
-    }
-    e.result = result;
-    e.out = *w_out;
-    return launch_emit(e, st);
+    return select_w_only(w, candidates, n_candidates, w_cfg, w_out, result, ws, ws_bytes, st, ev0, ev1);
   }
   if (metric == MOFQ_ERR_LAYER_OUTPUT_W_ONLY) {
     if ((rc = check_wo_output(w, x, candidates, n_candidates, w_cfg))) return rc;
