@@ -1,29 +1,31 @@
 #!/usr/bin/env python3
-"""Benchmark of the MoFQ weight-only hot path on one MI355X.
+"""Benchmark of the MoFQ quantize-and-score / format-select hot path on one MI355X.
 
-Workload (`config.workload`): the LLaMA-7B-shaped weight set, fp16, 32 blocks x 7
-linears = 224 tensors, 4-bit weight-only, per-channel scales searched over 100
-clip ratios in [0.5, 1], INT4 vs FP4-E2M1, per-layer select and emit of the codes.
-A step is one pass of the whole path (scale search + select + emit) over all 224
-tensors, which are resident in HBM before the timed region starts.
+Headline workload (`config.workload`): the LLaMA-7B-shaped weight set, fp16, 32 blocks x 7
+linears = 224 tensors, 4-bit weight-only, per-channel scales searched over 100 clip ratios
+in [0.5, 1], INT4 vs FP4-E2M1, per-layer select and emit of the codes.  A step is one pass
+of the whole path (scale search + select + emit) over all 224 tensors, which are resident in
+HBM before the timed region starts.
 
-Prints ONE JSON line: the elements x candidates scored per second (and the
-full-model select time), the roofline of the dominant kernel measured with HIP
-events inside the timed region, and the CPU oracle timed on a bounded sample of
-the same workload on the host cores.
+Prints ONE JSON line: the elements x candidates scored per second (and the full-model select
+time), the roofline of the dominant kernel measured with HIP events inside the timed region,
+the device ceilings measured in the same run (`ceilings`: copy, vector FMA, matrix cores),
+the CPU oracle timed on a bounded sample of the same workload (1 thread and all threads),
+and, under `secondary`, the other configurations of the same path, each timed the same way:
+the memory-bound single-candidate case, the group-wise search, W8A8 by layer-output error
+(exact and with the fp8 matrix cores), the weight-only layer-output select, and the
+65B-shaped set.
 
-`--workload` selects two further workloads of the same path, each with its own
-JSON line (same keys; no CPU baseline): `w4_group128` (group-wise scales, 50 clip
-ratios) and `w8a8` (weight-activation, layer-output error through the matrix
-cores, 2048 tokens).  `k1_hbm` is the memory-bound case: configs[0]'s recipe (fp32,
-absmax scale, no clip search) on a 16384 x 16384 tensor (1 GiB).  The default,
-`w4_channel`, is the headline workload.
+`--workload NAME` runs one of them alone (its own JSON line, same keys).
+`--full-parity` is not a benchmark: it holds every linear of a block range to the oracle
+(all rows: format choice, both error sums, codes, scales, clip indices) and prints a summary.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -36,23 +38,21 @@ N_CLIP_GROUP = 50
 GROUP = 128
 TOKENS = 2048
 N_FMT = 2
+HBM_PEAK_GBPS = 8000.0
 # Published dense matrix-core peaks (TFLOP/s or TOP/s) per operand type.
 MFMA_PEAK = {"bf16": 2500.0, "int8": 5000.0, "fp8": 5000.0}
-# Algorithmic work of the scale search per element, candidate and format: scale
-# (1 multiply), round (1), clamp/saturate (1), residual x - g*s (2), error
-# accumulation d*d + acc (2).
+# Work of the EXHAUSTIVE scale search per element, candidate and format: scale (1 multiply),
+# round (1), clamp/saturate (1), residual x - g*s (2), error accumulation d*d + acc (2).  The
+# per-channel search does not execute it (it sorts each row and locates level boundaries),
+# so this prices an equivalent rate, reported under its own key, never as a utilisation.
 FLOPS_PER_ELEM_CAND_FMT = 7
-# Vector-ALU peak the exhaustive search is priced against.  Of the 7 flop, 3 are fp32
-# (published fp32 vector peak 157.3 TFLOP/s) and 4 are fp64 (published fp64 vector peak
-# 78.6 TFLOP/s): 7 / (3/157.3 + 4/78.6) = 100.0 TFLOP/s.
-ALU_PEAK_TFLOPS = 7.0 / (3.0 / 157.3 + 4.0 / 78.6)
-# HBM bytes per launch of the search kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command,
-# scaled by what the same counters read for a plain 1 GiB copy (profiles/w_only_7b_k100_hbm_traffic.txt):
-# a launch over 46592 rows of 4096 fp16 columns reads 373 230 KiB (1.0013 x its 2 bytes per element) and
-# writes 10 192 KiB (224 bytes of per-channel records per row).  Only the 7B per-channel workload has
-# been measured.
-MEASURED_READ_PER_INPUT_BYTE = 373230.0 / (46592 * 4096 * 2 / 1024)
-MEASURED_WRITE_BYTES_PER_ROW = 10192.0 * 1024 / 46592
+# Counter-derived facts about sweep_sorted_kernel on 4096-column rows, measured by rocprofv3 runs
+# of this command (not in the run that prints them): where they come from is printed beside them.
+SORTED_KERNEL_COUNTERS = {
+    "from": "profiles/w_only_sorted_kernel_counters.txt, profiles/w_only_7b_k100_hbm_traffic.txt",
+    "read_per_input_byte": 373230.0 / (46592 * 4096 * 2 / 1024),     # FETCH_SIZE, scaled by a plain copy
+    "write_bytes_per_row": 10192.0 * 1024 / 46592,                   # WRITE_SIZE
+}
 
 
 def parse():
@@ -62,22 +62,79 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--model", default="7b", choices=["7b", "65b"],
                     help="65b = configs[4]: 560 linears, 129.5 GB of fp16 weights resident in HBM")
-    ap.add_argument("--workload", default="w4_channel",
-                    choices=["w4_channel", "w4_group128", "w8a8", "w4a16_output", "k1_hbm", "fp4_variants", "w4_units"])
+    ap.add_argument("--workload", default="all",
+                    choices=["all", "w4_channel", "w4_group128", "w8a8", "w4a16_output", "k1_hbm", "fp4_variants",
+                             "w4_units", "ceilings"])
     ap.add_argument("--fp8-unit", action="store_true",
-                    help="w8a8: E4M3 code product on the fp8 matrix cores (not within 1e-5 of the exact sum)")
+                    help="w8a8: E4M3 code product on the fp8 matrix cores")
     ap.add_argument("--blocks", type=int, default=0, help="debug: use only the first N blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-65b", action="store_true", help="all: leave the 65B-shaped set out of `secondary`")
     ap.add_argument("--single-stream", action="store_true",
                     help="w4_channel: no second stream (kernels run one at a time; for counter runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
+    ap.add_argument("--full-parity", action="store_true",
+                    help="hold every linear of --block-list to the oracle on all rows and print a summary")
+    ap.add_argument("--block-list", default="0", help="full-parity: blocks, e.g. 0,39,79 or 0:11")
     return ap.parse_args()
 
 
+def git_head():
+    try:
+        return subprocess.run(["git", "rev-parse", "--short", "HEAD"], cwd=ROOT, capture_output=True,
+                              text=True, timeout=5).stdout.strip() or None
+    except Exception:
+        return None
+
+
+# ---- device ceilings ----------------------------------------------------------------
+
+def measure_ceilings(dev):
+    """Stream copy, vector FMA and matrix-core loop rates of this device, with the library's
+    micro-kernels, HIP events around each launch, best of three."""
+    import torch
+    from paper_2305_12356_amd import binding as mq
+
+    stream = torch.cuda.current_stream()
+    buf = torch.empty(2 << 30, dtype=torch.uint8, device=dev)      # copy: 1 GiB -> 1 GiB
+    buf.zero_()
+
+    def rate(kind, iters):
+        best = 0.0
+        for rep in range(4):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            work = mq.device_ceiling(kind, buf, iters, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            if rep:                                             # the first launch warms up
+                best = max(best, work / (e0.elapsed_time(e1) * 1e-3))
+        return best
+
+    out = {
+        "copy_GBps": rate(mq.CEILING_COPY, 4) / 1e9,
+        "valu_fma_f32_TFLOPs": rate(mq.CEILING_FMA_F32, 20000) / 1e12,
+        "valu_fma_f64_TFLOPs": rate(mq.CEILING_FMA_F64, 10000) / 1e12,
+        "mfma_bf16_TFLOPs": rate(mq.CEILING_MFMA_BF16, 4000) / 1e12,
+        "mfma_int8_TOPs": rate(mq.CEILING_MFMA_INT8, 4000) / 1e12,
+        "mfma_fp8_TFLOPs": rate(mq.CEILING_MFMA_FP8, 4000) / 1e12,
+    }
+    # one fused multiply-add instruction of a wave = 128 flop: the issue rate behind the FMA figure
+    out["valu_wave_instr_per_s"] = out["valu_fma_f32_TFLOPs"] * 1e12 / 128.0
+    out["note"] = ("measured in this run with the library's micro-kernels (HIP events, best of 3): 1 GiB device copy "
+                   "(read + write bytes), register-only fused multiply-add loops (one plain instruction per wave and "
+                   "operation: the packed fp32 form behind the published 157.3 TFLOP/s is not used), register-only "
+                   "32x32 matrix-instruction loops")
+    del buf
+    return out
+
+
+# ---- CPU oracle beside it -------------------------------------------------------------
+
 def cpu_baseline(weights, outs, clip, cands):
-    """Time the oracle (as it stands) on a bounded sample of the same tensors and
-    check the library's results on those rows against it."""
+    """Time the oracle (as it stands) on a bounded sample of the same tensors, with all host
+    threads and with one, and check the library's results on those rows against it."""
     import numpy as np
     import mofq_inputs as mi
     from oracle import mofq_oracle as orc
@@ -109,16 +166,166 @@ def cpu_baseline(weights, outs, clip, cands):
                                   out.clip_idx[:n_rows].cpu().numpy(),
                                   out.unit_err[:n_rows].cpu().numpy())
         checked += n_rows
+    # one thread: the first 320 rows of q
+    one_rows = 320
+    w32 = mi.to_f32_numpy(weights[0][:one_rows])
+    t0 = time.perf_counter()
+    for f in cands:
+        orc.quantize(w32, f, orc.PER_CHANNEL, clip, threads=1)
+    one_t = time.perf_counter() - t0
+    one_rate = one_rows * w32.shape[1] * N_CLIP * N_FMT / one_t
     return {
         "value": total_ec / total_t, "unit": "elem*cand/s", "cores": threads, "kind": "oracle",
         "sample": "first rows of block 0 q/gate/down (" + ", ".join(desc) +
                   "), both formats x 100 clip ratios, full oracle search",
         "seconds": round(total_t, 3),
         "rows_checked_bit_exact": checked, "near_tie_rows": band,
+        "one_thread": {"value": one_rate, "unit": "elem*cand/s", "cores": 1, "seconds": round(one_t, 3),
+                       "sample": f"first {one_rows} rows of block 0 q, both formats x 100 clip ratios"},
     }
 
 
-def run_w8a8(args, shapes, dev, w_only=False):
+# ---- weight-only, tensor error: configs[1], [2], [4] ------------------------------------
+
+def make_weights(shapes, dev, dtype=None):
+    import torch
+    import mofq_inputs as mi
+    return [mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, mi.LINEAR_NAMES.index(name)),
+                                 dtype=dtype or torch.float16, device=dev) for b, name, o, n in shapes]
+
+
+def run_w4(args, shapes, dev, weights, group, model, steps, warmup, ceilings=None, want_cpu=False):
+    import torch
+    import mofq_inputs as mi
+    from paper_2305_12356_amd import binding as mq
+
+    n_clip = N_CLIP_GROUP if group else N_CLIP
+    clip = mi.clip_ratios(n_clip)
+    cands = [mq.INT4, mq.FP4_E2M1]
+    cfg = mq.Cfg(mq.PER_GROUP, clip, GROUP, True) if group else mq.Cfg(mq.PER_CHANNEL, clip)
+    qouts = [mq.alloc_qbuffers(o, n, 4, cfg, dev) for _, _, o, n in shapes]
+    results = mq.alloc_result(dev, len(shapes))
+    # one call for the whole model (mofq_select_layers): the per-tensor reduce / select /
+    # per-unit outputs of up to 12 tensors share a launch, and so do the searches of those of
+    # them that have one row length
+    batch = mq.LayerBatch(weights, qouts)
+    ws = torch.empty(batch.workspace_bytes(len(cands), cfg), dtype=torch.uint8, device=dev)
+    n_elems = sum(o * n for _, _, o, n in shapes)
+    stream = torch.cuda.current_stream()
+    # default priority: select + code emission beside the next batch's searches
+    side = None if args.single_stream else torch.cuda.Stream()
+
+    # the events the library records around each search launch, created (and recorded once,
+    # so that they exist) before the timed region
+    ev_pool = []
+    for _ in range(steps):
+        e0 = [torch.cuda.Event(enable_timing=True) for _ in weights]
+        e1 = [torch.cuda.Event(enable_timing=True) for _ in weights]
+        for e in e0 + e1:
+            e.record()
+        ev_pool.append((e0, e1))
+
+    def step(events=None):
+        e0 = e1 = None
+        if events is not None:
+            e0, e1 = ev_pool.pop()
+            events.extend((i, a, b) for i, (a, b) in enumerate(zip(e0, e1)))
+        mq.select_layers(batch, cands, cfg, results, ws, stream, e0, e1, side_stream=side)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed / steps * 1e3
+    elem_cand = n_elems * n_clip * N_FMT
+    value = elem_cand / (elapsed / steps)
+
+    # ---- dominant kernel: the search launches over the most common row length -----------
+    # Duration from the HIP events the library recorded around each launch: the begin event of a
+    # launch's first tensor, the end event of its last.
+    first = batch.search_groups(cands)
+    last = {f: i for i, f in enumerate(first)}
+    by_cols = {}
+    for step_i in range(steps):
+        ev = events[step_i * len(shapes):(step_i + 1) * len(shapes)]
+        for f, l in last.items():
+            members = [i for i in range(f, l + 1) if first[i] == f]
+            elems = sum(shapes[i][2] * shapes[i][3] for i in members)
+            rows = sum(shapes[i][2] for i in members)
+            by_cols.setdefault(shapes[f][3], []).append((elems, ev[f][1].elapsed_time(ev[l][2]) * 1e-3, rows))
+    dom_cols = max(by_cols, key=lambda c: sum(e for e, _, _ in by_cols[c]))
+    dom = by_cols[dom_cols]
+    dom_elems = sum(e for e, _, _ in dom)
+    dom_time = sum(t for _, t, _ in dom)
+    dom_rows = sum(r for _, _, r in dom)
+    alg_bytes_per_launch = dom_elems * 2 / len(dom)               # 2 bytes per element, read once
+    achieved = dom_elems * 2 / dom_time / 1e9
+    search_time = sum(t for v in by_cols.values() for _, t, _ in v) / steps
+    roofline = {
+        "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+        "kernel": (f"sweep_group_kernel<F16, INT4, FP4_E2M1, {GROUP}> on {dom_cols}-column rows" if group else
+                   f"sweep_sorted_kernel<F16, INT4, FP4_E2M1> instance for {dom_cols}-column rows"),
+        "limited_by": "vector instruction issue, not bytes: the search evaluates "
+                      f"{n_clip} x {N_FMT} scale candidates per element from LDS and registers",
+        "avg_launch_ms": dom_time / len(dom) * 1e3, "launches": len(dom),
+        "algorithmic_bytes_per_launch": alg_bytes_per_launch,
+        "algorithmic_bytes_per_elem": 2,
+        "search_ms_per_step": search_time * 1e3,
+        # what the exhaustive search would need for the same result: an equivalent rate, not a utilisation
+        "exhaustive_equivalent": {
+            "TFLOPs": dom_elems * n_clip * N_FMT * FLOPS_PER_ELEM_CAND_FMT / dom_time / 1e12,
+            "flops_per_elem_cand_fmt": FLOPS_PER_ELEM_CAND_FMT,
+            "note": "flop of scoring every element x candidate x format one by one (7 each) over the launch "
+                    "time; the kernel reaches the same result with far fewer instructions (sort + boundary "
+                    "search), so this is not a fraction of any peak",
+        },
+    }
+    if ceilings:
+        roofline["frac_of_measured_copy"] = achieved / ceilings["copy_GBps"]   # bytes moved per second, read or written
+    if not group and model == "7b" and dom_cols == 4096:
+        c = SORTED_KERNEL_COUNTERS
+        roofline["traffic"] = (alg_bytes_per_launch * c["read_per_input_byte"] +
+                               dom_rows / len(dom) * c["write_bytes_per_row"])
+        roofline["traffic_from"] = {"file": c["from"], "measured_in_this_run": False,
+                                    "how": "rocprofv3 FETCH_SIZE / WRITE_SIZE per row, scaled by a plain copy, "
+                                           "times the rows of this run's average launch"}
+
+    res = mq.read_results(results)
+    fp_pct = 100.0 * sum(1 for r in res if r.best == 1) / len(res)
+    out = {
+        "metric": f"weight-elems x candidates scored/sec (+ LLaMA-{model.upper()} full-model MoFQ select time)",
+        "value": value, "unit": "elem*cand/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "select_time_s": ms_per_step / 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 decisions, f64 errors", "data": "synthetic",
+        "config": {"workload": ("configs[2]: LLaMA-7B-shaped fp16 weight set, "
+                                f"{len(shapes)} linears, {n_elems} weights, 4-bit W-only group-wise "
+                                "(128 along the input dim, fp16 scales), 50 clip ratios in [0.5,1], "
+                                "INT4 vs FP4-E2M1, per-layer select + emit") if group else
+                               (("configs[4]: LLaMA-65B-shaped" if model == "65b" else
+                                 "configs[1]: LLaMA-7B-shaped") + " fp16 weight set, "
+                                f"{len(shapes)} linears, {n_elems} weights, 4-bit W-only per-channel, "
+                                "100 clip ratios in [0.5,1], INT4 vs FP4-E2M1, per-layer select + emit"),
+                   "n_clip": n_clip, "formats": ["INT4", "FP4_E2M1"], "fp_percent": fp_pct},
+        "roofline": roofline,
+    }
+    if want_cpu:
+        outs = [(qouts[i], res[i]) for i in range(len(shapes))]
+        out["cpu_baseline"] = cpu_baseline(weights, outs, clip, cands)
+    return out
+
+
+# ---- layer-output error: configs[3] and the weight-only variant -------------------------
+
+def run_w8a8(args, shapes, dev, weights, w_only, fp8_unit, steps, warmup, ceilings=None):
     """configs[3]: per linear, X [2048, in] bf16 with outlier channels, W bf16; per-tensor
     INT8 vs FP8-E4M3 for both; layer-output error through the matrix cores; select + emit.
     With w_only: the weight-only select by layer-output error (X stays bf16; W per-channel
@@ -128,7 +335,7 @@ def run_w8a8(args, shapes, dev, w_only=False):
     import mofq_inputs as mi
     from paper_2305_12356_amd import binding as mq
 
-    metric = mq.ERR_LAYER_OUTPUT_FP8_UNIT if args.fp8_unit else mq.ERR_LAYER_OUTPUT
+    metric = mq.ERR_LAYER_OUTPUT_FP8_UNIT if fp8_unit else mq.ERR_LAYER_OUTPUT
     cands = [mq.INT8, mq.FP8_E4M3]
     cfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
     bits = 8
@@ -137,17 +344,14 @@ def run_w8a8(args, shapes, dev, w_only=False):
         cfg = mq.Cfg(mq.PER_CHANNEL, mi.clip_ratios(1))
     xcfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
     xs = {}
-    weights, wouts, xouts = [], [], {}
+    xouts = {}
     results = mq.alloc_result(dev, len(shapes))
     ws_bytes = 0
-    for b, name, o, n in shapes:
+    for i, (b, name, o, n) in enumerate(shapes):
         if n not in xs:
             xs[n] = mi.activations(TOKENS, n, seed=mi.tensor_seed(3, 0, 0, n), device=dev)
             xouts[n] = None if w_only else mq.alloc_qbuffers(TOKENS, n, 8, xcfg, dev)
-        w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, mi.LINEAR_NAMES.index(name)),
-                                 dtype=torch.bfloat16, device=dev)
-        weights.append(w)
-        ws_bytes = max(ws_bytes, mq.workspace_bytes(w, xs[n], len(cands), metric, cfg))
+        ws_bytes = max(ws_bytes, mq.workspace_bytes(weights[i], xs[n], len(cands), metric, cfg))
     # one output buffer per distinct weight shape (the codes are not read back here)
     for b, name, o, n in shapes:
         if (o, n) not in xouts:
@@ -166,16 +370,16 @@ def run_w8a8(args, shapes, dev, w_only=False):
             mq.select_layer(w, xs[n], cands, metric, cfg, xouts[(o, n)], xouts[n], results[i], ws,
                             stream, e0, e1)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     events = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(events)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
+    ms_per_step = elapsed / steps * 1e3
 
     # the same pass with the linears dealt alternately to two streams of the caller (own
     # workspace and output buffers per stream): the short memory-bound quantize passes of one
@@ -199,29 +403,43 @@ def run_w8a8(args, shapes, dev, w_only=False):
     step2()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step2()
     torch.cuda.synchronize()
-    ms_two = (time.perf_counter() - t0) / args.steps * 1e3
+    ms_two = (time.perf_counter() - t0) / steps * 1e3
 
     # dominant kernel: the fused three-product GEMM; one launch per linear
     mnk = sum(TOKENS * o * n for _, _, o, n in shapes)
-    gemm_time = sum(e0.elapsed_time(e1) for _, e0, e1 in events) * 1e-3 / args.steps
-    kinds = ["bf16", "bf16", "bf16"] if w_only else ["bf16", "int8", "fp8" if args.fp8_unit else "bf16"]
+    gemm_time = sum(e0.elapsed_time(e1) for _, e0, e1 in events) * 1e-3 / steps
+    kinds = ["bf16", "bf16", "bf16"] if w_only else ["bf16", "int8", "fp8" if fp8_unit else "bf16"]
     flops = 2.0 * mnk * len(kinds)
     ideal = sum(2.0 * mnk / (MFMA_PEAK[k] * 1e12) for k in kinds)
     achieved = flops / gemm_time / 1e12
     peak = flops / ideal / 1e12
     res = mq.read_results(results)
-    out = {
+    roofline = {
+        "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+        "frac": achieved / peak, "traffic": None,
+        "kernel": "wa_gemm_kernel (reference, INT8-code and E4M3 products of one linear)",
+        "note": "three products per launch, " + " + ".join(kinds) + "; peak is the rate at which the "
+                "three would finish if each ran at the published dense peak of its own type "
+                "(bf16 2.5, int8 5.0, fp8 5.0 PFLOP/s)",
+        "gemm_ms_per_step": gemm_time * 1e3, "launches": len(events),
+        "flops_per_launch_avg": flops / len(shapes),
+    }
+    if ceilings:
+        key = {"bf16": "mfma_bf16_TFLOPs", "int8": "mfma_int8_TOPs", "fp8": "mfma_fp8_TFLOPs"}
+        ideal_m = sum(2.0 * mnk / (ceilings[key[k]] * 1e12) for k in kinds)
+        roofline["frac_of_measured_mfma"] = ideal_m / gemm_time
+    return {
         "metric": ("W4A16" if w_only else "W8A8") + " layer-output MoFQ select time over the LLaMA-7B linear shapes",
-        "value": ms_per_step / 1e3, "unit": "s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
+        "value": ms_per_step / 1e3, "unit": "s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
         "ms_per_step_two_caller_streams": ms_two,
         "scaling": "weak", "vs_baseline": None,
         "dtype": ("bf16 reference product, 4-bit grid values on the bf16 matrix cores, f64 error sums" if w_only else
                   "bf16 reference product, int8 codes, " +
-                  ("fp8 codes on the fp8 matrix cores" if args.fp8_unit else "e4m3 grid values on the bf16 matrix cores") +
+                  ("fp8 codes on the fp8 matrix cores" if fp8_unit else "e4m3 grid values on the bf16 matrix cores") +
                   ", f64 error sums"),
         "data": "synthetic",
         "config": {"workload": (f"weight-only select by layer-output error: {len(shapes)} linears of the LLaMA-7B shape, "
@@ -230,23 +448,13 @@ def run_w8a8(args, shapes, dev, w_only=False):
                                (f"configs[3]: {len(shapes)} linears of the LLaMA-7B shape, X [{TOKENS} x in] bf16 "
                                 "with 6 outlier channels x60, W bf16, per-tensor INT8 vs FP8-E4M3, "
                                 "layer-output error, per-layer select + emit"),
-                   "fp8_product": "fp8 matrix cores" if args.fp8_unit else "exact (bf16 matrix cores)",
+                   "fp8_product": "fp8 matrix cores" if fp8_unit else "exact (bf16 matrix cores)",
                    "fp_percent": 100.0 * sum(1 for r in res if r.best == 1) / len(res)},
-        "roofline": {
-            "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-            "frac": achieved / peak, "traffic": None,
-            "kernel": "wa_gemm_kernel (reference, INT8-code and E4M3 products of one linear)",
-            "note": "three products per launch, " + " + ".join(kinds) + "; peak is the rate at which the "
-                    "three would finish if each ran at the published dense peak of its own type "
-                    "(bf16 2.5, int8 5.0, fp8 5.0 PFLOP/s)",
-            "gemm_ms_per_step": gemm_time * 1e3, "launches": len(events),
-            "flops_per_launch_avg": flops / len(shapes),
-        },
+        "roofline": roofline,
     }
-    print(json.dumps(out))
 
 
-def run_k1_hbm(args, dev):
+def run_k1_hbm(args, dev, steps, warmup, ceilings=None):
     """configs[0]'s recipe at a size that does not fit in the caches: one 16384 x 16384 fp32
     tensor, per-channel absmax scale (one candidate), INT4 vs FP4-E2M1, select + emit."""
     import torch
@@ -262,44 +470,48 @@ def run_k1_hbm(args, dev):
     res = mq.alloc_result(dev)
     ws = torch.empty(mq.workspace_bytes(w, None, 2, mq.ERR_TENSOR, cfg), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         mq.select_layer(w, None, cands, mq.ERR_TENSOR, cfg, out, None, res, ws, stream)
     torch.cuda.synchronize()
     events = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         events.append((e0, e1))
         mq.select_layer(w, None, cands, mq.ERR_TENSOR, cfg, out, None, res, ws, stream, e0, e1)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-    sweep_s = sum(e0.elapsed_time(e1) for e0, e1 in events) * 1e-3 / args.steps
+    ms_per_step = elapsed / steps * 1e3
+    sweep_s = sum(e0.elapsed_time(e1) for e0, e1 in events) * 1e-3 / steps
     read_bytes = n * n * 4
     achieved = read_bytes / sweep_s / 1e9
     r = mq.read_result(res)
-    print(json.dumps({
+    roofline = {
+        "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+        # FETCH_SIZE / WRITE_SIZE of this kernel, scaled by a plain copy's
+        "traffic": (1048666 + 3642) * 1024.0,
+        "traffic_from": {"file": "profiles/k1_hbm_fp32_16384_kernel_stats.txt", "measured_in_this_run": False},
+        "kernel": "sweep_channel_single_kernel<F32, INT4, FP4_E2M1, 512 threads, 4 chunks>",
+        "note": "algorithmic bytes = 4 B per element read once by the scoring kernel; the emit pass "
+                "(4 B read + 0.5 B written per element) is in ms_per_step but not in this kernel",
+        "avg_launch_ms": sweep_s * 1e3, "launches": len(events),
+        "algorithmic_bytes_per_launch": read_bytes,
+        "select_emit_GBps": n * n * 4.5 / (elapsed / steps - sweep_s) / 1e9,
+    }
+    if ceilings:
+        roofline["frac_of_measured_copy"] = achieved / ceilings["copy_GBps"]
+    return {
         "metric": "weight-elems x candidates scored/sec (memory-bound case: one scale candidate)",
-        "value": n * n * N_FMT / (elapsed / args.steps), "unit": "elem*cand/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "value": n * n * N_FMT / (elapsed / steps), "unit": "elem*cand/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 decisions, f64 errors", "data": "synthetic",
         "config": {"workload": "configs[0]'s recipe on a 16384 x 16384 fp32 tensor (1 GiB): N(0, 0.02^2), 0.1 % of "
                                "entries x10, per-channel absmax scale, INT4 vs FP4-E2M1, tensor error, select + emit",
                    "best": int(r.best), "err": [float(r.err[0]), float(r.err[1])]},
-        "roofline": {
-            "bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
-            # FETCH_SIZE / WRITE_SIZE of this kernel, scaled by a plain copy's (profiles/k1_hbm_fp32_16384_kernel_stats.txt)
-            "traffic": (1048666 + 3642) * 1024.0,
-            "kernel": "sweep_channel_single_kernel<F32, INT4, FP4_E2M1, 512 threads, 4 chunks>",
-            "note": "algorithmic bytes = 4 B per element read once by the scoring kernel; the emit pass "
-                    "(4 B read + 0.5 B written per element) is in ms_per_step but not in this kernel",
-            "avg_launch_ms": sweep_s * 1e3, "launches": len(events),
-            "algorithmic_bytes_per_launch": read_bytes,
-            "select_emit_GBps": n * n * 4.5 / (elapsed / args.steps - sweep_s) / 1e9,
-        },
-    }))
+        "roofline": roofline,
+    }
 
 
 def run_fp4_variants(args, shapes, dev):
@@ -332,7 +544,7 @@ def run_fp4_variants(args, shapes, dev):
     e_new = sum(r.err[1] for r in res["redesigned"])
     e_ieee = sum(r.err[1] for r in res["ieee"])
     per_layer = [r1.err[1] / r2.err[1] for r1, r2 in zip(res["redesigned"], res["ieee"])]
-    print(json.dumps({
+    return {
         "metric": "tensor error of the redesigned FP4 relative to the IEEE-aligned FP4 (synthetic 7B-shaped weights)",
         "value": e_new / e_ieee, "unit": "ratio", "n_gpus": 1, "steps": 1, "warmup": 0,
         "ms_per_step": elapsed * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
@@ -343,7 +555,7 @@ def run_fp4_variants(args, shapes, dev):
                    "int4_error_relative_to_redesigned_fp4": e_int / e_new,
                    "layers_preferring_fp4_over_int4_percent": {
                        k: 100.0 * sum(1 for r in v if r.best == 1) / len(v) for k, v in res.items()}},
-    }))
+    }
 
 
 def run_w4_units(args, shapes, dev):
@@ -389,7 +601,7 @@ def run_w4_units(args, shapes, dev):
     fp_units = sum(int(t.sum().item()) for t in tags)
     n_units = sum(t.numel() for t in tags)
     n_elems = sum(o * n for _, _, o, n in shapes)
-    print(json.dumps({
+    return {
         "metric": "weight-elems x candidates scored/sec, per-unit format select (group 128)",
         "value": n_elems * N_CLIP_GROUP * N_FMT / (elapsed / args.steps), "unit": "elem*cand/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
@@ -399,7 +611,103 @@ def run_w4_units(args, shapes, dev):
                                "ratios, INT4 vs FP4-E2M1 chosen per group",
                    "mixed_error_relative_to_layer_wise": mix / layer,
                    "fp4_units_percent": 100.0 * fp_units / n_units},
-    }))
+    }
+
+
+# ---- the oracle over whole tensors (not a benchmark) -------------------------------------
+
+def parse_blocks(text, n_blocks):
+    out = []
+    for part in text.split(","):
+        if ":" in part:
+            a, b = part.split(":")
+            out.extend(range(int(a), int(b)))
+        else:
+            out.append(int(part))
+    assert all(0 <= b < n_blocks for b in out), "block out of range"
+    return out
+
+
+def full_parity(args, dev):
+    """Every linear of the listed blocks of the 7B- or 65B-shaped set through
+    mofq_select_layers (the launch configuration the benchmark times) and, whole, through
+    the oracle: per tensor the format choice, both candidates' error sums, and on ALL rows the
+    winner's codes, scales and clip indices (near-tie rule of tests/gpu_util.py)."""
+    import numpy as np
+    import torch
+
+    import mofq_inputs as mi
+    from oracle import mofq_oracle as orc
+    from paper_2305_12356_amd import binding as mq
+    from tests.gpu_util import compare_quantized, scales_to_f32, unpack_codes
+
+    group = args.workload == "w4_group128"
+    n_clip = N_CLIP_GROUP if group else N_CLIP
+    clip = mi.clip_ratios(n_clip)
+    cands = [mq.INT4, mq.FP4_E2M1]
+    cfg = mq.Cfg(mq.PER_GROUP, clip, GROUP, True) if group else mq.Cfg(mq.PER_CHANNEL, clip)
+    gran, grp, f16 = (orc.PER_GROUP, GROUP, True) if group else (orc.PER_CHANNEL, 0, False)
+    blocks = parse_blocks(args.block_list, mi.LLAMA_SHAPES[args.model]["blocks"])
+    all_shapes = mi.model_linear_shapes(args.model)
+    # the 7B-shaped set runs whole, as bench.py times it; of the 65B-shaped set only the listed blocks
+    shapes = all_shapes if args.model == "7b" else [s for s in all_shapes if s[0] in blocks]
+    weights = make_weights(shapes, dev)
+    qouts = [mq.alloc_qbuffers(o, n, 4, cfg, dev) for _, _, o, n in shapes]
+    results = mq.alloc_result(dev, len(shapes))
+    batch = mq.LayerBatch(weights, qouts)
+    ws = torch.empty(batch.workspace_bytes(2, cfg), dtype=torch.uint8, device=dev)
+    mq.select_layers(batch, cands, cfg, results, ws, torch.cuda.current_stream(), side_stream=torch.cuda.Stream())
+    torch.cuda.synchronize()
+    res = mq.read_results(results)
+    threads = orc.max_threads()
+    summary = {"mode": "full-parity", "model": args.model, "workload": "w4_group128" if group else "w4_channel",
+               "blocks": blocks, "n_clip": n_clip, "tensors_in_the_select_layers_call": len(shapes),
+               "tensors_checked": 0, "rows_checked": 0, "elements_checked": 0,
+               "choice_mismatches": 0, "error_sum_mismatches_rtol_1e-9": 0, "max_error_sum_rel_diff": 0.0,
+               "tensors_with_code_scale_or_index_mismatch": 0, "near_tie_units": 0, "fp_chosen": 0,
+               "oracle_seconds": 0.0, "oracle_threads": threads, "head": git_head(), "failures": []}
+    for i, (b, name, o, n) in enumerate(shapes):
+        if b not in blocks:
+            continue
+        w32 = mi.to_f32_numpy(weights[i])
+        t0 = time.perf_counter()
+        ref = orc.select_layer_w_only(w32, cands, gran, clip, grp, f16, want_table=True, threads=threads)
+        summary["oracle_seconds"] += time.perf_counter() - t0
+        r = res[i]
+        summary["tensors_checked"] += 1
+        summary["rows_checked"] += o
+        summary["elements_checked"] += o * n
+        summary["fp_chosen"] += int(ref.best == 1)
+        if r.best != ref.best:
+            summary["choice_mismatches"] += 1
+            summary["failures"].append(f"block {b} {name}: choice {r.best} vs oracle {ref.best}")
+        rel = max(abs(r.err[c] - ref.errs[c]) / ref.errs[c] for c in range(2))
+        summary["max_error_sum_rel_diff"] = max(summary["max_error_sum_rel_diff"], rel)
+        if rel > 1e-9 or abs(r.ref_energy - ref.ref_energy) > 1e-9 * ref.ref_energy:
+            summary["error_sum_mismatches_rtol_1e-9"] += 1
+            summary["failures"].append(f"block {b} {name}: error sums {list(r.err)[:2]} vs {ref.errs}")
+        try:
+            win = ref.per_candidate[r.best] if r.best != ref.best else ref.w
+            summary["near_tie_units"] += compare_quantized(
+                w32, cands[r.best], gran, grp, f16, np.asarray(clip, dtype=np.float32), win,
+                unpack_codes(qouts[i].codes, o, n, 4), scales_to_f32(qouts[i].scales),
+                qouts[i].clip_idx.cpu().numpy(), qouts[i].unit_err.cpu().numpy())
+        except AssertionError as e:
+            summary["tensors_with_code_scale_or_index_mismatch"] += 1
+            summary["failures"].append(f"block {b} {name}: {e}")
+        print(f"[full-parity] block {b} {name} {o}x{n}: best={r.best} oracle={ref.best} "
+              f"rel={rel:.2e} oracle_s={summary['oracle_seconds']:.1f}", file=sys.stderr, flush=True)
+    summary["oracle_elem_cand_per_s"] = summary["elements_checked"] * n_clip * N_FMT / max(summary["oracle_seconds"], 1e-9)
+    summary["ok"] = not summary["failures"]
+    print(json.dumps(summary))
+    return 0 if summary["ok"] else 1
+
+
+def brief(d):
+    """A secondary workload inside the headline line: the figures, not the boilerplate."""
+    keep = ("metric", "value", "unit", "ms_per_step", "ms_per_step_two_caller_streams", "steps", "warmup",
+            "higher_is_better", "dtype", "config", "roofline")
+    return {k: d[k] for k in keep if k in d}
 
 
 def main():
@@ -409,11 +717,9 @@ def main():
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     import mofq_inputs as mi
-    from paper_2305_12356_amd import binding as mq
 
     if not torch.cuda.is_available():
         print("bench.py needs an MI355X (cuda:0)", file=sys.stderr)
@@ -421,152 +727,87 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.full_parity:
+        sys.exit(full_parity(args, dev))
+
+    def note(msg):
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
     shapes = mi.model_linear_shapes(args.model)
     if args.blocks:
         shapes = [s for s in shapes if s[0] < args.blocks]
-    if args.workload in ("w8a8", "w4a16_output"):
-        run_w8a8(args, shapes, dev, w_only=args.workload == "w4a16_output")
+    wl = args.workload
+    if wl == "ceilings":
+        print(json.dumps(measure_ceilings(dev)))
         return
-    if args.workload == "k1_hbm":
-        run_k1_hbm(args, dev)
+    if wl in ("w8a8", "w4a16_output"):
+        weights = make_weights(shapes, dev, torch.bfloat16)
+        print(json.dumps(run_w8a8(args, shapes, dev, weights, wl == "w4a16_output", args.fp8_unit,
+                                  args.steps, args.warmup)))
         return
-    if args.workload == "fp4_variants":
-        run_fp4_variants(args, shapes, dev)
+    if wl == "k1_hbm":
+        print(json.dumps(run_k1_hbm(args, dev, args.steps, args.warmup)))
         return
-    if args.workload == "w4_units":
-        run_w4_units(args, shapes, dev)
+    if wl == "fp4_variants":
+        print(json.dumps(run_fp4_variants(args, shapes, dev)))
         return
-    group = args.workload == "w4_group128"
-    n_clip = N_CLIP_GROUP if group else N_CLIP
-    clip = mi.clip_ratios(n_clip)
-    cands = [mq.INT4, mq.FP4_E2M1]
-    cfg = mq.Cfg(mq.PER_GROUP, clip, GROUP, True) if group else mq.Cfg(mq.PER_CHANNEL, clip)
+    if wl == "w4_units":
+        print(json.dumps(run_w4_units(args, shapes, dev)))
+        return
+    if wl in ("w4_channel", "w4_group128"):
+        weights = make_weights(shapes, dev)
+        out = run_w4(args, shapes, dev, weights, wl == "w4_group128", args.model, args.steps, args.warmup,
+                     want_cpu=(wl == "w4_channel" and args.model == "7b" and not args.no_cpu_baseline and not args.blocks))
+        if args.copy_calibration:
+            src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+            dst = torch.empty_like(src)
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+            torch.cuda.synchronize()
+        print(json.dumps(out))
+        return
 
-    # ---- resident inputs and caller-owned outputs ---------------------------------
-    weights, qouts = [], []
-    results = mq.alloc_result(dev, len(shapes))
-    ws_bytes = 0
-    for i, (b, name, o, n) in enumerate(shapes):
-        w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, mi.LINEAR_NAMES.index(name)), device=dev)
-        weights.append(w)
-        qouts.append(mq.alloc_qbuffers(o, n, 4, cfg, dev))
-        ws_bytes = max(ws_bytes, mq.workspace_bytes(w, None, len(cands), mq.ERR_TENSOR, cfg))
-    # one call for the whole model (mofq_select_layers): the per-tensor reduce / select /
-    # per-unit outputs of up to 12 tensors share a launch, and so do the searches of those of
-    # them that have one row length
-    batch = mq.LayerBatch(weights, qouts)
-    ws = torch.empty(batch.workspace_bytes(len(cands), cfg), dtype=torch.uint8, device=dev)
-    n_elems = sum(o * n for _, _, o, n in shapes)
-    stream = torch.cuda.current_stream()
-    # default priority: select + code emission beside the next batch's searches
-    side = None if args.single_stream else torch.cuda.Stream()
-
-    # the events the library records around each search launch, created (and recorded once,
-    # so that they exist) before the timed region
-    ev_pool = []
-    for _ in range(args.steps):
-        e0 = [torch.cuda.Event(enable_timing=True) for _ in weights]
-        e1 = [torch.cuda.Event(enable_timing=True) for _ in weights]
-        for e in e0 + e1:
-            e.record()
-        ev_pool.append((e0, e1))
-
-    def step(events=None):
-        e0 = e1 = None
-        if events is not None:
-            e0, e1 = ev_pool.pop()
-            events.extend((i, a, b) for i, (a, b) in enumerate(zip(e0, e1)))
-        mq.select_layers(batch, cands, cfg, results, ws, stream, e0, e1, side_stream=side)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    events = []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(events)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-
-    ms_per_step = elapsed / args.steps * 1e3
-    elem_cand = n_elems * n_clip * N_FMT
-    value = elem_cand / (elapsed / args.steps)
-
-    # ---- dominant kernel: the scale-search instance for 4096-column rows ------------
-    # (q, k, v, o, gate, up: 78 % of all elements; the tensors of a batch with one row length
-    # share a launch).  Duration from the HIP events the library recorded around each launch: the
-    # begin event of a launch's first tensor, the end event of its last.
-    first = batch.search_groups(cands)
-    last = {f: i for i, f in enumerate(first)}
-    by_cols = {}
-    for step_i in range(args.steps):
-        ev = events[step_i * len(shapes):(step_i + 1) * len(shapes)]
-        for f, l in last.items():
-            elems = sum(shapes[i][2] * shapes[i][3] for i in range(f, l + 1) if first[i] == f)
-            by_cols.setdefault(shapes[f][3], []).append((elems, ev[f][1].elapsed_time(ev[l][2]) * 1e-3))
-    dom_cols = max(by_cols, key=lambda c: sum(e for e, _ in by_cols[c]))
-    dom = by_cols[dom_cols]
-    dom_flops = sum(e for e, _ in dom) * n_clip * N_FMT * FLOPS_PER_ELEM_CAND_FMT
-    dom_time = sum(t for _, t in dom)
-    achieved = dom_flops / dom_time / 1e12
-    traffic = None
-    if not group and args.model == "7b":
-        per = [o * n * 2 * MEASURED_READ_PER_INPUT_BYTE + o * MEASURED_WRITE_BYTES_PER_ROW
-               for _, _, o, n in shapes if n == dom_cols]
-        traffic = sum(per) * args.steps / len(by_cols[dom_cols])   # per launch (a launch covers several tensors)
-    search_time = sum(t for v in by_cols.values() for _, t in v) / args.steps
-    roofline = {
-        "bound": "alu", "achieved": achieved, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
-        "frac": achieved / ALU_PEAK_TFLOPS, "traffic": traffic,
-        "kernel": (f"sweep_group_kernel<F16, INT4, FP4_E2M1, {GROUP}> on {dom_cols}-column rows" if group else
-                   f"sweep_sorted_kernel<F16, INT4, FP4_E2M1> instance for {dom_cols}-column rows"),
-        "note": ("achieved counts the flop of the exhaustive element x candidate scoring" if group else
-                 "achieved counts the flop of the exhaustive element x candidate scoring (the "
-                 "algorithmic work); the kernel reaches the same result by sorting each row once and "
-                 "locating level boundaries by binary search, so frac can exceed 1"),
-        "avg_launch_ms": dom_time / len(dom) * 1e3, "launches": len(dom),
-        "algorithmic_bytes_per_launch": sum(e for e, _ in dom) * 2 / len(dom),
-        "flops_per_elem_cand_fmt": FLOPS_PER_ELEM_CAND_FMT,
-        "hbm_GBps_at_this_rate": sum(e for e, _ in dom) * 2 / dom_time / 1e9,
-        "search_ms_per_step": search_time * 1e3,
-    }
-    if not group and args.model == "7b":
-        # what the kernel itself does with the vector ALUs (hardware counters, not measured in this run)
-        roofline["kernel_valu_active_frac"] = 0.90
-        roofline["kernel_valu_active_frac_source"] = "profiles/w_only_sorted_kernel_counters.txt"
-
-    if args.copy_calibration:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
-
-    res = mq.read_results(results)
-    fp_pct = 100.0 * sum(1 for r in res if r.best == 1) / len(res)
-
-    out = {
-        "metric": f"weight-elems x candidates scored/sec (+ LLaMA-{args.model.upper()} full-model MoFQ select time)",
-        "value": value, "unit": "elem*cand/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "select_time_s": ms_per_step / 1e3,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 decisions, f64 errors", "data": "synthetic",
-        "config": {"workload": ("configs[2]: LLaMA-7B-shaped fp16 weight set, "
-                                f"{len(shapes)} linears, {n_elems} weights, 4-bit W-only group-wise "
-                                "(128 along the input dim, fp16 scales), 50 clip ratios in [0.5,1], "
-                                "INT4 vs FP4-E2M1, per-layer select + emit") if group else
-                               (("configs[4]: LLaMA-65B-shaped" if args.model == "65b" else
-                                 "configs[1]: LLaMA-7B-shaped") + " fp16 weight set, "
-                                f"{len(shapes)} linears, {n_elems} weights, 4-bit W-only per-channel, "
-                                "100 clip ratios in [0.5,1], INT4 vs FP4-E2M1, per-layer select + emit"),
-                   "n_clip": n_clip, "formats": ["INT4", "FP4_E2M1"], "fp_percent": fp_pct},
-        "roofline": roofline,
-    }
-    if not args.no_cpu_baseline and not group and args.model == "7b":
-        outs = [(qouts[i], res[i]) for i in range(len(shapes))]
-        out["cpu_baseline"] = cpu_baseline(weights, outs, clip, cands)
+    # ---- all: the headline workload, then the others under `secondary` ------------------
+    t_start = time.perf_counter()
+    note("device ceilings")
+    ceilings = measure_ceilings(dev)
+    shapes7 = mi.model_linear_shapes("7b")
+    if args.blocks:
+        shapes7 = [s for s in shapes7 if s[0] < args.blocks]
+    note("7B-shaped fp16 weights")
+    weights = make_weights(shapes7, dev)
+    note("configs[1]: per-channel, 100 clip ratios")
+    out = run_w4(args, shapes7, dev, weights, False, "7b", args.steps, args.warmup, ceilings,
+                 want_cpu=not args.no_cpu_baseline and not args.blocks)
+    out["ceilings"] = ceilings
+    sec = {}
+    few, few_w = max(1, min(args.steps, 3)), max(1, min(args.warmup, 1))
+    note("configs[2]: group 128, 50 clip ratios")
+    sec["w4_group128"] = brief(run_w4(args, shapes7, dev, weights, True, "7b", few, few_w, ceilings))
+    del weights
+    torch.cuda.empty_cache()
+    note("configs[0]'s recipe on 1 GiB")
+    sec["k1_hbm"] = brief(run_k1_hbm(args, dev, few, few_w, ceilings))
+    torch.cuda.empty_cache()
+    note("bf16 weights for the layer-output workloads")
+    weights = make_weights(shapes7, dev, torch.bfloat16)
+    note("configs[3]: W8A8, exact")
+    sec["w8a8"] = brief(run_w8a8(args, shapes7, dev, weights, False, False, few, few_w, ceilings))
+    note("configs[3]: W8A8, fp8 matrix cores")
+    sec["w8a8_fp8_unit"] = brief(run_w8a8(args, shapes7, dev, weights, False, True, few, few_w, ceilings))
+    note("weight-only select by layer-output error")
+    sec["w4a16_output"] = brief(run_w8a8(args, shapes7, dev, weights, True, False, few, few_w, ceilings))
+    del weights
+    torch.cuda.empty_cache()
+    if not args.no_65b and not args.blocks:
+        note("configs[4]: 65B-shaped set, 129.5 GB resident")
+        shapes65 = mi.model_linear_shapes("65b")
+        weights = make_weights(shapes65, dev)
+        sec["w4_channel_65b"] = brief(run_w4(args, shapes65, dev, weights, False, "65b", 2, 1, ceilings))
+        del weights
+        torch.cuda.empty_cache()
+    out["secondary"] = sec
+    out["bench_wall_s"] = round(time.perf_counter() - t_start, 1)
+    out["head"] = git_head()
     print(json.dumps(out))
 
 

@@ -320,6 +320,38 @@ int mofq_select_layer_timed(const mofq_tensor_t* w, const mofq_tensor_t* x,
                             void* ws, size_t ws_bytes, void* stream,
                             void* ev_score_begin, void* ev_score_end);
 
+/*
+ * What the device in front of us sustains, for reading roofline fractions against (not part
+ * of the quantization path; Section 1's motivation is the cost of low-bit arithmetic units,
+ * and a measurement harness needs the part's own rates beside the published peaks).  Enqueues
+ * one register-only micro-kernel (or `iters` plain copies) on `stream`; the caller times it
+ * with events.
+ *   kind    : MOFQ_CEILING_COPY      copies the first half of `scratch` to the second half,
+ *                                    `iters` times; *work = bytes read + written;
+ *             MOFQ_CEILING_FMA_F32 / _F64   `iters` rounds of 16 independent fused
+ *                                    multiply-adds per lane, 32 waves per compute unit;
+ *                                    *work = floating-point operations;
+ *             MOFQ_CEILING_MFMA_BF16 / _INT8 / _FP8   `iters` rounds of 4 independent 32x32
+ *                                    matrix instructions per wave (32x32x16 bf16, 32x32x32
+ *                                    int8, 32x32x64 e4m3), 32 waves per compute unit;
+ *                                    *work = operations (2 per multiply-add).
+ *   scratch : device, 16-byte aligned; at least 8 bytes per lane of the launch (64 KB per
+ *             compute unit) for the loop kinds, any size >= 32 bytes for the copy (which
+ *             should be far larger than the caches to mean anything).  Contents are
+ *             overwritten.
+ *   work    : HOST, receives the work of the enqueued launches.
+ */
+typedef enum {
+  MOFQ_CEILING_COPY = 0,
+  MOFQ_CEILING_FMA_F32 = 1,
+  MOFQ_CEILING_FMA_F64 = 2,
+  MOFQ_CEILING_MFMA_BF16 = 3,
+  MOFQ_CEILING_MFMA_INT8 = 4,
+  MOFQ_CEILING_MFMA_FP8 = 5
+} mofq_ceiling_t;
+int mofq_device_ceiling(int32_t kind, void* scratch, size_t scratch_bytes, int32_t iters,
+                        double* work, void* stream);
+
 /* Bytes of workspace the three calls above need for these arguments (the
  * largest over the three); 0 on invalid arguments.  Workspace contents are
  * scratch: nothing survives a call, calls sharing a workspace must be ordered

@@ -100,6 +100,8 @@ def _load():
     L.mofq_select_calibrated.restype = C.c_int
     L.mofq_select_calibrated.argtypes = [C.POINTER(TensorDesc), C.POINTER(C.c_int32), C.c_int32, vp,
                                          C.POINTER(QOut), vp, vp, C.c_size_t, vp]
+    L.mofq_device_ceiling.restype = C.c_int
+    L.mofq_device_ceiling.argtypes = [C.c_int32, vp, C.c_size_t, C.c_int32, C.POINTER(C.c_double), vp]
     L.mofq_num_units.restype = C.c_int64
     L.mofq_num_units.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32]
     L.mofq_status_string.restype = C.c_char_p
@@ -350,6 +352,20 @@ def select_layers(batch: LayerBatch, candidates: Sequence[int], cfg: Cfg, result
         rc = _lib.mofq_select_layers_timed(*args, e0, e1)
     if rc != 0:
         raise MofqError(rc, "mofq_select_layers")
+
+
+CEILING_COPY, CEILING_FMA_F32, CEILING_FMA_F64, CEILING_MFMA_BF16, CEILING_MFMA_INT8, CEILING_MFMA_FP8 = range(6)
+
+
+def device_ceiling(kind: int, scratch: torch.Tensor, iters: int, stream=None) -> float:
+    """mofq_device_ceiling: enqueue one rate-measuring micro-kernel (or `iters` plain copies of
+    half of `scratch`); returns the work of the launch (bytes or operations)."""
+    work = C.c_double(0.0)
+    rc = _lib.mofq_device_ceiling(kind, _ptr(scratch), scratch.numel() * scratch.element_size(), iters,
+                                  C.byref(work), _stream_handle(stream))
+    if rc != 0:
+        raise MofqError(rc, "mofq_device_ceiling")
+    return work.value
 
 
 def alloc_result(device, n: int = 1) -> torch.Tensor:

@@ -91,17 +91,41 @@ def test_65b_shapes_per_channel_k100(mq, name, o, n):
     _check_sampled(mq, w, orc.PER_CHANNEL, mi.clip_ratios(100), 0, False, 24, 3, f"65b-{name}")
 
 
-def test_whole_block_every_linear_decision(mq):
-    """All seven linears of one 7B-shaped block: each format choice against the oracle's
-    choice computed from the library's own per-format unit errors on all rows and from the
-    oracle on sampled rows (checked above); here: the choice and the FP fraction."""
-    picks = []
-    cfg = mq.Cfg(orc.PER_CHANNEL, mi.clip_ratios(100))
-    for li, (name, o, n) in enumerate(mi.block_linear_shapes("7b")):
-        w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, 1, li), device=DEV)
-        _, r, _ = _select(mq, w, cfg)
-        assert r.best == orc.select(list(r.err)[:2])
-        picks.append(r.best)
+def test_whole_block_all_rows_against_oracle(mq):
+    """All seven linears of one 7B-shaped block through one mofq_select_layers call with a second
+    stream (the launch configuration bench.py times), every row held to the oracle: per tensor the
+    format choice, both candidates' error sums and the reference energy, and the winner's codes,
+    scales, clip indices and unit errors on all rows (202 M weights x 200 candidates: about 45 s
+    of oracle time on 16 host threads)."""
+    clip = mi.clip_ratios(100)
+    cfg = mq.Cfg(orc.PER_CHANNEL, clip)
+    shapes = mi.block_linear_shapes("7b")
+    ws_ = [mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, 1, li), device=DEV) for li, (_, o, n) in enumerate(shapes)]
+    outs = [mq.alloc_qbuffers(o, n, 4, cfg, DEV) for _, o, n in shapes]
+    batch = mq.LayerBatch(ws_, outs)
+    results = mq.alloc_result(DEV, len(shapes))
+    ws = torch.empty(batch.workspace_bytes(2, cfg), dtype=torch.uint8, device=DEV)
+    print("[case] 7b block 1, all rows, through mofq_select_layers", flush=True)
+    mq.select_layers(batch, CANDS, cfg, results, ws, side_stream=torch.cuda.Stream())
+    torch.cuda.synchronize()
+    res = mq.read_results(results)
+    picks, band = [], 0
+    for i, (name, o, n) in enumerate(shapes):
+        w32 = mi.to_f32_numpy(ws_[i])
+        ref = orc.select_layer_w_only(w32, CANDS, orc.PER_CHANNEL, clip, want_table=True)
+        print(f"[case]   {name} {o}x{n}: best={res[i].best} oracle={ref.best}", flush=True)
+        assert res[i].best == ref.best and res[i].n == 2
+        assert np.allclose(list(res[i].err)[:2], ref.errs, rtol=ERR_RTOL)
+        assert np.isclose(res[i].ref_energy, ref.ref_energy, rtol=1e-12)
+        codes = outs[i].codes.cpu().numpy()
+        un = np.empty(o * n, dtype=np.uint8)
+        un[0::2] = codes & 0xF
+        un[1::2] = codes >> 4
+        band += compare_quantized(w32, CANDS[ref.best], orc.PER_CHANNEL, 0, False, np.asarray(clip, dtype=np.float32),
+                                  ref.w, un.reshape(o, n), scales_to_f32(outs[i].scales),
+                                  outs[i].clip_idx.cpu().numpy(), outs[i].unit_err.cpu().numpy())
+        picks.append(ref.best)
+    print(f"[case]   near-tie rows: {band}", flush=True)
     # Table 2 reports 88.9-97.9 % of layers choosing FP4 on real weights; Gaussian rows with
     # heavy-tailed outliers behave the same way
     assert sum(picks) >= 6
