@@ -354,7 +354,7 @@ def select_layers(batch: LayerBatch, candidates: Sequence[int], cfg: Cfg, result
         raise MofqError(rc, "mofq_select_layers")
 
 
-CEILING_COPY, CEILING_FMA_F32, CEILING_FMA_F64, CEILING_MFMA_BF16, CEILING_MFMA_INT8, CEILING_MFMA_FP8 = range(6)
+CEILING_COPY, CEILING_FMA_F32, CEILING_FMA_F64, CEILING_MFMA_BF16, CEILING_MFMA_INT8, CEILING_MFMA_FP8, CEILING_READ = range(7)
 
 
 def device_ceiling(kind: int, scratch: torch.Tensor, iters: int, stream=None) -> float:

@@ -32,6 +32,21 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const u32x4* __restrict_
   for (; i < n; i += stride) dst[i] = src[i];
 }
 
+// sink[thread] = xor of the n 16-byte chunks the thread visits (grid-stride, four in flight): a
+// pass that only reads, like the scoring kernels
+__global__ __launch_bounds__(kThreads) void read_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ sink, int64_t n) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (; i + 3 * stride < n; i += 4 * stride) {
+    const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc ^= (a ^ b) ^ (c ^ d);
+  }
+  for (; i < n; i += stride) acc ^= src[i];
+  if (acc[0] == 0x12345678u && acc[1] == 0x9ABCDEF0u && acc[2] == 1u && acc[3] == 2u)   // practically never: keeps the loads alive
+    sink[static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x] = acc;
+}
+
 // kChains independent fused multiply-add chains per lane, `iters` rounds: 2 flop per chain and
 // round.  The multiplier is below 1 in magnitude, so the values stay finite; the result is
 // stored so that the loop cannot be dropped.
@@ -117,6 +132,17 @@ extern "C" int mofq_device_ceiling(int32_t kind, void* scratch, size_t scratch_b
       for (int i = 0; i < iters; ++i)
         hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(kThreads), 0, st, src, const_cast<u32x4*>(src) + n, n);
       *work = 32.0 * static_cast<double>(n) * iters;         // bytes read + bytes written
+      break;
+    }
+    case MOFQ_CEILING_READ: {
+      // the first sink_bytes * 2 hold the (practically never written) sink, the rest is read
+      if (scratch_bytes < 4 * sink_bytes) return MOFQ_ERR_WORKSPACE;
+      char* base = static_cast<char*>(scratch);
+      const int64_t n = static_cast<int64_t>((scratch_bytes - 2 * sink_bytes) / 16);
+      for (int i = 0; i < iters; ++i)
+        hipLaunchKernelGGL(read_kernel, dim3(blocks), dim3(kThreads), 0, st,
+                           reinterpret_cast<const u32x4*>(base + 2 * sink_bytes), reinterpret_cast<u32x4*>(base), n);
+      *work = 16.0 * static_cast<double>(n) * iters;         // bytes read
       break;
     }
     case MOFQ_CEILING_FMA_F32:
