@@ -77,10 +77,16 @@ def parse():
     ap.add_argument("--full-parity", action="store_true",
                     help="hold every linear of --block-list to the oracle on all rows and print a summary")
     ap.add_argument("--block-list", default="0", help="full-parity: blocks, e.g. 0,39,79 or 0:11")
+    ap.add_argument("--head", default=None, help="commit to record in the output where no git checkout is at hand")
     return ap.parse_args()
 
 
+HEAD_OVERRIDE = None
+
+
 def git_head():
+    if HEAD_OVERRIDE:
+        return HEAD_OVERRIDE
     try:
         return subprocess.run(["git", "rev-parse", "--short", "HEAD"], cwd=ROOT, capture_output=True,
                               text=True, timeout=5).stdout.strip() or None
@@ -712,7 +718,9 @@ def brief(d):
 
 
 def main():
+    global HEAD_OVERRIDE
     args = parse()
+    HEAD_OVERRIDE = args.head
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no second device); "
               "use --gpus 1", file=sys.stderr)

@@ -200,6 +200,14 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   __shared__ double s_p2[NW];
   __shared__ double s_val[MAXL];
   static_assert(MOFQ_MAX_CLIP * 2 <= 256, "shortlist entries are bytes");
+  // Boundary search: with 16 waves the 15 boundaries of a candidate are dealt to SPLIT waves
+  // (4 boundaries each) so that every wave has search work; the partial level sums meet in LDS.
+  constexpr int SPLIT = (NW >= 16) ? 4 : 1;
+  constexpr int NBD = 15;                 // boundaries of a 16-level format; unused ones carry zeros
+  constexpr int QB = (NBD + SPLIT - 1) / SPLIT;   // boundaries per lane
+  static_assert(QB * SPLIT <= 16, "boundary tables have 16 entries");
+  __shared__ double s_pca[SPLIT > 1 ? NF * MOFQ_MAX_CLIP * SPLIT : 1];
+  __shared__ int s_pcb[SPLIT > 1 ? NF * MOFQ_MAX_CLIP * SPLIT : 1];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -381,11 +389,11 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   const double s_total = s_blk[NBLK];
 
   // ---- level boundaries of every candidate by binary search ------------------------------
-  // One lane per candidate, one wave per (format, 64 candidates); a lane walks the searches
-  // of all boundaries of its candidate side by side (independent chains hide the LDS latency)
-  // and adds up the two level sums itself.  Thresholds and level differences are wave-uniform.
+  // One lane per candidate (and per group of QB boundaries), one wave per (format, 64
+  // candidates, boundary group); a lane walks the searches of its boundaries side by side
+  // (independent chains hide the LDS latency) and adds up the two level sums itself.
+  // Thresholds and level differences are wave-uniform.
   {
-    constexpr int NBD = 15;                 // boundaries of a 16-level format; unused ones carry zeros
     // Lower bound over the first NP - 1 elements with the steps FIRST (twice when the row
     // length is 3 * 2^k), FIRST/2, .., 1: they add up to NP - 1 and no probe leaves that
     // range.  The last element is tested on its own afterwards.  Steps that are multiples of
@@ -393,11 +401,13 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
     const float x_last = bits_to_float<In>(sorted[phys(NP - 1)]);
     const float x_first = bits_to_float<In>(sorted[phys(FIRST - 1)]);   // the first step's probe
     const int chunks = (K + 63) >> 6;
-    for (int u = wave; u < NF * chunks; u += NW) {
-      const int f = u / chunks;                       // wave-uniform
-      const int k = (u - f * chunks) * 64 + lane;
+    for (int u = wave; u < NF * chunks * SPLIT; u += NW) {
+      const int sub = u % SPLIT, fc = u / SPLIT;      // wave-uniform
+      const int f = fc / chunks;
+      const int k = (fc - f * chunks) * 64 + lane;
+      const int q0 = sub * QB;                         // first boundary of this lane
       const float inv = s_inv[f][k < K ? k : K - 1];
-      int ppos[NBD];   // padded byte offset of the next probe; of the position at the end
+      int ppos[QB];   // padded byte offset of the next probe; of the position at the end
       // Branch-free: position = number of elements on levels <= q.  Every element before the
       // position passes the test; the NaN padding stops it at n.  The offset of the next
       // step's probe rides along in the position.  The first step probes the same element
@@ -406,8 +416,8 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
         constexpr int NEXT = NP_POW2 ? FIRST / 2 : FIRST;     // size of the step after the first
         const float t0 = x_first * inv;
 #pragma unroll
-        for (int q = 0; q < NBD; ++q)
-          ppos[q] = 2 * phys(NEXT - 1) + ((t0 <= a.thr[f][q]) ? 2 * phys(FIRST) : 0);
+        for (int q = 0; q < QB; ++q)
+          ppos[q] = 2 * phys(NEXT - 1) + ((t0 <= a.thr[f][q0 + q]) ? 2 * phys(FIRST) : 0);
       }
 #pragma unroll 1
       for (int st = (NP_POW2 ? LSTEPS - 2 : LSTEPS - 1); st >= 0; --st) {
@@ -415,24 +425,24 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
         const int next_probe = st > 0 ? 2 * phys((stp >> 1) - 1) : 0;
         const int stay = next_probe - 2 * phys(stp - 1), go = stay + 2 * phys(stp);   // wave-uniform
 #pragma unroll
-        for (int q = 0; q < NBD; ++q) {
+        for (int q = 0; q < QB; ++q) {
           const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + ppos[q]);
           const float t = scaled<In>(h, inv);
-          ppos[q] += (t <= a.thr[f][q]) ? go : stay;
+          ppos[q] += (t <= a.thr[f][q0 + q]) ? go : stay;
         }
       }
       const float t_last = x_last * inv;
       double ca = 0.0;
       int cb4 = 0;       // 4 sum_b (count below boundary b) (g_b^2 - g_{b+1}^2): an integer below 2^31
 #pragma unroll
-      for (int q = 0; q < NBD; ++q) {
+      for (int q = 0; q < QB; ++q) {
         // position in elements: the padded byte offset holds 132 bytes per 64 elements
         // (slot / 66 = slot * 993 >> 16 for every slot of a row of up to 24576 elements: the slot of
         // an element leaves a remainder of at most 63, so the quotient's fraction stays below 1 - 2/66
         // and the factor's excess of 5e-7 per slot cannot carry)
         const int slot = ppos[q] >> 1;
         const int j0 = slot - 2 * static_cast<int>(__umul24(static_cast<uint32_t>(slot), 993u) >> 16);
-        const int j = j0 + (t_last <= a.thr[f][q] ? 1 : 0);
+        const int j = j0 + (t_last <= a.thr[f][q0 + q] ? 1 : 0);
         constexpr int LB = (BS == 2) ? 1 : (BS == 4 ? 2 : 3);
         double p = s_blk[j >> LB];
         if constexpr (BS == 2) {
@@ -449,10 +459,35 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
             p += in ? val : 0.0;
           }
         }
-        ca = __builtin_fma(p, a.dgd[f][q], ca);
-        cb4 = __mul24(j, a.dg2q[f][q]) + cb4;
+        ca = __builtin_fma(p, a.dgd[f][q0 + q], ca);
+        cb4 = __mul24(j, a.dg2q[f][q0 + q]) + cb4;
       }
-      if (k < K) {
+      if constexpr (SPLIT == 1) {
+        if (k < K) {
+          const double gl = static_cast<double>(a.g_last[f]);
+          const double A = ca + gl * s_total;
+          const double B = 0.25 * static_cast<double>(cb4) + gl * gl * static_cast<double>(n);
+          const double sc = static_cast<double>(s_scale[f][k]);
+          s_fast[f][k] = (en - 2.0 * sc * A) + sc * sc * B;   // filtered error
+        }
+      } else {
+        if (k < K) {
+          s_pca[(f * MOFQ_MAX_CLIP + k) * SPLIT + sub] = ca;
+          s_pcb[(f * MOFQ_MAX_CLIP + k) * SPLIT + sub] = cb4;
+        }
+      }
+    }
+    if constexpr (SPLIT > 1) {
+      __syncthreads();
+      for (int idx = tid; idx < NF * K; idx += THREADS) {
+        const int f = idx / K, k = idx - f * K;
+        double ca = 0.0;
+        int cb4 = 0;
+#pragma unroll
+        for (int sub = 0; sub < SPLIT; ++sub) {   // fixed order
+          ca += s_pca[(f * MOFQ_MAX_CLIP + k) * SPLIT + sub];
+          cb4 += s_pcb[(f * MOFQ_MAX_CLIP + k) * SPLIT + sub];
+        }
         const double gl = static_cast<double>(a.g_last[f]);
         const double A = ca + gl * s_total;
         const double B = 0.25 * static_cast<double>(cb4) + gl * gl * static_cast<double>(n);
@@ -468,7 +503,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   // tree of depth at most D = 2E + 32 (thread-sequential, wave scan, across waves) and is off
   // by at most D u sum|x|; the level differences of one format add up to less than 16 and the
   // largest level is at most 8, so the level sum A is off by less than 32 D u sum|x| including
-  // its own 15 additions.  The energy is off by (E + 14) u sum x^2; counts, level squares and
+  // its own additions (15, and 3 more where the boundaries are dealt to four waves).  The energy is off by (E + 14) u sum x^2; counts, level squares and
   // s^2 are exact; the remaining products and additions round a handful of times on terms
   // bounded by the three summands.  Hence
   //   |filtered - exact| <= beta = u (40 D * 2 s sum|x| + (E + 32) sum x^2 + 8 s^2 g_max^2 n).
