@@ -710,6 +710,68 @@ def full_parity(args, dev):
     return 0 if summary["ok"] else 1
 
 
+def full_parity_wa(args, dev):
+    """Every linear of the listed blocks of the W8A8 workload (configs[3]) through
+    mofq_select_layer with both forms of the layer-output metric and, whole, through the oracle
+    (fp64 matrix products): both candidates' error sums and the reference energy to 1e-5, the
+    choice, and the winner's codes and scales of W and X bit for bit."""
+    import numpy as np
+    import torch
+
+    import mofq_inputs as mi
+    from oracle import mofq_oracle as orc
+    from paper_2305_12356_amd import binding as mq
+    from tests.gpu_util import scales_to_f32, unpack_codes
+
+    blocks = parse_blocks(args.block_list, mi.LLAMA_SHAPES["7b"]["blocks"])
+    shapes = [s_ for s_ in mi.model_linear_shapes("7b") if s_[0] in blocks]
+    cands = [mq.INT8, mq.FP8_E4M3]
+    cfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
+    xcfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
+    summary = {"mode": "full-parity", "workload": "w8a8", "blocks": blocks, "tokens": TOKENS, "linears_checked": 0,
+               "choice_mismatches": 0, "error_sum_mismatches_rtol_1e-5": 0, "max_error_sum_rel_diff_exact": 0.0,
+               "max_error_sum_rel_diff_fp8_unit": 0.0, "code_or_scale_mismatches": 0, "fp_chosen": 0,
+               "oracle_seconds": 0.0, "head": git_head(), "failures": []}
+    for b, name, o, n in shapes:
+        lin = mi.LINEAR_NAMES.index(name)
+        x = mi.activations(TOKENS, n, seed=mi.tensor_seed(3, b, lin, 1), device=dev)
+        w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(3, b, lin), dtype=torch.bfloat16, device=dev)
+        t0 = time.perf_counter()
+        ref = orc.select_layer_wa(mi.to_f32_numpy(x), mi.to_f32_numpy(w), cands, orc.PER_TENSOR)
+        summary["oracle_seconds"] += time.perf_counter() - t0
+        summary["linears_checked"] += 1
+        summary["fp_chosen"] += int(ref.best == 1)
+        for metric, key in ((mq.ERR_LAYER_OUTPUT, "exact"), (mq.ERR_LAYER_OUTPUT_FP8_UNIT, "fp8_unit")):
+            w_out = mq.alloc_qbuffers(o, n, 8, cfg, dev)
+            x_out = mq.alloc_qbuffers(TOKENS, n, 8, xcfg, dev)
+            res = mq.alloc_result(dev)
+            ws = torch.empty(mq.workspace_bytes(w, x, 2, metric, cfg), dtype=torch.uint8, device=dev)
+            mq.select_layer(w, x, cands, metric, cfg, w_out, x_out, res, ws)
+            torch.cuda.synchronize()
+            r = mq.read_result(res)
+            rel = max(abs(r.err[c] - ref.errs[c]) / ref.errs[c] for c in range(2))
+            rel = max(rel, abs(r.ref_energy - ref.ref_energy) / ref.ref_energy)
+            summary["max_error_sum_rel_diff_" + key] = max(summary["max_error_sum_rel_diff_" + key], rel)
+            if rel > 1e-5:
+                summary["error_sum_mismatches_rtol_1e-5"] += 1
+                summary["failures"].append(f"block {b} {name} {key}: {list(r.err)[:2]} vs {ref.errs}")
+            if r.best != ref.best:
+                summary["choice_mismatches"] += 1
+                summary["failures"].append(f"block {b} {name} {key}: choice {r.best} vs {ref.best}")
+            same = (np.array_equal(unpack_codes(w_out.codes, o, n, 8), ref.w.codes) and
+                    np.array_equal(unpack_codes(x_out.codes, TOKENS, n, 8), ref.x.codes) and
+                    np.array_equal(scales_to_f32(w_out.scales), ref.w.scale) and
+                    np.array_equal(scales_to_f32(x_out.scales), ref.x.scale))
+            if not same:
+                summary["code_or_scale_mismatches"] += 1
+                summary["failures"].append(f"block {b} {name} {key}: codes or scales differ")
+        print(f"[full-parity] w8a8 block {b} {name} {o}x{n}: oracle best={ref.best} "
+              f"oracle_s={summary['oracle_seconds']:.1f}", file=sys.stderr, flush=True)
+    summary["ok"] = not summary["failures"]
+    print(json.dumps(summary))
+    return 0 if summary["ok"] else 1
+
+
 def brief(d):
     """A secondary workload inside the headline line: the figures, not the boilerplate."""
     keep = ("metric", "value", "unit", "ms_per_step", "ms_per_step_two_caller_streams", "steps", "warmup",
@@ -737,7 +799,7 @@ def main():
     torch.cuda.set_device(0)
 
     if args.full_parity:
-        sys.exit(full_parity(args, dev))
+        sys.exit(full_parity_wa(args, dev) if args.workload == "w8a8" else full_parity(args, dev))
 
     def note(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)

@@ -421,9 +421,10 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
       }
 #pragma unroll 1
       for (int st = (NP_POW2 ? LSTEPS - 2 : LSTEPS - 1); st >= 0; --st) {
-        const int stp = 1 << st;
-        const int next_probe = st > 0 ? 2 * phys((stp >> 1) - 1) : 0;
-        const int stay = next_probe - 2 * phys(stp - 1), go = stay + 2 * phys(stp);   // wave-uniform
+        // wave-uniform constants of the step, computed on the scalar unit
+        const int stp = 1 << __builtin_amdgcn_readfirstlane(st);
+        const int next_probe = stp > 1 ? 2 * phys((stp >> 1) - 1) : 0;
+        const int stay = next_probe - 2 * phys(stp - 1), go = stay + 2 * phys(stp);
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
           const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + ppos[q]);
