@@ -32,15 +32,18 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const u32x4* __restrict_
   for (; i < n; i += stride) dst[i] = src[i];
 }
 
-// sink[thread] = xor of the n 16-byte chunks the thread visits (grid-stride, four in flight): a
+// sink[thread] = xor of the n 16-byte chunks the thread visits (grid-stride, eight in flight): a
 // pass that only reads, like the scoring kernels
 __global__ __launch_bounds__(kThreads) void read_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ sink, int64_t n) {
   const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
   int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
   u32x4 acc = {0u, 0u, 0u, 0u};
-  for (; i + 3 * stride < n; i += 4 * stride) {
-    const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc ^= (a ^ b) ^ (c ^ d);
+  for (; i + 7 * stride < n; i += 8 * stride) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(&src[i + u * stride]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
   }
   for (; i < n; i += stride) acc ^= src[i];
   if (acc[0] == 0x12345678u && acc[1] == 0x9ABCDEF0u && acc[2] == 1u && acc[3] == 2u)   // practically never: keeps the loads alive
