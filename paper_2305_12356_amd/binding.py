@@ -95,6 +95,15 @@ def _load():
     L.mofq_select_layers_workspace_bytes.restype = C.c_size_t
     L.mofq_select_layers_workspace_bytes.argtypes = [C.c_int32, C.POINTER(TensorDesc), C.c_int32,
                                                      C.POINTER(ScaleCfg)]
+    L.mofq_select_layers_wa.restype = C.c_int
+    L.mofq_select_layers_wa.argtypes = [C.c_int32, C.POINTER(TensorDesc), C.POINTER(TensorDesc),
+                                        C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.POINTER(ScaleCfg),
+                                        C.POINTER(QOut), C.POINTER(QOut), vp, vp, C.c_size_t, vp, vp]
+    L.mofq_select_layers_wa_timed.restype = C.c_int
+    L.mofq_select_layers_wa_timed.argtypes = L.mofq_select_layers_wa.argtypes + [C.POINTER(vp), C.POINTER(vp)]
+    L.mofq_select_layers_wa_workspace_bytes.restype = C.c_size_t
+    L.mofq_select_layers_wa_workspace_bytes.argtypes = [C.c_int32, C.POINTER(TensorDesc), C.POINTER(TensorDesc),
+                                                        C.c_int32, C.c_int32, C.POINTER(ScaleCfg)]
     L.mofq_calibrate_absmax.restype = C.c_int
     L.mofq_calibrate_absmax.argtypes = [C.POINTER(TensorDesc), vp, vp, C.c_size_t, vp]
     L.mofq_select_calibrated.restype = C.c_int
@@ -352,6 +361,46 @@ def select_layers(batch: LayerBatch, candidates: Sequence[int], cfg: Cfg, result
         rc = _lib.mofq_select_layers_timed(*args, e0, e1)
     if rc != 0:
         raise MofqError(rc, "mofq_select_layers")
+
+
+class WaLayerBatch:
+    """Host-side descriptor arrays of the linear layers of a model for mofq_select_layers_wa:
+    weights, their activations (the same tensor object may be given to consecutive layers) and
+    the output buffers (`x_outs` may be None: no activation outputs)."""
+
+    def __init__(self, weights: Sequence[torch.Tensor], acts: Sequence[torch.Tensor],
+                 w_outs: Sequence[QBuffers], x_outs: Optional[Sequence[QBuffers]]):
+        assert len(weights) == len(acts) == len(w_outs) and len(weights) > 0
+        assert x_outs is None or len(x_outs) == len(weights)
+        self.n = len(weights)
+        self._keep = (list(weights), list(acts), list(w_outs), list(x_outs) if x_outs is not None else None)
+        self.w = (TensorDesc * self.n)(*[tensor_desc(t) for t in weights])
+        self.x = (TensorDesc * self.n)(*[tensor_desc(t) for t in acts])
+        self.w_out = (QOut * self.n)(*[o.c() for o in w_outs])
+        self.x_out = (QOut * self.n)(*[o.c() for o in x_outs]) if x_outs is not None else None
+
+    def workspace_bytes(self, n_candidates: int, metric: int, cfg: Cfg) -> int:
+        return int(_lib.mofq_select_layers_wa_workspace_bytes(self.n, self.w, self.x, n_candidates, metric,
+                                                              C.byref(cfg.c)))
+
+
+def select_layers_wa(batch: WaLayerBatch, candidates: Sequence[int], metric: int, cfg: Cfg,
+                     results: torch.Tensor, ws: torch.Tensor, stream=None, side_stream=None,
+                     ev_begin=None, ev_end=None) -> None:
+    """mofq_select_layers_wa (or _timed with lists of torch.cuda.Event recorded around each
+    layer's matrix kernel): the weight-activation select of every layer of the batch; enqueue."""
+    cand = (C.c_int32 * len(candidates))(*candidates)
+    side = C.c_void_p(side_stream.cuda_stream) if side_stream is not None else C.c_void_p(0)
+    args = (batch.n, batch.w, batch.x, cand, len(candidates), metric, C.byref(cfg.c), batch.w_out, batch.x_out,
+            _ptr(results), _ptr(ws), ws.numel() * ws.element_size(), _stream_handle(stream), side)
+    if ev_begin is None:
+        rc = _lib.mofq_select_layers_wa(*args)
+    else:
+        e0 = (C.c_void_p * batch.n)(*[_event_handle(e).value for e in ev_begin])
+        e1 = (C.c_void_p * batch.n)(*[_event_handle(e).value for e in ev_end])
+        rc = _lib.mofq_select_layers_wa_timed(*args, e0, e1)
+    if rc != 0:
+        raise MofqError(rc, "mofq_select_layers_wa")
 
 
 CEILING_COPY, CEILING_FMA_F32, CEILING_FMA_F64, CEILING_MFMA_BF16, CEILING_MFMA_INT8, CEILING_MFMA_FP8, CEILING_READ = range(7)

@@ -428,6 +428,269 @@ int wa_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand
   return MOFQ_OK;
 }
 
+// Algorithm 1's loop body for one layer with the layer-output metric, any candidate list and
+// per-tensor or per-channel weight scales: the general path (one launch per step).
+int select_wa_general(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* candidates,
+                      int n_candidates, int metric, const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
+                      const mofq_qout_t* x_out, mofq_result_t* result, void* ws, size_t ws_bytes,
+                      hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  int rc;
+  const WaWs a = carve_wa(ws, w, x, n_candidates, w_cfg->gran);
+  if (!ws || ws_bytes < a.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+  if ((rc = wa_score(w, x, candidates, n_candidates, w_cfg,
+                     metric == MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT, a, st, ev0, ev1)))
+    return rc;
+  DecideParams d{};
+  d.units = a.blocks;
+  d.n_cand = n_candidates;
+  for (int c = 0; c < n_candidates; ++c) d.err[c] = candidates[c] == MOFQ_INT8 ? a.part[0] : a.part[1];
+  d.energy = a.part[2];
+  d.result = result;
+  if ((rc = launch_decide(d, st))) return rc;
+  // second quantize_layer call of Algorithm 1: W and X in the chosen format
+  for (int which = 0; which < 2; ++which) {
+    const mofq_tensor_t* t = which ? w : x;
+    const mofq_qout_t* o = which ? w_out : x_out;
+    if (!o) continue;
+    const WOnlyWs& rec = which ? a.wrec : a.xrec;
+    EmitParams e{};
+    e.w = t->data;
+    e.dtype = t->dtype;
+    e.rows = t->rows;
+    e.cols = t->cols;
+    e.ld = t->ld;
+    e.gran = which ? w_cfg->gran : MOFQ_PER_TENSOR;
+    e.group = 0;
+    e.n_cand = n_candidates;
+    for (int c = 0; c < n_candidates; ++c) {
+      e.fmt[c] = candidates[c];
+      e.scale[c] = rec.scale[c];
+      e.clip[c] = rec.clip[c];
+      e.err[c] = rec.err[c];
+    }
+    e.result = result;
+    e.out = *o;
+    if ((rc = launch_emit(e, st))) return rc;
+  }
+  return MOFQ_OK;
+}
+
+// ---- the fused weight-activation path ----------------------------------------------------
+// INT8 against FP8-E4M3 with per-tensor weight scales (the configuration of Section 5's
+// W8A8 experiments).  Per layer: the two quantize passes over X and W together
+// (launch_wa_prep), the matrix kernel, one small kernel for select + one-unit outputs, and a
+// copy of the chosen codes.  The weight's E4M3 codes are written straight into the caller's
+// code buffer by the quantize pass (they are an operand of the fp8-unit product, and the
+// output itself if E4M3 is chosen); if INT8 is chosen its codes are copied over them.  An
+// activation that the previous layer of the call already used (same descriptor: the q/k/v
+// or gate/up projections of a block) is quantized once.
+bool wa_fused(const int32_t* cand, int n_cand, const mofq_scale_cfg_t* w_cfg) {
+  return n_cand == 2 && w_cfg->gran == MOFQ_PER_TENSOR && cand[0] != cand[1] &&
+         (cand[0] == MOFQ_INT8 || cand[0] == MOFQ_FP8_E4M3) && (cand[1] == MOFQ_INT8 || cand[1] == MOFQ_FP8_E4M3);
+}
+
+struct WaFusedTensorWs {
+  uint8_t* i8;
+  uint8_t* f8;
+  uint8_t* g;
+  float* absmax_part;
+  double* sse_part;
+  float* scale;
+};
+struct WaFusedWs {
+  WaFusedTensorWs x[2], w[2];   // two slots each: layer i + 1 is prepared while layer i is multiplied
+  double* part[2][3];           // per slot: INT8 error, E4M3 error, reference energy per output tile
+  int slots;
+  size_t bytes;
+};
+
+WaFusedWs carve_wa_fused(void* ws, int n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x, bool exact) {
+  WaFusedWs a{};
+  int64_t max_x = 0, max_w = 0;
+  int max_blocks = 0;
+  for (int i = 0; i < n_layers; ++i) {
+    max_x = std::max<int64_t>(max_x, x[i].rows * x[i].cols);
+    max_w = std::max<int64_t>(max_w, w[i].rows * w[i].cols);
+    max_blocks = std::max(max_blocks, wa_gemm_blocks(x[i].rows, w[i].rows));
+  }
+  a.slots = n_layers > 1 ? 2 : 1;
+  Carver c(ws);
+  for (int s = 0; s < a.slots; ++s) {
+    for (int which = 0; which < 2; ++which) {
+      WaFusedTensorWs& t = which ? a.w[s] : a.x[s];
+      const size_t n = static_cast<size_t>(which ? max_w : max_x);
+      t.i8 = c.take<uint8_t>(n);
+      t.f8 = which ? nullptr : c.take<uint8_t>(n);   // the weight's live in the caller's code buffer
+      t.g = exact ? c.take<uint8_t>(2 * n) : nullptr;
+      t.absmax_part = c.take<float>(kTensorBlocks);
+      t.sse_part = c.take<double>(2 * kTensorBlocks);
+      t.scale = c.take<float>(2);
+    }
+    for (int q = 0; q < 3; ++q) a.part[s][q] = c.take<double>(max_blocks);
+  }
+  a.bytes = (c.off + kAlign - 1) / kAlign * kAlign;
+  return a;
+}
+
+// A few events that order two streams against each other, recorded in rotation.
+struct EventRing {
+  static constexpr int N = 4;
+  hipEvent_t ev[N] = {};
+  EventRing() = default;
+  EventRing(const EventRing&) = delete;
+  EventRing& operator=(const EventRing&) = delete;
+  ~EventRing() {
+    for (hipEvent_t e : ev)
+      if (e) (void)hipEventDestroy(e);
+  }
+  int init() {
+    for (hipEvent_t& e : ev)
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return MOFQ_ERR_HIP;
+    return MOFQ_OK;
+  }
+  // mark(i, s): everything enqueued on s so far; await(i, s): s waits for the i-th mark.  At
+  // most N - 1 marks may lie between a mark and its await.
+  int mark(int i, hipStream_t s) { return hip_status(hipEventRecord(ev[i % N], s)); }
+  int await(int i, hipStream_t s) { return hip_status(hipStreamWaitEvent(s, ev[i % N], 0)); }
+};
+
+// Arguments are validated by the caller except for the workspace.  x_out may be null (no
+// activation outputs), ev_begin / ev_end may be null.
+int select_layers_wa(int n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand,
+                     int n_cand, int metric, const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
+                     const mofq_qout_t* x_out, mofq_result_t* results, void* ws, size_t ws_bytes,
+                     hipStream_t st, void* side_stream, void* const* ev_begin, void* const* ev_end) {
+  int rc;
+  auto ev = [](void* const* list, int i) { return list ? static_cast<hipEvent_t>(list[i]) : nullptr; };
+  if (!wa_fused(cand, n_cand, w_cfg)) {
+    for (int i = 0; i < n_layers; ++i)
+      if ((rc = select_wa_general(&w[i], &x[i], cand, n_cand, metric, w_cfg, &w_out[i], x_out ? &x_out[i] : nullptr,
+                                  &results[i], ws, ws_bytes, st, ev(ev_begin, i), ev(ev_end, i))))
+        return rc;
+    return MOFQ_OK;
+  }
+  const bool fp8_unit = metric == MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT;
+  const WaFusedWs a = carve_wa_fused(ws, n_layers, w, x, !fp8_unit);
+  if (!ws || ws_bytes < a.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+  int fmt_slot[MOFQ_MAX_CANDIDATES] = {0, 0, 0, 0};
+  for (int c = 0; c < n_cand; ++c) fmt_slot[c] = cand[c] == MOFQ_FP8_E4M3;
+
+  // slot of layer i's weight: i % slots.  Slot of its activation: the previous layer's if the
+  // descriptor is the same (then nothing is quantized again), else the other one.
+  auto same_x = [&](int i) {
+    return i > 0 && x[i].data == x[i - 1].data && x[i].rows == x[i - 1].rows && x[i].cols == x[i - 1].cols &&
+           x[i].ld == x[i - 1].ld;
+  };
+  auto prep = [&](int i, int xs, hipStream_t s) {
+    const int ws_ = i % a.slots;
+    WaPrepTensor px{}, pw{};
+    if (!same_x(i)) {
+      px.data = x[i].data; px.rows = x[i].rows; px.cols = x[i].cols; px.ld = x[i].ld;
+      px.ratio = 1.0f;   // activations: per tensor at the full range (Section 3.2)
+      px.absmax_part = a.x[xs].absmax_part; px.sse_part = a.x[xs].sse_part;
+      px.q_i8 = a.x[xs].i8; px.q_f8 = a.x[xs].f8; px.q_g = a.x[xs].g; px.scale = a.x[xs].scale;
+    }
+    pw.data = w[i].data; pw.rows = w[i].rows; pw.cols = w[i].cols; pw.ld = w[i].ld;
+    pw.ratio = w_cfg->clip_ratios[0];
+    pw.absmax_part = a.w[ws_].absmax_part; pw.sse_part = a.w[ws_].sse_part;
+    pw.q_i8 = a.w[ws_].i8; pw.q_f8 = static_cast<uint8_t*>(w_out[i].codes); pw.q_g = a.w[ws_].g;
+    pw.scale = a.w[ws_].scale;
+    return launch_wa_prep(px, pw, s);
+  };
+  auto product = [&](int i, int xs) {
+    const int ws_ = i % a.slots;
+    WaGemmParams g{};
+    g.q[0].kind = WA_INT8;
+    g.q[0].x = a.x[xs].i8; g.q[0].w = a.w[ws_].i8;
+    g.q[0].sx = a.x[xs].scale; g.q[0].sw = a.w[ws_].scale;
+    g.q[0].part = a.part[ws_][0];
+    g.q[1].kind = fp8_unit ? WA_FP8 : WA_GRID_BF16;
+    g.q[1].x = fp8_unit ? a.x[xs].f8 : a.x[xs].g;
+    g.q[1].w = fp8_unit ? static_cast<const uint8_t*>(w_out[i].codes) : a.w[ws_].g;
+    g.q[1].sx = a.x[xs].scale + 1; g.q[1].sw = a.w[ws_].scale + 1;
+    g.q[1].part = a.part[ws_][1];
+    g.x = x[i].data; g.ldx = x[i].ld;
+    g.w = w[i].data; g.ldw = w[i].ld;
+    g.w_per_channel = 0;
+    g.M = x[i].rows; g.N = w[i].rows; g.K = w[i].cols;
+    g.part_p = a.part[ws_][2];
+    int r;
+    if (ev(ev_begin, i) && hipEventRecord(ev(ev_begin, i), st) != hipSuccess) return static_cast<int>(MOFQ_ERR_HIP);
+    if ((r = launch_wa_gemm(g, st))) return r;
+    if (ev(ev_end, i) && hipEventRecord(ev(ev_end, i), st) != hipSuccess) return static_cast<int>(MOFQ_ERR_HIP);
+    WaFinishParams f{};
+    f.d.units = wa_gemm_blocks(x[i].rows, w[i].rows);
+    f.d.n_cand = n_cand;
+    for (int c = 0; c < n_cand; ++c) { f.d.err[c] = a.part[ws_][fmt_slot[c]]; f.fmt_slot[c] = fmt_slot[c]; }
+    f.d.energy = a.part[ws_][2];
+    f.d.result = &results[i];
+    if (x_out) {
+      f.t[0].n_blocks = wa_prep_blocks(x[i].rows, x[i].cols);
+      f.t[0].sse_part = a.x[xs].sse_part; f.t[0].scale = a.x[xs].scale;
+      f.t[0].out_scales = x_out[i].scales; f.t[0].out_clip = x_out[i].clip_idx; f.t[0].out_unit_err = x_out[i].unit_err;
+    }
+    f.t[1].n_blocks = wa_prep_blocks(w[i].rows, w[i].cols);
+    f.t[1].sse_part = a.w[ws_].sse_part; f.t[1].scale = a.w[ws_].scale;
+    f.t[1].out_scales = w_out[i].scales; f.t[1].out_clip = w_out[i].clip_idx; f.t[1].out_unit_err = w_out[i].unit_err;
+    return launch_wa_finish(f, st);
+  };
+  auto codes = [&](int i, int xs, hipStream_t s) {
+    const int ws_ = i % a.slots;
+    WaCopyParams p{};
+    p.result = &results[i];
+    p.n_cand = n_cand;
+    for (int c = 0; c < n_cand; ++c) p.fmt_slot[c] = fmt_slot[c];
+    if (x_out) {
+      p.t[0].src[0] = a.x[xs].i8; p.t[0].src[1] = a.x[xs].f8;
+      p.t[0].dst = static_cast<uint8_t*>(x_out[i].codes);
+      p.t[0].bytes = x[i].rows * x[i].cols;
+    }
+    p.t[1].src[0] = a.w[ws_].i8; p.t[1].src[1] = static_cast<const uint8_t*>(w_out[i].codes);
+    p.t[1].dst = static_cast<uint8_t*>(w_out[i].codes);
+    p.t[1].bytes = w[i].rows * w[i].cols;
+    return launch_wa_copy(p, s);
+  };
+
+  SideWork sw(st, a.slots == 2 ? side_stream : nullptr);
+  if ((rc = sw.init())) return rc;
+  if (!sw.two) {
+    // one stream: layer by layer
+    int xs = 1;
+    for (int i = 0; i < n_layers; ++i) {
+      if (!same_x(i)) xs = (xs + 1) % a.slots;
+      if ((rc = prep(i, xs, st))) return rc;
+      if ((rc = product(i, xs))) return rc;
+      if ((rc = codes(i, xs, st))) return rc;
+    }
+    return MOFQ_OK;
+  }
+  // Two streams: the quantize passes of layer i + 1 and the code copy of layer i - 1 run on the
+  // side stream beside layer i's matrix kernel, which stays on the caller's stream.  On the
+  // side stream layer i + 1's passes come after layer i - 1's copy, which waits for layer
+  // i - 1's select: by then the slot they write (its weight slot, and an activation slot that
+  // layer i does not use) is no longer read.
+  EventRing ready, decided;
+  if ((rc = ready.init()) || (rc = decided.init())) return rc;
+  hipStream_t st2 = sw.side;
+  auto join = [&](int status) { return sw.join(status); };
+  if ((rc = sw.fork())) return join(rc);
+  int xs_cur = 0;
+  if ((rc = prep(0, xs_cur, st2)) || (rc = ready.mark(0, st2))) return join(rc);
+  for (int i = 0; i < n_layers; ++i) {
+    if ((rc = ready.await(i, st))) return join(rc);               // layer i's operands are written
+    int xs_next = xs_cur;
+    if (i + 1 < n_layers) {
+      if (!same_x(i + 1)) xs_next = 1 - xs_cur;
+      if ((rc = prep(i + 1, xs_next, st2)) || (rc = ready.mark(i + 1, st2))) return join(rc);
+    }
+    if ((rc = product(i, xs_cur))) return join(rc);
+    if ((rc = decided.mark(i, st)) || (rc = decided.await(i, st2))) return join(rc);   // layer i's choice is known
+    if ((rc = codes(i, xs_cur, st2))) return join(rc);
+    xs_cur = xs_next;
+  }
+  return join(MOFQ_OK);
+}
+
 // Algorithm 1's loop body for one weight tensor with the tensor-error metric: search every
 // candidate, reduce + select on the device, emit the winner.  Arguments are already validated
 // except for the workspace.
@@ -539,8 +802,13 @@ size_t mofq_workspace_bytes(const mofq_tensor_t* w, const mofq_tensor_t* x, int3
     return carve_w_only(nullptr, units, n_candidates, w_cfg->gran, w_cfg->n_clip).bytes;
   if ((metric == MOFQ_ERR_LAYER_OUTPUT || metric == MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT) && x &&
       x->rows > 0 && x->cols == w->cols &&
-      (w_cfg->gran == MOFQ_PER_TENSOR || w_cfg->gran == MOFQ_PER_CHANNEL))
-    return carve_wa(nullptr, w, x, n_candidates, w_cfg->gran).bytes;
+      (w_cfg->gran == MOFQ_PER_TENSOR || w_cfg->gran == MOFQ_PER_CHANNEL)) {
+    // the larger of the general path's need and, where it can apply, the fused path's
+    size_t b = carve_wa(nullptr, w, x, n_candidates, w_cfg->gran).bytes;
+    if (n_candidates == 2 && w_cfg->gran == MOFQ_PER_TENSOR)
+      b = std::max(b, carve_wa_fused(nullptr, 1, w, x, metric == MOFQ_ERR_LAYER_OUTPUT).bytes);
+    return b;
+  }
   if (metric == MOFQ_ERR_LAYER_OUTPUT_W_ONLY && x && x->rows > 0 && x->cols == w->cols && n_candidates <= 2 &&
       (w_cfg->gran == MOFQ_PER_TENSOR || w_cfg->gran == MOFQ_PER_CHANNEL))
     return carve_wo_output(nullptr, w, x, n_candidates, w_cfg).bytes;
@@ -1026,6 +1294,55 @@ int mofq_select_layer(const mofq_tensor_t* w, const mofq_tensor_t* x, const int3
                                  result, ws, ws_bytes, stream, nullptr, nullptr);
 }
 
+size_t mofq_select_layers_wa_workspace_bytes(int32_t n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x,
+                                             int32_t n_candidates, int32_t metric,
+                                             const mofq_scale_cfg_t* w_cfg) {
+  if (n_layers < 1 || !w || !x || !w_cfg) return 0;
+  if (metric != MOFQ_ERR_LAYER_OUTPUT && metric != MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT) return 0;
+  size_t need = 0;
+  for (int i = 0; i < n_layers; ++i) {
+    const size_t b = mofq_workspace_bytes(&w[i], &x[i], n_candidates, metric, w_cfg);
+    if (!b) return 0;
+    need = std::max(need, b);
+  }
+  if (n_candidates == 2 && w_cfg->gran == MOFQ_PER_TENSOR)
+    need = std::max(need, carve_wa_fused(nullptr, n_layers, w, x, metric == MOFQ_ERR_LAYER_OUTPUT).bytes);
+  return need;
+}
+
+int mofq_select_layers_wa_timed(int32_t n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x,
+                                const int32_t* candidates, int32_t n_candidates, int32_t metric,
+                                const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
+                                const mofq_qout_t* x_out, mofq_result_t* results, void* ws,
+                                size_t ws_bytes, void* stream, void* side_stream,
+                                void* const* ev_begin, void* const* ev_end) {
+  if (n_layers < 1 || !w || !x || !w_out || !results) return MOFQ_ERR_INVALID_ARG;
+  if (metric != MOFQ_ERR_LAYER_OUTPUT && metric != MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT) return MOFQ_ERR_INVALID_ARG;
+  int rc = check_candidates(candidates, n_candidates);
+  if (rc) return rc;
+  // everything is validated before anything is enqueued
+  for (int i = 0; i < n_layers; ++i) {
+    if ((rc = check_tensor(&w[i]))) return rc;
+    if ((rc = check_cfg(&w[i], w_cfg))) return rc;
+    if ((rc = check_out(&w_out[i], true))) return rc;
+    if ((rc = check_wa(&w[i], &x[i], candidates, n_candidates, w_cfg))) return rc;
+    if (x_out && (rc = check_out(&x_out[i], true))) return rc;
+  }
+  const size_t need = mofq_select_layers_wa_workspace_bytes(n_layers, w, x, n_candidates, metric, w_cfg);
+  if (!ws || !need || ws_bytes < need || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+  return select_layers_wa(n_layers, w, x, candidates, n_candidates, metric, w_cfg, w_out, x_out, results, ws,
+                          ws_bytes, static_cast<hipStream_t>(stream), side_stream, ev_begin, ev_end);
+}
+
+int mofq_select_layers_wa(int32_t n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x,
+                          const int32_t* candidates, int32_t n_candidates, int32_t metric,
+                          const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out, const mofq_qout_t* x_out,
+                          mofq_result_t* results, void* ws, size_t ws_bytes, void* stream,
+                          void* side_stream) {
+  return mofq_select_layers_wa_timed(n_layers, w, x, candidates, n_candidates, metric, w_cfg, w_out, x_out,
+                                     results, ws, ws_bytes, stream, side_stream, nullptr, nullptr);
+}
+
 int mofq_select_layer_static(const mofq_tensor_t* w, const int32_t* candidates, int32_t n_candidates,
                              const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
                              mofq_result_t* result, void* stream) {
@@ -1100,44 +1417,9 @@ int mofq_select_layer_timed(const mofq_tensor_t* w, const mofq_tensor_t* x,
     return MOFQ_ERR_INVALID_ARG;
   if ((rc = check_wa(w, x, candidates, n_candidates, w_cfg))) return rc;
   if (x_out && (rc = check_out(x_out, true))) return rc;
-  const WaWs a = carve_wa(ws, w, x, n_candidates, w_cfg->gran);
-  if (!ws || ws_bytes < a.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
-  if ((rc = wa_score(w, x, candidates, n_candidates, w_cfg,
-                     metric == MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT, a, st, ev0, ev1)))
-    return rc;
-  DecideParams d{};
-  d.units = a.blocks;
-  d.n_cand = n_candidates;
-  for (int c = 0; c < n_candidates; ++c) d.err[c] = candidates[c] == MOFQ_INT8 ? a.part[0] : a.part[1];
-  d.energy = a.part[2];
-  d.result = result;
-  if ((rc = launch_decide(d, st))) return rc;
-  // second quantize_layer call of Algorithm 1: W and X in the chosen format
-  for (int which = 0; which < 2; ++which) {
-    const mofq_tensor_t* t = which ? w : x;
-    const mofq_qout_t* o = which ? w_out : x_out;
-    if (!o) continue;
-    const WOnlyWs& rec = which ? a.wrec : a.xrec;
-    EmitParams e{};
-    e.w = t->data;
-    e.dtype = t->dtype;
-    e.rows = t->rows;
-    e.cols = t->cols;
-    e.ld = t->ld;
-    e.gran = which ? w_cfg->gran : MOFQ_PER_TENSOR;
-    e.group = 0;
-    e.n_cand = n_candidates;
-    for (int c = 0; c < n_candidates; ++c) {
-      e.fmt[c] = candidates[c];
-      e.scale[c] = rec.scale[c];
-      e.clip[c] = rec.clip[c];
-      e.err[c] = rec.err[c];
-    }
-    e.result = result;
-    e.out = *o;
-    if ((rc = launch_emit(e, st))) return rc;
-  }
-  return MOFQ_OK;
+  return select_layers_wa(1, w, x, candidates, n_candidates, metric, w_cfg, w_out, x_out, result, ws, ws_bytes,
+                          st, nullptr, ev_score_begin ? &ev_score_begin : nullptr,
+                          ev_score_end ? &ev_score_end : nullptr);
 }
 
 }  // extern "C"

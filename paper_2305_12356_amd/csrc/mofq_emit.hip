@@ -15,10 +15,10 @@ constexpr int kDecideThreads = 1024;
 
 // Sum of v[0..n) over the block in a fixed order (thread-strided partials, then
 // wave sums, then the waves in order); the result is valid on thread 0.
-MOFQ_DEV double block_sum(const double* v, int64_t n, double* s_red) {
+MOFQ_DEV double block_sum(const double* v, int64_t n, double* s_red, int64_t step = 1) {
   const int tid = threadIdx.x;
   double t = 0.0;
-  for (int64_t i = tid; i < n; i += kDecideThreads) t += v[i];
+  for (int64_t i = tid; i < n; i += kDecideThreads) t += v[i * step];
   t = wave_sum(t);
   __syncthreads();
   if ((tid & 63) == 0) s_red[tid >> 6] = t;
@@ -111,6 +111,57 @@ MOFQ_DEV int decide_body(const DecideParams& p, double* s_red) {
     if (p.energy_out) *p.energy_out = energy;
   }
   return best;
+}
+
+// The weight-activation path after its matrix kernel: select from the per-tile partials, then
+// the one-unit outputs of the chosen format for X and W.
+__global__ __launch_bounds__(kDecideThreads) void wa_finish_kernel(const WaFinishParams a) {
+  __shared__ double s_red[kDecideThreads / 64];
+  __shared__ int s_best;
+  const int b = decide_body(a.d, s_red);
+  if (threadIdx.x == 0) s_best = (b < 0 || b >= a.d.n_cand) ? 0 : b;   // no candidate beat infinity: keep the first
+  __syncthreads();
+  const int f = a.fmt_slot[s_best];
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    const WaFinishTensor& t = a.t[which];
+    if (t.n_blocks < 1) continue;   // uniform
+    double e = 0.0;
+    if (t.out_unit_err) e = block_sum(t.sse_part + f, t.n_blocks, s_red, 2);
+    if (threadIdx.x == 0) {
+      if (t.out_unit_err) *t.out_unit_err = e;
+      if (t.out_scales) *static_cast<float*>(t.out_scales) = t.scale[f];
+      if (t.out_clip) *t.out_clip = 0;
+    }
+  }
+}
+
+// Copy of the chosen format's codes (16-byte pieces, grid-stride, four in flight per lane).
+// Workgroups are dealt to the two tensors in proportion to their sizes.
+struct WaCopyArgs {
+  WaCopyParams p;
+  int32_t n_blocks[2];
+};
+__global__ __launch_bounds__(256) void wa_copy_kernel(const WaCopyArgs a) {
+  int best = a.p.result->best;
+  if (best < 0 || best >= a.p.n_cand) best = 0;
+  const int f = a.p.fmt_slot[__builtin_amdgcn_readfirstlane(best)];
+  const bool second = static_cast<int>(blockIdx.x) >= a.n_blocks[0];
+  const WaCopyTensor t = second ? a.p.t[1] : a.p.t[0];
+  const int nb = second ? a.n_blocks[1] : a.n_blocks[0];
+  const int b = static_cast<int>(blockIdx.x) - (second ? a.n_blocks[0] : 0);
+  const uint8_t* src = f ? t.src[1] : t.src[0];
+  if (!t.dst || src == t.dst) return;   // uniform
+  const u32x4* s4 = reinterpret_cast<const u32x4*>(src);
+  u32x4* d4 = reinterpret_cast<u32x4*>(t.dst);
+  const int64_t n = t.bytes / 16;
+  const int64_t stride = static_cast<int64_t>(nb) * 256;
+  int64_t i = static_cast<int64_t>(b) * 256 + threadIdx.x;
+  for (; i + 3 * stride < n; i += 4 * stride) {
+    const u32x4 v0 = s4[i], v1 = s4[i + stride], v2 = s4[i + 2 * stride], v3 = s4[i + 3 * stride];
+    d4[i] = v0; d4[i + stride] = v1; d4[i + 2 * stride] = v2; d4[i + 3 * stride] = v3;
+  }
+  for (; i < n; i += stride) d4[i] = s4[i];
 }
 
 // ---- emit -------------------------------------------------------------------------
@@ -307,6 +358,33 @@ int launch_finish_batch(const FinishParams* p, int n, hipStream_t st) {
     a.p[i] = p[i];
   }
   hipLaunchKernelGGL(finish_batch_kernel, dim3(static_cast<unsigned>(n)), dim3(kDecideThreads), 0, st, a);
+  return hip_status(hipGetLastError());
+}
+
+int launch_wa_finish(const WaFinishParams& p, hipStream_t st) {
+  if (p.d.units < 1 || p.d.n_cand < 1 || p.d.n_cand > MOFQ_MAX_CANDIDATES || !p.d.result) return MOFQ_ERR_INVALID_ARG;
+  for (int c = 0; c < p.d.n_cand; ++c)
+    if (!p.d.err[c] || p.fmt_slot[c] < 0 || p.fmt_slot[c] > 1) return MOFQ_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(wa_finish_kernel, dim3(1), dim3(kDecideThreads), 0, st, p);
+  return hip_status(hipGetLastError());
+}
+
+int launch_wa_copy(const WaCopyParams& p, hipStream_t st) {
+  if (!p.result || p.n_cand < 1 || p.n_cand > MOFQ_MAX_CANDIDATES) return MOFQ_ERR_INVALID_ARG;
+  WaCopyArgs a{};
+  a.p = p;
+  const int64_t cap = p.max_blocks > 0 ? p.max_blocks : 256 * 8;
+  int64_t want[2] = {0, 0};
+  for (int i = 0; i < 2; ++i) {
+    if (!p.t[i].dst) continue;
+    if (p.t[i].bytes < 16 || p.t[i].bytes % 16 != 0 || !p.t[i].src[0] || !p.t[i].src[1]) return MOFQ_ERR_INVALID_ARG;
+    want[i] = (p.t[i].bytes / 16 + 256 * 4 - 1) / (256 * 4);
+  }
+  const int64_t total = want[0] + want[1];
+  if (total < 1) return MOFQ_OK;
+  for (int i = 0; i < 2; ++i)
+    if (want[i]) a.n_blocks[i] = static_cast<int32_t>(total <= cap ? want[i] : std::max<int64_t>(1, want[i] * cap / total));
+  hipLaunchKernelGGL(wa_copy_kernel, dim3(static_cast<unsigned>(a.n_blocks[0] + a.n_blocks[1])), dim3(256), 0, st, a);
   return hip_status(hipGetLastError());
 }
 

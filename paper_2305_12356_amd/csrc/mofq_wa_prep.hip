@@ -1,0 +1,205 @@
+// Per-tensor 8-bit quantization of the two inputs of a linear layer for the layer-output
+// metric of the weight-activation case (Section 3.2: A_out = W * A_in with both inputs
+// quantized; Section 5: INT8 against FP8-E4M3, activations per tensor).  The activation X
+// and the weight W of a layer go through every pass together, one launch per pass:
+//
+//   1. largest magnitude of each tensor (per-workgroup partial maxima);
+//   2. both formats at once: the INT8 codes, the E4M3 codes and, where the exact E4M3
+//      product is wanted, the E4M3 grid values as bf16, all from one read of the tensor,
+//      with the tensor error of each format as per-workgroup partial sums in fp64.
+//
+// The small dependent steps (folding the partial maxima, the two scales) are redone by every
+// workgroup of pass 2 from the partials, so no one-workgroup kernel sits between the passes.
+// Nothing is accumulated atomically: every sum has a fixed order.
+#include "mofq_device.h"
+#include "mofq_internal.h"
+
+namespace mofq {
+
+namespace {
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+
+struct PrepTensor {
+  const uint16_t* data;
+  int64_t n_chunks, cpr, ld;   // 8-element chunks in the tensor and per row; elements between rows
+  int32_t n_blocks;            // workgroups that walk this tensor; 0: the tensor is skipped
+  float ratio;                 // clip ratio of the scale
+  float* absmax_part;
+  double* sse_part;
+  uint8_t* q_i8;
+  uint8_t* q_f8;
+  uint8_t* q_g;
+  float* scale;
+};
+struct PrepArgs {
+  PrepTensor t[2];
+};
+
+// Workgroups [0, t[0].n_blocks) walk t[0], the rest t[1]; returns the workgroup's index
+// within its tensor.
+MOFQ_DEV int my_tensor(const PrepArgs& a, PrepTensor& t) {
+  const int nb0 = a.t[0].n_blocks;
+  const bool second = static_cast<int>(blockIdx.x) >= nb0;
+  t = second ? a.t[1] : a.t[0];
+  return static_cast<int>(blockIdx.x) - (second ? nb0 : 0);
+}
+
+// Address of chunk c: rows are dense in the outputs, `ld` apart in the input.
+MOFQ_DEV const uint16_t* chunk_src(const PrepTensor& t, int64_t c) {
+  if (t.ld == t.cpr * 8) return t.data + c * 8;   // uniform: dense input, no division
+  const int64_t row = c / t.cpr;
+  return t.data + row * t.ld + (c - row * t.cpr) * 8;
+}
+
+__global__ __launch_bounds__(kThreads) void wa_absmax_pair_kernel(const PrepArgs a) {
+  using L = Load8<BF16>;
+  __shared__ float s_wmax[kThreads / 64];
+  PrepTensor t;
+  const int b = my_tensor(a, t);
+  const int tid = threadIdx.x;
+  const int64_t stride = static_cast<int64_t>(t.n_blocks) * kThreads;
+  float amax = 0.0f;
+  int64_t c = static_cast<int64_t>(b) * kThreads + tid;
+  for (; c + 3 * stride < t.n_chunks; c += 4 * stride) {   // four 16-byte loads in flight per lane
+    float v[4][8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) L::load(chunk_src(t, c + u * stride), v[u]);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) amax = __builtin_fmaxf(amax, __builtin_fabsf(v[u][i]));
+  }
+  for (; c < t.n_chunks; c += stride) {
+    float v[8];
+    L::load(chunk_src(t, c), v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) amax = __builtin_fmaxf(amax, __builtin_fabsf(v[i]));
+  }
+  amax = wave_max(amax);
+  if ((tid & 63) == 0) s_wmax[tid >> 6] = amax;
+  __syncthreads();
+  if (tid == 0)
+    t.absmax_part[b] = __builtin_fmaxf(__builtin_fmaxf(s_wmax[0], s_wmax[1]), __builtin_fmaxf(s_wmax[2], s_wmax[3]));
+}
+
+// One chunk in both formats: codes, optional grid values, squared differences.
+MOFQ_DEV void quant_chunk(const PrepTensor& t, int64_t c, const float (&v)[8], float iA, float iB, double sAd,
+                          double sBd, double& accA, double& accB) {
+  uint32_t wi[2] = {0u, 0u};
+  int wf[2] = {0, 0};
+  u32x4 gb;
+#pragma unroll
+  for (int i = 0; i < 8; i += 2) {
+    const float q0 = Codec<MOFQ_INT8>::grid(v[i] * iA), q1 = Codec<MOFQ_INT8>::grid(v[i + 1] * iA);
+    wi[i >> 2] |= (static_cast<uint32_t>(static_cast<int>(q0)) & 0xFFu) << (8 * (i & 3));
+    wi[i >> 2] |= (static_cast<uint32_t>(static_cast<int>(q1)) & 0xFFu) << (8 * ((i & 3) + 1));
+    const double d0 = __builtin_fma(-static_cast<double>(q0), sAd, static_cast<double>(v[i]));
+    const double d1 = __builtin_fma(-static_cast<double>(q1), sAd, static_cast<double>(v[i + 1]));
+    accA = __builtin_fma(d0, d0, accA);
+    accA = __builtin_fma(d1, d1, accA);
+    // E4M3 through the pack-convert (round to nearest even, subnormals kept; saturating once
+    // the input is clamped), which agrees with the codec on every finite fp32 pattern
+    const int p = __builtin_amdgcn_cvt_pk_fp8_f32(med3(v[i] * iB, -448.0f, 448.0f),
+                                                  med3(v[i + 1] * iB, -448.0f, 448.0f), 0, false);
+    const f32x2 g = __builtin_amdgcn_cvt_pk_f32_fp8(p, false);
+    wf[i >> 2] |= (p & 0xFFFF) << (16 * ((i >> 1) & 1));
+    gb[i >> 1] = (f2u(g[0]) >> 16) | (f2u(g[1]) & 0xFFFF0000u);   // at most 4 significant bits: exact in bf16
+    const double e0 = __builtin_fma(-static_cast<double>(g[0]), sBd, static_cast<double>(v[i]));
+    const double e1 = __builtin_fma(-static_cast<double>(g[1]), sBd, static_cast<double>(v[i + 1]));
+    accB = __builtin_fma(e0, e0, accB);
+    accB = __builtin_fma(e1, e1, accB);
+  }
+  u32x2 oi, of;
+  oi[0] = wi[0];
+  oi[1] = wi[1];
+  of[0] = static_cast<uint32_t>(wf[0]);
+  of[1] = static_cast<uint32_t>(wf[1]);
+  reinterpret_cast<u32x2*>(t.q_i8)[c] = oi;
+  reinterpret_cast<u32x2*>(t.q_f8)[c] = of;
+  if (t.q_g) reinterpret_cast<u32x4*>(t.q_g)[c] = gb;
+}
+
+__global__ __launch_bounds__(kThreads) void wa_quant_pair_kernel(const PrepArgs a) {
+  using L = Load8<BF16>;
+  __shared__ float s_tmp[kThreads / 64];
+  __shared__ double s_part[kThreads / 64][2];
+  PrepTensor t;
+  const int b = my_tensor(a, t);
+  const int tid = threadIdx.x;
+  // the tensor's largest magnitude from the partials of the first pass
+  float amax = 0.0f;
+  for (int i = tid; i < t.n_blocks; i += kThreads) amax = __builtin_fmaxf(amax, t.absmax_part[i]);
+  amax = wave_max(amax);
+  if ((tid & 63) == 0) s_tmp[tid >> 6] = amax;
+  __syncthreads();
+  amax = __builtin_fmaxf(__builtin_fmaxf(s_tmp[0], s_tmp[1]), __builtin_fmaxf(s_tmp[2], s_tmp[3]));
+  const float sA = unit_scale(amax, t.ratio, Codec<MOFQ_INT8>::QMAX, false);
+  const float sB = unit_scale(amax, t.ratio, Codec<MOFQ_FP8_E4M3>::QMAX, false);
+  if (b == 0 && tid == 0) { t.scale[0] = sA; t.scale[1] = sB; }
+  const float iA = 1.0f / sA, iB = 1.0f / sB;
+  const double sAd = static_cast<double>(sA), sBd = static_cast<double>(sB);
+  double accA = 0.0, accB = 0.0;
+  const int64_t stride = static_cast<int64_t>(t.n_blocks) * kThreads;
+  int64_t c = static_cast<int64_t>(b) * kThreads + tid;
+  for (; c + stride < t.n_chunks; c += 2 * stride) {
+    float v[2][8];
+    L::load(chunk_src(t, c), v[0]);
+    L::load(chunk_src(t, c + stride), v[1]);
+    quant_chunk(t, c, v[0], iA, iB, sAd, sBd, accA, accB);
+    quant_chunk(t, c + stride, v[1], iA, iB, sAd, sBd, accA, accB);
+  }
+  for (; c < t.n_chunks; c += stride) {
+    float v[8];
+    L::load(chunk_src(t, c), v);
+    quant_chunk(t, c, v, iA, iB, sAd, sBd, accA, accB);
+  }
+  accA = wave_sum(accA);
+  accB = wave_sum(accB);
+  if ((tid & 63) == 0) { s_part[tid >> 6][0] = accA; s_part[tid >> 6][1] = accB; }
+  __syncthreads();
+  if (tid < 2)
+    t.sse_part[static_cast<int64_t>(b) * 2 + tid] = (s_part[0][tid] + s_part[1][tid]) + (s_part[2][tid] + s_part[3][tid]);
+}
+
+bool fill(const WaPrepTensor& p, PrepTensor* t) {
+  *t = PrepTensor{};
+  if (!p.data) return true;   // skipped
+  if (p.rows < 1 || p.cols < 8 || p.cols % 8 != 0 || p.ld < p.cols || p.ld % 8 != 0) return false;
+  if (!p.absmax_part || !p.sse_part || !p.q_i8 || !p.q_f8 || !p.scale) return false;
+  t->data = static_cast<const uint16_t*>(p.data);
+  t->cpr = p.cols / 8;
+  t->n_chunks = p.rows * t->cpr;
+  t->ld = p.ld;
+  t->n_blocks = wa_prep_blocks(p.rows, p.cols);
+  t->ratio = p.ratio;
+  t->absmax_part = p.absmax_part;
+  t->sse_part = p.sse_part;
+  t->q_i8 = p.q_i8;
+  t->q_f8 = p.q_f8;
+  t->q_g = p.q_g;
+  t->scale = p.scale;
+  return true;
+}
+
+}  // namespace
+
+int wa_prep_blocks(int64_t rows, int64_t cols) {
+  const int64_t n_chunks = rows * (cols / 8);
+  const int64_t b = (n_chunks + kThreads - 1) / kThreads;
+  return static_cast<int>(b < 1 ? 1 : (b > kTensorBlocks ? kTensorBlocks : b));
+}
+
+int launch_wa_prep(const WaPrepTensor& x, const WaPrepTensor& w, hipStream_t st) {
+  PrepArgs a{};
+  if (!fill(x, &a.t[0]) || !fill(w, &a.t[1])) return MOFQ_ERR_INVALID_ARG;
+  const int blocks = a.t[0].n_blocks + a.t[1].n_blocks;
+  if (blocks < 1) return MOFQ_OK;
+  hipLaunchKernelGGL(wa_absmax_pair_kernel, dim3(blocks), dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL(wa_quant_pair_kernel, dim3(blocks), dim3(kThreads), 0, st, a);
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace mofq
