@@ -350,32 +350,54 @@ def run_w8a8(args, shapes, dev, weights, w_only, fp8_unit, steps, warmup, ceilin
         metric, cands, bits = mq.ERR_LAYER_OUTPUT_W_ONLY, [mq.INT4, mq.FP4_E2M1], 4
         cfg = mq.Cfg(mq.PER_CHANNEL, mi.clip_ratios(1))
     xcfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
-    xs = {}
-    xouts = {}
     results = mq.alloc_result(dev, len(shapes))
-    ws_bytes = 0
-    for i, (b, name, o, n) in enumerate(shapes):
-        if n not in xs:
-            xs[n] = mi.activations(TOKENS, n, seed=mi.tensor_seed(3, 0, 0, n), device=dev)
-            xouts[n] = None if w_only else mq.alloc_qbuffers(TOKENS, n, 8, xcfg, dev)
-        ws_bytes = max(ws_bytes, mq.workspace_bytes(weights[i], xs[n], len(cands), metric, cfg))
-    # one output buffer per distinct weight shape (the codes are not read back here)
-    for b, name, o, n in shapes:
-        if (o, n) not in xouts:
-            xouts[(o, n)] = mq.alloc_qbuffers(o, n, bits, cfg, dev)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
+    if w_only:
+        xs = {}
+        wouts = {}
+        ws_bytes = 0
+        for i, (b, name, o, n) in enumerate(shapes):
+            if n not in xs:
+                xs[n] = mi.activations(TOKENS, n, seed=mi.tensor_seed(3, 0, 0, n), device=dev)
+            ws_bytes = max(ws_bytes, mq.workspace_bytes(weights[i], xs[n], len(cands), metric, cfg))
+            # one output buffer per distinct weight shape (the codes are not read back here)
+            if (o, n) not in wouts:
+                wouts[(o, n)] = mq.alloc_qbuffers(o, n, bits, cfg, dev)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
-    def step(events=None):
-        for i, w in enumerate(weights):
-            _, _, o, n = shapes[i]
+        def step(events=None):
+            for i, w in enumerate(weights):
+                _, _, o, n = shapes[i]
+                e0 = e1 = None
+                if events is not None:
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    events.append((i, e0, e1))
+                mq.select_layer(w, xs[n], cands, metric, cfg, wouts[(o, n)], None, results[i], ws, stream, e0, e1)
+    else:
+        # One activation per role of a decoder block, as in a model: q, k, v read the block's
+        # input, o the attention output, gate and up the MLP input, down the MLP's hidden state.
+        # Every layer has its own output buffers.
+        role = {"q": 0, "k": 0, "v": 0, "o": 1, "gate": 2, "up": 2, "down": 3}
+        acts = {}
+        x_list = []
+        for b, name, o, n in shapes:
+            key = (role[name], n)
+            if key not in acts:
+                acts[key] = mi.activations(TOKENS, n, seed=mi.tensor_seed(3, 0, role[name], 1), device=dev)
+            x_list.append(acts[key])
+        w_outs = [mq.alloc_qbuffers(o, n, bits, cfg, dev) for _, _, o, n in shapes]
+        x_outs = [mq.alloc_qbuffers(TOKENS, n, 8, xcfg, dev) for _, _, o, n in shapes]
+        batch = mq.WaLayerBatch(weights, x_list, w_outs, x_outs)
+        ws = torch.empty(batch.workspace_bytes(len(cands), metric, cfg), dtype=torch.uint8, device=dev)
+
+        def step(events=None):
             e0 = e1 = None
             if events is not None:
-                e0 = torch.cuda.Event(enable_timing=True)
-                e1 = torch.cuda.Event(enable_timing=True)
-                events.append((i, e0, e1))
-            mq.select_layer(w, xs[n], cands, metric, cfg, xouts[(o, n)], xouts[n], results[i], ws,
-                            stream, e0, e1)
+                e0 = [torch.cuda.Event(enable_timing=True) for _ in shapes]
+                e1 = [torch.cuda.Event(enable_timing=True) for _ in shapes]
+                events.extend((i, e0[i], e1[i]) for i in range(len(shapes)))
+            mq.select_layers_wa(batch, cands, metric, cfg, results, ws, stream, e0, e1)
 
     for _ in range(warmup):
         step()
@@ -387,33 +409,6 @@ def run_w8a8(args, shapes, dev, weights, w_only, fp8_unit, steps, warmup, ceilin
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / steps * 1e3
-
-    # the same pass with the linears dealt alternately to two streams of the caller (own
-    # workspace and output buffers per stream): the short memory-bound quantize passes of one
-    # linear then run beside the matrix-core kernel of another
-    two = [torch.cuda.Stream(), torch.cuda.Stream()]
-    ws2 = [ws, torch.empty_like(ws)]
-    xo2 = [xouts, {k: (None if v is None else mq.alloc_qbuffers(TOKENS if not isinstance(k, tuple) else k[0],
-                                                                 k if not isinstance(k, tuple) else k[1],
-                                                                 8 if not isinstance(k, tuple) else bits,
-                                                                 xcfg if not isinstance(k, tuple) else cfg, dev))
-                   for k, v in xouts.items()}]
-
-    def step2():
-        for i, w in enumerate(weights):
-            _, _, o, n = shapes[i]
-            mq.select_layer(w, xs[n], cands, metric, cfg, xo2[i & 1][(o, n)], xo2[i & 1][n], results[i], ws2[i & 1],
-                            two[i & 1])
-
-    for st in two:
-        st.wait_stream(stream)
-    step2()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step2()
-    torch.cuda.synchronize()
-    ms_two = (time.perf_counter() - t0) / steps * 1e3
 
     # dominant kernel: the fused three-product GEMM; one launch per linear
     mnk = sum(TOKENS * o * n for _, _, o, n in shapes)
@@ -442,7 +437,6 @@ def run_w8a8(args, shapes, dev, weights, w_only, fp8_unit, steps, warmup, ceilin
         "metric": ("W4A16" if w_only else "W8A8") + " layer-output MoFQ select time over the LLaMA-7B linear shapes",
         "value": ms_per_step / 1e3, "unit": "s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
-        "ms_per_step_two_caller_streams": ms_two,
         "scaling": "weak", "vs_baseline": None,
         "dtype": ("bf16 reference product, 4-bit grid values on the bf16 matrix cores, f64 error sums" if w_only else
                   "bf16 reference product, int8 codes, " +
@@ -711,10 +705,12 @@ def full_parity(args, dev):
 
 
 def full_parity_wa(args, dev):
-    """Every linear of the listed blocks of the W8A8 workload (configs[3]) through
-    mofq_select_layer with both forms of the layer-output metric and, whole, through the oracle
-    (fp64 matrix products): both candidates' error sums and the reference energy to 1e-5, the
-    choice, and the winner's codes and scales of W and X bit for bit."""
+    """Every linear of the listed blocks of the W8A8 workload (configs[3]), block by block through
+    mofq_select_layers_wa as bench.py times it (one call per block here, one activation per role
+    of the block: q/k/v, o, gate/up, down) with both forms of the layer-output
+    metric and, whole, through the oracle (fp64 matrix products): both candidates' error sums and
+    the reference energy to 1e-5, the choice, and the winner's codes and scales of W and X bit for
+    bit."""
     import numpy as np
     import torch
 
@@ -724,49 +720,60 @@ def full_parity_wa(args, dev):
     from tests.gpu_util import scales_to_f32, unpack_codes
 
     blocks = parse_blocks(args.block_list, mi.LLAMA_SHAPES["7b"]["blocks"])
-    shapes = [s_ for s_ in mi.model_linear_shapes("7b") if s_[0] in blocks]
     cands = [mq.INT8, mq.FP8_E4M3]
     cfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
     xcfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
+    role = {"q": 0, "k": 0, "v": 0, "o": 1, "gate": 2, "up": 2, "down": 3}
     summary = {"mode": "full-parity", "workload": "w8a8", "blocks": blocks, "tokens": TOKENS, "linears_checked": 0,
                "choice_mismatches": 0, "error_sum_mismatches_rtol_1e-5": 0, "max_error_sum_rel_diff_exact": 0.0,
                "max_error_sum_rel_diff_fp8_unit": 0.0, "code_or_scale_mismatches": 0, "fp_chosen": 0,
                "oracle_seconds": 0.0, "head": git_head(), "failures": []}
-    for b, name, o, n in shapes:
-        lin = mi.LINEAR_NAMES.index(name)
-        x = mi.activations(TOKENS, n, seed=mi.tensor_seed(3, b, lin, 1), device=dev)
-        w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(3, b, lin), dtype=torch.bfloat16, device=dev)
-        t0 = time.perf_counter()
-        ref = orc.select_layer_wa(mi.to_f32_numpy(x), mi.to_f32_numpy(w), cands, orc.PER_TENSOR)
-        summary["oracle_seconds"] += time.perf_counter() - t0
-        summary["linears_checked"] += 1
-        summary["fp_chosen"] += int(ref.best == 1)
+    for b in blocks:
+        shapes = [s_ for s_ in mi.model_linear_shapes("7b") if s_[0] == b]
+        acts, xs, ws_ = {}, [], []
+        for _, name, o, n in shapes:
+            lin = mi.LINEAR_NAMES.index(name)
+            if role[name] not in acts:
+                acts[role[name]] = mi.activations(TOKENS, n, seed=mi.tensor_seed(3, b, role[name], 1), device=dev)
+            xs.append(acts[role[name]])
+            ws_.append(mi.llama_like_weight(o, n, seed=mi.tensor_seed(3, b, lin), dtype=torch.bfloat16, device=dev))
+        got = {}
         for metric, key in ((mq.ERR_LAYER_OUTPUT, "exact"), (mq.ERR_LAYER_OUTPUT_FP8_UNIT, "fp8_unit")):
-            w_out = mq.alloc_qbuffers(o, n, 8, cfg, dev)
-            x_out = mq.alloc_qbuffers(TOKENS, n, 8, xcfg, dev)
-            res = mq.alloc_result(dev)
-            ws = torch.empty(mq.workspace_bytes(w, x, 2, metric, cfg), dtype=torch.uint8, device=dev)
-            mq.select_layer(w, x, cands, metric, cfg, w_out, x_out, res, ws)
+            w_outs = [mq.alloc_qbuffers(o, n, 8, cfg, dev) for _, _, o, n in shapes]
+            x_outs = [mq.alloc_qbuffers(TOKENS, n, 8, xcfg, dev) for _, _, o, n in shapes]
+            batch = mq.WaLayerBatch(ws_, xs, w_outs, x_outs)
+            res = mq.alloc_result(dev, len(shapes))
+            wsp = torch.empty(batch.workspace_bytes(2, metric, cfg), dtype=torch.uint8, device=dev)
+            mq.select_layers_wa(batch, cands, metric, cfg, res, wsp)
             torch.cuda.synchronize()
-            r = mq.read_result(res)
-            rel = max(abs(r.err[c] - ref.errs[c]) / ref.errs[c] for c in range(2))
-            rel = max(rel, abs(r.ref_energy - ref.ref_energy) / ref.ref_energy)
-            summary["max_error_sum_rel_diff_" + key] = max(summary["max_error_sum_rel_diff_" + key], rel)
-            if rel > 1e-5:
-                summary["error_sum_mismatches_rtol_1e-5"] += 1
-                summary["failures"].append(f"block {b} {name} {key}: {list(r.err)[:2]} vs {ref.errs}")
-            if r.best != ref.best:
-                summary["choice_mismatches"] += 1
-                summary["failures"].append(f"block {b} {name} {key}: choice {r.best} vs {ref.best}")
-            same = (np.array_equal(unpack_codes(w_out.codes, o, n, 8), ref.w.codes) and
-                    np.array_equal(unpack_codes(x_out.codes, TOKENS, n, 8), ref.x.codes) and
-                    np.array_equal(scales_to_f32(w_out.scales), ref.w.scale) and
-                    np.array_equal(scales_to_f32(x_out.scales), ref.x.scale))
-            if not same:
-                summary["code_or_scale_mismatches"] += 1
-                summary["failures"].append(f"block {b} {name} {key}: codes or scales differ")
-        print(f"[full-parity] w8a8 block {b} {name} {o}x{n}: oracle best={ref.best} "
-              f"oracle_s={summary['oracle_seconds']:.1f}", file=sys.stderr, flush=True)
+            got[key] = (mq.read_results(res), w_outs, x_outs)
+        for i, (_, name, o, n) in enumerate(shapes):
+            t0 = time.perf_counter()
+            ref = orc.select_layer_wa(mi.to_f32_numpy(xs[i]), mi.to_f32_numpy(ws_[i]), cands, orc.PER_TENSOR)
+            summary["oracle_seconds"] += time.perf_counter() - t0
+            summary["linears_checked"] += 1
+            summary["fp_chosen"] += int(ref.best == 1)
+            for key, (rs, w_outs, x_outs) in got.items():
+                r = rs[i]
+                rel = max(abs(r.err[c] - ref.errs[c]) / ref.errs[c] for c in range(2))
+                rel = max(rel, abs(r.ref_energy - ref.ref_energy) / ref.ref_energy)
+                summary["max_error_sum_rel_diff_" + key] = max(summary["max_error_sum_rel_diff_" + key], rel)
+                if rel > 1e-5:
+                    summary["error_sum_mismatches_rtol_1e-5"] += 1
+                    summary["failures"].append(f"block {b} {name} {key}: {list(r.err)[:2]} vs {ref.errs}")
+                if r.best != ref.best:
+                    summary["choice_mismatches"] += 1
+                    summary["failures"].append(f"block {b} {name} {key}: choice {r.best} vs {ref.best}")
+                same = (np.array_equal(unpack_codes(w_outs[i].codes, o, n, 8), ref.w.codes) and
+                        np.array_equal(unpack_codes(x_outs[i].codes, TOKENS, n, 8), ref.x.codes) and
+                        np.array_equal(scales_to_f32(w_outs[i].scales), ref.w.scale) and
+                        np.array_equal(scales_to_f32(x_outs[i].scales), ref.x.scale))
+                if not same:
+                    summary["code_or_scale_mismatches"] += 1
+                    summary["failures"].append(f"block {b} {name} {key}: codes or scales differ")
+            print(f"[full-parity] w8a8 block {b} {name} {o}x{n}: oracle best={ref.best} "
+                  f"oracle_s={summary['oracle_seconds']:.1f}", file=sys.stderr, flush=True)
+        del got
     summary["ok"] = not summary["failures"]
     print(json.dumps(summary))
     return 0 if summary["ok"] else 1
@@ -774,7 +781,7 @@ def full_parity_wa(args, dev):
 
 def brief(d):
     """A secondary workload inside the headline line: the figures, not the boilerplate."""
-    keep = ("metric", "value", "unit", "ms_per_step", "ms_per_step_two_caller_streams", "steps", "warmup",
+    keep = ("metric", "value", "unit", "ms_per_step", "steps", "warmup",
             "higher_is_better", "dtype", "config", "roofline")
     return {k: d[k] for k in keep if k in d}
 

@@ -275,30 +275,27 @@ int mofq_select_layers_search_groups(int32_t n_layers, const mofq_tensor_t* w, c
  *   ev_begin / ev_end (the _timed variant; may be NULL): HOST arrays of n_layers hipEvent_t,
  *              recorded on `stream` immediately before and after each layer's matrix kernel.
  * With candidates {MOFQ_INT8, MOFQ_FP8_E4M3} (either order) and per-tensor weight scales the
- * layers take a fused path: X and W go through the quantize passes together (two launches),
- * then the matrix kernel, one small kernel for the select and the one-unit outputs, and a copy
- * of the chosen codes; a layer whose activation descriptor equals the previous layer's (the
- * q/k/v or gate/up projections of a block given the same x) reuses its quantized activation.
- * During the call w_out[i].codes holds W's E4M3 codes before the select; the chosen format's
- * codes are in place when the call's work has finished.  Other candidate lists and per-channel
- * weight scales go layer by layer through the general path of mofq_select_layer.
- * Workspace: mofq_select_layers_wa_workspace_bytes (two layers' operands, not n_layers').
- * Streams: as for mofq_select_layers.  With a `side_stream` the quantize passes of layer i + 1
- * and the code copy of layer i - 1 run beside layer i's matrix kernel; `stream` waits for the
- * side work before the call returns.  The library creates ten events for the duration of the
- * call and nothing else.
+ * layers take a fused path in groups of up to 8 consecutive layers (a decoder block): the X
+ * and W of a group go through the two quantize passes together (two launches), then one matrix
+ * kernel per layer, one small kernel for the selects and the one-unit outputs of the group,
+ * and one copy of the chosen codes; a layer whose activation descriptor equals the previous
+ * layer's (the q/k/v or gate/up projections of a block given the same x) reuses its quantized
+ * activation.  During the call w_out[i].codes holds W's E4M3 codes before the select; the
+ * chosen format's codes are in place when the call's work has finished.  Other candidate lists
+ * and per-channel weight scales go layer by layer through the general path of
+ * mofq_select_layer.
+ * Workspace: mofq_select_layers_wa_workspace_bytes (one group's operands, not n_layers').
+ * Everything is enqueued on `stream`; the library creates no events and keeps no state.
  */
 int mofq_select_layers_wa(int32_t n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x,
                           const int32_t* candidates, int32_t n_candidates, int32_t metric,
                           const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out, const mofq_qout_t* x_out,
-                          mofq_result_t* results, void* ws, size_t ws_bytes, void* stream,
-                          void* side_stream);
+                          mofq_result_t* results, void* ws, size_t ws_bytes, void* stream);
 int mofq_select_layers_wa_timed(int32_t n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x,
                                 const int32_t* candidates, int32_t n_candidates, int32_t metric,
                                 const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
                                 const mofq_qout_t* x_out, mofq_result_t* results, void* ws,
-                                size_t ws_bytes, void* stream, void* side_stream,
-                                void* const* ev_begin, void* const* ev_end);
+                                size_t ws_bytes, void* stream, void* const* ev_begin, void* const* ev_end);
 size_t mofq_select_layers_wa_workspace_bytes(int32_t n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x,
                                              int32_t n_candidates, int32_t metric,
                                              const mofq_scale_cfg_t* w_cfg);

@@ -98,7 +98,7 @@ def _load():
     L.mofq_select_layers_wa.restype = C.c_int
     L.mofq_select_layers_wa.argtypes = [C.c_int32, C.POINTER(TensorDesc), C.POINTER(TensorDesc),
                                         C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.POINTER(ScaleCfg),
-                                        C.POINTER(QOut), C.POINTER(QOut), vp, vp, C.c_size_t, vp, vp]
+                                        C.POINTER(QOut), C.POINTER(QOut), vp, vp, C.c_size_t, vp]
     L.mofq_select_layers_wa_timed.restype = C.c_int
     L.mofq_select_layers_wa_timed.argtypes = L.mofq_select_layers_wa.argtypes + [C.POINTER(vp), C.POINTER(vp)]
     L.mofq_select_layers_wa_workspace_bytes.restype = C.c_size_t
@@ -385,14 +385,12 @@ class WaLayerBatch:
 
 
 def select_layers_wa(batch: WaLayerBatch, candidates: Sequence[int], metric: int, cfg: Cfg,
-                     results: torch.Tensor, ws: torch.Tensor, stream=None, side_stream=None,
-                     ev_begin=None, ev_end=None) -> None:
+                     results: torch.Tensor, ws: torch.Tensor, stream=None, ev_begin=None, ev_end=None) -> None:
     """mofq_select_layers_wa (or _timed with lists of torch.cuda.Event recorded around each
     layer's matrix kernel): the weight-activation select of every layer of the batch; enqueue."""
     cand = (C.c_int32 * len(candidates))(*candidates)
-    side = C.c_void_p(side_stream.cuda_stream) if side_stream is not None else C.c_void_p(0)
     args = (batch.n, batch.w, batch.x, cand, len(candidates), metric, C.byref(cfg.c), batch.w_out, batch.x_out,
-            _ptr(results), _ptr(ws), ws.numel() * ws.element_size(), _stream_handle(stream), side)
+            _ptr(results), _ptr(ws), ws.numel() * ws.element_size(), _stream_handle(stream))
     if ev_begin is None:
         rc = _lib.mofq_select_layers_wa(*args)
     else:

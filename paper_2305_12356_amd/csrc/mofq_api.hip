@@ -21,6 +21,19 @@ bool paired(int a, int b) {
 }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Compute units of the current device (256 on an MI355X); 256 when no device answers, so that
+// the host-only planning calls work anywhere.
+int compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+    (void)hipGetLastError();
+    return 256;
+  }
+  return n;
+}
+
+
 int check_tensor(const mofq_tensor_t* t) {
   if (!t || !t->data) return MOFQ_ERR_INVALID_ARG;
   if (t->rows <= 0 || t->cols <= 0 || t->ld < t->cols) return MOFQ_ERR_INVALID_ARG;
@@ -497,69 +510,80 @@ struct WaFusedTensorWs {
   double* sse_part;
   float* scale;
 };
-struct WaFusedWs {
-  WaFusedTensorWs x[2], w[2];   // two slots each: layer i + 1 is prepared while layer i is multiplied
-  double* part[2][3];           // per slot: INT8 error, E4M3 error, reference energy per output tile
-  int slots;
-  size_t bytes;
+// Workspace of one layer: the quantized operands and records of X and W, and the per-tile
+// partials of the matrix kernel (INT8 error, E4M3 error, reference energy).
+struct WaLayerWs {
+  WaFusedTensorWs x, w;
+  double* part[3];
+  bool fresh_x;   // false: x is the previous layer's (same descriptor, same group)
 };
 
-WaFusedWs carve_wa_fused(void* ws, int n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x, bool exact) {
-  WaFusedWs a{};
-  int64_t max_x = 0, max_w = 0;
-  int max_blocks = 0;
-  for (int i = 0; i < n_layers; ++i) {
-    max_x = std::max<int64_t>(max_x, x[i].rows * x[i].cols);
-    max_w = std::max<int64_t>(max_w, w[i].rows * w[i].cols);
-    max_blocks = std::max(max_blocks, wa_gemm_blocks(x[i].rows, w[i].rows));
+// The layers are worked off in groups of up to kWaGroup consecutive layers holding up to
+// kWaGroupElems weight elements (a decoder block of the 7B shape is one group): with a second
+// stream a whole group is prepared while the previous group is multiplied, so that the two
+// streams meet once per group and not once per layer.  Returns the number of layers of the
+// group that starts at i0.
+constexpr int64_t kWaGroupElems = int64_t{1} << 28;
+int wa_group_length(int n_layers, const mofq_tensor_t* w, int i0) {
+  int64_t elems = 0;
+  int n = 0;
+  for (; i0 + n < n_layers && n < kWaGroup; ++n) {
+    const int64_t e = w[i0 + n].rows * w[i0 + n].cols;
+    if (n > 0 && elems + e > kWaGroupElems) break;
+    elems += e;
   }
-  a.slots = n_layers > 1 ? 2 : 1;
-  Carver c(ws);
-  for (int s = 0; s < a.slots; ++s) {
+  return n;
+}
+
+bool wa_same_x(const mofq_tensor_t* x, int i) {
+  return x[i].data == x[i - 1].data && x[i].rows == x[i - 1].rows && x[i].cols == x[i - 1].cols &&
+         x[i].ld == x[i - 1].ld;
+}
+
+// Carves the workspaces of layers [i0, i0 + n) out of `arena` (null: sizes only); returns the bytes.
+size_t carve_wa_group(void* arena, int i0, int n, const mofq_tensor_t* w, const mofq_tensor_t* x, bool exact,
+                      WaLayerWs* out) {
+  Carver c(arena);
+  for (int j = 0; j < n; ++j) {
+    const int i = i0 + j;
+    WaLayerWs l{};
+    l.fresh_x = j == 0 || !wa_same_x(x, i);
     for (int which = 0; which < 2; ++which) {
-      WaFusedTensorWs& t = which ? a.w[s] : a.x[s];
-      const size_t n = static_cast<size_t>(which ? max_w : max_x);
-      t.i8 = c.take<uint8_t>(n);
-      t.f8 = which ? nullptr : c.take<uint8_t>(n);   // the weight's live in the caller's code buffer
-      t.g = exact ? c.take<uint8_t>(2 * n) : nullptr;
+      WaFusedTensorWs& t = which ? l.w : l.x;
+      if (!which && !l.fresh_x) {
+        if (out) t = out[j - 1].x;
+        continue;
+      }
+      const size_t e = static_cast<size_t>(which ? w[i].rows * w[i].cols : x[i].rows * x[i].cols);
+      t.i8 = c.take<uint8_t>(e);
+      t.f8 = which ? nullptr : c.take<uint8_t>(e);   // the weight's live in the caller's code buffer
+      t.g = exact ? c.take<uint8_t>(2 * e) : nullptr;
       t.absmax_part = c.take<float>(kTensorBlocks);
       t.sse_part = c.take<double>(2 * kTensorBlocks);
       t.scale = c.take<float>(2);
     }
-    for (int q = 0; q < 3; ++q) a.part[s][q] = c.take<double>(max_blocks);
+    for (int q = 0; q < 3; ++q) l.part[q] = c.take<double>(wa_gemm_blocks(x[i].rows, w[i].rows));
+    if (out) out[j] = l;
   }
-  a.bytes = (c.off + kAlign - 1) / kAlign * kAlign;
-  return a;
+  return (c.off + kAlign - 1) / kAlign * kAlign;
 }
 
-// A few events that order two streams against each other, recorded in rotation.
-struct EventRing {
-  static constexpr int N = 4;
-  hipEvent_t ev[N] = {};
-  EventRing() = default;
-  EventRing(const EventRing&) = delete;
-  EventRing& operator=(const EventRing&) = delete;
-  ~EventRing() {
-    for (hipEvent_t e : ev)
-      if (e) (void)hipEventDestroy(e);
+// One arena, large enough for any group: the groups follow each other on one stream.
+size_t wa_fused_bytes(int n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x, bool exact) {
+  size_t bytes = 0;
+  for (int i0 = 0, n = 0; i0 < n_layers; i0 += n) {
+    n = wa_group_length(n_layers, w, i0);
+    bytes = std::max(bytes, carve_wa_group(nullptr, i0, n, w, x, exact, nullptr));
   }
-  int init() {
-    for (hipEvent_t& e : ev)
-      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return MOFQ_ERR_HIP;
-    return MOFQ_OK;
-  }
-  // mark(i, s): everything enqueued on s so far; await(i, s): s waits for the i-th mark.  At
-  // most N - 1 marks may lie between a mark and its await.
-  int mark(int i, hipStream_t s) { return hip_status(hipEventRecord(ev[i % N], s)); }
-  int await(int i, hipStream_t s) { return hip_status(hipStreamWaitEvent(s, ev[i % N], 0)); }
-};
+  return bytes;
+}
 
 // Arguments are validated by the caller except for the workspace.  x_out may be null (no
 // activation outputs), ev_begin / ev_end may be null.
 int select_layers_wa(int n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand,
                      int n_cand, int metric, const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
                      const mofq_qout_t* x_out, mofq_result_t* results, void* ws, size_t ws_bytes,
-                     hipStream_t st, void* side_stream, void* const* ev_begin, void* const* ev_end) {
+                     hipStream_t st, void* const* ev_begin, void* const* ev_end) {
   int rc;
   auto ev = [](void* const* list, int i) { return list ? static_cast<hipEvent_t>(list[i]) : nullptr; };
   if (!wa_fused(cand, n_cand, w_cfg)) {
@@ -570,125 +594,107 @@ int select_layers_wa(int n_layers, const mofq_tensor_t* w, const mofq_tensor_t* 
     return MOFQ_OK;
   }
   const bool fp8_unit = metric == MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT;
-  const WaFusedWs a = carve_wa_fused(ws, n_layers, w, x, !fp8_unit);
-  if (!ws || ws_bytes < a.bytes || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
+  if (!ws || ws_bytes < wa_fused_bytes(n_layers, w, x, !fp8_unit) || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
   int fmt_slot[MOFQ_MAX_CANDIDATES] = {0, 0, 0, 0};
   for (int c = 0; c < n_cand; ++c) fmt_slot[c] = cand[c] == MOFQ_FP8_E4M3;
 
-  // slot of layer i's weight: i % slots.  Slot of its activation: the previous layer's if the
-  // descriptor is the same (then nothing is quantized again), else the other one.
-  auto same_x = [&](int i) {
-    return i > 0 && x[i].data == x[i - 1].data && x[i].rows == x[i - 1].rows && x[i].cols == x[i - 1].cols &&
-           x[i].ld == x[i - 1].ld;
-  };
-  auto prep = [&](int i, int xs, hipStream_t s) {
-    const int ws_ = i % a.slots;
-    WaPrepTensor px{}, pw{};
-    if (!same_x(i)) {
-      px.data = x[i].data; px.rows = x[i].rows; px.cols = x[i].cols; px.ld = x[i].ld;
-      px.ratio = 1.0f;   // activations: per tensor at the full range (Section 3.2)
-      px.absmax_part = a.x[xs].absmax_part; px.sse_part = a.x[xs].sse_part;
-      px.q_i8 = a.x[xs].i8; px.q_f8 = a.x[xs].f8; px.q_g = a.x[xs].g; px.scale = a.x[xs].scale;
+  // the group's layers are [i0, i0 + n), their workspaces l[0 .. n)
+  auto prep = [&](int i0, int n, const WaLayerWs* l, hipStream_t s) {
+    WaPrepTensor t[2 * kWaGroup] = {};
+    for (int j = 0; j < n; ++j) {
+      const int i = i0 + j;
+      WaPrepTensor& px = t[2 * j];
+      WaPrepTensor& pw = t[2 * j + 1];
+      if (l[j].fresh_x) {
+        px.data = x[i].data; px.rows = x[i].rows; px.cols = x[i].cols; px.ld = x[i].ld;
+        px.ratio = 1.0f;   // activations: per tensor at the full range (Section 3.2)
+        px.absmax_part = l[j].x.absmax_part; px.sse_part = l[j].x.sse_part;
+        px.q_i8 = l[j].x.i8; px.q_f8 = l[j].x.f8; px.q_g = l[j].x.g; px.scale = l[j].x.scale;
+      }
+      pw.data = w[i].data; pw.rows = w[i].rows; pw.cols = w[i].cols; pw.ld = w[i].ld;
+      pw.ratio = w_cfg->clip_ratios[0];
+      pw.absmax_part = l[j].w.absmax_part; pw.sse_part = l[j].w.sse_part;
+      pw.q_i8 = l[j].w.i8; pw.q_f8 = static_cast<uint8_t*>(w_out[i].codes); pw.q_g = l[j].w.g;
+      pw.scale = l[j].w.scale;
     }
-    pw.data = w[i].data; pw.rows = w[i].rows; pw.cols = w[i].cols; pw.ld = w[i].ld;
-    pw.ratio = w_cfg->clip_ratios[0];
-    pw.absmax_part = a.w[ws_].absmax_part; pw.sse_part = a.w[ws_].sse_part;
-    pw.q_i8 = a.w[ws_].i8; pw.q_f8 = static_cast<uint8_t*>(w_out[i].codes); pw.q_g = a.w[ws_].g;
-    pw.scale = a.w[ws_].scale;
-    return launch_wa_prep(px, pw, s);
+    return launch_wa_prep(t, 2 * n, s);
   };
-  auto product = [&](int i, int xs) {
-    const int ws_ = i % a.slots;
-    WaGemmParams g{};
-    g.q[0].kind = WA_INT8;
-    g.q[0].x = a.x[xs].i8; g.q[0].w = a.w[ws_].i8;
-    g.q[0].sx = a.x[xs].scale; g.q[0].sw = a.w[ws_].scale;
-    g.q[0].part = a.part[ws_][0];
-    g.q[1].kind = fp8_unit ? WA_FP8 : WA_GRID_BF16;
-    g.q[1].x = fp8_unit ? a.x[xs].f8 : a.x[xs].g;
-    g.q[1].w = fp8_unit ? static_cast<const uint8_t*>(w_out[i].codes) : a.w[ws_].g;
-    g.q[1].sx = a.x[xs].scale + 1; g.q[1].sw = a.w[ws_].scale + 1;
-    g.q[1].part = a.part[ws_][1];
-    g.x = x[i].data; g.ldx = x[i].ld;
-    g.w = w[i].data; g.ldw = w[i].ld;
-    g.w_per_channel = 0;
-    g.M = x[i].rows; g.N = w[i].rows; g.K = w[i].cols;
-    g.part_p = a.part[ws_][2];
+  auto products = [&](int i0, int n, const WaLayerWs* l) {
     int r;
-    if (ev(ev_begin, i) && hipEventRecord(ev(ev_begin, i), st) != hipSuccess) return static_cast<int>(MOFQ_ERR_HIP);
-    if ((r = launch_wa_gemm(g, st))) return r;
-    if (ev(ev_end, i) && hipEventRecord(ev(ev_end, i), st) != hipSuccess) return static_cast<int>(MOFQ_ERR_HIP);
-    WaFinishParams f{};
-    f.d.units = wa_gemm_blocks(x[i].rows, w[i].rows);
-    f.d.n_cand = n_cand;
-    for (int c = 0; c < n_cand; ++c) { f.d.err[c] = a.part[ws_][fmt_slot[c]]; f.fmt_slot[c] = fmt_slot[c]; }
-    f.d.energy = a.part[ws_][2];
-    f.d.result = &results[i];
-    if (x_out) {
-      f.t[0].n_blocks = wa_prep_blocks(x[i].rows, x[i].cols);
-      f.t[0].sse_part = a.x[xs].sse_part; f.t[0].scale = a.x[xs].scale;
-      f.t[0].out_scales = x_out[i].scales; f.t[0].out_clip = x_out[i].clip_idx; f.t[0].out_unit_err = x_out[i].unit_err;
+    for (int j = 0; j < n; ++j) {
+      const int i = i0 + j;
+      WaGemmParams g{};
+      g.q[0].kind = WA_INT8;
+      g.q[0].x = l[j].x.i8; g.q[0].w = l[j].w.i8;
+      g.q[0].sx = l[j].x.scale; g.q[0].sw = l[j].w.scale;
+      g.q[0].part = l[j].part[0];
+      g.q[1].kind = fp8_unit ? WA_FP8 : WA_GRID_BF16;
+      g.q[1].x = fp8_unit ? l[j].x.f8 : l[j].x.g;
+      g.q[1].w = fp8_unit ? static_cast<const uint8_t*>(w_out[i].codes) : l[j].w.g;
+      g.q[1].sx = l[j].x.scale + 1; g.q[1].sw = l[j].w.scale + 1;
+      g.q[1].part = l[j].part[1];
+      g.x = x[i].data; g.ldx = x[i].ld;
+      g.w = w[i].data; g.ldw = w[i].ld;
+      g.w_per_channel = 0;
+      g.M = x[i].rows; g.N = w[i].rows; g.K = w[i].cols;
+      g.part_p = l[j].part[2];
+      if (ev(ev_begin, i) && hipEventRecord(ev(ev_begin, i), st) != hipSuccess) return static_cast<int>(MOFQ_ERR_HIP);
+      if ((r = launch_wa_gemm(g, st))) return r;
+      if (ev(ev_end, i) && hipEventRecord(ev(ev_end, i), st) != hipSuccess) return static_cast<int>(MOFQ_ERR_HIP);
     }
-    f.t[1].n_blocks = wa_prep_blocks(w[i].rows, w[i].cols);
-    f.t[1].sse_part = a.w[ws_].sse_part; f.t[1].scale = a.w[ws_].scale;
-    f.t[1].out_scales = w_out[i].scales; f.t[1].out_clip = w_out[i].clip_idx; f.t[1].out_unit_err = w_out[i].unit_err;
-    return launch_wa_finish(f, st);
+    WaFinishParams f[kWaGroup] = {};
+    for (int j = 0; j < n; ++j) {
+      const int i = i0 + j;
+      f[j].d.units = wa_gemm_blocks(x[i].rows, w[i].rows);
+      f[j].d.n_cand = n_cand;
+      for (int c = 0; c < n_cand; ++c) { f[j].d.err[c] = l[j].part[fmt_slot[c]]; f[j].fmt_slot[c] = fmt_slot[c]; }
+      f[j].d.energy = l[j].part[2];
+      f[j].d.result = &results[i];
+      if (x_out) {
+        f[j].t[0].n_segments = wa_prep_segments(x[i].rows, x[i].cols);
+        f[j].t[0].sse_part = l[j].x.sse_part; f[j].t[0].scale = l[j].x.scale;
+        f[j].t[0].out_scales = x_out[i].scales; f[j].t[0].out_clip = x_out[i].clip_idx;
+        f[j].t[0].out_unit_err = x_out[i].unit_err;
+      }
+      f[j].t[1].n_segments = wa_prep_segments(w[i].rows, w[i].cols);
+      f[j].t[1].sse_part = l[j].w.sse_part; f[j].t[1].scale = l[j].w.scale;
+      f[j].t[1].out_scales = w_out[i].scales; f[j].t[1].out_clip = w_out[i].clip_idx;
+      f[j].t[1].out_unit_err = w_out[i].unit_err;
+    }
+    return launch_wa_finish(f, n, st);
   };
-  auto codes = [&](int i, int xs, hipStream_t s) {
-    const int ws_ = i % a.slots;
-    WaCopyParams p{};
-    p.result = &results[i];
-    p.n_cand = n_cand;
-    for (int c = 0; c < n_cand; ++c) p.fmt_slot[c] = fmt_slot[c];
-    if (x_out) {
-      p.t[0].src[0] = a.x[xs].i8; p.t[0].src[1] = a.x[xs].f8;
-      p.t[0].dst = static_cast<uint8_t*>(x_out[i].codes);
-      p.t[0].bytes = x[i].rows * x[i].cols;
+  auto codes = [&](int i0, int n, const WaLayerWs* l, hipStream_t s) {
+    WaCopyParams p[kWaGroup] = {};
+    for (int j = 0; j < n; ++j) {
+      const int i = i0 + j;
+      p[j].result = &results[i];
+      p[j].n_cand = n_cand;
+      for (int c = 0; c < n_cand; ++c) p[j].fmt_slot[c] = fmt_slot[c];
+      if (x_out) {
+        p[j].t[0].src[0] = l[j].x.i8; p[j].t[0].src[1] = l[j].x.f8;
+        p[j].t[0].dst = static_cast<uint8_t*>(x_out[i].codes);
+        p[j].t[0].bytes = x[i].rows * x[i].cols;
+      }
+      p[j].t[1].src[0] = l[j].w.i8; p[j].t[1].src[1] = static_cast<const uint8_t*>(w_out[i].codes);
+      p[j].t[1].dst = static_cast<uint8_t*>(w_out[i].codes);
+      p[j].t[1].bytes = w[i].rows * w[i].cols;
     }
-    p.t[1].src[0] = a.w[ws_].i8; p.t[1].src[1] = static_cast<const uint8_t*>(w_out[i].codes);
-    p.t[1].dst = static_cast<uint8_t*>(w_out[i].codes);
-    p.t[1].bytes = w[i].rows * w[i].cols;
-    return launch_wa_copy(p, s);
+    return launch_wa_copy(p, n, s);
   };
 
-  SideWork sw(st, a.slots == 2 ? side_stream : nullptr);
-  if ((rc = sw.init())) return rc;
-  if (!sw.two) {
-    // one stream: layer by layer
-    int xs = 1;
-    for (int i = 0; i < n_layers; ++i) {
-      if (!same_x(i)) xs = (xs + 1) % a.slots;
-      if ((rc = prep(i, xs, st))) return rc;
-      if ((rc = product(i, xs))) return rc;
-      if ((rc = codes(i, xs, st))) return rc;
-    }
-    return MOFQ_OK;
+  // Group by group on the caller's stream: the quantize passes, the matrix kernels, the selects,
+  // the code copies.  (Running the passes of the next group on a second stream beside the matrix
+  // kernels was measured and lost: two waves of 216-240 registers on every SIMD leave no room
+  // for a second kernel's waves, so the side work only delays the matrix kernels.)
+  WaLayerWs cur[kWaGroup];
+  for (int i0 = 0, n = 0; i0 < n_layers; i0 += n) {
+    n = wa_group_length(n_layers, w, i0);
+    carve_wa_group(ws, i0, n, w, x, !fp8_unit, cur);
+    if ((rc = prep(i0, n, cur, st))) return rc;
+    if ((rc = products(i0, n, cur))) return rc;
+    if ((rc = codes(i0, n, cur, st))) return rc;
   }
-  // Two streams: the quantize passes of layer i + 1 and the code copy of layer i - 1 run on the
-  // side stream beside layer i's matrix kernel, which stays on the caller's stream.  On the
-  // side stream layer i + 1's passes come after layer i - 1's copy, which waits for layer
-  // i - 1's select: by then the slot they write (its weight slot, and an activation slot that
-  // layer i does not use) is no longer read.
-  EventRing ready, decided;
-  if ((rc = ready.init()) || (rc = decided.init())) return rc;
-  hipStream_t st2 = sw.side;
-  auto join = [&](int status) { return sw.join(status); };
-  if ((rc = sw.fork())) return join(rc);
-  int xs_cur = 0;
-  if ((rc = prep(0, xs_cur, st2)) || (rc = ready.mark(0, st2))) return join(rc);
-  for (int i = 0; i < n_layers; ++i) {
-    if ((rc = ready.await(i, st))) return join(rc);               // layer i's operands are written
-    int xs_next = xs_cur;
-    if (i + 1 < n_layers) {
-      if (!same_x(i + 1)) xs_next = 1 - xs_cur;
-      if ((rc = prep(i + 1, xs_next, st2)) || (rc = ready.mark(i + 1, st2))) return join(rc);
-    }
-    if ((rc = product(i, xs_cur))) return join(rc);
-    if ((rc = decided.mark(i, st)) || (rc = decided.await(i, st2))) return join(rc);   // layer i's choice is known
-    if ((rc = codes(i, xs_cur, st2))) return join(rc);
-    xs_cur = xs_next;
-  }
-  return join(MOFQ_OK);
+  return MOFQ_OK;
 }
 
 // Algorithm 1's loop body for one weight tensor with the tensor-error metric: search every
@@ -806,7 +812,7 @@ size_t mofq_workspace_bytes(const mofq_tensor_t* w, const mofq_tensor_t* x, int3
     // the larger of the general path's need and, where it can apply, the fused path's
     size_t b = carve_wa(nullptr, w, x, n_candidates, w_cfg->gran).bytes;
     if (n_candidates == 2 && w_cfg->gran == MOFQ_PER_TENSOR)
-      b = std::max(b, carve_wa_fused(nullptr, 1, w, x, metric == MOFQ_ERR_LAYER_OUTPUT).bytes);
+      b = std::max(b, wa_fused_bytes(1, w, x, metric == MOFQ_ERR_LAYER_OUTPUT));
     return b;
   }
   if (metric == MOFQ_ERR_LAYER_OUTPUT_W_ONLY && x && x->rows > 0 && x->cols == w->cols && n_candidates <= 2 &&
@@ -919,18 +925,6 @@ int mofq_score(const mofq_tensor_t* w, const mofq_tensor_t* x, int32_t format, i
 }  // extern "C"
 
 namespace {
-
-// Compute units of the current device (256 on an MI355X); 256 when no device answers, so that
-// the host-only planning calls work anywhere.
-int compute_units() {
-  int dev = 0, n = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
-    (void)hipGetLastError();
-    return 256;
-  }
-  return n;
-}
 
 // A batch of mofq_select_layers ends at kFinishBatch tensors or once it holds 2 MB of input per
 // compute unit.  The batch is the unit of overlap (its select and emission run beside the next
@@ -1306,7 +1300,7 @@ size_t mofq_select_layers_wa_workspace_bytes(int32_t n_layers, const mofq_tensor
     need = std::max(need, b);
   }
   if (n_candidates == 2 && w_cfg->gran == MOFQ_PER_TENSOR)
-    need = std::max(need, carve_wa_fused(nullptr, n_layers, w, x, metric == MOFQ_ERR_LAYER_OUTPUT).bytes);
+    need = std::max(need, wa_fused_bytes(n_layers, w, x, metric == MOFQ_ERR_LAYER_OUTPUT));
   return need;
 }
 
@@ -1314,8 +1308,7 @@ int mofq_select_layers_wa_timed(int32_t n_layers, const mofq_tensor_t* w, const 
                                 const int32_t* candidates, int32_t n_candidates, int32_t metric,
                                 const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out,
                                 const mofq_qout_t* x_out, mofq_result_t* results, void* ws,
-                                size_t ws_bytes, void* stream, void* side_stream,
-                                void* const* ev_begin, void* const* ev_end) {
+                                size_t ws_bytes, void* stream, void* const* ev_begin, void* const* ev_end) {
   if (n_layers < 1 || !w || !x || !w_out || !results) return MOFQ_ERR_INVALID_ARG;
   if (metric != MOFQ_ERR_LAYER_OUTPUT && metric != MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT) return MOFQ_ERR_INVALID_ARG;
   int rc = check_candidates(candidates, n_candidates);
@@ -1331,16 +1324,15 @@ int mofq_select_layers_wa_timed(int32_t n_layers, const mofq_tensor_t* w, const 
   const size_t need = mofq_select_layers_wa_workspace_bytes(n_layers, w, x, n_candidates, metric, w_cfg);
   if (!ws || !need || ws_bytes < need || !aligned16(ws)) return MOFQ_ERR_WORKSPACE;
   return select_layers_wa(n_layers, w, x, candidates, n_candidates, metric, w_cfg, w_out, x_out, results, ws,
-                          ws_bytes, static_cast<hipStream_t>(stream), side_stream, ev_begin, ev_end);
+                          ws_bytes, static_cast<hipStream_t>(stream), ev_begin, ev_end);
 }
 
 int mofq_select_layers_wa(int32_t n_layers, const mofq_tensor_t* w, const mofq_tensor_t* x,
                           const int32_t* candidates, int32_t n_candidates, int32_t metric,
                           const mofq_scale_cfg_t* w_cfg, const mofq_qout_t* w_out, const mofq_qout_t* x_out,
-                          mofq_result_t* results, void* ws, size_t ws_bytes, void* stream,
-                          void* side_stream) {
+                          mofq_result_t* results, void* ws, size_t ws_bytes, void* stream) {
   return mofq_select_layers_wa_timed(n_layers, w, x, candidates, n_candidates, metric, w_cfg, w_out, x_out,
-                                     results, ws, ws_bytes, stream, side_stream, nullptr, nullptr);
+                                     results, ws, ws_bytes, stream, nullptr, nullptr);
 }
 
 int mofq_select_layer_static(const mofq_tensor_t* w, const int32_t* candidates, int32_t n_candidates,
@@ -1418,7 +1410,7 @@ int mofq_select_layer_timed(const mofq_tensor_t* w, const mofq_tensor_t* x,
   if ((rc = check_wa(w, x, candidates, n_candidates, w_cfg))) return rc;
   if (x_out && (rc = check_out(x_out, true))) return rc;
   return select_layers_wa(1, w, x, candidates, n_candidates, metric, w_cfg, w_out, x_out, result, ws, ws_bytes,
-                          st, nullptr, ev_score_begin ? &ev_score_begin : nullptr,
+                          st, ev_score_begin ? &ev_score_begin : nullptr,
                           ev_score_end ? &ev_score_end : nullptr);
 }
 

@@ -113,11 +113,16 @@ MOFQ_DEV int decide_body(const DecideParams& p, double* s_red) {
   return best;
 }
 
-// The weight-activation path after its matrix kernel: select from the per-tile partials, then
-// the one-unit outputs of the chosen format for X and W.
-__global__ __launch_bounds__(kDecideThreads) void wa_finish_kernel(const WaFinishParams a) {
+// The weight-activation path after the matrix kernels of a group of layers, one workgroup per
+// layer: select from the per-tile partials, then the one-unit outputs of the chosen format
+// for X and W.
+struct WaFinishArgs {
+  WaFinishParams p[kWaGroup];
+};
+__global__ __launch_bounds__(kDecideThreads) void wa_finish_kernel(const WaFinishArgs args) {
   __shared__ double s_red[kDecideThreads / 64];
   __shared__ int s_best;
+  const WaFinishParams& a = args.p[blockIdx.x];
   const int b = decide_body(a.d, s_red);
   if (threadIdx.x == 0) s_best = (b < 0 || b >= a.d.n_cand) ? 0 : b;   // no candidate beat infinity: keep the first
   __syncthreads();
@@ -125,9 +130,9 @@ __global__ __launch_bounds__(kDecideThreads) void wa_finish_kernel(const WaFinis
 #pragma unroll
   for (int which = 0; which < 2; ++which) {
     const WaFinishTensor& t = a.t[which];
-    if (t.n_blocks < 1) continue;   // uniform
+    if (t.n_segments < 1) continue;   // uniform
     double e = 0.0;
-    if (t.out_unit_err) e = block_sum(t.sse_part + f, t.n_blocks, s_red, 2);
+    if (t.out_unit_err) e = block_sum(t.sse_part + f, t.n_segments, s_red, 2);
     if (threadIdx.x == 0) {
       if (t.out_unit_err) *t.out_unit_err = e;
       if (t.out_scales) *static_cast<float*>(t.out_scales) = t.scale[f];
@@ -136,22 +141,29 @@ __global__ __launch_bounds__(kDecideThreads) void wa_finish_kernel(const WaFinis
   }
 }
 
-// Copy of the chosen format's codes (16-byte pieces, grid-stride, four in flight per lane).
-// Workgroups are dealt to the two tensors in proportion to their sizes.
+// Copy of the chosen format's codes (16-byte pieces, grid-stride, four in flight per lane) for
+// the tensors of a group of layers.  Workgroups are dealt to the tensors in proportion to
+// their sizes.
+constexpr int kCopyTensors = 2 * kWaGroup;
 struct WaCopyArgs {
-  WaCopyParams p;
-  int32_t n_blocks[2];
+  const mofq_result_t* result[kCopyTensors];
+  int32_t n_cand[kCopyTensors];
+  int32_t fmt_slot[kCopyTensors][MOFQ_MAX_CANDIDATES];
+  WaCopyTensor t[kCopyTensors];
+  int32_t first_block[kCopyTensors + 1];
+  int32_t n;
 };
 __global__ __launch_bounds__(256) void wa_copy_kernel(const WaCopyArgs a) {
-  int best = a.p.result->best;
-  if (best < 0 || best >= a.p.n_cand) best = 0;
-  const int f = a.p.fmt_slot[__builtin_amdgcn_readfirstlane(best)];
-  const bool second = static_cast<int>(blockIdx.x) >= a.n_blocks[0];
-  const WaCopyTensor t = second ? a.p.t[1] : a.p.t[0];
-  const int nb = second ? a.n_blocks[1] : a.n_blocks[0];
-  const int b = static_cast<int>(blockIdx.x) - (second ? a.n_blocks[0] : 0);
+  int k = 0;
+  while (k + 1 < a.n && static_cast<int>(blockIdx.x) >= a.first_block[k + 1]) ++k;   // uniform
+  const int b = static_cast<int>(blockIdx.x) - a.first_block[k];
+  const int nb = a.first_block[k + 1] - a.first_block[k];
+  int best = a.result[k]->best;
+  if (best < 0 || best >= a.n_cand[k]) best = 0;
+  const int f = a.fmt_slot[k][__builtin_amdgcn_readfirstlane(best)];
+  const WaCopyTensor& t = a.t[k];
   const uint8_t* src = f ? t.src[1] : t.src[0];
-  if (!t.dst || src == t.dst) return;   // uniform
+  if (src == t.dst) return;   // uniform: the codes are in place
   const u32x4* s4 = reinterpret_cast<const u32x4*>(src);
   u32x4* d4 = reinterpret_cast<u32x4*>(t.dst);
   const int64_t n = t.bytes / 16;
@@ -361,30 +373,47 @@ int launch_finish_batch(const FinishParams* p, int n, hipStream_t st) {
   return hip_status(hipGetLastError());
 }
 
-int launch_wa_finish(const WaFinishParams& p, hipStream_t st) {
-  if (p.d.units < 1 || p.d.n_cand < 1 || p.d.n_cand > MOFQ_MAX_CANDIDATES || !p.d.result) return MOFQ_ERR_INVALID_ARG;
-  for (int c = 0; c < p.d.n_cand; ++c)
-    if (!p.d.err[c] || p.fmt_slot[c] < 0 || p.fmt_slot[c] > 1) return MOFQ_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(wa_finish_kernel, dim3(1), dim3(kDecideThreads), 0, st, p);
+int launch_wa_finish(const WaFinishParams* p, int n, hipStream_t st) {
+  if (!p || n < 1 || n > kWaGroup) return MOFQ_ERR_INVALID_ARG;
+  WaFinishArgs a{};
+  for (int i = 0; i < n; ++i) {
+    const DecideParams& d = p[i].d;
+    if (d.units < 1 || d.n_cand < 1 || d.n_cand > MOFQ_MAX_CANDIDATES || !d.result) return MOFQ_ERR_INVALID_ARG;
+    for (int c = 0; c < d.n_cand; ++c)
+      if (!d.err[c] || p[i].fmt_slot[c] < 0 || p[i].fmt_slot[c] > 1) return MOFQ_ERR_INVALID_ARG;
+    a.p[i] = p[i];
+  }
+  hipLaunchKernelGGL(wa_finish_kernel, dim3(static_cast<unsigned>(n)), dim3(kDecideThreads), 0, st, a);
   return hip_status(hipGetLastError());
 }
 
-int launch_wa_copy(const WaCopyParams& p, hipStream_t st) {
-  if (!p.result || p.n_cand < 1 || p.n_cand > MOFQ_MAX_CANDIDATES) return MOFQ_ERR_INVALID_ARG;
+int launch_wa_copy(const WaCopyParams* p, int n, hipStream_t st) {
+  if (!p || n < 1 || n > kWaGroup) return MOFQ_ERR_INVALID_ARG;
   WaCopyArgs a{};
-  a.p = p;
-  const int64_t cap = p.max_blocks > 0 ? p.max_blocks : 256 * 8;
-  int64_t want[2] = {0, 0};
-  for (int i = 0; i < 2; ++i) {
-    if (!p.t[i].dst) continue;
-    if (p.t[i].bytes < 16 || p.t[i].bytes % 16 != 0 || !p.t[i].src[0] || !p.t[i].src[1]) return MOFQ_ERR_INVALID_ARG;
-    want[i] = (p.t[i].bytes / 16 + 256 * 4 - 1) / (256 * 4);
+  int64_t want[kCopyTensors];
+  int64_t total = 0;
+  for (int i = 0; i < n; ++i) {
+    if (!p[i].result || p[i].n_cand < 1 || p[i].n_cand > MOFQ_MAX_CANDIDATES) return MOFQ_ERR_INVALID_ARG;
+    for (int which = 0; which < 2; ++which) {
+      const WaCopyTensor& t = p[i].t[which];
+      if (!t.dst) continue;
+      if (t.bytes < 16 || t.bytes % 16 != 0 || !t.src[0] || !t.src[1]) return MOFQ_ERR_INVALID_ARG;
+      const int k = a.n++;
+      a.result[k] = p[i].result;
+      a.n_cand[k] = p[i].n_cand;
+      for (int c = 0; c < MOFQ_MAX_CANDIDATES; ++c) a.fmt_slot[k][c] = p[i].fmt_slot[c];
+      a.t[k] = t;
+      want[k] = (t.bytes / 16 + 256 * 4 - 1) / (256 * 4);
+      total += want[k];
+    }
   }
-  const int64_t total = want[0] + want[1];
-  if (total < 1) return MOFQ_OK;
-  for (int i = 0; i < 2; ++i)
-    if (want[i]) a.n_blocks[i] = static_cast<int32_t>(total <= cap ? want[i] : std::max<int64_t>(1, want[i] * cap / total));
-  hipLaunchKernelGGL(wa_copy_kernel, dim3(static_cast<unsigned>(a.n_blocks[0] + a.n_blocks[1])), dim3(256), 0, st, a);
+  if (a.n < 1) return MOFQ_OK;
+  const int64_t cap = 256 * 8;
+  for (int k = 0; k < a.n; ++k) {
+    const int64_t nb = total <= cap ? want[k] : std::max<int64_t>(1, want[k] * cap / total);
+    a.first_block[k + 1] = a.first_block[k] + static_cast<int32_t>(nb);
+  }
+  hipLaunchKernelGGL(wa_copy_kernel, dim3(static_cast<unsigned>(a.first_block[a.n])), dim3(256), 0, st, a);
   return hip_status(hipGetLastError());
 }
 

@@ -156,29 +156,34 @@ struct WaGemmParams {
 int wa_gemm_blocks(int64_t M, int64_t N);
 int launch_wa_gemm(const WaGemmParams& p, hipStream_t stream);
 
-// The fused weight-activation path (both 8-bit formats as candidates, per-tensor scales).
-// Pass 1 + 2 over the two inputs of a layer in one launch each: largest magnitude, then both
-// quantized copies and the tensor error of each format.  A tensor with data == nullptr is
-// skipped (an activation that the previous layer already prepared).
+// The fused weight-activation path (both 8-bit formats as candidates, per-tensor scales)
+// works on groups of up to kWaGroup layers: one launch per step for the whole group.
+constexpr int kWaGroup = 8;
+
+// Pass 1 + 2 over the inputs of the group's layers (up to 2 * kWaGroup tensors, one launch per
+// pass): largest magnitude, then both quantized copies and the tensor error of each format.
+// A tensor with data == nullptr is skipped (an activation that the previous layer already
+// prepared).  The tensor error is left as partial sums over wa_prep_segments() fixed pieces of
+// the tensor.
 struct WaPrepTensor {
   const void* data;          // bf16 [rows][cols], rows `ld` elements apart
   int64_t rows, cols, ld;
   float ratio;               // clip ratio of the scale (1 for activations)
-  float* absmax_part;        // [wa_prep_blocks(rows, cols)]
-  double* sse_part;          // [wa_prep_blocks(rows, cols)][2]: INT8, E4M3
+  float* absmax_part;        // [kTensorBlocks]
+  double* sse_part;          // [wa_prep_segments(rows, cols)][2]: INT8, E4M3
   uint8_t* q_i8;             // [rows][cols] int8 codes, dense
   uint8_t* q_f8;             // [rows][cols] e4m3 codes, dense
   uint8_t* q_g;              // [rows][cols] e4m3 grid values as bf16, dense; or nullptr
   float* scale;              // [2]: INT8 scale, E4M3 scale
 };
-int wa_prep_blocks(int64_t rows, int64_t cols);
-int launch_wa_prep(const WaPrepTensor& x, const WaPrepTensor& w, hipStream_t stream);
+int wa_prep_segments(int64_t rows, int64_t cols);
+int launch_wa_prep(const WaPrepTensor* t, int n, hipStream_t stream);
 
-// After the matrix kernel: fixed-order sums of its per-tile partials, Algorithm 1's select,
-// the result record, and the one-unit outputs (scale, clip index 0, tensor error) of the
-// chosen format for both tensors -- one workgroup.
+// After the matrix kernels of a group: per layer (one workgroup each) the fixed-order sums of
+// its per-tile partials, Algorithm 1's select, the result record, and the one-unit outputs
+// (scale, clip index 0, tensor error) of the chosen format for both tensors.
 struct WaFinishTensor {
-  int32_t n_blocks;          // 0: no outputs for this tensor
+  int32_t n_segments;        // 0: no outputs for this tensor
   const double* sse_part;    // as written by launch_wa_prep
   const float* scale;
   void* out_scales;          // one float; may be nullptr
@@ -190,11 +195,11 @@ struct WaFinishParams {
   int32_t fmt_slot[MOFQ_MAX_CANDIDATES];   // per candidate: 0 INT8, 1 E4M3
   WaFinishTensor t[2];                     // X, W
 };
-int launch_wa_finish(const WaFinishParams& p, hipStream_t stream);
+int launch_wa_finish(const WaFinishParams* p, int n, hipStream_t stream);
 
-// Codes of the chosen format into the caller's buffers: a copy of the quantized operand the
-// matrix kernel used (no second quantization).  Where the chosen format's codes already sit
-// in the destination (src == dst) nothing is moved.
+// Codes of the chosen format into the caller's buffers, for the layers of a group in one
+// launch: a copy of the quantized operand the matrix kernel used (no second quantization).
+// Where the chosen format's codes already sit in the destination (src == dst) nothing is moved.
 struct WaCopyTensor {
   const uint8_t* src[2];     // INT8 codes, E4M3 codes
   uint8_t* dst;              // nullptr: nothing to do
@@ -205,9 +210,8 @@ struct WaCopyParams {
   int32_t n_cand;
   int32_t fmt_slot[MOFQ_MAX_CANDIDATES];
   WaCopyTensor t[2];
-  int32_t max_blocks;        // 0: fill the device
 };
-int launch_wa_copy(const WaCopyParams& p, hipStream_t stream);
+int launch_wa_copy(const WaCopyParams* p, int n, hipStream_t stream);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? MOFQ_OK : MOFQ_ERR_HIP; }
 

@@ -1,16 +1,21 @@
-// Per-tensor 8-bit quantization of the two inputs of a linear layer for the layer-output
-// metric of the weight-activation case (Section 3.2: A_out = W * A_in with both inputs
-// quantized; Section 5: INT8 against FP8-E4M3, activations per tensor).  The activation X
-// and the weight W of a layer go through every pass together, one launch per pass:
+// Per-tensor 8-bit quantization of the inputs of linear layers for the layer-output metric of
+// the weight-activation case (Section 3.2: A_out = W * A_in with both inputs quantized;
+// Section 5: INT8 against FP8-E4M3, activations per tensor).  The activations and weights of a
+// group of layers go through every pass together, one launch per pass:
 //
 //   1. largest magnitude of each tensor (per-workgroup partial maxima);
 //   2. both formats at once: the INT8 codes, the E4M3 codes and, where the exact E4M3
 //      product is wanted, the E4M3 grid values as bf16, all from one read of the tensor,
-//      with the tensor error of each format as per-workgroup partial sums in fp64.
+//      with the tensor error of each format as partial sums in fp64.
 //
 // The small dependent steps (folding the partial maxima, the two scales) are redone by every
 // workgroup of pass 2 from the partials, so no one-workgroup kernel sits between the passes.
-// Nothing is accumulated atomically: every sum has a fixed order.
+// Nothing is accumulated atomically.  A tensor is cut into a fixed number of segments that
+// depends only on its shape; a workgroup takes whole segments and leaves one partial error sum
+// per segment, so the sums do not depend on how many workgroups a launch has (which varies
+// with how many tensors share it).
+#include <algorithm>
+
 #include "mofq_device.h"
 #include "mofq_internal.h"
 
@@ -21,11 +26,13 @@ namespace {
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
+constexpr int kMaxTensors = 2 * kWaGroup;
 
 struct PrepTensor {
   const uint16_t* data;
   int64_t n_chunks, cpr, ld;   // 8-element chunks in the tensor and per row; elements between rows
-  int32_t n_blocks;            // workgroups that walk this tensor; 0: the tensor is skipped
+  int32_t n_seg;               // segments of the tensor
+  int32_t seg_chunks;          // chunks per segment (the last one may be shorter)
   float ratio;                 // clip ratio of the scale
   float* absmax_part;
   double* sse_part;
@@ -35,16 +42,18 @@ struct PrepTensor {
   float* scale;
 };
 struct PrepArgs {
-  PrepTensor t[2];
+  PrepTensor t[kMaxTensors];
+  int32_t first_block[kMaxTensors + 1];   // workgroups [first_block[k], first_block[k + 1]) walk tensor k
+  int32_t n;
 };
 
-// Workgroups [0, t[0].n_blocks) walk t[0], the rest t[1]; returns the workgroup's index
-// within its tensor.
-MOFQ_DEV int my_tensor(const PrepArgs& a, PrepTensor& t) {
-  const int nb0 = a.t[0].n_blocks;
-  const bool second = static_cast<int>(blockIdx.x) >= nb0;
-  t = second ? a.t[1] : a.t[0];
-  return static_cast<int>(blockIdx.x) - (second ? nb0 : 0);
+// The workgroup's tensor, its index among the tensor's workgroups and their number.
+MOFQ_DEV const PrepTensor& my_tensor(const PrepArgs& a, int& b, int& nb) {
+  int k = 0;
+  while (k + 1 < a.n && static_cast<int>(blockIdx.x) >= a.first_block[k + 1]) ++k;   // uniform
+  b = static_cast<int>(blockIdx.x) - a.first_block[k];
+  nb = a.first_block[k + 1] - a.first_block[k];
+  return a.t[k];
 }
 
 // Address of chunk c: rows are dense in the outputs, `ld` apart in the input.
@@ -54,21 +63,24 @@ MOFQ_DEV const uint16_t* chunk_src(const PrepTensor& t, int64_t c) {
   return t.data + row * t.ld + (c - row * t.cpr) * 8;
 }
 
-__global__ __launch_bounds__(kThreads) void wa_absmax_pair_kernel(const PrepArgs a) {
+constexpr int kInFlight = 4;   // 16-byte loads in flight per lane (largest-magnitude pass)
+constexpr int kQuantInFlight = 2;   // quantize pass: every further chunk in flight costs some 17 registers
+
+__global__ __launch_bounds__(kThreads) void wa_absmax_kernel(const PrepArgs a) {
   using L = Load8<BF16>;
   __shared__ float s_wmax[kThreads / 64];
-  PrepTensor t;
-  const int b = my_tensor(a, t);
+  int b, nb;
+  const PrepTensor& t = my_tensor(a, b, nb);
   const int tid = threadIdx.x;
-  const int64_t stride = static_cast<int64_t>(t.n_blocks) * kThreads;
+  const int64_t stride = static_cast<int64_t>(nb) * kThreads;
   float amax = 0.0f;
   int64_t c = static_cast<int64_t>(b) * kThreads + tid;
-  for (; c + 3 * stride < t.n_chunks; c += 4 * stride) {   // four 16-byte loads in flight per lane
-    float v[4][8];
+  for (; c + (kInFlight - 1) * stride < t.n_chunks; c += kInFlight * stride) {
+    float v[kInFlight][8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) L::load(chunk_src(t, c + u * stride), v[u]);
+    for (int u = 0; u < kInFlight; ++u) L::load(chunk_src(t, c + u * stride), v[u]);
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < kInFlight; ++u)
 #pragma unroll
       for (int i = 0; i < 8; ++i) amax = __builtin_fmaxf(amax, __builtin_fabsf(v[u][i]));
   }
@@ -86,8 +98,14 @@ __global__ __launch_bounds__(kThreads) void wa_absmax_pair_kernel(const PrepArgs
 }
 
 // One chunk in both formats: codes, optional grid values, squared differences.
-MOFQ_DEV void quant_chunk(const PrepTensor& t, int64_t c, const float (&v)[8], float iA, float iB, double sAd,
+MOFQ_DEV void quant_chunk(const PrepTensor& t, int64_t c, const u32x4 raw, float iA, float iB, double sAd,
                           double sBd, double& accA, double& accB) {
+  float v[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = u2f(raw[i] << 16);           // bf16 is the top half of an fp32
+    v[2 * i + 1] = u2f(raw[i] & 0xFFFF0000u);
+  }
   uint32_t wi[2] = {0u, 0u};
   int wf[2] = {0, 0};
   u32x4 gb;
@@ -111,6 +129,9 @@ MOFQ_DEV void quant_chunk(const PrepTensor& t, int64_t c, const float (&v)[8], f
     const double e1 = __builtin_fma(-static_cast<double>(g[1]), sBd, static_cast<double>(v[i + 1]));
     accB = __builtin_fma(e0, e0, accB);
     accB = __builtin_fma(e1, e1, accB);
+    // one pair at a time: the two fp64 chains are sequential anyway, and scheduling all eight
+    // elements of a chunk together costs some 130 registers
+    __builtin_amdgcn_sched_barrier(0);
   }
   u32x2 oi, of;
   oi[0] = wi[0];
@@ -122,16 +143,15 @@ MOFQ_DEV void quant_chunk(const PrepTensor& t, int64_t c, const float (&v)[8], f
   if (t.q_g) reinterpret_cast<u32x4*>(t.q_g)[c] = gb;
 }
 
-__global__ __launch_bounds__(kThreads) void wa_quant_pair_kernel(const PrepArgs a) {
-  using L = Load8<BF16>;
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(5))) void wa_quant_kernel(const PrepArgs a) {
   __shared__ float s_tmp[kThreads / 64];
   __shared__ double s_part[kThreads / 64][2];
-  PrepTensor t;
-  const int b = my_tensor(a, t);
+  int b, nb;
+  const PrepTensor& t = my_tensor(a, b, nb);
   const int tid = threadIdx.x;
-  // the tensor's largest magnitude from the partials of the first pass
+  // the tensor's largest magnitude from the partials of the first pass (same launch shape)
   float amax = 0.0f;
-  for (int i = tid; i < t.n_blocks; i += kThreads) amax = __builtin_fmaxf(amax, t.absmax_part[i]);
+  for (int i = tid; i < nb; i += kThreads) amax = __builtin_fmaxf(amax, t.absmax_part[i]);
   amax = wave_max(amax);
   if ((tid & 63) == 0) s_tmp[tid >> 6] = amax;
   __syncthreads();
@@ -141,39 +161,47 @@ __global__ __launch_bounds__(kThreads) void wa_quant_pair_kernel(const PrepArgs 
   if (b == 0 && tid == 0) { t.scale[0] = sA; t.scale[1] = sB; }
   const float iA = 1.0f / sA, iB = 1.0f / sB;
   const double sAd = static_cast<double>(sA), sBd = static_cast<double>(sB);
-  double accA = 0.0, accB = 0.0;
-  const int64_t stride = static_cast<int64_t>(t.n_blocks) * kThreads;
-  int64_t c = static_cast<int64_t>(b) * kThreads + tid;
-  for (; c + stride < t.n_chunks; c += 2 * stride) {
-    float v[2][8];
-    L::load(chunk_src(t, c), v[0]);
-    L::load(chunk_src(t, c + stride), v[1]);
-    quant_chunk(t, c, v[0], iA, iB, sAd, sBd, accA, accB);
-    quant_chunk(t, c + stride, v[1], iA, iB, sAd, sBd, accA, accB);
+  const bool dense = t.ld == t.cpr * 8;
+  for (int seg = b; seg < t.n_seg; seg += nb) {
+    const int64_t lo = static_cast<int64_t>(seg) * t.seg_chunks;
+    const int64_t hi = (lo + t.seg_chunks < t.n_chunks) ? lo + t.seg_chunks : t.n_chunks;
+    double accA = 0.0, accB = 0.0;
+    int64_t c = lo + tid;
+    // dense input (uniform): several loads in flight; rows apart: one chunk at a time
+    for (; dense && c + (kQuantInFlight - 1) * kThreads < hi; c += kQuantInFlight * kThreads) {
+      u32x4 raw[kQuantInFlight];
+#pragma unroll
+      for (int u = 0; u < kQuantInFlight; ++u) raw[u] = *reinterpret_cast<const u32x4*>(t.data + (c + u * kThreads) * 8);
+#pragma unroll
+      for (int u = 0; u < kQuantInFlight; ++u) {
+        quant_chunk(t, c + u * kThreads, raw[u], iA, iB, sAd, sBd, accA, accB);
+        __builtin_amdgcn_sched_barrier(0);   // one chunk at a time: keeps the register count low
+      }
+    }
+    for (; c < hi; c += kThreads) {
+      const u32x4 raw = *reinterpret_cast<const u32x4*>(chunk_src(t, c));
+      quant_chunk(t, c, raw, iA, iB, sAd, sBd, accA, accB);
+    }
+    accA = wave_sum(accA);
+    accB = wave_sum(accB);
+    __syncthreads();   // the previous segment's partials have been read
+    if ((tid & 63) == 0) { s_part[tid >> 6][0] = accA; s_part[tid >> 6][1] = accB; }
+    __syncthreads();
+    if (tid < 2)
+      t.sse_part[static_cast<int64_t>(seg) * 2 + tid] = (s_part[0][tid] + s_part[1][tid]) + (s_part[2][tid] + s_part[3][tid]);
   }
-  for (; c < t.n_chunks; c += stride) {
-    float v[8];
-    L::load(chunk_src(t, c), v);
-    quant_chunk(t, c, v, iA, iB, sAd, sBd, accA, accB);
-  }
-  accA = wave_sum(accA);
-  accB = wave_sum(accB);
-  if ((tid & 63) == 0) { s_part[tid >> 6][0] = accA; s_part[tid >> 6][1] = accB; }
-  __syncthreads();
-  if (tid < 2)
-    t.sse_part[static_cast<int64_t>(b) * 2 + tid] = (s_part[0][tid] + s_part[1][tid]) + (s_part[2][tid] + s_part[3][tid]);
 }
 
 bool fill(const WaPrepTensor& p, PrepTensor* t) {
   *t = PrepTensor{};
-  if (!p.data) return true;   // skipped
   if (p.rows < 1 || p.cols < 8 || p.cols % 8 != 0 || p.ld < p.cols || p.ld % 8 != 0) return false;
   if (!p.absmax_part || !p.sse_part || !p.q_i8 || !p.q_f8 || !p.scale) return false;
   t->data = static_cast<const uint16_t*>(p.data);
   t->cpr = p.cols / 8;
   t->n_chunks = p.rows * t->cpr;
   t->ld = p.ld;
-  t->n_blocks = wa_prep_blocks(p.rows, p.cols);
+  t->n_seg = wa_prep_segments(p.rows, p.cols);
+  t->seg_chunks = static_cast<int32_t>((t->n_chunks + t->n_seg - 1) / t->n_seg);
   t->ratio = p.ratio;
   t->absmax_part = p.absmax_part;
   t->sse_part = p.sse_part;
@@ -186,19 +214,35 @@ bool fill(const WaPrepTensor& p, PrepTensor* t) {
 
 }  // namespace
 
-int wa_prep_blocks(int64_t rows, int64_t cols) {
+int wa_prep_segments(int64_t rows, int64_t cols) {
   const int64_t n_chunks = rows * (cols / 8);
   const int64_t b = (n_chunks + kThreads - 1) / kThreads;
   return static_cast<int>(b < 1 ? 1 : (b > kTensorBlocks ? kTensorBlocks : b));
 }
 
-int launch_wa_prep(const WaPrepTensor& x, const WaPrepTensor& w, hipStream_t st) {
+int launch_wa_prep(const WaPrepTensor* p, int n, hipStream_t st) {
+  if (!p || n < 1 || n > kMaxTensors) return MOFQ_ERR_INVALID_ARG;
   PrepArgs a{};
-  if (!fill(x, &a.t[0]) || !fill(w, &a.t[1])) return MOFQ_ERR_INVALID_ARG;
-  const int blocks = a.t[0].n_blocks + a.t[1].n_blocks;
-  if (blocks < 1) return MOFQ_OK;
-  hipLaunchKernelGGL(wa_absmax_pair_kernel, dim3(blocks), dim3(kThreads), 0, st, a);
-  hipLaunchKernelGGL(wa_quant_pair_kernel, dim3(blocks), dim3(kThreads), 0, st, a);
+  int64_t total_seg = 0;
+  for (int i = 0; i < n; ++i) {
+    if (!p[i].data) continue;   // skipped
+    if (!fill(p[i], &a.t[a.n])) return MOFQ_ERR_INVALID_ARG;
+    if (a.t[a.n].n_chunks > (int64_t{1} << 40)) return MOFQ_ERR_UNSUPPORTED;
+    total_seg += a.t[a.n].n_seg;
+    ++a.n;
+  }
+  if (a.n < 1) return MOFQ_OK;
+  // One workgroup per segment while the launch stays within 16 workgroups per compute unit's
+  // worth (4096); beyond that every tensor gets its share and workgroups take several segments.
+  constexpr int64_t kMaxBlocks = 4096;
+  for (int k = 0; k < a.n; ++k) {
+    int64_t nb = a.t[k].n_seg;
+    if (total_seg > kMaxBlocks) nb = std::max<int64_t>(1, nb * kMaxBlocks / total_seg);
+    a.first_block[k + 1] = a.first_block[k] + static_cast<int32_t>(nb);
+  }
+  const int blocks = a.first_block[a.n];
+  hipLaunchKernelGGL(wa_absmax_kernel, dim3(blocks), dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL(wa_quant_kernel, dim3(blocks), dim3(kThreads), 0, st, a);
   return hip_status(hipGetLastError());
 }
 
