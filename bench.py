@@ -197,8 +197,8 @@ def cpu_baseline(weights, outs, clip, cands):
 def make_weights(shapes, dev, dtype=None):
     import torch
     import mofq_inputs as mi
-    return [mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, mi.LINEAR_NAMES.index(name)),
-                                 dtype=dtype or torch.float16, device=dev) for b, name, o, n in shapes]
+    return [mi.model_weight(1, b, mi.LINEAR_NAMES.index(name), o, n, dtype=dtype or torch.float16, device=dev)
+            for b, name, o, n in shapes]
 
 
 def run_w4(args, shapes, dev, weights, group, model, steps, warmup, ceilings=None, want_cpu=False):
@@ -531,7 +531,7 @@ def run_fp4_variants(args, shapes, dev):
     ws = out = None
     t0 = time.perf_counter()
     for i, (b, name, o, n) in enumerate(shapes):
-        w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, mi.LINEAR_NAMES.index(name)), device=dev)
+        w = mi.model_weight(1, b, mi.LINEAR_NAMES.index(name), o, n, device=dev)
         need = mq.workspace_bytes(w, None, 2, mq.ERR_TENSOR, cfg)
         if ws is None or ws.numel() < need:
             ws = torch.empty(need, dtype=torch.uint8, device=dev)
@@ -576,7 +576,7 @@ def run_w4_units(args, shapes, dev):
     mixed = torch.zeros(len(shapes), dtype=torch.float64, device=dev)
     ws_bytes = 0
     for b, name, o, n in shapes:
-        w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, mi.LINEAR_NAMES.index(name)), device=dev)
+        w = mi.model_weight(1, b, mi.LINEAR_NAMES.index(name), o, n, device=dev)
         weights.append(w)
         outs.append(mq.alloc_qbuffers(o, n, 4, cfg, dev))
         tags.append(torch.empty(o * (n // GROUP), dtype=torch.uint8, device=dev))
@@ -736,7 +736,7 @@ def full_parity_wa(args, dev):
             if role[name] not in acts:
                 acts[role[name]] = mi.activations(TOKENS, n, seed=mi.tensor_seed(3, b, role[name], 1), device=dev)
             xs.append(acts[role[name]])
-            ws_.append(mi.llama_like_weight(o, n, seed=mi.tensor_seed(3, b, lin), dtype=torch.bfloat16, device=dev))
+            ws_.append(mi.model_weight(3, b, lin, o, n, dtype=torch.bfloat16, device=dev))
         got = {}
         for metric, key in ((mq.ERR_LAYER_OUTPUT, "exact"), (mq.ERR_LAYER_OUTPUT_FP8_UNIT, "fp8_unit")):
             w_outs = [mq.alloc_qbuffers(o, n, 8, cfg, dev) for _, _, o, n in shapes]

@@ -11,6 +11,7 @@ The real LLaMA weights and calibration activations the paper samples
 """
 from __future__ import annotations
 
+import hashlib
 import zlib
 from typing import List, Tuple
 
@@ -93,6 +94,24 @@ def llama_like_weight(rows: int, cols: int, seed: int, dtype=torch.float16,
         rows_idx = mask.nonzero(as_tuple=True)[0]
         w[mask] = sigma[rows_idx, 0] * kappa * t3
     return w.to(dtype).contiguous()
+
+
+def layer_outlier_frac(config_id: int, block: int, linear: int) -> float:
+    """Share of heavy-tail entries of one layer of a model-shaped set: log-uniform over
+    [1.3e-5, 5e-3], fixed by (config, block, linear).  Layers differ in how heavy their tails
+    are; with this spread about one layer in eight is close enough to Gaussian for the integer
+    format to win the 4-bit select, the others prefer the floating-point format."""
+    digest = hashlib.sha256(f"mofq-tail:{config_id}:{block}:{linear}".encode()).digest()
+    u = int.from_bytes(digest[:6], "little") / float(1 << 48)
+    return float(1.3e-5 * (5e-3 / 1.3e-5) ** u)
+
+
+def model_weight(config_id: int, block: int, linear: int, rows: int, cols: int,
+                 dtype=torch.float16, device="cpu") -> torch.Tensor:
+    """The weight of linear `linear` of block `block` in the model-shaped set of a config:
+    llama_like_weight with the layer's seed and the layer's share of heavy-tail entries."""
+    return llama_like_weight(rows, cols, seed=tensor_seed(config_id, block, linear), dtype=dtype,
+                             device=device, outlier_frac=layer_outlier_frac(config_id, block, linear))
 
 
 def outlier_channels(in_features: int, n: int = 6, seed: int = 1234) -> np.ndarray:

@@ -75,19 +75,19 @@ def _check_sampled(mq, w, gran, clip, group, f16, n_sample, seed, label):
 
 @pytest.mark.parametrize("name,o,n", [("q", 4096, 4096), ("gate", 11008, 4096), ("down", 4096, 11008)])
 def test_7b_shapes_per_channel_k100(mq, name, o, n):
-    w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, 0, mi.LINEAR_NAMES.index(name)), device=DEV)
+    w = mi.model_weight(1, 0, mi.LINEAR_NAMES.index(name), o, n, device=DEV)
     _check_sampled(mq, w, orc.PER_CHANNEL, mi.clip_ratios(100), 0, False, 48, 1, f"7b-{name}")
 
 
 @pytest.mark.parametrize("name,o,n", [("q", 4096, 4096), ("down", 4096, 11008)])
 def test_7b_shapes_group128_k50(mq, name, o, n):
-    w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(2, 0, mi.LINEAR_NAMES.index(name)), device=DEV)
+    w = mi.model_weight(2, 0, mi.LINEAR_NAMES.index(name), o, n, device=DEV)
     _check_sampled(mq, w, orc.PER_GROUP, mi.clip_ratios(50), 128, True, 24, 2, f"7b-group-{name}")
 
 
 @pytest.mark.parametrize("name,o,n", [("q", 8192, 8192), ("gate", 22016, 8192), ("down", 8192, 22016)])
 def test_65b_shapes_per_channel_k100(mq, name, o, n):
-    w = mi.llama_like_weight(o, n, seed=mi.tensor_seed(4, 0, mi.LINEAR_NAMES.index(name)), device=DEV)
+    w = mi.model_weight(4, 0, mi.LINEAR_NAMES.index(name), o, n, device=DEV)
     _check_sampled(mq, w, orc.PER_CHANNEL, mi.clip_ratios(100), 0, False, 24, 3, f"65b-{name}")
 
 
@@ -100,7 +100,7 @@ def test_whole_block_all_rows_against_oracle(mq):
     clip = mi.clip_ratios(100)
     cfg = mq.Cfg(orc.PER_CHANNEL, clip)
     shapes = mi.block_linear_shapes("7b")
-    ws_ = [mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, 1, li), device=DEV) for li, (_, o, n) in enumerate(shapes)]
+    ws_ = [mi.model_weight(1, 1, li, o, n, device=DEV) for li, (_, o, n) in enumerate(shapes)]
     outs = [mq.alloc_qbuffers(o, n, 4, cfg, DEV) for _, o, n in shapes]
     batch = mq.LayerBatch(ws_, outs)
     results = mq.alloc_result(DEV, len(shapes))
@@ -126,9 +126,11 @@ def test_whole_block_all_rows_against_oracle(mq):
                                   outs[i].clip_idx.cpu().numpy(), outs[i].unit_err.cpu().numpy())
         picks.append(ref.best)
     print(f"[case]   near-tie rows: {band}", flush=True)
-    # Table 2 reports 88.9-97.9 % of layers choosing FP4 on real weights; Gaussian rows with
-    # heavy-tailed outliers behave the same way
-    assert sum(picks) >= 6
+    # Table 2 reports 88.9-97.9 % of layers choosing FP4 on real weights.  Here the layers' shares
+    # of heavy-tail entries differ (mofq_inputs.layer_outlier_frac): gate and up of this block
+    # are nearly Gaussian, where INT4 is the better format; the others prefer FP4
+    print(f"[case]   choices (0 = INT4, 1 = FP4): {picks}", flush=True)
+    assert sum(picks) >= 4
 
 
 def test_7b_first_batch_through_select_layers(mq):
@@ -139,7 +141,7 @@ def test_7b_first_batch_through_select_layers(mq):
     clip = mi.clip_ratios(100)
     cfg = mq.Cfg(orc.PER_CHANNEL, clip)
     shapes = [(b, li, o, n) for b in range(2) for li, (_, o, n) in enumerate(mi.block_linear_shapes("7b"))][:10]
-    ws_ = [mi.llama_like_weight(o, n, seed=mi.tensor_seed(1, b, li), device=DEV) for b, li, o, n in shapes]
+    ws_ = [mi.model_weight(1, b, li, o, n, device=DEV) for b, li, o, n in shapes]
     outs = [mq.alloc_qbuffers(o, n, 4, cfg, DEV) for _, _, o, n in shapes]
     batch = mq.LayerBatch(ws_, outs)
     first = batch.search_groups(CANDS)
