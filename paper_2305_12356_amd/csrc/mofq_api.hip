@@ -121,6 +121,7 @@ struct SweepEmit {
   uint8_t* i8;
   void* f8;
   int f8_as_bf16;
+  void* grid[2];   // per-channel pair: bf16 grid values of candidate 0 and candidate 1
 };
 
 // Parameters of the launch that scores candidates c0 .. c0 + n - 1 (n = 2: a pair of different
@@ -179,6 +180,10 @@ int sweep_candidates(const mofq_tensor_t* t, const int32_t* cand, int n_cand,
       p.emit_i8 = em->i8;
       p.emit_f8 = em->f8;
       p.emit_f8_as_bf16 = em->f8_as_bf16;
+      // launch slots are in (INT, FP) order whatever the candidates' order
+      const bool swapped = p.fmt[0] != cand[c0];
+      p.emit_grid[0] = em->grid[swapped ? 1 : 0];
+      p.emit_grid[1] = em->grid[swapped ? 0 : 1];
     }
     rc = launch_sweep(p, st);
     if (rc != MOFQ_OK) return rc;
@@ -298,26 +303,32 @@ int wo_output_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_
                     const mofq_scale_cfg_t* w_cfg, const WoOutWs& a, hipStream_t st,
                     hipEvent_t ev0, hipEvent_t ev1) {
   int rc;
-  if ((rc = sweep_candidates(w, cand, n_cand, w_cfg, a.wrec, st))) return rc;
+  // A pair of different formats with per-channel absmax scales (one clip ratio): the scoring pass
+  // holds each row in registers and writes both candidates' grid values itself.
+  const bool fused = n_cand == 2 && paired(cand[0], cand[1]) && w_cfg->gran == MOFQ_PER_CHANNEL && w_cfg->n_clip == 1;
+  const SweepEmit em{nullptr, nullptr, 0, {a.wg[0], a.wg[1]}};
+  if ((rc = sweep_candidates(w, cand, n_cand, w_cfg, a.wrec, st, nullptr, fused ? &em : nullptr))) return rc;
   WaGemmParams g{};
   for (int c = 0; c < n_cand; ++c) {
-    EmitParams e{};
-    e.w = w->data;
-    e.dtype = w->dtype;
-    e.rows = w->rows;
-    e.cols = w->cols;
-    e.ld = w->ld;
-    e.gran = w_cfg->gran;
-    e.group = 0;
-    e.n_cand = 1;
-    e.fmt[0] = cand[c];
-    e.scale[0] = a.wrec.scale[c];
-    e.clip[0] = a.wrec.clip[c];
-    e.err[0] = a.wrec.err[c];
-    e.result = nullptr;
-    e.out.codes = a.wg[c];
-    e.as_bf16_values = 1;
-    if ((rc = launch_emit(e, st))) return rc;
+    if (!fused) {
+      EmitParams e{};
+      e.w = w->data;
+      e.dtype = w->dtype;
+      e.rows = w->rows;
+      e.cols = w->cols;
+      e.ld = w->ld;
+      e.gran = w_cfg->gran;
+      e.group = 0;
+      e.n_cand = 1;
+      e.fmt[0] = cand[c];
+      e.scale[0] = a.wrec.scale[c];
+      e.clip[0] = a.wrec.clip[c];
+      e.err[0] = a.wrec.err[c];
+      e.result = nullptr;
+      e.out.codes = a.wg[c];
+      e.as_bf16_values = 1;
+      if ((rc = launch_emit(e, st))) return rc;
+    }
     g.q[c].kind = WA_GRID_BF16;
     g.q[c].x = x->data;          // the unquantized input, scale 1
     g.q[c].w = a.wg[c];
@@ -389,7 +400,7 @@ int wa_score(const mofq_tensor_t* w, const mofq_tensor_t* x, const int32_t* cand
   if (n_cand == 2)
     both = (cand[0] == MOFQ_INT8 && cand[1] == MOFQ_FP8_E4M3) || (cand[0] == MOFQ_FP8_E4M3 && cand[1] == MOFQ_INT8);
   const bool fused_x = both, fused_w = both && w_cfg->gran == MOFQ_PER_TENSOR;
-  const SweepEmit ex{a.xq[0], a.xq[1], fp8_unit ? 0 : 1}, ew{a.wq[0], a.wq[1], fp8_unit ? 0 : 1};
+  const SweepEmit ex{a.xq[0], a.xq[1], fp8_unit ? 0 : 1, {nullptr, nullptr}}, ew{a.wq[0], a.wq[1], fp8_unit ? 0 : 1, {nullptr, nullptr}};
   if ((rc = sweep_candidates(x, cand, n_cand, &xc, a.xrec, st, nullptr, fused_x ? &ex : nullptr))) return rc;
   if ((rc = sweep_candidates(w, cand, n_cand, w_cfg, a.wrec, st, nullptr, fused_w ? &ew : nullptr))) return rc;
   WaGemmParams g{};

@@ -42,6 +42,9 @@ struct SweepParams {
   uint8_t* emit_i8;         // int8 codes, or nullptr
   void* emit_f8;            // e4m3 codes (1 byte) or grid values as bf16 (2 bytes)
   int32_t emit_f8_as_bf16;
+  // per-channel pair of two different formats (bf16 input) with one clip ratio only: the pass
+  // also writes the grid values of format slot f as bf16, dense [rows][cols], to emit_grid[f]
+  void* emit_grid[kMaxFmt];
 };
 
 constexpr int kTensorBlocks = 1024;  // partial results of per-tensor passes

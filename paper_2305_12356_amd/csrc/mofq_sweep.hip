@@ -36,6 +36,7 @@ struct SweepArgs {
   uint8_t* emit_i8;          // per-tensor 8-bit pair: also write the codes (see SweepParams)
   void* emit_f8;
   int32_t emit_f8_as_bf16;
+  uint16_t* emit_grid[kMaxFmt];   // per-channel single-candidate pair: grid values as bf16 (see SweepParams)
   float clip[MOFQ_MAX_CLIP];
 };
 
@@ -319,8 +320,10 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(CH <= 4
 #ifndef K1_WAVES
 #define K1_WAVES 4
 #endif
-template <typename In, int FA, int FB, int THREADS, int CH>
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(K1_WAVES))) void sweep_channel_single_kernel(const SweepArgs a) {
+// GRID: the pass also writes the grid values of both formats as bf16 (dense rows), the operands
+// of the weight-only layer-output products, so that they cost no further read of the tensor.
+template <typename In, int FA, int FB, int THREADS, int CH, bool GRID = false>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(GRID ? 2 : K1_WAVES))) void sweep_channel_single_kernel(const SweepArgs a) {
   using L = Load8<In>;
   constexpr int NF = (FB >= 0) ? 2 : 1;
   constexpr int FBX = (FB >= 0) ? FB : FA;
@@ -374,10 +377,37 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(K1_WAVE
   uint32_t carry = 0;
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
+    if constexpr (GRID) {
+      // grid values have at most 7 significant bits: exact in bf16 (the top half of an fp32)
+      u32x4 ga, gb;
 #pragma unroll
-    for (int i = 0; i < 8; i += 2) {
-      score2_f64<FA>(accA, x[j * 8 + i], x[j * 8 + i + 1], iA, sAd, carry);
-      if constexpr (NF == 2) score2_f64<FBX>(accB, x[j * 8 + i], x[j * 8 + i + 1], iB, sBd, carry);
+      for (int i = 0; i < 8; i += 2) {
+        const float x0 = x[j * 8 + i], x1 = x[j * 8 + i + 1];
+        const f32x2 qa = grid2<FA>(x0 * iA, x1 * iA, carry);
+        const f32x2 qb = grid2<FBX>(x0 * iB, x1 * iB, carry);
+        ga[i >> 1] = (f2u(qa[0]) >> 16) | (f2u(qa[1]) & 0xFFFF0000u);
+        gb[i >> 1] = (f2u(qb[0]) >> 16) | (f2u(qb[1]) & 0xFFFF0000u);
+        const double a0 = __builtin_fma(-static_cast<double>(qa[0]), sAd, static_cast<double>(x0));
+        const double a1 = __builtin_fma(-static_cast<double>(qa[1]), sAd, static_cast<double>(x1));
+        accA = __builtin_fma(a0, a0, accA);
+        accA = __builtin_fma(a1, a1, accA);
+        const double b0 = __builtin_fma(-static_cast<double>(qb[0]), sBd, static_cast<double>(x0));
+        const double b1 = __builtin_fma(-static_cast<double>(qb[1]), sBd, static_cast<double>(x1));
+        accB = __builtin_fma(b0, b0, accB);
+        accB = __builtin_fma(b1, b1, accB);
+      }
+      const int64_t c0 = (static_cast<int64_t>(j) * THREADS + tid) * 8;
+      if (c0 < a.cols) {
+        const int64_t e8 = (row * a.cols + c0) / 8;
+        reinterpret_cast<u32x4*>(a.emit_grid[0])[e8] = ga;
+        reinterpret_cast<u32x4*>(a.emit_grid[1])[e8] = gb;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; i += 2) {
+        score2_f64<FA>(accA, x[j * 8 + i], x[j * 8 + i + 1], iA, sAd, carry);
+        if constexpr (NF == 2) score2_f64<FBX>(accB, x[j * 8 + i], x[j * 8 + i + 1], iB, sBd, carry);
+      }
     }
   }
   accA = wave_sum(accA);
@@ -869,7 +899,14 @@ int launch_channel(const SweepArgs& a, hipStream_t st) {
   const int64_t chunks = a.cols / 8;
 #define MOFQ_CH(THREADS, CH)                                                            \
   if (chunks <= static_cast<int64_t>(THREADS) * (CH)) {                                  \
-    if (a.n_clip == 1)                                                                   \
+    if (a.emit_grid[0]) {                                                                \
+      if constexpr (std::is_same<In, BF16>::value && FB >= 0) {                          \
+        if (a.n_clip != 1 || !a.emit_grid[1]) return MOFQ_ERR_UNSUPPORTED;               \
+        hipLaunchKernelGGL((sweep_channel_single_kernel<In, FA, FB, THREADS, CH, true>), grid, dim3(THREADS), 0, st, a); \
+      } else {                                                                           \
+        return MOFQ_ERR_UNSUPPORTED;                                                     \
+      }                                                                                  \
+    } else if (a.n_clip == 1)                                                            \
       hipLaunchKernelGGL((sweep_channel_single_kernel<In, FA, FB, THREADS, CH>), grid, dim3(THREADS), 0, st, a); \
     else                                                                                 \
       hipLaunchKernelGGL((sweep_channel_kernel<In, FA, FB, THREADS, CH>), grid, dim3(THREADS), 0, st, a); \
@@ -980,6 +1017,11 @@ int launch_sweep(const SweepParams& p, hipStream_t st) {
     a.emit_i8 = p.emit_i8;
     a.emit_f8 = p.emit_f8;
     a.emit_f8_as_bf16 = p.emit_f8_as_bf16;
+  }
+  if (p.emit_grid[0] || p.emit_grid[1]) {
+    if (p.gran != MOFQ_PER_CHANNEL || p.n_clip != 1 || p.n_fmt != 2) return MOFQ_ERR_UNSUPPORTED;
+    a.emit_grid[0] = static_cast<uint16_t*>(p.emit_grid[0]);
+    a.emit_grid[1] = static_cast<uint16_t*>(p.emit_grid[1]);
   }
   a.units = mofq_num_units(p.rows, p.cols, p.gran, p.group);
   for (int k = 0; k < p.n_clip; ++k) a.clip[k] = p.clip[k];

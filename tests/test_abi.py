@@ -172,3 +172,47 @@ def test_select_layers_long_candidate_lists_host_only(lib):
         assert rc in (0, -5), rc
     c5 = (C.c_int32 * 5)(lib.INT4, lib.FP4_E2M1, lib.INT4, lib.FP4_E2M1, lib.INT4)
     assert L.mofq_select_layers(n, w, c5, 5, C.byref(cfg), out, res, ws, 1 << 20, None, None) == -1
+
+
+def test_select_layers_wa_host_side(lib):
+    """mofq_select_layers_wa: workspace sizing and argument validation happen on the host, before
+    anything is enqueued (fake device addresses are never touched)."""
+    L = lib._lib
+    one = np.ones(1, dtype=np.float32)
+    cfg = lib.ScaleCfg(lib.PER_TENSOR, 0, lib.F32, 1, one.ctypes.data_as(C.POINTER(C.c_float)))
+    # a decoder block at a small size: q, k, v share one activation, gate and up another
+    dims = [(256, 128), (256, 128), (256, 128), (128, 128), (384, 128), (384, 128), (128, 384)]
+    n = len(dims)
+    w = (lib.TensorDesc * n)(*[lib.TensorDesc(0x100000 * (i + 1), lib.BF16, o, k, k) for i, (o, k) in enumerate(dims)])
+    xaddr = [0xA00000, 0xA00000, 0xA00000, 0xB00000, 0xC00000, 0xC00000, 0xD00000]
+    x = (lib.TensorDesc * n)(*[lib.TensorDesc(xaddr[i], lib.BF16, 64, k, k) for i, (o, k) in enumerate(dims)])
+    w_out = (lib.QOut * n)(*[lib.QOut(0x2000000 + 0x100000 * i, 0x3000000 + 256 * i, None, None) for i in range(n)])
+    cand = (C.c_int32 * 2)(lib.INT8, lib.FP8_E4M3)
+    need = {m: L.mofq_select_layers_wa_workspace_bytes(n, w, x, 2, m, C.byref(cfg))
+            for m in (lib.ERR_LAYER_OUTPUT, lib.ERR_LAYER_OUTPUT_FP8_UNIT)}
+    single = max(L.mofq_workspace_bytes(C.byref(w[i]), C.byref(x[i]), 2, lib.ERR_LAYER_OUTPUT, C.byref(cfg)) for i in range(n))
+    assert need[lib.ERR_LAYER_OUTPUT] >= single > 0
+    # the exact product also keeps the E4M3 grid values of X and W as bf16
+    assert need[lib.ERR_LAYER_OUTPUT] > need[lib.ERR_LAYER_OUTPUT_FP8_UNIT] > 0
+    # operands of one group of layers, not of the whole model: a second block adds nothing
+    w2 = (lib.TensorDesc * (2 * n))(*(list(w) + list(w)))
+    x2 = (lib.TensorDesc * (2 * n))(*(list(x) + list(x)))
+    assert L.mofq_select_layers_wa_workspace_bytes(2 * n, w2, x2, 2, lib.ERR_LAYER_OUTPUT, C.byref(cfg)) <= 2 * need[lib.ERR_LAYER_OUTPUT]
+    # sizes: wrong metric, mismatched inner dimension
+    assert L.mofq_select_layers_wa_workspace_bytes(n, w, x, 2, lib.ERR_TENSOR, C.byref(cfg)) == 0
+    xbad = (lib.TensorDesc * n)(*[lib.TensorDesc(xaddr[i], lib.BF16, 64, 64, 64) for i in range(n)])
+    assert L.mofq_select_layers_wa_workspace_bytes(n, w, xbad, 2, lib.ERR_LAYER_OUTPUT, C.byref(cfg)) == 0
+    res, ws = C.c_void_p(0x5000000), C.c_void_p(0x6000000)
+    args = lambda **kw: [kw.get("n", n), kw.get("w", w), kw.get("x", x), kw.get("cand", cand), kw.get("n_cand", 2),
+                         kw.get("metric", lib.ERR_LAYER_OUTPUT), C.byref(cfg), kw.get("w_out", w_out), None,
+                         res, ws, kw.get("ws_bytes", need[lib.ERR_LAYER_OUTPUT]), None]
+    assert L.mofq_select_layers_wa(*args(n=0)) == -1
+    assert L.mofq_select_layers_wa(*args(metric=lib.ERR_TENSOR)) == -1
+    assert L.mofq_select_layers_wa(*args(x=xbad)) == -1
+    assert L.mofq_select_layers_wa(*args(ws_bytes=need[lib.ERR_LAYER_OUTPUT] - 1)) == -4
+    cand4 = (C.c_int32 * 2)(lib.INT4, lib.FP4_E2M1)
+    assert L.mofq_select_layers_wa(*args(cand=cand4)) == -2          # no 4-bit matrix-core path
+    w16 = (lib.TensorDesc * n)(*[lib.TensorDesc(0x100000 * (i + 1), lib.F16, o, k, k) for i, (o, k) in enumerate(dims)])
+    assert L.mofq_select_layers_wa(*args(w=w16)) == -2               # the reference product takes bf16
+    no_codes = (lib.QOut * n)(*[lib.QOut(None, 0x3000000, None, None) for _ in range(n)])
+    assert L.mofq_select_layers_wa(*args(w_out=no_codes)) == -1

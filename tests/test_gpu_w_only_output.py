@@ -92,6 +92,17 @@ def test_ragged_tiles(mq, m, n, k):
     check_layer(mq, x, w, [I4, FP4], orc.PER_CHANNEL, mi.clip_ratios(3), "ragged")
 
 
+@pytest.mark.parametrize("k", [64, 2048, 8192, 11008, 16384, 24576, 32768])
+def test_absmax_pair_every_row_length(mq, k):
+    """Per-channel absmax scales and a pair of formats: the scoring pass writes both candidates'
+    grid values itself; one case per instance of that kernel (row lengths up to the limit)."""
+    x = mi.activations(70, k, seed=92 + k, device=DEV)
+    w = mi.llama_like_weight(40, k, seed=93 + k, dtype=torch.bfloat16, device=DEV)
+    check_layer(mq, x, w, [FP4, I4], orc.PER_CHANNEL, mi.clip_ratios(1), f"absmax-pair-{k}")
+    if k in (64, 11008):
+        check_layer(mq, x, w, [I8, FP8], orc.PER_CHANNEL, np.array([0.8], dtype=np.float32), f"absmax-pair8-{k}")
+
+
 def test_single_candidate_and_eight_bit_weights(mq):
     x = mi.activations(128, 512, seed=86, device=DEV)
     w = mi.llama_like_weight(256, 512, seed=87, dtype=torch.bfloat16, device=DEV)
