@@ -84,10 +84,12 @@ typedef enum {
    * cores: half the matrix time of that product.  Inside one instruction the unit aligns
    * the 8 products of each group of 8 consecutive k to the group's largest exponent sum
    * and drops (towards zero) what lies more than 13 bits below it, so the FP8 error sum
-   * carries a relative deviation of about 3e-6 plus a random part of about
-   * 2.5e-2 / sqrt(tokens * out_features): within 1e-5 for the 2048-token LLaMA-shaped
-   * layers (measured at most 4.4e-6), a few 1e-5 for layers of a few ten thousand
-   * outputs.  The INT8 product is exact in both modes. */
+   * carries a relative deviation that grows with the spread of magnitudes inside a layer
+   * (how far its largest outliers stretch the per-tensor scales) plus a random part of
+   * about 2.5e-2 / sqrt(tokens * out_features): measured 1e-6 .. 7e-6 on most 2048-token
+   * LLaMA-shaped layers, up to 3.2e-5 on some, a few 1e-5 for layers of a few ten
+   * thousand outputs.  The INT8 product and the reference energy are exact in both
+   * modes. */
   MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT = 2,
   /* Layer-output error of the weight-only case (Section 4.1 names tensor error and
    * layer-output error as the two metrics that suffice there): the input stays in 16
