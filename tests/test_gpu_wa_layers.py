@@ -239,3 +239,43 @@ def test_argument_errors(mq):
         mq.select_layers_wa(bad, [I8, FP8], mq.ERR_LAYER_OUTPUT, cfg, res, big)
     assert e.value.status == -1
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_batches_equal_single_calls_and_oracle(mq, seed):
+    """Random layer lists (1 to 20 layers, so up to three groups), random shapes, activations
+    shared by runs of consecutive layers, some tensors as views with rows further apart than
+    their length: the batched call equals the single calls bit for bit, and one layer of each
+    list is held to the oracle."""
+    rng = np.random.default_rng(8100 + seed)
+    n_layers = int(rng.integers(1, 21))
+    tokens = int(rng.integers(1, 300))
+    ws, xs = [], []
+    x = None
+    for i in range(n_layers):
+        k = 64 * int(rng.integers(1, 12))
+        if x is None or x.shape[1] != k or rng.random() < 0.5:
+            pad = 64 if rng.random() < 0.3 else 0
+            full = mi.activations(tokens, k + pad, seed=int(rng.integers(1 << 30)), device=DEV,
+                                  n_outlier=int(rng.integers(0, 7)))
+            x = full[:, :k]                      # rows `k + pad` elements apart
+        o = int(rng.integers(1, 400))
+        pad = 8 * int(rng.integers(0, 3))
+        wfull = mi.llama_like_weight(o, k + pad, seed=int(rng.integers(1 << 30)), dtype=torch.bfloat16, device=DEV)
+        ws.append(wfull[:, :k])
+        xs.append(x)
+    cands = [[I8, FP8], [FP8, I8]][int(rng.integers(2))]
+    metric = [mq.ERR_LAYER_OUTPUT, mq.ERR_LAYER_OUTPUT_FP8_UNIT][int(rng.integers(2))]
+    cfg = mq.Cfg(orc.PER_TENSOR, np.array([float(rng.choice([1.0, 0.75]))], dtype=np.float32))
+    print(f"[case] random batch {seed}: {n_layers} layers, {tokens} tokens, cands={cands}, metric={metric}", flush=True)
+    got = run_batched(mq, ws, xs, cands, metric, cfg)
+    same_outputs(got, run_single(mq, ws, xs, cands, metric, cfg))
+    if cfg.c.clip_ratios[0] == 1.0 and metric == mq.ERR_LAYER_OUTPUT:
+        i = int(rng.integers(n_layers))
+        ref = orc.select_layer_wa(mi.to_f32_numpy(xs[i].contiguous()), mi.to_f32_numpy(ws[i].contiguous()), cands,
+                                  orc.PER_TENSOR)
+        r, w_out, x_out = got
+        assert r[i].best == ref.best
+        assert np.allclose(list(r[i].err)[:2], ref.errs, rtol=E_RTOL, atol=1e-300)
+        assert np.array_equal(unpack_codes(w_out[i].codes, *ws[i].shape, 8), ref.w.codes)
+        assert np.array_equal(unpack_codes(x_out[i].codes, *xs[i].shape, 8), ref.x.codes)
