@@ -48,6 +48,8 @@ MFMA_PEAK = {"bf16": 2500.0, "int8": 5000.0, "fp8": 5000.0}
 FLOPS_PER_ELEM_CAND_FMT = 7
 # Counter-derived facts about sweep_sorted_kernel on 4096-column rows, measured by rocprofv3 runs
 # of this command (not in the run that prints them): where they come from is printed beside them.
+TAIL_SPREAD = False   # set from --tail-spread
+
 SORTED_KERNEL_COUNTERS = {
     "from": "profiles/w_only_sorted_kernel_counters.txt, profiles/w_only_7b_k100_hbm_traffic.txt",
     "read_per_input_byte": 373236.0 / (46592 * 4096 * 2 / 1024),     # FETCH_SIZE, scaled by a plain copy
@@ -72,6 +74,9 @@ def parse():
     ap.add_argument("--no-65b", action="store_true", help="all: leave the 65B-shaped set out of `secondary`")
     ap.add_argument("--single-stream", action="store_true",
                     help="w4_channel: no second stream (kernels run one at a time; for counter runs)")
+    ap.add_argument("--tail-spread", action="store_true",
+                    help="model-shaped sets with a per-layer share of heavy-tail entries (both outcomes of the "
+                         "4-bit select occur) instead of BASELINE.json's 0.05 % in every layer")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     ap.add_argument("--full-parity", action="store_true",
@@ -197,7 +202,8 @@ def cpu_baseline(weights, outs, clip, cands):
 def make_weights(shapes, dev, dtype=None):
     import torch
     import mofq_inputs as mi
-    return [mi.model_weight(1, b, mi.LINEAR_NAMES.index(name), o, n, dtype=dtype or torch.float16, device=dev)
+    return [mi.model_weight(1, b, mi.LINEAR_NAMES.index(name), o, n, dtype=dtype or torch.float16, device=dev,
+                            tail_spread=TAIL_SPREAD)
             for b, name, o, n in shapes]
 
 
@@ -321,7 +327,9 @@ def run_w4(args, shapes, dev, weights, group, model, steps, warmup, ceilings=Non
                                  "configs[1]: LLaMA-7B-shaped") + " fp16 weight set, "
                                 f"{len(shapes)} linears, {n_elems} weights, 4-bit W-only per-channel, "
                                 "100 clip ratios in [0.5,1], INT4 vs FP4-E2M1, per-layer select + emit"),
-                   "n_clip": n_clip, "formats": ["INT4", "FP4_E2M1"], "fp_percent": fp_pct},
+                   "n_clip": n_clip, "formats": ["INT4", "FP4_E2M1"], "fp_percent": fp_pct,
+                   "weights": ("per-layer share of heavy-tail entries, log-uniform over [1.3e-5, 5e-3] (--tail-spread)"
+                               if TAIL_SPREAD else "rows N(0, sigma^2), sigma ~ U(0.01, 0.04), 0.05 % Student-t(3) outliers")},
         "roofline": roofline,
     }
     if want_cpu:
@@ -531,7 +539,7 @@ def run_fp4_variants(args, shapes, dev):
     ws = out = None
     t0 = time.perf_counter()
     for i, (b, name, o, n) in enumerate(shapes):
-        w = mi.model_weight(1, b, mi.LINEAR_NAMES.index(name), o, n, device=dev)
+        w = mi.model_weight(1, b, mi.LINEAR_NAMES.index(name), o, n, device=dev, tail_spread=TAIL_SPREAD)
         need = mq.workspace_bytes(w, None, 2, mq.ERR_TENSOR, cfg)
         if ws is None or ws.numel() < need:
             ws = torch.empty(need, dtype=torch.uint8, device=dev)
@@ -576,7 +584,7 @@ def run_w4_units(args, shapes, dev):
     mixed = torch.zeros(len(shapes), dtype=torch.float64, device=dev)
     ws_bytes = 0
     for b, name, o, n in shapes:
-        w = mi.model_weight(1, b, mi.LINEAR_NAMES.index(name), o, n, device=dev)
+        w = mi.model_weight(1, b, mi.LINEAR_NAMES.index(name), o, n, device=dev, tail_spread=TAIL_SPREAD)
         weights.append(w)
         outs.append(mq.alloc_qbuffers(o, n, 4, cfg, dev))
         tags.append(torch.empty(o * (n // GROUP), dtype=torch.uint8, device=dev))
@@ -661,7 +669,8 @@ def full_parity(args, dev):
     torch.cuda.synchronize()
     res = mq.read_results(results)
     threads = orc.max_threads()
-    summary = {"mode": "full-parity", "model": args.model, "workload": "w4_group128" if group else "w4_channel",
+    summary = {"mode": "full-parity", "model": args.model, "tail_spread": TAIL_SPREAD,
+               "workload": "w4_group128" if group else "w4_channel",
                "blocks": blocks, "n_clip": n_clip, "tensors_in_the_select_layers_call": len(shapes),
                "tensors_checked": 0, "rows_checked": 0, "elements_checked": 0,
                "choice_mismatches": 0, "error_sum_mismatches_rtol_1e-9": 0, "max_error_sum_rel_diff": 0.0,
@@ -724,7 +733,8 @@ def full_parity_wa(args, dev):
     cfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
     xcfg = mq.Cfg(mq.PER_TENSOR, mi.clip_ratios(1))
     role = {"q": 0, "k": 0, "v": 0, "o": 1, "gate": 2, "up": 2, "down": 3}
-    summary = {"mode": "full-parity", "workload": "w8a8", "blocks": blocks, "tokens": TOKENS, "linears_checked": 0,
+    summary = {"mode": "full-parity", "workload": "w8a8", "tail_spread": TAIL_SPREAD, "blocks": blocks,
+               "tokens": TOKENS, "linears_checked": 0,
                "choice_mismatches": 0, "error_sum_mismatches_rtol_1e-5": 0, "max_error_sum_rel_diff_exact": 0.0,
                "max_error_sum_rel_diff_fp8_unit": 0.0, "fp8_unit_layers_beyond_1e-5": 0,
                "code_or_scale_mismatches": 0, "fp_chosen": 0,
@@ -737,7 +747,7 @@ def full_parity_wa(args, dev):
             if role[name] not in acts:
                 acts[role[name]] = mi.activations(TOKENS, n, seed=mi.tensor_seed(3, b, role[name], 1), device=dev)
             xs.append(acts[role[name]])
-            ws_.append(mi.model_weight(3, b, lin, o, n, dtype=torch.bfloat16, device=dev))
+            ws_.append(mi.model_weight(3, b, lin, o, n, dtype=torch.bfloat16, device=dev, tail_spread=TAIL_SPREAD))
         got = {}
         for metric, key in ((mq.ERR_LAYER_OUTPUT, "exact"), (mq.ERR_LAYER_OUTPUT_FP8_UNIT, "fp8_unit")):
             w_outs = [mq.alloc_qbuffers(o, n, 8, cfg, dev) for _, _, o, n in shapes]
@@ -799,9 +809,10 @@ def brief(d):
 
 
 def main():
-    global HEAD_OVERRIDE
+    global HEAD_OVERRIDE, TAIL_SPREAD
     args = parse()
     HEAD_OVERRIDE = args.head
+    TAIL_SPREAD = args.tail_spread
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no second device); "
               "use --gpus 1", file=sys.stderr)

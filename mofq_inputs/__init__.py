@@ -97,21 +97,24 @@ def llama_like_weight(rows: int, cols: int, seed: int, dtype=torch.float16,
 
 
 def layer_outlier_frac(config_id: int, block: int, linear: int) -> float:
-    """Share of heavy-tail entries of one layer of a model-shaped set: log-uniform over
-    [1.3e-5, 5e-3], fixed by (config, block, linear).  Layers differ in how heavy their tails
-    are; with this spread about one layer in eight is close enough to Gaussian for the integer
-    format to win the 4-bit select, the others prefer the floating-point format."""
+    """Share of heavy-tail entries of one layer in the tail-spread variant of a model-shaped set:
+    log-uniform over [1.3e-5, 5e-3], fixed by (config, block, linear).  Layers then differ in how
+    heavy their tails are; with this spread about one layer in eight is close enough to Gaussian
+    for the integer format to win the 4-bit select, the others prefer the floating-point format."""
     digest = hashlib.sha256(f"mofq-tail:{config_id}:{block}:{linear}".encode()).digest()
     u = int.from_bytes(digest[:6], "little") / float(1 << 48)
     return float(1.3e-5 * (5e-3 / 1.3e-5) ** u)
 
 
 def model_weight(config_id: int, block: int, linear: int, rows: int, cols: int,
-                 dtype=torch.float16, device="cpu") -> torch.Tensor:
+                 dtype=torch.float16, device="cpu", tail_spread: bool = False) -> torch.Tensor:
     """The weight of linear `linear` of block `block` in the model-shaped set of a config:
-    llama_like_weight with the layer's seed and the layer's share of heavy-tail entries."""
+    llama_like_weight with the layer's seed.  By default every layer has the same share of
+    heavy-tail entries (0.05 %); with `tail_spread` the share differs per layer
+    (layer_outlier_frac), which makes both outcomes of the 4-bit select occur in one set."""
+    frac = layer_outlier_frac(config_id, block, linear) if tail_spread else 5e-4
     return llama_like_weight(rows, cols, seed=tensor_seed(config_id, block, linear), dtype=dtype,
-                             device=device, outlier_frac=layer_outlier_frac(config_id, block, linear))
+                             device=device, outlier_frac=frac)
 
 
 def outlier_channels(in_features: int, n: int = 6, seed: int = 1234) -> np.ndarray:

@@ -100,7 +100,7 @@ def test_whole_block_all_rows_against_oracle(mq):
     clip = mi.clip_ratios(100)
     cfg = mq.Cfg(orc.PER_CHANNEL, clip)
     shapes = mi.block_linear_shapes("7b")
-    ws_ = [mi.model_weight(1, 1, li, o, n, device=DEV) for li, (_, o, n) in enumerate(shapes)]
+    ws_ = [mi.model_weight(1, 1, li, o, n, device=DEV, tail_spread=True) for li, (_, o, n) in enumerate(shapes)]
     outs = [mq.alloc_qbuffers(o, n, 4, cfg, DEV) for _, o, n in shapes]
     batch = mq.LayerBatch(ws_, outs)
     results = mq.alloc_result(DEV, len(shapes))
@@ -126,9 +126,9 @@ def test_whole_block_all_rows_against_oracle(mq):
                                   outs[i].clip_idx.cpu().numpy(), outs[i].unit_err.cpu().numpy())
         picks.append(ref.best)
     print(f"[case]   near-tie rows: {band}", flush=True)
-    # Table 2 reports 88.9-97.9 % of layers choosing FP4 on real weights.  Here the layers' shares
-    # of heavy-tail entries differ (mofq_inputs.layer_outlier_frac): gate and up of this block
-    # are nearly Gaussian, where INT4 is the better format; the others prefer FP4
+    # Table 2 reports 88.9-97.9 % of layers choosing FP4 on real weights.  This block is drawn with
+    # the layers' shares of heavy-tail entries spread out (mofq_inputs.model_weight, tail_spread):
+    # gate and up are nearly Gaussian, where INT4 is the better format; the others prefer FP4
     print(f"[case]   choices (0 = INT4, 1 = FP4): {picks}", flush=True)
     assert sum(picks) >= 4
 
