@@ -153,8 +153,8 @@ def run_fp8_unit(mq, x, w, w_gran):
 # FP8 error sum over M x N outputs moves by a bias of about 3e-6 (the perturbation's own
 # square) plus a random term that shrinks as 1 / sqrt(M N).  Measured on 16 layers: at most
 # 4.4e-6 at the 2048-token LLaMA shapes tested here, 2.6e-5 .. 3.8e-5 at a few ten thousand
-# outputs.  (Layers whose largest outliers stretch the per-tensor scales further lose more: three
-# of the 42 full-size layers of bench.py's full-parity runs came out at 1.1e-5 .. 3.2e-5.)
+# outputs.  (Layers whose largest outliers stretch the per-tensor scales further lose more: five
+# of the 63 full-size layers of bench.py's full-parity runs came out at 1.1e-5 .. 3.2e-5.)
 def fp8_unit_bound(m, n):
     return 5e-6 + 2.5e-2 / np.sqrt(float(m) * float(n))
 
