@@ -520,6 +520,12 @@ struct WaFusedTensorWs {
   float* absmax_part;
   double* sse_part;
   float* scale;
+  // fp8-unit product: the column split (see WaPrepTensor); null for the exact product
+  uint8_t* f8_main;
+  float* colmax;
+  uint8_t* col_slot;
+  int32_t* side_cols;
+  uint16_t* side;
 };
 // Workspace of one layer: the quantized operands and records of X and W, and the per-tile
 // partials of the matrix kernel (INT8 error, E4M3 error, reference energy).
@@ -572,6 +578,17 @@ size_t carve_wa_group(void* arena, int i0, int n, const mofq_tensor_t* w, const 
       t.absmax_part = c.take<float>(kTensorBlocks);
       t.sse_part = c.take<double>(2 * kTensorBlocks);
       t.scale = c.take<float>(2);
+      if (!exact) {
+        const size_t rows = static_cast<size_t>(which ? w[i].rows : x[i].rows);
+        t.side = c.take<uint16_t>(rows * kWaSideCols);
+        if (!which) {
+          const size_t cols = static_cast<size_t>(x[i].cols);
+          t.f8_main = c.take<uint8_t>(e);
+          t.colmax = c.take<float>(cols);
+          t.col_slot = c.take<uint8_t>(cols);
+          t.side_cols = c.take<int32_t>(kWaSideCols + 1);
+        }
+      }
     }
     for (int q = 0; q < 3; ++q) l.part[q] = c.take<double>(wa_gemm_blocks(x[i].rows, w[i].rows));
     if (out) out[j] = l;
@@ -621,12 +638,18 @@ int select_layers_wa(int n_layers, const mofq_tensor_t* w, const mofq_tensor_t* 
         px.ratio = 1.0f;   // activations: per tensor at the full range (Section 3.2)
         px.absmax_part = l[j].x.absmax_part; px.sse_part = l[j].x.sse_part;
         px.q_i8 = l[j].x.i8; px.q_f8 = l[j].x.f8; px.q_g = l[j].x.g; px.scale = l[j].x.scale;
+        px.is_x = 1;
+        px.colmax = l[j].x.colmax; px.col_slot = l[j].x.col_slot; px.side_cols = l[j].x.side_cols;
+        px.q_f8_main = l[j].x.f8_main; px.side = l[j].x.side;
       }
       pw.data = w[i].data; pw.rows = w[i].rows; pw.cols = w[i].cols; pw.ld = w[i].ld;
       pw.ratio = w_cfg->clip_ratios[0];
       pw.absmax_part = l[j].w.absmax_part; pw.sse_part = l[j].w.sse_part;
       pw.q_i8 = l[j].w.i8; pw.q_f8 = static_cast<uint8_t*>(w_out[i].codes); pw.q_g = l[j].w.g;
       pw.scale = l[j].w.scale;
+      // the weight's side operand follows its activation's pick of columns
+      pw.is_x = 0;
+      pw.col_slot = l[j].x.col_slot; pw.side_cols = l[j].x.side_cols; pw.side = l[j].w.side;
     }
     return launch_wa_prep(t, 2 * n, s);
   };
@@ -640,7 +663,9 @@ int select_layers_wa(int n_layers, const mofq_tensor_t* w, const mofq_tensor_t* 
       g.q[0].sx = l[j].x.scale; g.q[0].sw = l[j].w.scale;
       g.q[0].part = l[j].part[0];
       g.q[1].kind = fp8_unit ? WA_FP8 : WA_GRID_BF16;
-      g.q[1].x = fp8_unit ? l[j].x.f8 : l[j].x.g;
+      g.q[1].x = fp8_unit ? l[j].x.f8_main : l[j].x.g;
+      g.q[1].xs = fp8_unit ? l[j].x.side : nullptr;
+      g.q[1].ws = fp8_unit ? l[j].w.side : nullptr;
       g.q[1].w = fp8_unit ? static_cast<const uint8_t*>(w_out[i].codes) : l[j].w.g;
       g.q[1].sx = l[j].x.scale + 1; g.q[1].sw = l[j].w.scale + 1;
       g.q[1].part = l[j].part[1];

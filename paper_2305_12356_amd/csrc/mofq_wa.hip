@@ -55,6 +55,7 @@ typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 
+constexpr int SIDE_K = kWaSideCols;             // K extent of a product's optional second part: one 16-bit stage
 constexpr int TM = 256, TN = 128;               // workgroup tile; 8 waves (two per SIMD), 64 x 64 each
 constexpr int WM = 64, WN = 64;                 // wave tile: 2 x 2 matrix-core tiles of 32 x 32
 constexpr int NW = (TM / WM) * (TN / WN);       // waves per workgroup
@@ -64,6 +65,7 @@ struct QProd {
   const void* x; const void* w;                 // dense [M][K], [N][K] in the product's operand type
   const float* sx; const float* sw;             // scales: sx one value or null (= 1); sw one value or [N]
   double* part;                                 // [blocks]
+  const void* xs; const void* ws;               // optional second part: bf16 grid values, dense [M][SIDE_K], [N][SIDE_K]
 };
 struct GemmArgs {
   const uint16_t* x; int64_t ldx;               // bf16 [M][K]
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   // ---- one product: K loop over its own operand arrays ---------------------------------
   // KIND selects arrays, element size and matrix instruction; acc is f32x16 or i32x16.
-  auto product = [&](auto kind_c, auto& acc, const void* xq, const void* wq) {
+  auto product = [&](auto kind_c, auto& acc, const void* xq, const void* wq, const int kdim) {
     constexpr int KIND = decltype(kind_c)::value;
     constexpr int EB = (KIND == K_REF || KIND == K_GRID) ? 2 : 1;   // bytes per element
     constexpr int TK = ROW_B / EB;                                  // K elements per stage
@@ -177,7 +179,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int NF = (KIND == K_F8) ? 2 : 1;                      // 16-byte chunks per fragment
     const char* xb; const char* wb; int64_t xrow, wrow;
     if constexpr (KIND == K_REF) { xb = reinterpret_cast<const char*>(a.x); wb = reinterpret_cast<const char*>(a.w); xrow = a.ldx * 2; wrow = a.ldw * 2; }
-    else { xb = static_cast<const char*>(xq); wb = static_cast<const char*>(wq); xrow = wrow = static_cast<int64_t>(a.K) * EB; }
+    else { xb = static_cast<const char*>(xq); wb = static_cast<const char*>(wq); xrow = wrow = static_cast<int64_t>(kdim) * EB; }
 
     // This lane's global source of each of its wave's deposits at k = 0 (deposit i of a
     // stage covers chunk slots 64 i .. 64 i + 63 and is issued by wave i % NW).
@@ -199,8 +201,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // K is a multiple of 64 elements, so the last stage of an 8-bit product may hold only
     // half a row (64 bytes).  Its deposits then fetch the valid half twice (addresses stay
     // inside the row) and the matrix groups of the missing half are skipped.
-    const int KT = (a.K + TK - 1) / TK;
-    const bool half_tail = (EB == 1) && (a.K % TK) != 0;   // 16-bit stages hold 64 elements: never
+    const int KT = (kdim + TK - 1) / TK;
+    const bool half_tail = (EB == 1) && (kdim % TK) != 0;   // 16-bit stages hold 64 elements: never
     auto issue = [&](int kt, int lo, int hi) {   // deposits [lo, hi) of stage kt
       unsigned char* st = s_buf + (kt % NST) * STAGE;
       const int64_t kb = static_cast<int64_t>(kt) * ROW_B;
@@ -343,7 +345,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     return wave_sum(e_q);
   };
 
-  product(std::integral_constant<int, K_REF>{}, acc_r, nullptr, nullptr);
+  product(std::integral_constant<int, K_REF>{}, acc_r, nullptr, nullptr, a.K);
   double e_q[2] = {0.0, 0.0};
   auto quantized = [&](auto kind_c, auto slot_c) {
     constexpr int KIND = decltype(kind_c)::value;
@@ -357,7 +359,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         for (int j = 0; j < TJ; ++j)
 #pragma unroll
           for (int e = 0; e < 16; ++e) acc_q[i][j][e] = 0;
-      product(kind_c, acc_q, a.q[SLOT].x, a.q[SLOT].w);
+      product(kind_c, acc_q, a.q[SLOT].x, a.q[SLOT].w, a.K);
+      // The columns split off from an fp8-unit product: one K step from their grid values on
+      // the bf16 matrix cores into the same accumulators (both accumulate in fp32).
+      if constexpr (KIND == K_F8)
+        if (a.q[SLOT].xs) product(std::integral_constant<int, K_GRID>{}, acc_q, a.q[SLOT].xs, a.q[SLOT].ws, SIDE_K);
       // the first reduction also sums Y^2
       e_q[SLOT] = sq_diff(std::integral_constant<bool, SLOT == 0>{}, acc_q, a.q[SLOT].sx, a.q[SLOT].sw);
     }
@@ -390,7 +396,11 @@ int launch_wa_gemm(const WaGemmParams& p, hipStream_t st) {
   GemmArgs a{};
   a.x = static_cast<const uint16_t*>(p.x); a.ldx = p.ldx;
   a.w = static_cast<const uint16_t*>(p.w); a.ldw = p.ldw;
-  for (int i = 0; i < 2; ++i) a.q[i] = QProd{p.q[i].x, p.q[i].w, p.q[i].sx, p.q[i].sw, p.q[i].part};
+  for (int i = 0; i < 2; ++i) {
+    if ((p.q[i].xs != nullptr) != (p.q[i].ws != nullptr)) return MOFQ_ERR_INVALID_ARG;
+    if (p.q[i].xs && p.q[i].kind != WA_FP8) return MOFQ_ERR_INVALID_ARG;
+    a.q[i] = QProd{p.q[i].x, p.q[i].w, p.q[i].sx, p.q[i].sw, p.q[i].part, p.q[i].xs, p.q[i].ws};
+  }
   a.w_per_channel = p.w_per_channel;
   a.M = static_cast<int32_t>(p.M); a.N = static_cast<int32_t>(p.N); a.K = static_cast<int32_t>(p.K);
   a.tiles_m = static_cast<int32_t>((p.M + TM - 1) / TM);

@@ -40,6 +40,15 @@ struct PrepTensor {
   uint8_t* q_f8;
   uint8_t* q_g;
   float* scale;
+  // column split (fp8-unit product); null / 0 otherwise
+  int32_t is_x;
+  int32_t ld_i32;              // elements between rows (for the column passes)
+  int32_t rows_i32, cols_i32;
+  float* colmax;
+  uint8_t* col_slot;
+  int32_t* side_cols;
+  uint8_t* q_f8_main;
+  uint16_t* side;
 };
 struct PrepArgs {
   PrepTensor t[kMaxTensors];
@@ -141,6 +150,129 @@ MOFQ_DEV void quant_chunk(const PrepTensor& t, int64_t c, const u32x4 raw, float
   reinterpret_cast<u32x2*>(t.q_i8)[c] = oi;
   reinterpret_cast<u32x2*>(t.q_f8)[c] = of;
   if (t.q_g) reinterpret_cast<u32x4*>(t.q_g)[c] = gb;
+  if (t.q_f8_main) {   // uniform: the activation of an fp8-unit product
+    // slot bytes of the chunk's 8 columns: bit 7 set = not split off = keep the code
+    const uint32_t col8 = static_cast<uint32_t>(c) % static_cast<uint32_t>(t.cpr);   // fewer than 2^31 chunks (checked by the host)
+    const u32x2 m = reinterpret_cast<const u32x2*>(t.col_slot)[col8];
+    u32x2 om;
+    om[0] = of[0] & (((m[0] >> 7) & 0x01010101u) * 0xFFu);
+    om[1] = of[1] & (((m[1] >> 7) & 0x01010101u) * 0xFFu);
+    reinterpret_cast<u32x2*>(t.q_f8_main)[c] = om;
+  }
+}
+
+// ---- column split for the fp8-unit product ------------------------------------------------
+
+// Largest magnitude of every column of an activation: a workgroup takes 64 columns, a thread 8
+// of them (one 16-byte load per row) on every 32nd row.
+__global__ __launch_bounds__(kThreads) void wa_colmax_kernel(const PrepArgs a) {
+  __shared__ float s_max[32][65];
+  int b, nb;
+  const PrepTensor& t = my_tensor(a, b, nb);
+  const int tid = threadIdx.x;
+  const int cx = tid & 7, ry = tid >> 3;
+  const int col0 = b * 64 + cx * 8;          // nb = cols / 64 workgroups
+  float m[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) m[i] = 0.0f;
+  for (int r = ry; r < t.rows_i32; r += 32) {
+    float v[8];
+    Load8<BF16>::load(t.data + static_cast<int64_t>(r) * t.ld_i32 + col0, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m[i] = __builtin_fmaxf(m[i], __builtin_fabsf(v[i]));
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s_max[ry][cx * 8 + i] = m[i];
+  __syncthreads();
+  if (tid < 64) {
+    float r = 0.0f;
+#pragma unroll
+    for (int y = 0; y < 32; ++y) r = __builtin_fmaxf(r, s_max[y][tid]);
+    t.colmax[b * 64 + tid] = r;
+  }
+}
+
+// Which columns to split off: those whose largest magnitude exceeds kOutlierFactor times the
+// typical one, in ascending order, at most kWaSideCols of them.  "Typical" is the mean over the
+// columns that do not exceed kOutlierFactor times the mean over all columns, so that the
+// outliers themselves do not hide each other where they are many.  One workgroup per
+// activation.  (Any choice gives the same sum; the choice only decides how much the fp8 unit's
+// alignment can lose.)
+constexpr float kOutlierFactor = 4.0f;
+__global__ __launch_bounds__(kThreads) void wa_pick_kernel(const PrepArgs a) {
+  __shared__ double s_sum[2][kThreads / 64];
+  __shared__ uint32_t s_cnt[2][kThreads / 64];
+  const PrepTensor& t = a.t[blockIdx.x];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int K = t.cols_i32;
+  double sum = 0.0;
+  for (int c = tid; c < K; c += kThreads) sum += static_cast<double>(t.colmax[c]);
+  sum = wave_sum(sum);
+  if (lane == 0) s_sum[0][wave] = sum;
+  __syncthreads();
+  const float thr0 = kOutlierFactor * static_cast<float>(((s_sum[0][0] + s_sum[0][1]) + (s_sum[0][2] + s_sum[0][3])) / K);
+  double sum1 = 0.0;
+  uint32_t n1 = 0;
+  for (int c = tid; c < K; c += kThreads) {
+    const float v = t.colmax[c];
+    if (!(v > thr0)) { sum1 += static_cast<double>(v); ++n1; }
+  }
+  sum1 = wave_sum(sum1);
+  uint32_t n1w = n1;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) n1w += static_cast<uint32_t>(__shfl_xor(static_cast<int>(n1w), d, 64));
+  if (lane == 0) { s_sum[1][wave] = sum1; s_cnt[1][wave] = n1w; }
+  __syncthreads();
+  const uint32_t n_typ = (s_cnt[1][0] + s_cnt[1][1]) + (s_cnt[1][2] + s_cnt[1][3]);
+  const double typ = ((s_sum[1][0] + s_sum[1][1]) + (s_sum[1][2] + s_sum[1][3])) / (n_typ > 0 ? n_typ : 1);
+  const float thr = n_typ > 0 ? kOutlierFactor * static_cast<float>(typ) : thr0;
+  // thread t owns the columns [t * per, (t + 1) * per): count, scan over the threads, assign slots
+  const int per = (K + kThreads - 1) / kThreads;
+  const int lo = tid * per, hi = (lo + per < K) ? lo + per : K;
+  uint32_t n = 0;
+  for (int c = lo; c < hi; ++c) n += (t.colmax[c] > thr) ? 1u : 0u;
+  uint32_t incl = n;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t o = static_cast<uint32_t>(__shfl_up(static_cast<int>(incl), d, 64));
+    if (lane >= d) incl += o;
+  }
+  if (lane == 63) s_cnt[0][wave] = incl;
+  __syncthreads();
+  uint32_t base = incl - n;
+  for (int w = 0; w < wave; ++w) base += s_cnt[0][w];
+  for (int c = lo; c < hi; ++c) {
+    uint8_t slot = 0xFFu;
+    if (t.colmax[c] > thr) {
+      if (base < static_cast<uint32_t>(kWaSideCols)) { slot = static_cast<uint8_t>(base); t.side_cols[base] = c; }
+      ++base;
+    }
+    t.col_slot[c] = slot;
+  }
+  if (tid == kThreads - 1) t.side_cols[kWaSideCols] = static_cast<int32_t>(base < static_cast<uint32_t>(kWaSideCols) ? base : kWaSideCols);
+}
+
+// The side operand of a tensor: the E4M3 grid values of its split-off columns as bf16, dense
+// [rows][kWaSideCols], zero in the slots beyond the number of split-off columns.  Runs after the
+// quantize pass (which leaves the E4M3 scale in t.scale[1]).
+__global__ __launch_bounds__(kThreads) void wa_side_kernel(const PrepArgs a) {
+  int b, nb;
+  const PrepTensor& t = my_tensor(a, b, nb);
+  const int count = t.side_cols[kWaSideCols];
+  const float inv = 1.0f / t.scale[1];
+  const int64_t n = static_cast<int64_t>(t.rows_i32) * kWaSideCols;
+  for (int64_t e = static_cast<int64_t>(b) * kThreads + threadIdx.x; e < n; e += static_cast<int64_t>(nb) * kThreads) {
+    const int slot = static_cast<int>(e % kWaSideCols);
+    const int64_t row = e / kWaSideCols;
+    uint16_t out = 0;
+    if (slot < count) {
+      const float x = u2f(static_cast<uint32_t>(t.data[row * t.ld_i32 + t.side_cols[slot]]) << 16);
+      const int p = __builtin_amdgcn_cvt_pk_fp8_f32(med3(x * inv, -448.0f, 448.0f), 0.0f, 0, false);
+      const f32x2 g = __builtin_amdgcn_cvt_pk_f32_fp8(p, false);
+      out = static_cast<uint16_t>(f2u(g[0]) >> 16);   // exact: at most 4 significant bits
+    }
+    t.side[e] = out;
+  }
 }
 
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(5))) void wa_quant_kernel(const PrepArgs a) {
@@ -209,6 +341,21 @@ bool fill(const WaPrepTensor& p, PrepTensor* t) {
   t->q_f8 = p.q_f8;
   t->q_g = p.q_g;
   t->scale = p.scale;
+  if (p.side) {
+    if (!p.col_slot || !p.side_cols || p.cols % 64 != 0 || p.rows > (1 << 30) || p.cols > (1 << 20) ||
+        p.ld > (int64_t{1} << 30))
+      return false;
+    if (p.is_x && (!p.colmax || !p.q_f8_main || t->n_chunks >= (int64_t{1} << 31))) return false;
+    t->is_x = p.is_x;
+    t->ld_i32 = static_cast<int32_t>(p.ld);
+    t->rows_i32 = static_cast<int32_t>(p.rows);
+    t->cols_i32 = static_cast<int32_t>(p.cols);
+    t->colmax = p.colmax;
+    t->col_slot = p.col_slot;
+    t->side_cols = p.side_cols;
+    t->q_f8_main = p.is_x ? p.q_f8_main : nullptr;
+    t->side = p.side;
+  }
   return true;
 }
 
@@ -242,7 +389,28 @@ int launch_wa_prep(const WaPrepTensor* p, int n, hipStream_t st) {
   }
   const int blocks = a.first_block[a.n];
   hipLaunchKernelGGL(wa_absmax_kernel, dim3(blocks), dim3(kThreads), 0, st, a);
+  // column split: the activations' column maxima and the pick come before the quantize pass
+  // (which zeroes the picked columns in the fp8 operand), the side operands after it (they
+  // use the scale it leaves)
+  PrepArgs xs{}, sd{};
+  for (int k = 0; k < a.n; ++k) {
+    if (!a.t[k].side) continue;
+    if (a.t[k].is_x) {
+      xs.t[xs.n] = a.t[k];
+      xs.first_block[xs.n + 1] = xs.first_block[xs.n] + a.t[k].cols_i32 / 64;
+      ++xs.n;
+    }
+    sd.t[sd.n] = a.t[k];
+    const int64_t nb = (static_cast<int64_t>(a.t[k].rows_i32) * kWaSideCols + kThreads * 4 - 1) / (kThreads * 4);
+    sd.first_block[sd.n + 1] = sd.first_block[sd.n] + static_cast<int32_t>(std::min<int64_t>(nb, 1024));
+    ++sd.n;
+  }
+  if (xs.n) {
+    hipLaunchKernelGGL(wa_colmax_kernel, dim3(xs.first_block[xs.n]), dim3(kThreads), 0, st, xs);
+    hipLaunchKernelGGL(wa_pick_kernel, dim3(xs.n), dim3(kThreads), 0, st, xs);
+  }
   hipLaunchKernelGGL(wa_quant_kernel, dim3(blocks), dim3(kThreads), 0, st, a);
+  if (sd.n) hipLaunchKernelGGL(wa_side_kernel, dim3(sd.first_block[sd.n]), dim3(kThreads), 0, st, sd);
   return hip_status(hipGetLastError());
 }
 

@@ -182,13 +182,9 @@ def test_fp8_unit_block_decisions_and_codes(mq):
     names, ws, xs = block_like(200, 256, 704, seed=7200, tame=("attn_out",))
     cfg = mq.Cfg(orc.PER_TENSOR, mi.clip_ratios(1))
     got = run_batched(mq, ws, xs, [I8, FP8], mq.ERR_LAYER_OUTPUT_FP8_UNIT, cfg)
-    # the INT8 error is exact in this mode too; the E4M3 error carries the fp8 unit's alignment
-    # (bounded in test_gpu_wa.py); decisions, codes and scales are the oracle's
-    against_oracle(mq, got, ws, xs, [I8, FP8], orc.PER_TENSOR, exact=False)
-    for i, (w, x) in enumerate(zip(ws, xs)):
-        ref = orc.select_layer_wa(mi.to_f32_numpy(x), mi.to_f32_numpy(w), [I8, FP8], orc.PER_TENSOR)
-        assert np.isclose(got[0][i].err[0], ref.errs[0], rtol=E_RTOL)
-        assert np.isclose(got[0][i].err[1], ref.errs[1], rtol=2e-4)
+    # with the activations' outlier columns split off into an exact K step, the E4M3 product on
+    # the fp8 matrix cores meets the same tolerance as the exact form
+    against_oracle(mq, got, ws, xs, [I8, FP8], orc.PER_TENSOR, exact=True)
 
 
 def test_without_activation_outputs(mq):
