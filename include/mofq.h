@@ -83,13 +83,17 @@ typedef enum {
    * instead of being formed from the (bf16-exact) grid values on the bf16 matrix
    * cores: half the matrix time of that product.  Inside one instruction the unit aligns
    * the 8 products of each group of 8 consecutive k to the group's largest exponent sum
-   * and drops (towards zero) what lies more than 13 bits below it, so the FP8 error sum
-   * carries a relative deviation that grows with the spread of magnitudes inside a layer
-   * (how far its largest outliers stretch the per-tensor scales) plus a random part of
-   * about 2.5e-2 / sqrt(tokens * out_features): measured 1e-6 .. 7e-6 on most 2048-token
-   * LLaMA-shaped layers, up to 3.2e-5 on some, a few 1e-5 for layers of a few ten
-   * thousand outputs.  The INT8 product and the reference energy are exact in both
-   * modes. */
+   * and drops (towards zero) what lies more than 13 bits below it, which hurts where a group
+   * holds an outlier channel of the activation.  With candidates {INT8, FP8_E4M3} and
+   * per-tensor weight scales the library therefore splits those columns off (up to 64
+   * columns whose largest magnitude is more than 4 times the typical column's) and adds
+   * their share of the sum by one exact K step on the bf16 matrix cores: the FP8 error sum
+   * is then within 1e-5 of the exact form (measured 4e-7 at most on 2048-token
+   * LLaMA-shaped layers, 1e-6 on layers of some ten thousand outputs; layers of a few
+   * thousand outputs keep a random part of about 1e-3 / sqrt(tokens * out_features)).
+   * With other candidate lists or per-channel weight scales nothing is split off and
+   * the deviation is 1e-6 .. 3e-5 at full size, up to 1e-4 on small layers.  The INT8
+   * product and the reference energy are exact in both modes. */
   MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT = 2,
   /* Layer-output error of the weight-only case (Section 4.1 names tensor error and
    * layer-output error as the two metrics that suffice there): the input stays in 16
