@@ -15,6 +15,7 @@
 // per segment, so the sums do not depend on how many workgroups a launch has (which varies
 // with how many tensors share it).
 #include <algorithm>
+#include <type_traits>
 
 #include "mofq_device.h"
 #include "mofq_internal.h"
@@ -175,7 +176,21 @@ __global__ __launch_bounds__(kThreads) void wa_colmax_kernel(const PrepArgs a) {
   float m[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) m[i] = 0.0f;
-  for (int r = ry; r < t.rows_i32; r += 32) {
+  int r = ry;
+  for (; r + 7 * 32 < t.rows_i32; r += 8 * 32) {   // eight loads in flight per lane
+    u32x4 raw[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      raw[u] = *reinterpret_cast<const u32x4*>(t.data + static_cast<int64_t>(r + u * 32) * t.ld_i32 + col0);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        m[2 * i] = __builtin_fmaxf(m[2 * i], __builtin_fabsf(u2f(raw[u][i] << 16)));
+        m[2 * i + 1] = __builtin_fmaxf(m[2 * i + 1], __builtin_fabsf(u2f(raw[u][i] & 0xFFFF0000u)));
+      }
+  }
+  for (; r < t.rows_i32; r += 32) {
     float v[8];
     Load8<BF16>::load(t.data + static_cast<int64_t>(r) * t.ld_i32 + col0, v);
 #pragma unroll
@@ -199,57 +214,92 @@ __global__ __launch_bounds__(kThreads) void wa_colmax_kernel(const PrepArgs a) {
 // activation.  (Any choice gives the same sum; the choice only decides how much the fp8 unit's
 // alignment can lose.)
 constexpr float kOutlierFactor = 4.0f;
+constexpr int kPickCached = 12288;   // column maxima held in LDS up to this many columns
 __global__ __launch_bounds__(kThreads) void wa_pick_kernel(const PrepArgs a) {
+  __shared__ float s_col[kPickCached];
+  __shared__ __attribute__((aligned(16))) uint8_t s_slot[kPickCached];
   __shared__ double s_sum[2][kThreads / 64];
   __shared__ uint32_t s_cnt[2][kThreads / 64];
   const PrepTensor& t = a.t[blockIdx.x];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = t.cols_i32;
-  double sum = 0.0;
-  for (int c = tid; c < K; c += kThreads) sum += static_cast<double>(t.colmax[c]);
-  sum = wave_sum(sum);
-  if (lane == 0) s_sum[0][wave] = sum;
-  __syncthreads();
-  const float thr0 = kOutlierFactor * static_cast<float>(((s_sum[0][0] + s_sum[0][1]) + (s_sum[0][2] + s_sum[0][3])) / K);
-  double sum1 = 0.0;
-  uint32_t n1 = 0;
-  for (int c = tid; c < K; c += kThreads) {
-    const float v = t.colmax[c];
-    if (!(v > thr0)) { sum1 += static_cast<double>(v); ++n1; }
-  }
-  sum1 = wave_sum(sum1);
-  uint32_t n1w = n1;
+  const bool cached = K <= kPickCached;   // uniform
+  if (cached) {
+    // all of a thread's loads are issued before the first is used (K is a multiple of 64)
+    constexpr int NV = kPickCached / (kThreads * 4);
+    u32x4 v[NV];
 #pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) n1w += static_cast<uint32_t>(__shfl_xor(static_cast<int>(n1w), d, 64));
-  if (lane == 0) { s_sum[1][wave] = sum1; s_cnt[1][wave] = n1w; }
-  __syncthreads();
-  const uint32_t n_typ = (s_cnt[1][0] + s_cnt[1][1]) + (s_cnt[1][2] + s_cnt[1][3]);
-  const double typ = ((s_sum[1][0] + s_sum[1][1]) + (s_sum[1][2] + s_sum[1][3])) / (n_typ > 0 ? n_typ : 1);
-  const float thr = n_typ > 0 ? kOutlierFactor * static_cast<float>(typ) : thr0;
-  // thread t owns the columns [t * per, (t + 1) * per): count, scan over the threads, assign slots
-  const int per = (K + kThreads - 1) / kThreads;
-  const int lo = tid * per, hi = (lo + per < K) ? lo + per : K;
-  uint32_t n = 0;
-  for (int c = lo; c < hi; ++c) n += (t.colmax[c] > thr) ? 1u : 0u;
-  uint32_t incl = n;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t o = static_cast<uint32_t>(__shfl_up(static_cast<int>(incl), d, 64));
-    if (lane >= d) incl += o;
-  }
-  if (lane == 63) s_cnt[0][wave] = incl;
-  __syncthreads();
-  uint32_t base = incl - n;
-  for (int w = 0; w < wave; ++w) base += s_cnt[0][w];
-  for (int c = lo; c < hi; ++c) {
-    uint8_t slot = 0xFFu;
-    if (t.colmax[c] > thr) {
-      if (base < static_cast<uint32_t>(kWaSideCols)) { slot = static_cast<uint8_t>(base); t.side_cols[base] = c; }
-      ++base;
+    for (int u = 0; u < NV; ++u) {
+      const int c = (u * kThreads + tid) * 4;
+      if (c < K) v[u] = *reinterpret_cast<const u32x4*>(t.colmax + c);
     }
-    t.col_slot[c] = slot;
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      const int c = (u * kThreads + tid) * 4;
+      if (c < K) *reinterpret_cast<u32x4*>(&s_col[c]) = v[u];
+    }
+    __syncthreads();
   }
-  if (tid == kThreads - 1) t.side_cols[kWaSideCols] = static_cast<int32_t>(base < static_cast<uint32_t>(kWaSideCols) ? base : kWaSideCols);
+  // two copies of the rest, so that neither reads through a run-time choice of memory
+  auto rest = [&](auto cached_c) {
+    constexpr bool CACHED = decltype(cached_c)::value;
+    auto col = [&](int c) {
+      if constexpr (CACHED) return s_col[c];
+      else return t.colmax[c];
+    };
+    double sum = 0.0;
+    for (int c = tid; c < K; c += kThreads) sum += static_cast<double>(col(c));
+    sum = wave_sum(sum);
+    if (lane == 0) s_sum[0][wave] = sum;
+    __syncthreads();
+    const float thr0 = kOutlierFactor * static_cast<float>(((s_sum[0][0] + s_sum[0][1]) + (s_sum[0][2] + s_sum[0][3])) / K);
+    double sum1 = 0.0;
+    uint32_t n1 = 0;
+    for (int c = tid; c < K; c += kThreads) {
+      const float v = col(c);
+      if (!(v > thr0)) { sum1 += static_cast<double>(v); ++n1; }
+    }
+    sum1 = wave_sum(sum1);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) n1 += static_cast<uint32_t>(__shfl_xor(static_cast<int>(n1), d, 64));
+    if (lane == 0) { s_sum[1][wave] = sum1; s_cnt[1][wave] = n1; }
+    __syncthreads();
+    const uint32_t n_typ = (s_cnt[1][0] + s_cnt[1][1]) + (s_cnt[1][2] + s_cnt[1][3]);
+    const double typ = ((s_sum[1][0] + s_sum[1][1]) + (s_sum[1][2] + s_sum[1][3])) / (n_typ > 0 ? n_typ : 1);
+    const float thr = n_typ > 0 ? kOutlierFactor * static_cast<float>(typ) : thr0;
+    // thread t owns the columns [t * per, (t + 1) * per): count, scan over the threads, assign slots
+    const int per = (K + kThreads - 1) / kThreads;
+    const int lo = tid * per, hi = (lo + per < K) ? lo + per : K;
+    uint32_t n = 0;
+    for (int c = lo; c < hi; ++c) n += (col(c) > thr) ? 1u : 0u;
+    uint32_t incl = n;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t o = static_cast<uint32_t>(__shfl_up(static_cast<int>(incl), d, 64));
+      if (lane >= d) incl += o;
+    }
+    if (lane == 63) s_cnt[0][wave] = incl;
+    __syncthreads();
+    uint32_t base = incl - n;
+    for (int w = 0; w < wave; ++w) base += s_cnt[0][w];
+    for (int c = lo; c < hi; ++c) {
+      uint8_t slot = 0xFFu;
+      if (col(c) > thr) {
+        if (base < static_cast<uint32_t>(kWaSideCols)) { slot = static_cast<uint8_t>(base); t.side_cols[base] = c; }
+        ++base;
+      }
+      if constexpr (CACHED) s_slot[c] = slot;
+      else t.col_slot[c] = slot;
+    }
+    if constexpr (CACHED) {   // the slot bytes leave in 16-byte pieces
+      __syncthreads();
+      for (int c = tid * 16; c < K; c += kThreads * 16)
+        *reinterpret_cast<u32x4*>(t.col_slot + c) = *reinterpret_cast<const u32x4*>(&s_slot[c]);
+    }
+    if (tid == kThreads - 1) t.side_cols[kWaSideCols] = static_cast<int32_t>(base < static_cast<uint32_t>(kWaSideCols) ? base : kWaSideCols);
+  };
+  if (cached) rest(std::true_type{});
+  else rest(std::false_type{});
 }
 
 // The side operand of a tensor: the E4M3 grid values of its split-off columns as bf16, dense
