@@ -267,3 +267,21 @@ def test_fp8_unit_column_split_cases(mq, n_outlier, scale):
     assert abs(dev) <= (FP8_UNIT_RTOL if n_outlier <= 64 else 1e-3)
     assert r.best == ref.best
     assert np.array_equal(unpack_codes(w_out.codes, N, K, 8), ref.w.codes)
+
+
+@pytest.mark.parametrize("K", [12288, 16384, 32768])
+def test_fp8_unit_wide_rows(mq, K):
+    """Rows beyond what the column pick keeps in LDS (12288 columns), up to the longest row the
+    layer-output metric takes: both forms of the metric against the oracle."""
+    M, N = 72, 136
+    x = mi.activations(M, K, seed=520 + K, device=DEV)
+    w = mi.llama_like_weight(N, K, seed=521 + K, dtype=torch.bfloat16, device=DEV)
+    check_layer(mq, x, w, [I8, FP8], orc.PER_TENSOR, f"wide-{K}")
+    ref = orc.select_layer_wa(mi.to_f32_numpy(x), mi.to_f32_numpy(w), [I8, FP8], orc.PER_TENSOR)
+    r, w_out = run_fp8_unit(mq, x, w, orc.PER_TENSOR)
+    dev = r.err[1] / ref.errs[1] - 1
+    print(f"[case] fp8 unit, {K} columns: deviation {dev:+.3e}", flush=True)
+    assert np.isclose(r.err[0], ref.errs[0], rtol=E_RTOL)
+    assert abs(dev) <= FP8_UNIT_RTOL + 1e-3 / np.sqrt(M * N)   # 9792 outputs: see test_gpu_random_layers.py
+    assert r.best == ref.best
+    assert np.array_equal(unpack_codes(w_out.codes, N, K, 8), ref.w.codes)
