@@ -17,6 +17,7 @@ FLAGS = [
     "-ffp-contract=off",              # every fp32 step of the decision arithmetic is its own operation
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
+    "-Wno-pass-failed",               # occupancy attributes are upper targets; instances that use more registers say so
 ]
 
 
