@@ -67,8 +67,10 @@ def parse():
     ap.add_argument("--workload", default="all",
                     choices=["all", "w4_channel", "w4_group128", "w8a8", "w4a16_output", "k1_hbm", "fp4_variants",
                              "w4_units", "ceilings"])
-    ap.add_argument("--fp8-unit", action="store_true",
-                    help="w8a8: E4M3 code product on the fp8 matrix cores")
+    ap.add_argument("--exact-e4m3", action="store_true",
+                    help="w8a8: E4M3 product from the grid values on the bf16 matrix cores (MOFQ_ERR_LAYER_OUTPUT) "
+                         "instead of the E4M3 codes on the fp8 matrix cores (MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT)")
+    ap.add_argument("--fp8-unit", action="store_true", help="w8a8: the default (kept for older command lines)")
     ap.add_argument("--blocks", type=int, default=0, help="debug: use only the first N blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-65b", action="store_true", help="all: leave the 65B-shaped set out of `secondary`")
@@ -457,7 +459,9 @@ def run_w8a8(args, shapes, dev, weights, w_only, fp8_unit, steps, warmup, ceilin
                                (f"configs[3]: {len(shapes)} linears of the LLaMA-7B shape, X [{TOKENS} x in] bf16 "
                                 "with 6 outlier channels x60, W bf16, per-tensor INT8 vs FP8-E4M3, "
                                 "layer-output error, per-layer select + emit"),
-                   "fp8_product": "fp8 matrix cores" if fp8_unit else "exact (bf16 matrix cores)",
+                   "fp8_product": ("E4M3 codes on the fp8 matrix cores, the activation's outlier columns in one K step "
+                                   "on the bf16 matrix cores (MOFQ_ERR_LAYER_OUTPUT_FP8_UNIT)") if fp8_unit else
+                                  "E4M3 grid values on the bf16 matrix cores (MOFQ_ERR_LAYER_OUTPUT)",
                    "fp_percent": 100.0 * sum(1 for r in res if r.best == 1) / len(res)},
         "roofline": roofline,
     }
@@ -839,8 +843,8 @@ def main():
         return
     if wl in ("w8a8", "w4a16_output"):
         weights = make_weights(shapes, dev, torch.bfloat16)
-        print(json.dumps(run_w8a8(args, shapes, dev, weights, wl == "w4a16_output", args.fp8_unit,
-                                  args.steps, args.warmup)))
+        print(json.dumps(run_w8a8(args, shapes, dev, weights, wl == "w4a16_output",
+                                  wl == "w8a8" and not args.exact_e4m3, args.steps, args.warmup)))
         return
     if wl == "k1_hbm":
         print(json.dumps(run_k1_hbm(args, dev, args.steps, args.warmup)))
@@ -887,10 +891,10 @@ def main():
     torch.cuda.empty_cache()
     note("bf16 weights for the layer-output workloads")
     weights = make_weights(shapes7, dev, torch.bfloat16)
-    note("configs[3]: W8A8, exact")
-    sec["w8a8"] = brief(run_w8a8(args, shapes7, dev, weights, False, False, few, few_w, ceilings))
-    note("configs[3]: W8A8, fp8 matrix cores")
-    sec["w8a8_fp8_unit"] = brief(run_w8a8(args, shapes7, dev, weights, False, True, few, few_w, ceilings))
+    note("configs[3]: W8A8, int8 and fp8 matrix cores for the quantized products")
+    sec["w8a8"] = brief(run_w8a8(args, shapes7, dev, weights, False, True, few, few_w, ceilings))
+    note("configs[3]: W8A8, E4M3 product from grid values on the bf16 matrix cores")
+    sec["w8a8_exact_e4m3"] = brief(run_w8a8(args, shapes7, dev, weights, False, False, few, few_w, ceilings))
     note("weight-only select by layer-output error")
     sec["w4a16_output"] = brief(run_w8a8(args, shapes7, dev, weights, True, False, few, few_w, ceilings))
     del weights
