@@ -36,6 +36,7 @@ struct PrepTensor {
   int32_t seg_chunks;          // chunks per segment (the last one may be shorter)
   float ratio;                 // clip ratio of the scale
   float* absmax_part;
+  int32_t n_absmax;            // partial maxima to fold; 0 = one per workgroup of the quantize pass
   double* sse_part;
   uint8_t* q_i8;
   uint8_t* q_f8;
@@ -73,7 +74,7 @@ MOFQ_DEV const uint16_t* chunk_src(const PrepTensor& t, int64_t c) {
   return t.data + row * t.ld + (c - row * t.cpr) * 8;
 }
 
-constexpr int kInFlight = 4;   // 16-byte loads in flight per lane (largest-magnitude pass)
+constexpr int kInFlight = 8;   // 16-byte loads in flight per lane (largest-magnitude pass)
 constexpr int kQuantInFlight = 2;   // quantize pass: every further chunk in flight costs some 17 registers
 
 __global__ __launch_bounds__(kThreads) void wa_absmax_kernel(const PrepArgs a) {
@@ -220,6 +221,7 @@ __global__ __launch_bounds__(kThreads) void wa_pick_kernel(const PrepArgs a) {
   __shared__ __attribute__((aligned(16))) uint8_t s_slot[kPickCached];
   __shared__ double s_sum[2][kThreads / 64];
   __shared__ uint32_t s_cnt[2][kThreads / 64];
+  __shared__ float s_amax[kThreads / 64];
   const PrepTensor& t = a.t[blockIdx.x];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = t.cols_i32;
@@ -248,10 +250,18 @@ __global__ __launch_bounds__(kThreads) void wa_pick_kernel(const PrepArgs a) {
       else return t.colmax[c];
     };
     double sum = 0.0;
-    for (int c = tid; c < K; c += kThreads) sum += static_cast<double>(col(c));
+    float amax = 0.0f;
+    for (int c = tid; c < K; c += kThreads) {
+      const float v = col(c);
+      sum += static_cast<double>(v);
+      amax = __builtin_fmaxf(amax, v);
+    }
     sum = wave_sum(sum);
-    if (lane == 0) s_sum[0][wave] = sum;
+    amax = wave_max(amax);
+    if (lane == 0) { s_sum[0][wave] = sum; s_amax[wave] = amax; }
     __syncthreads();
+    // the tensor's largest magnitude is the largest column maximum: the first pass skips it
+    if (tid == 0) t.absmax_part[0] = __builtin_fmaxf(__builtin_fmaxf(s_amax[0], s_amax[1]), __builtin_fmaxf(s_amax[2], s_amax[3]));
     const float thr0 = kOutlierFactor * static_cast<float>(((s_sum[0][0] + s_sum[0][1]) + (s_sum[0][2] + s_sum[0][3])) / K);
     double sum1 = 0.0;
     uint32_t n1 = 0;
@@ -331,9 +341,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(5))) v
   int b, nb;
   const PrepTensor& t = my_tensor(a, b, nb);
   const int tid = threadIdx.x;
-  // the tensor's largest magnitude from the partials of the first pass (same launch shape)
+  // the tensor's largest magnitude from the partials of the first pass (same launch shape) or
+  // from the one the column pass left
   float amax = 0.0f;
-  for (int i = tid; i < nb; i += kThreads) amax = __builtin_fmaxf(amax, t.absmax_part[i]);
+  const int na = t.n_absmax ? t.n_absmax : nb;
+  for (int i = tid; i < na; i += kThreads) amax = __builtin_fmaxf(amax, t.absmax_part[i]);
   amax = wave_max(amax);
   if ((tid & 63) == 0) s_tmp[tid >> 6] = amax;
   __syncthreads();
@@ -438,7 +450,16 @@ int launch_wa_prep(const WaPrepTensor* p, int n, hipStream_t st) {
     a.first_block[k + 1] = a.first_block[k] + static_cast<int32_t>(nb);
   }
   const int blocks = a.first_block[a.n];
-  hipLaunchKernelGGL(wa_absmax_kernel, dim3(blocks), dim3(kThreads), 0, st, a);
+  // first pass: every tensor but the activations of a column split, whose largest magnitude
+  // comes out of the column maxima
+  PrepArgs am{};
+  for (int k = 0; k < a.n; ++k) {
+    if (a.t[k].side && a.t[k].is_x) { a.t[k].n_absmax = 1; continue; }
+    am.t[am.n] = a.t[k];
+    am.first_block[am.n + 1] = am.first_block[am.n] + (a.first_block[k + 1] - a.first_block[k]);
+    ++am.n;
+  }
+  if (am.n) hipLaunchKernelGGL(wa_absmax_kernel, dim3(am.first_block[am.n]), dim3(kThreads), 0, st, am);
   // column split: the activations' column maxima and the pick come before the quantize pass
   // (which zeroes the picked columns in the fp8 operand), the side operands after it (they
   // use the scale it leaves)
