@@ -1,18 +1,23 @@
 // Scale search for one output channel per workgroup without scoring every
 // (element, candidate) pair.
 //
-// For a fixed scale the quantized value of an element is a non-decreasing step
-// function of the element, so the elements that fall on one grid level form a
-// contiguous run of the sorted row.  The squared error of a candidate is then
+// For a fixed scale the magnitude of the quantized value is a non-decreasing step function
+// of the element's magnitude (rounding and the fp32 product are symmetric in the sign), so
+// the elements that fall on one level magnitude form a contiguous run of the row sorted by
+// magnitude.  The squared error of a candidate is then
 //
-//   sum (x - g s)^2 = sum x^2  -  2 s * sum_L g_L * S_L  +  s^2 * sum_L g_L^2 * n_L ,
+//   sum (x - g s)^2 = sum x^2  -  2 s * sum_L |g_L| * S_L  +  s^2 * sum_L g_L^2 * n_L ,
 //
-// with S_L, n_L the sum and count of the elements on level L.  The kernel sorts the
-// row once (in-place LDS radix sort of the 16-bit patterns), builds prefix sums of the
-// sorted values, and finds every level boundary of every candidate by binary search with
-// the exact fp32 decision arithmetic (t = fl32(x * fl32(1/s)) against the rounding
-// threshold of the boundary).  That is O(n log n + K * levels * log n) per row
-// instead of O(n * K).
+// with S_L, n_L the sum of magnitudes and the count of the elements on the level pair +-g_L.
+// INT4 is the one asymmetry: a negative element beyond -7.5 s lands on -8 where a positive
+// one stays on 7; those elements (the negative ones past one more boundary) add their sum
+// once more and 64 - 49 per element to the two level sums.  The kernel sorts the row once by
+// magnitude (in-place LDS radix sort of the low 15 bits of the 16-bit patterns), builds
+// prefix sums of the sorted magnitudes (and, sparser, of the negative elements' magnitudes
+// and their number), and finds every level boundary of every candidate by binary search with
+// the exact fp32 decision arithmetic (t = fl32(|x| * fl32(1/s)) against the rounding
+// threshold of the boundary): 7 searches per candidate for E2M1, 8 for INT4.  That is
+// O(n log n + K * levels * log n) per row instead of O(n * K).
 //
 // The formula cancels (the error is a few per cent of sum x^2), so it serves as a filter
 // with a rigorous rounding bound: every candidate whose filtered error is within a wide
@@ -50,24 +55,23 @@ struct SortedArgs {
   int64_t cols;                    // of every tensor
   int32_t scale_f16, n_clip;
   float clip[MOFQ_MAX_CLIP];
-  // per format slot: level(t) <= b  <=>  t <= thr[b];  levels ascending g_0 < g_1 < ...
-  float thr[2][16];
-  double dgd[2][16];  // g_b - g_{b+1}
-  int32_t dg2q[2][16];  // 4 (g_b^2 - g_{b+1}^2): an integer for every 4-bit format
-  float g_last[2];    // largest level
+  // per format slot: level magnitudes 0 = m_0 < m_1 < ... < m_7;  |level|(t) <= m_b  <=>  t <= thr[b]
+  // for b = 0..6.  Entry 7 is INT4's extra boundary (|t| below it: a negative element stays on -7)
+  // with the weights of the step from 7 to 8; unused (zero weights) for E2M1.
+  float thr[2][8];
+  double dgd[2][8];   // m_b - m_{b+1};  entry 7: 8 - 7
+  int32_t dg2q[2][8]; // 4 (m_b^2 - m_{b+1}^2): an integer for every 4-bit format;  entry 7: 4 (64 - 49)
+  float g_last[2];    // m_7
   float g_absmax[2];  // largest |level|
-  int32_t nb[2];      // number of boundaries (levels - 1)
 };
 
-// ---- order-preserving 16-bit keys ----------------------------------------------------
-// Two 16-bit patterns per register.  Key of a pattern h: its complement when the sign bit is
-// set, h with the sign bit set otherwise; the halves never interact.
+// ---- sort keys ------------------------------------------------------------------------
+// The key of an element is the low 15 bits of its own 16-bit pattern (the magnitude; fp16 and
+// bf16 magnitudes order like their patterns); the sign bit rides along untouched.
 typedef short i16x2 __attribute__((ext_vector_type(2)));
 MOFQ_DEV uint32_t sign_fill2(uint32_t w) {   // each half: 0xFFFF where its top bit is set, else 0
   return __builtin_bit_cast(uint32_t, __builtin_bit_cast(i16x2, w) >> 15);
 }
-MOFQ_DEV uint32_t to_key2(uint32_t w) { return w ^ (sign_fill2(w) | 0x80008000u); }
-MOFQ_DEV uint32_t from_key2(uint32_t k) { return ~(k ^ (sign_fill2(k) & 0x7FFF7FFFu)); }
 
 template <typename In> MOFQ_DEV float bits_to_float(uint32_t h);
 template <> MOFQ_DEV float bits_to_float<F16>(uint32_t h) {
@@ -75,14 +79,14 @@ template <> MOFQ_DEV float bits_to_float<F16>(uint32_t h) {
 }
 template <> MOFQ_DEV float bits_to_float<BF16>(uint32_t h) { return u2f(h << 16); }
 
-// fl32(x * inv) for the element with bit pattern h.  For fp16 the widening and the product are
+// fl32(|x| * inv) for the element with bit pattern h.  For fp16 the widening and the product are
 // one mixed-precision fused multiply-add with a zero addend: the same single rounding of the
-// exact product (only the sign of a zero result can differ, which no comparison sees).
+// exact product.
 template <typename In> MOFQ_DEV float scaled(uint32_t h, float inv);
 template <> MOFQ_DEV float scaled<F16>(uint32_t h, float inv) {
-  return __builtin_fmaf(static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h))), inv, 0.0f);
+  return __builtin_fmaf(__builtin_fabsf(static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)))), inv, 0.0f);
 }
-template <> MOFQ_DEV float scaled<BF16>(uint32_t h, float inv) { return u2f(h << 16) * inv; }
+template <> MOFQ_DEV float scaled<BF16>(uint32_t h, float inv) { return __builtin_fabsf(u2f(h << 16)) * inv; }
 
 // Padded position of sorted element i (in elements): a 2-element gap after every 64.
 // Additive over sums of distinct powers of two, which the search below relies on.
@@ -189,7 +193,6 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   double* const s_blk = reinterpret_cast<double*>(s_raw + KEYB);   // [NBLK + 1], valid after the sort
   __shared__ uint32_t s_dig_tot[16];
   __shared__ float s_scale[NF][MOFQ_MAX_CLIP];
-  __shared__ float s_inv[NF][MOFQ_MAX_CLIP];
   __shared__ double s_fast[NF][MOFQ_MAX_CLIP];
   __shared__ float s_wmax[NW];
   __shared__ double s_wsum[3][NW];
@@ -198,14 +201,27 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   __shared__ uint8_t s_list[MAXL];   // format * MOFQ_MAX_CLIP + candidate
   __shared__ int s_nlist;
   __shared__ double s_p2[NW];
-  __shared__ double s_val[MAXL];
+  // re-scored errors of the shortlist: over the prefix sums, which are no longer needed by then
+  double* const s_val = reinterpret_cast<double*>(s_raw + KEYB);
+  static_assert(MAXL * 8 <= CNTB, "shortlist values do not fit");
   static_assert(MOFQ_MAX_CLIP * 2 <= 256, "shortlist entries are bytes");
-  // Boundary search: with 16 waves the 15 boundaries of a candidate are dealt to SPLIT waves
-  // (4 boundaries each) so that every wave has search work; the partial level sums meet in LDS.
+  // INT4's negative elements beyond its last boundary: exclusive prefix of the negative elements'
+  // magnitudes and of their number at every BSN-th position of the sorted row
+  constexpr bool TAIL_A = FA == MOFQ_INT4, TAIL_B = (FB >= 0) && FBX == MOFQ_INT4;
+  constexpr bool ANY_TAIL = TAIL_A || TAIL_B;
+  constexpr int BSN = (THREADS == 256 && CH == 4) ? 32 : 16;   // what the LDS left beside the workgroups of a CU allows
+  constexpr int NNEG = ANY_TAIL ? NP / BSN + 1 : 1;
+  __shared__ double s_nsum[NNEG];
+  __shared__ uint16_t s_ncnt[NNEG];
+  __shared__ double s_wnsum[NW];
+  __shared__ uint32_t s_wncnt[NW];
+  static_assert(NP < 65536, "counts of negative elements are 16 bits");
+  // Boundary search: with 16 waves the 8 boundaries of a candidate are dealt to SPLIT waves
+  // (2 boundaries each) so that every wave has search work; the partial level sums meet in LDS.
   constexpr int SPLIT = (NW >= 16) ? 4 : 1;
-  constexpr int NBD = 15;                 // boundaries of a 16-level format; unused ones carry zeros
-  constexpr int QB = (NBD + SPLIT - 1) / SPLIT;   // boundaries per lane
-  static_assert(QB * SPLIT <= 16, "boundary tables have 16 entries");
+  constexpr int NBD = 8;                  // 7 magnitude boundaries and INT4's extra one
+  constexpr int QB = NBD / SPLIT;         // boundaries per lane
+  static_assert(QB * SPLIT == NBD, "the boundaries must deal out evenly");
   __shared__ double s_pca[SPLIT > 1 ? NF * MOFQ_MAX_CLIP * SPLIT : 1];
   __shared__ int s_pcb[SPLIT > 1 ? NF * MOFQ_MAX_CLIP * SPLIT : 1];
 
@@ -246,7 +262,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
       en = __builtin_fma(d0, d0, en);
       en = __builtin_fma(d1, d1, en);
       l1f += __builtin_fabsf(v0) + __builtin_fabsf(v1);
-      keys[i] = ok ? to_key2(raw[i]) : 0xFFFFFFFFu;   // padding sorts last
+      keys[i] = ok ? raw[i] : 0x7FFF7FFFu;   // padding: the largest magnitude pattern sorts last
     }
     *reinterpret_cast<u32x4*>(&s_keys[tid * E + j * 8]) = keys;
   }
@@ -273,18 +289,20 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
     const int f = idx / K, k = idx - f * K;
     const float qmax = (f == 0) ? Codec<FA>::QMAX : Codec<FBX>::QMAX;
     const float s = unit_scale(amax, a.clip[k], qmax, a.scale_f16 != 0);
-    s_scale[f][k] = s;
-    s_inv[f][k] = 1.0f / s;
+    s_scale[f][k] = s;   // its reciprocal is taken where it is used: a table of them would cost a workgroup per compute unit
   }
 
-  // ---- LSD radix sort of the keys, 4 bits per pass; thread t owns positions [tE, tE+E) ---
-  // LAST: the pass that writes the elements' bit patterns into the padded layout.
+  // ---- LSD radix sort by magnitude: digits of 4, 4, 4 and 3 bits of the low 15 bits of the
+  // patterns; thread t owns positions [tE, tE+E).  LAST: the pass of the top digit, which writes
+  // the patterns into the padded layout.
   auto radix_pass = [&](auto last_tag, const int shift) {
     constexpr bool LAST = decltype(last_tag)::value;
+    constexpr int WIDTH = LAST ? 3 : 4;   // the sign bit is no part of the key
     constexpr int PER = THREADS / 64;   // counters of one digit per lane in the scan
     constexpr int DPW = 16 / NW;        // digits scanned by one wave
+    constexpr int ND = 1 << WIDTH;      // digits that occur in this pass
 #pragma unroll
-    for (int d = 0; d < 16; ++d) s_cnt[d][tid] = 0;
+    for (int d = 0; d < ND; ++d) s_cnt[d][tid] = 0;
     uint32_t kreg[E / 2];
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
@@ -294,13 +312,14 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
     }
 #pragma unroll
     for (int i = 0; i < E; ++i)   // own column: plain LDS add; positions are counted in bytes
-      atomicAdd(&s_cnt[__builtin_amdgcn_ubfe(kreg[i >> 1], shift + (i & 1) * 16, 4)][tid], 2u);
+      atomicAdd(&s_cnt[__builtin_amdgcn_ubfe(kreg[i >> 1], shift + (i & 1) * 16, WIDTH)][tid], 2u);
     __syncthreads();
     // per digit: exclusive scan of the counts across threads (kept in registers), digit totals aside
     uint32_t c[DPW][PER], base[DPW];
 #pragma unroll
     for (int m = 0; m < DPW; ++m) {
       const int d = wave + m * NW;
+      if (m * NW >= ND || d >= ND) continue;   // wave-uniform
       uint32_t sum = 0;
 #pragma unroll
       for (int i = 0; i < PER; ++i) { c[m][i] = s_cnt[d][lane * PER + i]; sum += c[m][i]; }
@@ -313,10 +332,11 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
     {
       // lane d of every wave: first position of digit d
       uint32_t unused;
-      const uint32_t start = wave_excl_scan_u32(lane < 16 ? s_dig_tot[lane & 15] : 0u, unused);
+      const uint32_t start = wave_excl_scan_u32(lane < ND ? s_dig_tot[lane & 15] : 0u, unused);
 #pragma unroll
       for (int m = 0; m < DPW; ++m) {
         const int d = wave + m * NW;
+        if (m * NW >= ND || d >= ND) continue;   // wave-uniform
         uint32_t bpos = base[m] + static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(start), d));
 #pragma unroll
         for (int i = 0; i < PER; ++i) { s_cnt[d][lane * PER + i] = bpos; bpos += c[m][i]; }
@@ -326,11 +346,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
     uint32_t pos[E];
 #pragma unroll
     for (int i = 0; i < E; ++i)   // stable: thread order, then i
-      pos[i] = atomicAdd(&s_cnt[__builtin_amdgcn_ubfe(kreg[i >> 1], shift + (i & 1) * 16, 4)][tid], 2u);
-    if constexpr (LAST) {   // back to the elements' own patterns
-#pragma unroll
-      for (int i = 0; i < E / 2; ++i) kreg[i] = from_key2(kreg[i]);
-    }
+      pos[i] = atomicAdd(&s_cnt[__builtin_amdgcn_ubfe(kreg[i >> 1], shift + (i & 1) * 16, WIDTH)][tid], 2u);
 #pragma unroll
     for (int i = 0; i < E; ++i) {
       const uint32_t v = (kreg[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
@@ -343,17 +359,35 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
 #pragma unroll 1
   for (int pass = 0; pass < 3; ++pass) radix_pass(std::false_type{}, pass * 4);
   radix_pass(std::true_type{}, 12);
-  // The buffer now holds the elements' own bit patterns in ascending order of value.  Padding
-  // became the pattern 0x7FFF (a NaN in fp16 and bf16), which fails every "<= threshold" test.
+  // The buffer now holds the elements' own bit patterns in ascending order of magnitude.  Padding
+  // is the pattern 0x7FFF (a NaN in fp16 and bf16), which fails every "<= threshold" test.
   const uint16_t* sorted = s_keys;       // padded layout: element i at sorted[phys(i)]
 
-  // ---- prefix sums of the sorted values: exclusive prefix at every BS-th position ----------
+  // ---- prefix sums of the sorted magnitudes: exclusive prefix at every BS-th position; for INT4
+  // also of the negative elements' magnitudes and of their number at every BSN-th position -------
   {
     constexpr int NB8 = 8 / BS;             // prefix entries per 8 elements
+    constexpr int R8 = BSN / 8;             // 8-element pieces per entry of the negative elements' prefix
     double bs[CH][NB8], tsum = 0.0;
+    double ng[CH], nsum = 0.0;
+    uint32_t nc[CH], ncnt = 0;
     // no padding among this wave's positions: the common case needs no per-element test (the
     // second copy of the loop only pays where it is short)
     const bool wave_full = CH <= 4 && __builtin_amdgcn_readfirstlane((wave + 1) * 64 * E) <= n;
+    // A wave whose largest magnitude stays below 7 on every candidate's INT4 scale holds no element
+    // beyond INT4's last boundary (7.5 less one fp32 step) and neither does any wave before it:
+    // their negative elements are left out of these prefixes (only differences between positions
+    // at or beyond the first such element are ever taken) and their entries are never read.
+    bool need_neg = false;
+    if constexpr (ANY_TAIL) {
+      constexpr int FT = TAIL_A ? 0 : 1;
+      float s_min = __builtin_inff();
+      for (int k = lane; k < K; k += 64) s_min = __builtin_fminf(s_min, s_scale[FT][k]);
+      s_min = -wave_max(-s_min);
+      const float inv_max = 1.0f / s_min;   // the largest reciprocal: the correctly rounded quotient does not increase with the scale
+      const float x_hi = __builtin_fabsf(bits_to_float<In>(sorted[phys((wave + 1) * 64 * E - 1)]));
+      need_neg = !(__builtin_amdgcn_readfirstlane(f2u(x_hi * inv_max)) < f2u(7.0f));   // non-negative floats order like their patterns; a NaN is above
+    }
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
       const uint32_t* cp = reinterpret_cast<const uint32_t*>(&sorted[phys(tid * E + j * 8)]);
@@ -365,16 +399,35 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
         for (int i = g * BS; i < (g + 1) * BS; ++i) {
           const uint32_t h = (v[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
           const int pos = tid * E + j * 8 + i;
-          const double val = static_cast<double>(bits_to_float<In>(h));
+          const double val = static_cast<double>(__builtin_fabsf(bits_to_float<In>(h)));
           b += (wave_full || pos < n) ? val : 0.0;
         }
         bs[j][g] = b;
         tsum += b;
       }
+      ng[j] = 0.0;
+      nc[j] = 0;
+      if (need_neg) {   // wave-uniform; the padding pattern is positive
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t w = v[i] & sign_fill2(v[i]);   // positive halves become +0
+          ng[j] += static_cast<double>(__builtin_fabsf(bits_to_float<In>(w & 0xFFFFu)));
+          ng[j] += static_cast<double>(__builtin_fabsf(bits_to_float<In>(w >> 16)));
+          nc[j] += static_cast<uint32_t>(__builtin_popcount(v[i] & 0x80008000u));
+        }
+        nsum += ng[j];
+        ncnt += nc[j];
+      }
     }
     double wtot;
     double base = wave_excl_scan_f64(tsum, wtot);
-    if (lane == 0) s_wsum[2][wave] = wtot;
+    double nbase = 0.0, wntot = 0.0;
+    uint32_t cbase = 0, wctot = 0;
+    if (need_neg) {
+      nbase = wave_excl_scan_f64(nsum, wntot);
+      cbase = wave_excl_scan_u32(ncnt, wctot);
+    }
+    if (lane == 0) { s_wsum[2][wave] = wtot; s_wnsum[wave] = wntot; s_wncnt[wave] = wctot; }
     __syncthreads();                       // also: every thread is done reading the sort buffers
     double wbase = 0.0;
     for (int w = 0; w < wave; ++w) wbase += s_wsum[2][w];
@@ -384,6 +437,19 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
 #pragma unroll
       for (int g = 0; g < NB8; ++g) { s_blk[(tid * CH + j) * NB8 + g] = base; base += bs[j][g]; }
     if (tid == THREADS - 1) s_blk[NBLK] = base;
+    if constexpr (ANY_TAIL) {
+      if (need_neg || wave == NW - 1) {   // the last wave also leaves the totals
+        for (int w = 0; w < wave; ++w) { nbase += s_wnsum[w]; cbase += s_wncnt[w]; }
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+          const int g8 = tid * CH + j;
+          if (g8 % R8 == 0) { s_nsum[g8 / R8] = nbase; s_ncnt[g8 / R8] = static_cast<uint16_t>(cbase); }
+          nbase += ng[j];
+          cbase += nc[j];
+        }
+        if (tid == THREADS - 1) { s_nsum[NNEG - 1] = nbase; s_ncnt[NNEG - 1] = static_cast<uint16_t>(cbase); }
+      }
+    }
     __syncthreads();
   }
   const double s_total = s_blk[NBLK];
@@ -398,25 +464,25 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
     // length is 3 * 2^k), FIRST/2, .., 1: they add up to NP - 1 and no probe leaves that
     // range.  The last element is tested on its own afterwards.  Steps that are multiples of
     // 64 or distinct smaller powers of two keep the padded offsets additive.
-    const float x_last = bits_to_float<In>(sorted[phys(NP - 1)]);
-    const float x_first = bits_to_float<In>(sorted[phys(FIRST - 1)]);   // the first step's probe
+    const uint32_t h_last = sorted[phys(NP - 1)];
+    const uint32_t h_first = sorted[phys(FIRST - 1)];   // the first step's probe
     const int chunks = (K + 63) >> 6;
-    for (int u = wave; u < NF * chunks * SPLIT; u += NW) {
-      const int sub = u % SPLIT, fc = u / SPLIT;      // wave-uniform
-      const int f = fc / chunks;
-      const int k = (fc - f * chunks) * 64 + lane;
+    // NQ: boundaries this lane searches; TAIL: the last of them is INT4's extra one
+    auto unit = [&](auto nq_tag, auto tail_tag, const int f, const int k, const int sub) {
+      constexpr int NQ = decltype(nq_tag)::value;
+      constexpr bool TAIL = decltype(tail_tag)::value;
       const int q0 = sub * QB;                         // first boundary of this lane
-      const float inv = s_inv[f][k < K ? k : K - 1];
-      int ppos[QB];   // padded byte offset of the next probe; of the position at the end
-      // Branch-free: position = number of elements on levels <= q.  Every element before the
-      // position passes the test; the NaN padding stops it at n.  The offset of the next
-      // step's probe rides along in the position.  The first step probes the same element
+      const float inv = 1.0f / s_scale[f][k < K ? k : K - 1];
+      int ppos[NQ];   // padded byte offset of the next probe; of the position at the end
+      // Branch-free: position = number of elements on level magnitudes <= m_q.  Every element
+      // before the position passes the test; the NaN padding stops it at n.  The offset of the
+      // next step's probe rides along in the position.  The first step probes the same element
       // for every boundary: one product serves them all.
       {
         constexpr int NEXT = NP_POW2 ? FIRST / 2 : FIRST;     // size of the step after the first
-        const float t0 = x_first * inv;
+        const float t0 = scaled<In>(h_first, inv);
 #pragma unroll
-        for (int q = 0; q < QB; ++q)
+        for (int q = 0; q < NQ; ++q)
           ppos[q] = 2 * phys(NEXT - 1) + ((t0 <= a.thr[f][q0 + q]) ? 2 * phys(FIRST) : 0);
       }
 #pragma unroll 1
@@ -426,17 +492,17 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
         const int next_probe = stp > 1 ? 2 * phys((stp >> 1) - 1) : 0;
         const int stay = next_probe - 2 * phys(stp - 1), go = stay + 2 * phys(stp);
 #pragma unroll
-        for (int q = 0; q < QB; ++q) {
+        for (int q = 0; q < NQ; ++q) {
           const uint32_t h = *reinterpret_cast<const uint16_t*>(s_raw + ppos[q]);
           const float t = scaled<In>(h, inv);
           ppos[q] += (t <= a.thr[f][q0 + q]) ? go : stay;
         }
       }
-      const float t_last = x_last * inv;
+      const float t_last = scaled<In>(h_last, inv);
       double ca = 0.0;
-      int cb4 = 0;       // 4 sum_b (count below boundary b) (g_b^2 - g_{b+1}^2): an integer below 2^31
+      int cb4 = 0;       // 4 sum_b (count below boundary b) (m_b^2 - m_{b+1}^2): an integer below 2^31
 #pragma unroll
-      for (int q = 0; q < QB; ++q) {
+      for (int q = 0; q < NQ; ++q) {
         // position in elements: the padded byte offset holds 132 bytes per 64 elements
         // (slot / 66 = slot * 993 >> 16 for every slot of a row of up to 24576 elements: the slot of
         // an element leaves a remainder of at most 63, so the quotient's fraction stays below 1 - 2/66
@@ -444,24 +510,48 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
         const int slot = ppos[q] >> 1;
         const int j0 = slot - 2 * static_cast<int>(__umul24(static_cast<uint32_t>(slot), 993u) >> 16);
         const int j = j0 + (t_last <= a.thr[f][q0 + q] ? 1 : 0);
-        constexpr int LB = (BS == 2) ? 1 : (BS == 4 ? 2 : 3);
-        double p = s_blk[j >> LB];
-        if constexpr (BS == 2) {
-          // an odd position adds the element before it, which sits at the offset rounded down
-          // to 4 bytes (an even position reads its own element there and drops it; j = NP is even)
-          const uint32_t hv = *reinterpret_cast<const uint16_t*>(s_raw + (ppos[q] & ~3));
-          p += static_cast<double>(bits_to_float<In>(hv & static_cast<uint32_t>(-(j & 1))));
-        } else {
-          const int jb = phys(j & ~(BS - 1));
+        if constexpr (TAIL) if (q == NQ - 1) {   // (the statement ends with `continue`)
+          // negative elements at positions >= j: the totals less the prefix at j, which is the
+          // entry of j's block plus the negative ones among the block's first j % BSN elements
+          // (a block is 4-byte aligned and lies within one 64-element run of the padded layout)
+          const int blk = j / BSN, rem = j % BSN;
+          double pn = s_nsum[blk];
+          uint32_t cn = s_ncnt[blk];
+          // j = NP (rem = 0) reads nothing beyond the row: the addresses are clamped to the last block
+          const uint32_t* bp = reinterpret_cast<const uint32_t*>(&sorted[phys((blk < NP / BSN ? blk : NP / BSN - 1) * BSN)]);
 #pragma unroll
-          for (int i = 0; i < BS - 1; ++i) {
-            const bool in = i < (j & (BS - 1));
-            const double val = static_cast<double>(bits_to_float<In>(sorted[in ? jb + i : 0]));
-            p += in ? val : 0.0;
+          for (int w = 0; w < BSN / 2; ++w) {
+            uint32_t v = bp[w];
+            v &= sign_fill2(v);                                   // negative elements only
+            v &= (2 * w + 1 < rem) ? 0xFFFFFFFFu : ((2 * w < rem) ? 0x0000FFFFu : 0u);   // the first rem elements only
+            pn += static_cast<double>(__builtin_fabsf(bits_to_float<In>(v & 0xFFFFu)));
+            pn += static_cast<double>(__builtin_fabsf(bits_to_float<In>(v >> 16)));
+            cn += static_cast<uint32_t>(__builtin_popcount(v & 0x80008000u));
           }
+          ca = __builtin_fma(s_nsum[NNEG - 1] - pn, a.dgd[f][q0 + q], ca);
+          cb4 = __mul24(static_cast<int>(s_ncnt[NNEG - 1]) - static_cast<int>(cn), a.dg2q[f][q0 + q]) + cb4;
+          continue;
         }
-        ca = __builtin_fma(p, a.dgd[f][q0 + q], ca);
-        cb4 = __mul24(j, a.dg2q[f][q0 + q]) + cb4;
+        {
+          constexpr int LB = (BS == 2) ? 1 : (BS == 4 ? 2 : 3);
+          double p = s_blk[j >> LB];
+          if constexpr (BS == 2) {
+            // an odd position adds the element before it, which sits at the offset rounded down
+            // to 4 bytes (an even position reads its own element there and drops it; j = NP is even)
+            const uint32_t hv = *reinterpret_cast<const uint16_t*>(s_raw + (ppos[q] & ~3));
+            p += static_cast<double>(__builtin_fabsf(bits_to_float<In>(hv & static_cast<uint32_t>(-(j & 1)))));
+          } else {
+            const int jb = phys(j & ~(BS - 1));
+#pragma unroll
+            for (int i = 0; i < BS - 1; ++i) {
+              const bool in = i < (j & (BS - 1));
+              const double val = static_cast<double>(__builtin_fabsf(bits_to_float<In>(sorted[in ? jb + i : 0])));
+              p += in ? val : 0.0;
+            }
+          }
+          ca = __builtin_fma(p, a.dgd[f][q0 + q], ca);
+          cb4 = __mul24(j, a.dg2q[f][q0 + q]) + cb4;
+        }
       }
       if constexpr (SPLIT == 1) {
         if (k < K) {
@@ -476,6 +566,20 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
           s_pca[(f * MOFQ_MAX_CLIP + k) * SPLIT + sub] = ca;
           s_pcb[(f * MOFQ_MAX_CLIP + k) * SPLIT + sub] = cb4;
         }
+      }
+    };
+    for (int u = wave; u < NF * chunks * SPLIT; u += NW) {
+      const int sub = u % SPLIT, fc = u / SPLIT;      // wave-uniform
+      const int f = fc / chunks;
+      const int k = (fc - f * chunks) * 64 + lane;
+      const bool tail = (f == 0) ? TAIL_A : TAIL_B;   // wave-uniform
+      if constexpr (SPLIT == 1) {
+        if (tail) unit(std::integral_constant<int, 8>{}, std::true_type{}, f, k, sub);
+        else unit(std::integral_constant<int, 7>{}, std::false_type{}, f, k, sub);
+      } else {
+        // E2M1's slot 7 carries zero weights and a threshold no element passes
+        if (tail && sub == SPLIT - 1) unit(std::integral_constant<int, QB>{}, std::true_type{}, f, k, sub);
+        else unit(std::integral_constant<int, QB>{}, std::false_type{}, f, k, sub);
       }
     }
     if constexpr (SPLIT > 1) {
@@ -500,11 +604,14 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   __syncthreads();
 
   // ---- shortlist: candidates the filter cannot separate from the best ---------------------
-  // Rounding of the filtered error, with u = 2^-53.  Every prefix sum comes from a summation
-  // tree of depth at most D = 2E + 32 (thread-sequential, wave scan, across waves) and is off
-  // by at most D u sum|x|; the level differences of one format add up to less than 16 and the
-  // largest level is at most 8, so the level sum A is off by less than 32 D u sum|x| including
-  // its own additions (15, and 3 more where the boundaries are dealt to four waves).  The energy is off by (E + 14) u sum x^2; counts, level squares and
+  // Rounding of the filtered error, with u = 2^-53.  Every prefix sum (of magnitudes: no
+  // cancellation) comes from a summation tree of depth at most D = 2E + 32 (thread-sequential,
+  // wave scan, across waves, the elements of a partly covered block) and is off by at most
+  // D u sum|x|; the level differences of one format add up to at most 7, the largest level of
+  // the symmetric part is at most 7 and INT4's extra level adds the difference of two such
+  // prefix sums once, so the level sum A is off by less than 32 D u sum|x| including its own
+  // additions (8, and 3 more where the boundaries are dealt to four waves).  The energy is off
+  // by (E + 14) u sum x^2; counts, level squares and
   // s^2 are exact; the remaining products and additions round a handful of times on terms
   // bounded by the three summands.  Hence
   //   |filtered - exact| <= beta = u (40 D * 2 s sum|x| + (E + 32) sum x^2 + 8 s^2 g_max^2 n).
@@ -552,7 +659,7 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
     const int fk = s_list[e];
     const int f = __builtin_amdgcn_readfirstlane(fk / MOFQ_MAX_CLIP);
     const int k = __builtin_amdgcn_readfirstlane(fk % MOFQ_MAX_CLIP);
-    const float s = s_scale[f][k], inv = s_inv[f][k];
+    const float s = s_scale[f][k], inv = 1.0f / s;
     const double sd = static_cast<double>(s);
     double acc = 0.0;
 #pragma unroll
@@ -603,38 +710,37 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
 
 // ---- host: rounding thresholds of the level boundaries ---------------------------------------
 
-// Levels of a 4-bit format in ascending order, and for each boundary b the largest fp32 t
-// that still lands on level b or below.
+// Level magnitudes of a 4-bit format in ascending order, and for each boundary b the largest
+// fp32 t = |x| / s that still lands on magnitude m_b or below.  Rounding is to nearest with ties
+// to the even code, which is symmetric in the sign.
 void fill_levels(int fmt, SortedArgs& a, int slot) {
-  double lv[16];
-  bool up_is_even[16];   // at the midpoint between lv[b] and lv[b+1], does the tie go to lv[b+1]?
-  int nl = 0;
-  if (fmt == MOFQ_INT4) {
-    for (int q = -8; q <= 7; ++q) lv[nl++] = q;
-    for (int b = 0; b + 1 < nl; ++b) up_is_even[b] = (static_cast<int>(lv[b + 1]) % 2 == 0);
-  } else {  // E2M1: magnitudes by code 0..7; the even code wins a tie
+  double m[9];
+  bool up_is_even[8];   // at the midpoint between m[b] and m[b+1], does the tie go to m[b+1]?
+  const bool int4 = fmt == MOFQ_INT4;
+  if (int4) {
+    for (int q = 0; q <= 8; ++q) m[q] = q;   // 8 only on the negative side
+  } else {  // E2M1: magnitudes by code 0..7
     const double mag[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
-    for (int c = 7; c >= 1; --c) lv[nl++] = -mag[c];
-    lv[nl++] = 0.0;
-    for (int c = 1; c <= 7; ++c) lv[nl++] = mag[c];
-    for (int b = 0; b + 1 < nl; ++b) {
-      // magnitude code of the upper level: index b+1 -> code |b+1-7|
-      const int code_up = std::abs(b + 1 - 7), code_lo = std::abs(b - 7);
-      (void)code_lo;
-      up_is_even[b] = (code_up % 2 == 0);
-    }
+    for (int c = 0; c < 8; ++c) m[c] = mag[c];
+    m[8] = mag[7];
   }
-  a.nb[slot] = nl - 1;
-  a.g_last[slot] = static_cast<float>(lv[nl - 1]);
-  a.g_absmax[slot] = static_cast<float>(std::fmax(std::fabs(lv[0]), std::fabs(lv[nl - 1])));
-  for (int b = 0; b < 16; ++b) { a.thr[slot][b] = 0.0f; a.dgd[slot][b] = 0.0; a.dg2q[slot][b] = 0; }
-  for (int b = 0; b + 1 < nl; ++b) {
-    const float mid = static_cast<float>(0.5 * (lv[b] + lv[b + 1]));   // exact in fp32
-    // tie goes up  -> level <= b needs t <  mid -> t <= the float just below mid
-    // tie goes down-> level <= b needs t <= mid
+  for (int b = 0; b < 8; ++b) up_is_even[b] = ((b + 1) % 2 == 0);   // INT4: the integer b + 1; E2M1: the code b + 1
+  a.g_last[slot] = static_cast<float>(m[7]);
+  a.g_absmax[slot] = static_cast<float>(m[8]);
+  for (int b = 0; b < 8; ++b) { a.thr[slot][b] = -INFINITY; a.dgd[slot][b] = 0.0; a.dg2q[slot][b] = 0; }
+  for (int b = 0; b < 7; ++b) {
+    const float mid = static_cast<float>(0.5 * (m[b] + m[b + 1]));   // exact in fp32
+    // tie goes up  -> magnitude <= m_b needs t <  mid -> t <= the float just below mid
+    // tie goes down-> magnitude <= m_b needs t <= mid
     a.thr[slot][b] = up_is_even[b] ? std::nextafterf(mid, -INFINITY) : mid;
-    a.dgd[slot][b] = lv[b] - lv[b + 1];
-    a.dg2q[slot][b] = static_cast<int32_t>(4.0 * (lv[b] * lv[b] - lv[b + 1] * lv[b + 1]));   // exact
+    a.dgd[slot][b] = m[b] - m[b + 1];
+    a.dg2q[slot][b] = static_cast<int32_t>(4.0 * (m[b] * m[b] - m[b + 1] * m[b + 1]));   // exact
+  }
+  if (int4) {
+    // a negative element stays on -7 while t < 7.5 (the tie goes to the even 8); beyond, it lands on -8
+    a.thr[slot][7] = std::nextafterf(7.5f, -INFINITY);
+    a.dgd[slot][7] = m[8] - m[7];
+    a.dg2q[slot][7] = static_cast<int32_t>(4.0 * (m[8] * m[8] - m[7] * m[7]));
   }
 }
 
