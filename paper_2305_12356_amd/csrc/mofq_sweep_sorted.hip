@@ -54,6 +54,7 @@ struct SortedArgs {
   uint32_t row0[kSweepGroupMax];   // number of the first row of tensor i (unused entries: 0xFFFFFFFF)
   int64_t cols;                    // of every tensor
   int32_t scale_f16, n_clip;
+  int32_t nbin, ntbin;             // histogram kernel: counters of the row's histogram and of INT4's negative elements
   float clip[MOFQ_MAX_CLIP];
   // per format slot: level magnitudes 0 = m_0 < m_1 < ... < m_7;  |level|(t) <= m_b  <=>  t <= thr[b]
   // for b = 0..6.  Entry 7 is INT4's extra boundary (|t| below it: a negative element stays on -7)
@@ -708,6 +709,415 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
   }
 }
 
+// ---- the same search from a histogram of the magnitudes' bit patterns --------------------------
+//
+// The decision "fl32(|x| * inv) <= threshold" is monotone in the magnitude's bit pattern, so for
+// every (candidate, boundary) there is one largest pattern H that passes, and the elements on
+// level magnitudes up to m_b are those with pattern <= H.  Instead of sorting the row, the kernel
+// counts the elements per pattern (16-bit counters, two per word, LDS adds), forms count and
+// magnitude-sum prefixes over groups of 8 patterns (a group shares its exponent, so its elements'
+// magnitudes are v0 + i ulp and its sum is v0 C + ulp sum i c_i, exact in fp64), finds H from
+// an fp32 estimate proven with four exact decisions (a pattern-space binary search where the
+// estimate is off by more than one pattern), and reads count and sum up to H from the group
+// prefix and one 16-byte read of the group's counters.  Only the patterns between the smallest
+// threshold and the row's largest magnitude get a counter: elements below every threshold sit on
+// level 0 for every candidate and drop out of both level sums.  How many patterns that is
+// depends on the clip ratios alone, so the host sizes the histogram (dynamic LDS) and uses the
+// sorting kernel where it would not fit.  INT4's negative elements beyond its extra boundary
+// are counted in a second, short histogram over the top of the range.
+//
+// Filter, shortlist and exact fp64 re-score are those of the sorting kernel; the re-score walks
+// the row in its registers.
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+MOFQ_DEV uint32_t dot2(uint32_t a, uint32_t b, uint32_t c) {   // a.lo b.lo + a.hi b.hi + c
+  return __builtin_amdgcn_udot2(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b), c, false);
+}
+
+// bit pattern of x >= 0 rounded toward zero to the input type; largest finite pattern
+template <typename In> MOFQ_DEV uint32_t pattern_rtz(float x);
+template <> MOFQ_DEV uint32_t pattern_rtz<F16>(float x) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(x, 0.0f)) & 0xFFFFu;
+}
+template <> MOFQ_DEV uint32_t pattern_rtz<BF16>(float x) { return f2u(x) >> 16; }
+template <typename In> struct Pattern;
+template <> struct Pattern<F16> { static constexpr int MAX_FINITE = 0x7BFF; };
+template <> struct Pattern<BF16> { static constexpr int MAX_FINITE = 0x7F7F; };
+
+constexpr int kHistMaxBins = 8192;      // patterns with a counter (16 KB)
+constexpr int kHistMaxTailBins = 2048;  // of INT4's negative elements
+
+// Count and magnitude sum of the histogram's elements with pattern <= lo + bin, for
+// -1 <= bin (bin = -1: none); bins beyond the last are empty, so bin is clamped to it.
+// hist: counters, two per word; cntp / sump: exclusive prefixes per group of 8 bins.
+template <typename In>
+MOFQ_DEV void hist_prefix(const uint32_t* hist, const uint32_t* cntp, const double* sump, int lo, int nbin,
+                          int bin, uint32_t& C, double& S) {
+  const bool none = bin < 0;
+  const int bc = none ? 0 : (bin < nbin - 1 ? bin : nbin - 1);
+  const int g = bc >> 3, r = bc & 7;
+  const u32x4 w = *reinterpret_cast<const u32x4*>(hist + 4 * g);
+  uint32_t cin = 0, win = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    // counters 2i and 2i + 1 of the group: both where 2i + 1 <= r, the low one where 2i == r
+    const uint32_t m = (r >= 2 * i + 1) ? 0xFFFFFFFFu : ((r == 2 * i) ? 0x0000FFFFu : 0u);
+    const uint32_t v = w[i] & m;
+    cin = dot2(v, 0x00010001u, cin);
+    win = dot2(v, static_cast<uint32_t>(2 * i) | (static_cast<uint32_t>(2 * i + 1) << 16), win);
+  }
+  const float v0 = bits_to_float<In>(static_cast<uint32_t>(lo + 8 * g));
+  const float ulp = bits_to_float<In>(static_cast<uint32_t>(lo + 8 * g + 1)) - v0;   // exact
+  double s = sump[g];
+  s = __builtin_fma(static_cast<double>(v0), static_cast<double>(cin), s);
+  s = __builtin_fma(static_cast<double>(ulp), static_cast<double>(win), s);
+  C = none ? 0u : cntp[g] + cin;
+  S = none ? 0.0 : s;
+}
+
+// Exclusive prefixes of count and magnitude sum per group of 8 bins; the totals in entry ng.
+// Thread t takes the groups [t gp, (t + 1) gp), gp <= GPMAX.  Called by all threads.
+template <typename In, int THREADS, int GPMAX>
+MOFQ_DEV void hist_group_prefixes(const uint32_t* hist, uint32_t* cntp, double* sump, int lo, int ng, int gp,
+                                  uint32_t* s_wc, double* s_ws) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint32_t c8[GPMAX];
+  double s8[GPMAX];
+  uint32_t ct = 0;
+  double st = 0.0;
+#pragma unroll
+  for (int i = 0; i < GPMAX; ++i) {
+    const int g = tid * gp + i;
+    c8[i] = 0;
+    s8[i] = 0.0;
+    if (i < gp && g < ng) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(hist + 4 * g);
+      uint32_t c = 0, wsum = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        c = dot2(w[j], 0x00010001u, c);
+        wsum = dot2(w[j], static_cast<uint32_t>(2 * j) | (static_cast<uint32_t>(2 * j + 1) << 16), wsum);
+      }
+      const float v0 = bits_to_float<In>(static_cast<uint32_t>(lo + 8 * g));
+      const float ulp = bits_to_float<In>(static_cast<uint32_t>(lo + 8 * g + 1)) - v0;
+      c8[i] = c;
+      s8[i] = __builtin_fma(static_cast<double>(ulp), static_cast<double>(wsum), static_cast<double>(v0) * static_cast<double>(c));
+      ct += c;
+      st += s8[i];
+    }
+  }
+  uint32_t wct;
+  double wst;
+  uint32_t cb = wave_excl_scan_u32(ct, wct);
+  double sb = wave_excl_scan_f64(st, wst);
+  if (lane == 0) { s_wc[wave] = wct; s_ws[wave] = wst; }
+  __syncthreads();
+  for (int w = 0; w < wave; ++w) { cb += s_wc[w]; sb += s_ws[w]; }
+#pragma unroll
+  for (int i = 0; i < GPMAX; ++i) {
+    const int g = tid * gp + i;
+    if (i < gp && g < ng) { cntp[g] = cb; sump[g] = sb; }
+    cb += c8[i];
+    sb += s8[i];
+  }
+  if (tid == THREADS - 1) { cntp[ng] = cb; sump[ng] = sb; }
+  __syncthreads();
+}
+
+template <typename In, int FA, int FB, int CH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(CH <= 2 ? 6 : (CH <= 6 ? 5 : 4))))
+void sweep_hist_kernel(const SortedArgs a) {
+  using L = Load8<In>;
+  constexpr int THREADS = 256;
+  constexpr int NF = (FB >= 0) ? 2 : 1;
+  constexpr int FBX = (FB >= 0) ? FB : FA;
+  constexpr int NW = THREADS / 64;
+  constexpr int E = CH * 8;            // elements per thread
+  constexpr int MAXL = NF * MOFQ_MAX_CLIP;
+  constexpr bool TAIL_A = FA == MOFQ_INT4, TAIL_B = (FB >= 0) && FBX == MOFQ_INT4;
+  constexpr bool ANY_TAIL = TAIL_A || TAIL_B;
+  constexpr int GPMAX = kHistMaxBins / 8 / THREADS;   // groups per thread at most
+  static_assert(kHistMaxTailBins / 8 <= THREADS, "one group of the short histogram per thread");
+
+  // dynamic LDS: [sump | tsump | hist | thist | cntp | tcntp]
+  extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
+  const int nbin = a.nbin, ntbin = ANY_TAIL ? a.ntbin : 0;   // multiples of 8
+  const int ng = nbin >> 3, ntg = ntbin >> 3;
+  double* const sump = reinterpret_cast<double*>(s_dyn);
+  double* const tsump = sump + (ng + 1);
+  uint32_t* const hist = reinterpret_cast<uint32_t*>(s_dyn + (((ng + 1) + (ntg + 1)) * 8 + 15) / 16 * 16);
+  uint32_t* const thist = hist + (nbin >> 1);
+  uint32_t* const cntp = thist + (ntbin >> 1);
+  uint32_t* const tcntp = cntp + (ng + 1);
+
+  __shared__ float s_scale[NF][MOFQ_MAX_CLIP];
+  __shared__ double s_fast[NF][MOFQ_MAX_CLIP];
+  __shared__ float s_wmax[NW];
+  __shared__ double s_wsum[2][NW];
+  __shared__ uint32_t s_wc[NW];
+  __shared__ double s_ws[NW];
+  __shared__ double s_thr[NF];
+  __shared__ int s_direct[NF];   // the winning candidate where no element-wise pass is needed, else -1
+  __shared__ uint8_t s_list[MAXL];   // format * MOFQ_MAX_CLIP + candidate
+  __shared__ int s_nlist;
+  __shared__ double s_p2[NW];
+  __shared__ double s_val[MAXL];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  uint32_t tensor = 0;                                                    // wave-uniform
+#pragma unroll
+  for (int i = 1; i < kSweepGroupMax; ++i) tensor += (blockIdx.x >= a.row0[i]);
+  const int64_t row = blockIdx.x - a.row0[tensor];
+  const SortedTensor& T = a.t[tensor];
+  const typename L::elem* src = static_cast<const typename L::elem*>(T.w) + row * T.ld;
+  const int K = a.n_clip;
+  const int n = static_cast<int>(a.cols);
+
+  // ---- load the row (it stays in registers): absmax, energy; clear the counters ----------------
+  u32x4 rawv[CH];
+  float amax = 0.0f, l1f = 0.0f;
+  uint32_t amax2 = 0;   // fp16 rows: running maximum of |x| in both halves of a register
+  double en = 0.0;
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const int64_t c0 = (static_cast<int64_t>(j) * THREADS + tid) * 8;
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    if (c0 < a.cols) raw = *reinterpret_cast<const u32x4*>(src + c0);
+    rawv[j] = raw;
+  }
+  {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    for (int i = tid; i < ng + ntg; i += THREADS) reinterpret_cast<u32x4*>(hist)[i] = zero;   // hist and thist are adjacent
+  }
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t h0 = rawv[j][i] & 0xFFFFu, h1 = rawv[j][i] >> 16;
+      const float v0 = bits_to_float<In>(h0), v1 = bits_to_float<In>(h1);
+      if constexpr (std::is_same<In, F16>::value) {
+        amax2 = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(f16x2, amax2),
+                                                                       __builtin_bit_cast(f16x2, rawv[j][i] & 0x7FFF7FFFu)));
+      } else {
+        amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fabsf(v0), __builtin_fabsf(v1)));
+      }
+      const double d0 = static_cast<double>(v0), d1 = static_cast<double>(v1);
+      en = __builtin_fma(d0, d0, en);
+      en = __builtin_fma(d1, d1, en);
+      l1f += __builtin_fabsf(v0) + __builtin_fabsf(v1);
+    }
+  }
+  if constexpr (std::is_same<In, F16>::value)
+    amax = __builtin_fmaxf(bits_to_float<In>(amax2 & 0xFFFFu), bits_to_float<In>(amax2 >> 16));
+  amax = wave_max(amax);
+  en = wave_sum(en);
+  // sum |x| only enters the rounding bounds below (see the sorting kernel)
+  double l1 = static_cast<double>(wave_sum_f32(l1f)) * (1.0 + 0x1p-17);
+  if (lane == 0) { s_wmax[wave] = amax; s_wsum[0][wave] = en; s_wsum[1][wave] = l1; }
+  __syncthreads();   // also: the counters are clear
+  amax = s_wmax[0];
+  en = s_wsum[0][0];
+  l1 = s_wsum[1][0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) {
+    amax = __builtin_fmaxf(amax, s_wmax[w]);
+    en += s_wsum[0][w];
+    l1 += s_wsum[1][w];
+  }
+  for (int idx = tid; idx < NF * K; idx += THREADS) {
+    const int f = idx / K, k = idx - f * K;
+    const float qmax = (f == 0) ? Codec<FA>::QMAX : Codec<FBX>::QMAX;
+    s_scale[f][k] = unit_scale(amax, a.clip[k], qmax, a.scale_f16 != 0);
+  }
+
+  // ---- the histogram covers the nbin patterns up to the largest magnitude's (a non-finite
+  // element lands in the last counter: the row's error is non-finite anyway) --------------------
+  const int hmax = static_cast<int>(pattern_rtz<In>(amax < 3.0e38f ? amax : 3.0e38f));   // exact for a finite amax
+  const int lo = (((hmax + 1 - nbin) > 0 ? (hmax + 1 - nbin) : 0) + 7) & ~7;
+  const int tlo = (((hmax + 1 - ntbin) > 0 ? (hmax + 1 - ntbin) : 0) + 7) & ~7;
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t hs = (rawv[j][i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
+      const int h = static_cast<int>(hs & 0x7FFFu);
+      const int bin = h - lo;
+      if (bin >= 0) {   // padding and whatever lies below every threshold has no counter
+        const int bc = bin < nbin - 1 ? bin : nbin - 1;
+        atomicAdd(&hist[bc >> 1], 1u << ((bc & 1) * 16));
+      }
+      if constexpr (ANY_TAIL) {
+        const int tb = h - tlo;
+        if (tb >= 0 && (hs & 0x8000u)) {
+          const int tc = tb < ntbin - 1 ? tb : ntbin - 1;
+          atomicAdd(&thist[tc >> 1], 1u << ((tc & 1) * 16));
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- group prefixes ----------------------------------------------------------------------------
+  hist_group_prefixes<In, THREADS, GPMAX>(hist, cntp, sump, lo, ng, (ng + THREADS - 1) / THREADS, s_wc, s_ws);
+  if constexpr (ANY_TAIL) hist_group_prefixes<In, THREADS, 1>(thist, tcntp, tsump, tlo, ntg, 1, s_wc, s_ws);
+  const uint32_t c_total = cntp[ng];
+  const double s_total = sump[ng];
+
+  // ---- level boundaries of every candidate: one lane per candidate, one wave per (format, 64
+  // candidates) --------------------------------------------------------------------------------
+  {
+    const int chunks = (K + 63) >> 6;
+    auto unit = [&](auto tail_tag, const int f, const int k) {
+      constexpr bool TAIL = decltype(tail_tag)::value;
+      const float s = s_scale[f][k < K ? k : K - 1];
+      const float inv = 1.0f / s;
+      // H = the largest finite pattern h with fl32(v(h) * inv) <= thr.  v(0) = 0 passes.
+      auto threshold_pattern = [&](const float thr) {
+        auto pass = [&](int h) { return scaled<In>(static_cast<uint32_t>(h), inv) <= thr; };
+        int hc = static_cast<int>(pattern_rtz<In>(thr * s));
+        hc = hc < 1 ? 1 : (hc > Pattern<In>::MAX_FINITE - 2 ? Pattern<In>::MAX_FINITE - 2 : hc);
+        const bool p0 = pass(hc - 1), p1 = pass(hc), p2 = pass(hc + 1), p3 = pass(hc + 2);
+        int H = hc - 2 + (p0 ? 1 : 0) + (p1 ? 1 : 0) + (p2 ? 1 : 0) + (p3 ? 1 : 0);
+        if (!(p0 && !p3)) {   // the estimate is off by more than a pattern (or no finite pattern fails)
+          int lo_h = 0, hi_h = Pattern<In>::MAX_FINITE;   // pass(lo_h) holds; the answer is in [lo_h, hi_h]
+          while (lo_h < hi_h) {
+            const int mid = (lo_h + hi_h + 1) >> 1;
+            if (pass(mid)) lo_h = mid;
+            else hi_h = mid - 1;
+          }
+          H = lo_h;
+        }
+        return H;
+      };
+      double ca = 0.0;
+      int cb4 = 0;       // 4 sum_b (count up to boundary b) (m_b^2 - m_{b+1}^2): an integer below 2^31
+      bool bad = false;  // a threshold below the histogram's range: the candidate goes to the exact pass
+      // one boundary at a time (a rolled loop: unrolled, the eight of them cost some 80 registers)
+#pragma unroll 1
+      for (int q = 0; q < 7; ++q) {
+        const int bin = threshold_pattern(a.thr[f][q]) - lo;
+        bad = bad || bin < -1;
+        uint32_t C;
+        double S;
+        hist_prefix<In>(hist, cntp, sump, lo, nbin, bin, C, S);
+        ca = __builtin_fma(S, a.dgd[f][q], ca);
+        cb4 = __mul24(static_cast<int>(C), a.dg2q[f][q]) + cb4;
+      }
+      if constexpr (TAIL) {
+        // negative elements with a pattern above H: the short histogram's totals less its prefix
+        const int bin = threshold_pattern(a.thr[f][7]) - tlo;
+        bad = bad || bin < -1;
+        uint32_t C;
+        double S;
+        hist_prefix<In>(thist, tcntp, tsump, tlo, ntbin, bin, C, S);
+        ca = __builtin_fma(tsump[ntg] - S, a.dgd[f][7], ca);
+        cb4 = __mul24(static_cast<int>(tcntp[ntg] - C), a.dg2q[f][7]) + cb4;
+      }
+      if (k < K) {
+        const double gl = static_cast<double>(a.g_last[f]);
+        const double A = ca + gl * s_total;
+        const double B = 0.25 * static_cast<double>(cb4) + gl * gl * static_cast<double>(c_total);
+        const double sc = static_cast<double>(s);
+        const double v = (en - 2.0 * sc * A) + sc * sc * B;   // filtered error
+        s_fast[f][k] = bad ? __builtin_nan("") : v;
+      }
+    };
+    for (int u = wave; u < NF * chunks; u += NW) {
+      const int f = u / chunks;                         // wave-uniform
+      const int k = (u - f * chunks) * 64 + lane;
+      const bool tail = (f == 0) ? TAIL_A : TAIL_B;
+      if (tail) unit(std::true_type{}, f, k);
+      else unit(std::false_type{}, f, k);
+    }
+  }
+  __syncthreads();
+
+  // ---- shortlist (bounds as in the sorting kernel: the sums here come from shorter trees) -----
+  for (int f = wave; f < NF; f += NW) {
+    double m = __builtin_inf();
+    int km = 0;
+    float smax = 0.0f;
+    for (int k = lane; k < K; k += 64) {
+      const double v = s_fast[f][k];
+      if (v < m) { m = v; km = k; }
+      smax = __builtin_fmaxf(smax, s_scale[f][k]);
+    }
+    wave_argmin(m, km);
+    smax = wave_max(smax);
+    const double sm = static_cast<double>(smax), gm = static_cast<double>(a.g_absmax[f]);
+    const double nd = static_cast<double>(n);
+    const double mag = en + 2.0 * sm * gm * l1 + sm * sm * gm * gm * nd;
+    const double thr = m + 0x1p-33 * mag;   // twice the margin: both values carry the error
+    int cnt = 0;
+    for (int k0 = 0; k0 < K; k0 += 64) {
+      const int k = k0 + lane;
+      cnt += __builtin_popcountll(__ballot(k < K && !(s_fast[f][k < K ? k : 0] > thr)));
+    }
+    const double beta = 0x1p-53 * (40.0 * (2 * E + 32) * 2.0 * sm * l1 + (E + 32) * en + 8.0 * sm * sm * gm * gm * nd);
+    const bool direct = cnt == 1 && beta <= 0x1p-34 * m;   // false for a zero or non-finite error
+    if (lane == 0) { s_thr[f] = thr; s_direct[f] = direct ? km : -1; }
+  }
+  if (tid == 0) s_nlist = 0;
+  __syncthreads();
+  for (int idx = tid; idx < NF * K; idx += THREADS) {
+    const int f = idx / K, k = idx - f * K;
+    if (s_direct[f] < 0 && !(s_fast[f][k] > s_thr[f]))
+      s_list[atomicAdd(&s_nlist, 1)] = static_cast<uint8_t>(f * MOFQ_MAX_CLIP + k);   // any order
+  }
+  __syncthreads();
+  const int n_list = s_nlist;
+
+  // ---- exact fp64 re-score of the shortlist, element by element ------------------------------
+  uint32_t carry = 0;
+  for (int e = 0; e < n_list; ++e) {
+    const int fk = s_list[e];
+    const int f = __builtin_amdgcn_readfirstlane(fk / MOFQ_MAX_CLIP);
+    const int k = __builtin_amdgcn_readfirstlane(fk % MOFQ_MAX_CLIP);
+    const float s = s_scale[f][k], inv = 1.0f / s;
+    const double sd = static_cast<double>(s);
+    double acc = 0.0;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {   // padding is zero and scores zero
+        const float x0 = bits_to_float<In>(rawv[j][i] & 0xFFFFu);
+        const float x1 = bits_to_float<In>(rawv[j][i] >> 16);
+        if (f == 0) rescore2<FA>(acc, x0, x1, inv, sd, carry);
+        else rescore2<FBX>(acc, x0, x1, inv, sd, carry);
+      }
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) s_p2[wave] = acc;
+    __syncthreads();
+    if (tid == 0) {
+      double t = s_p2[0];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) t += s_p2[w];
+      s_val[e] = t;
+    }
+    __syncthreads();
+  }
+
+  if (tid < NF) {
+    const int f = tid;
+    double best = __builtin_inf();
+    int bk = s_direct[f];
+    if (bk >= 0) best = s_fast[f][bk];
+    for (int e = 0; e < n_list; ++e) {   // smallest error, then smallest index: the first smallest
+      const int fk = s_list[e];
+      if (fk / MOFQ_MAX_CLIP != f) continue;
+      const int k = fk % MOFQ_MAX_CLIP;
+      if (s_val[e] < best || (s_val[e] == best && k < bk)) { best = s_val[e]; bk = k; }
+    }
+    if (bk < 0) { bk = 0; best = __builtin_nan(""); }   // only on non-finite input
+    T.rec.scale[f][row] = s_scale[f][bk];
+    T.rec.clip[f][row] = bk;
+    T.rec.err[f][row] = best;
+    if (f == 0 && T.rec.energy) T.rec.energy[row] = en;
+  }
+}
+
 // ---- host: rounding thresholds of the level boundaries ---------------------------------------
 
 // Level magnitudes of a 4-bit format in ascending order, and for each boundary b the largest
@@ -762,13 +1172,73 @@ int launch_shape(const SortedArgs& a, int64_t total_rows, hipStream_t st) {
   return MOFQ_ERR_UNSUPPORTED;
 }
 
+// The histogram kernel: dynamic LDS for [sum prefixes | counters | count prefixes] of both histograms.
+template <typename In, int FA, int FB>
+int launch_hist_shape(const SortedArgs& a, int64_t total_rows, hipStream_t st) {
+  const dim3 grid(static_cast<unsigned>(total_rows));
+  const int64_t chunks = a.cols / 8;
+  const int ng = a.nbin / 8, ntg = a.ntbin / 8;
+  const size_t lds = (static_cast<size_t>((ng + 1) + (ntg + 1)) * 8 + 15) / 16 * 16 + 2 * static_cast<size_t>(a.nbin + a.ntbin) +
+                     4 * static_cast<size_t>((ng + 1) + (ntg + 1));
+#define MOFQ_HIST(CH)                                                                         \
+  if (chunks <= 256 * (CH)) {                                                                  \
+    hipLaunchKernelGGL((sweep_hist_kernel<In, FA, FB, CH>), grid, dim3(256), lds, st, a);       \
+    return hip_status(hipGetLastError());                                                      \
+  }
+  MOFQ_HIST(1)   //  2048 columns
+  MOFQ_HIST(2)   //  4096
+  MOFQ_HIST(4)   //  8192
+  MOFQ_HIST(6)   // 12288
+  MOFQ_HIST(12)  // 24576
+#undef MOFQ_HIST
+  return MOFQ_ERR_UNSUPPORTED;
+}
+
 template <typename In>
 int launch_fmt(const SweepParams& p, const SortedArgs& a, int64_t total_rows, hipStream_t st) {
   const int fa = p.fmt[0], fb = p.n_fmt == 2 ? p.fmt[1] : -1;
-  if (fa == MOFQ_INT4 && fb == MOFQ_FP4_E2M1) return launch_shape<In, MOFQ_INT4, MOFQ_FP4_E2M1>(a, total_rows, st);
-  if (fa == MOFQ_INT4 && fb == -1) return launch_shape<In, MOFQ_INT4, -1>(a, total_rows, st);
-  if (fa == MOFQ_FP4_E2M1 && fb == -1) return launch_shape<In, MOFQ_FP4_E2M1, -1>(a, total_rows, st);
+  const bool hist = a.nbin > 0;
+  if (fa == MOFQ_INT4 && fb == MOFQ_FP4_E2M1)
+    return hist ? launch_hist_shape<In, MOFQ_INT4, MOFQ_FP4_E2M1>(a, total_rows, st) : launch_shape<In, MOFQ_INT4, MOFQ_FP4_E2M1>(a, total_rows, st);
+  if (fa == MOFQ_INT4 && fb == -1)
+    return hist ? launch_hist_shape<In, MOFQ_INT4, -1>(a, total_rows, st) : launch_shape<In, MOFQ_INT4, -1>(a, total_rows, st);
+  if (fa == MOFQ_FP4_E2M1 && fb == -1)
+    return hist ? launch_hist_shape<In, MOFQ_FP4_E2M1, -1>(a, total_rows, st) : launch_shape<In, MOFQ_FP4_E2M1, -1>(a, total_rows, st);
   return MOFQ_ERR_UNSUPPORTED;
+}
+
+// How many bit patterns lie between a threshold t = c * amax and amax at most: a pattern is
+// (exponent, mantissa) read as an integer, i.e. PPB * (log2 of the value + a term in [0, 0.0861))
+// up to a constant, so two values a factor 1 / c apart are at most PPB * (log2(1 / c) + 0.0861) + 1
+// patterns apart (fewer among subnormals).  The scale's own roundings move a threshold by less than
+// a pattern; the kernel rounds the first counter's pattern up to a multiple of 8.
+int hist_bins(double ratio_amax_over_threshold, int ppb) {
+  const double lg = std::log2(ratio_amax_over_threshold);
+  const double bins = ppb * ((lg > 0.0 ? lg : 0.0) + 0.09) + 24.0;
+  if (!(bins < 1.0e6)) return 1 << 20;
+  return (static_cast<int>(std::ceil(bins)) + 7) / 8 * 8;
+}
+
+// Sizes of the histograms for this configuration, or 0 where they would not fit (then the
+// sorting kernel runs).  They depend on the formats, the clip ratios and the dtype only.
+void hist_sizes(const SweepParams& p, SortedArgs& a) {
+  a.nbin = 0;
+  a.ntbin = 0;
+  float r_min = INFINITY;
+  for (int k = 0; k < p.n_clip; ++k) {
+    if (!(p.clip[k] > 0.0f) || !std::isfinite(p.clip[k])) return;
+    r_min = std::fmin(r_min, p.clip[k]);
+  }
+  const int ppb = p.dtype == MOFQ_F16 ? 1024 : 128;
+  int nbin = 16, ntbin = 0;
+  for (int f = 0; f < p.n_fmt; ++f) {
+    const double qmax = p.fmt[f] == MOFQ_INT4 ? 7.0 : 6.0;
+    nbin = std::max(nbin, hist_bins(qmax / (static_cast<double>(a.thr[f][0]) * r_min), ppb));
+    if (p.fmt[f] == MOFQ_INT4) ntbin = std::max(16, hist_bins(qmax / (static_cast<double>(a.thr[f][7]) * r_min), ppb));
+  }
+  if (nbin > kHistMaxBins || ntbin > kHistMaxTailBins) return;
+  a.nbin = nbin;
+  a.ntbin = ntbin;
 }
 
 }  // namespace
@@ -816,6 +1286,7 @@ int launch_sweep_sorted_group(const SweepParams* ps, int n, hipStream_t st) {
   a.n_clip = p.n_clip;
   for (int k = 0; k < p.n_clip; ++k) a.clip[k] = p.clip[k];
   for (int f = 0; f < p.n_fmt; ++f) fill_levels(p.fmt[f], a, f);
+  hist_sizes(p, a);
   return p.dtype == MOFQ_F16 ? launch_fmt<F16>(p, a, total_rows, st) : launch_fmt<BF16>(p, a, total_rows, st);
 }
 
