@@ -717,8 +717,8 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
 // counts the elements per pattern (16-bit counters, two per word, LDS adds), forms count and
 // magnitude-sum prefixes over groups of 8 patterns (a group shares its exponent, so its elements'
 // magnitudes are v0 + i ulp and its sum is v0 C + ulp sum i c_i, exact in fp64), finds H from
-// an fp32 estimate proven with four exact decisions (a pattern-space binary search where the
-// estimate is off by more than one pattern), and reads count and sum up to H from the group
+// an fp32 estimate proven with two exact decisions (a pattern-space binary search where the
+// estimate is off), and reads count and sum up to H from the group
 // prefix and one 16-byte read of the group's counters.  Only the patterns between the smallest
 // threshold and the row's largest magnitude get a counter: elements below every threshold sit on
 // level 0 for every candidate and drop out of both level sums.  How many patterns that is
@@ -748,20 +748,21 @@ constexpr int kHistMaxTailBins = 2048;  // of INT4's negative elements
 
 // Count and magnitude sum of the histogram's elements with pattern <= lo + bin, for
 // -1 <= bin (bin = -1: none); bins beyond the last are empty, so bin is clamped to it.
-// hist: counters, two per word; cntp / sump: exclusive prefixes per group of 8 bins.
+// hist: counters, two per word; cntp / sump: exclusive prefixes per group of 8 bins;
+// keep[r]: which of a group's eight counters are at or below position r (a table in LDS: one
+// read instead of sixteen compare-and-select instructions).
 template <typename In>
-MOFQ_DEV void hist_prefix(const uint32_t* hist, const uint32_t* cntp, const double* sump, int lo, int nbin,
-                          int bin, uint32_t& C, double& S) {
+MOFQ_DEV void hist_prefix(const uint32_t* hist, const uint32_t* cntp, const double* sump, const u32x4* keep, int lo,
+                          int nbin, int bin, uint32_t& C, double& S) {
   const bool none = bin < 0;
   const int bc = none ? 0 : (bin < nbin - 1 ? bin : nbin - 1);
   const int g = bc >> 3, r = bc & 7;
   const u32x4 w = *reinterpret_cast<const u32x4*>(hist + 4 * g);
+  const u32x4 m = keep[r];   // the group's counters 0..r: 16-bit masks, two per word
   uint32_t cin = 0, win = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    // counters 2i and 2i + 1 of the group: both where 2i + 1 <= r, the low one where 2i == r
-    const uint32_t m = (r >= 2 * i + 1) ? 0xFFFFFFFFu : ((r == 2 * i) ? 0x0000FFFFu : 0u);
-    const uint32_t v = w[i] & m;
+    const uint32_t v = w[i] & m[i];
     cin = dot2(v, 0x00010001u, cin);
     win = dot2(v, static_cast<uint32_t>(2 * i) | (static_cast<uint32_t>(2 * i + 1) << 16), win);
   }
@@ -824,7 +825,7 @@ MOFQ_DEV void hist_group_prefixes(const uint32_t* hist, uint32_t* cntp, double* 
 }
 
 template <typename In, int FA, int FB, int CH>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(CH <= 2 ? 6 : (CH <= 6 ? 5 : 4))))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(CH <= 2 ? 5 : (CH <= 6 ? 4 : 3))))
 void sweep_hist_kernel(const SortedArgs a) {
   using L = Load8<In>;
   constexpr int THREADS = 256;
@@ -861,6 +862,7 @@ void sweep_hist_kernel(const SortedArgs a) {
   __shared__ int s_nlist;
   __shared__ double s_p2[NW];
   __shared__ double s_val[MAXL];
+  __shared__ __attribute__((aligned(16))) uint32_t s_keep[8][4];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -873,6 +875,11 @@ void sweep_hist_kernel(const SortedArgs a) {
   const typename L::elem* src = static_cast<const typename L::elem*>(T.w) + row * T.ld;
   const int K = a.n_clip;
   const int n = static_cast<int>(a.cols);
+  if (tid < 32) {   // word tid % 4 of the mask for position tid / 4
+    const int r = tid >> 2, i = tid & 3;
+    s_keep[r][i] = (r >= 2 * i + 1) ? 0xFFFFFFFFu : ((r == 2 * i) ? 0x0000FFFFu : 0u);
+  }
+  const u32x4* const keep = reinterpret_cast<const u32x4*>(&s_keep[0][0]);
 
   // ---- load the row (it stays in registers): absmax, energy; clear the counters ----------------
   u32x4 rawv[CH];
@@ -975,11 +982,11 @@ void sweep_hist_kernel(const SortedArgs a) {
       // H = the largest finite pattern h with fl32(v(h) * inv) <= thr.  v(0) = 0 passes.
       auto threshold_pattern = [&](const float thr) {
         auto pass = [&](int h) { return scaled<In>(static_cast<uint32_t>(h), inv) <= thr; };
-        int hc = static_cast<int>(pattern_rtz<In>(thr * s));
-        hc = hc < 1 ? 1 : (hc > Pattern<In>::MAX_FINITE - 2 ? Pattern<In>::MAX_FINITE - 2 : hc);
-        const bool p0 = pass(hc - 1), p1 = pass(hc), p2 = pass(hc + 1), p3 = pass(hc + 2);
-        int H = hc - 2 + (p0 ? 1 : 0) + (p1 ? 1 : 0) + (p2 ? 1 : 0) + (p3 ? 1 : 0);
-        if (!(p0 && !p3)) {   // the estimate is off by more than a pattern (or no finite pattern fails)
+        // estimate: the pattern of thr * s rounded toward zero, which is H unless a pattern's
+        // value lies in the gap of a few fp32 steps between that product and the real boundary
+        int H = static_cast<int>(pattern_rtz<In>(thr * s));
+        H = H > Pattern<In>::MAX_FINITE - 1 ? Pattern<In>::MAX_FINITE - 1 : H;
+        if (!(pass(H) && !pass(H + 1))) {   // (also: no finite pattern fails)
           int lo_h = 0, hi_h = Pattern<In>::MAX_FINITE;   // pass(lo_h) holds; the answer is in [lo_h, hi_h]
           while (lo_h < hi_h) {
             const int mid = (lo_h + hi_h + 1) >> 1;
@@ -1000,7 +1007,7 @@ void sweep_hist_kernel(const SortedArgs a) {
         bad = bad || bin < -1;
         uint32_t C;
         double S;
-        hist_prefix<In>(hist, cntp, sump, lo, nbin, bin, C, S);
+        hist_prefix<In>(hist, cntp, sump, keep, lo, nbin, bin, C, S);
         ca = __builtin_fma(S, a.dgd[f][q], ca);
         cb4 = __mul24(static_cast<int>(C), a.dg2q[f][q]) + cb4;
       }
@@ -1010,7 +1017,7 @@ void sweep_hist_kernel(const SortedArgs a) {
         bad = bad || bin < -1;
         uint32_t C;
         double S;
-        hist_prefix<In>(thist, tcntp, tsump, tlo, ntbin, bin, C, S);
+        hist_prefix<In>(thist, tcntp, tsump, keep, tlo, ntbin, bin, C, S);
         ca = __builtin_fma(tsump[ntg] - S, a.dgd[f][7], ca);
         cb4 = __mul24(static_cast<int>(tcntp[ntg] - C), a.dg2q[f][7]) + cb4;
       }

@@ -1,8 +1,11 @@
-"""Seeded random sweep aimed at the sorted per-channel search (16-bit rows of 1024 to 24576
-columns, 4-bit formats, 8 or more clip ratios): every instance of the kernel (row-length
-tilings up to 1024 threads), ragged row ends, one and two formats, fp16 scales, and value
-distributions with heavy duplicates, wide dynamic range, subnormals and outliers, through
-the same element-by-element parity check against the oracle as the hand-picked cases."""
+"""Seeded random sweep aimed at the two per-channel searches that do not score every (element,
+candidate) pair (16-bit rows of 1024 to 24576 columns, 4-bit formats, 8 or more clip ratios):
+the histogram kernel (clip ratios whose thresholds span few enough bit patterns: every bf16
+case here, fp16 with ratios from about 0.1 up) and the sorting kernel (fp16 with smaller
+ratios); every row-length instance of both, ragged row ends, one and two formats, fp16 scales,
+clip tables in any order, and value distributions with heavy duplicates, wide dynamic range,
+subnormals and outliers, through the same element-by-element parity check against the oracle
+as the hand-picked cases."""
 import numpy as np
 import pytest
 import torch
@@ -29,3 +32,30 @@ def test_random_sorted_search_config(mq, seed):  # noqa: F811
     f16 = bool(rng.integers(2))
     w = _values(rng, rows, cols, int(rng.integers(5)), dtype)
     check_tensor(mq, w, list(cands), orc.PER_CHANNEL, mi.clip_ratios(n_clip), 0, f16, label=f"sorted-{seed}")
+
+
+LOW_RATIOS = [0.3, 0.12, 0.05, 0.02]   # fp16: the first two go to the histogram kernel, the others to the sorting one
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_clip_tables(mq, seed):  # noqa: F811
+    """Clip ratios down to 0.02, in descending, ascending or shuffled order, with repeats."""
+    rng = np.random.default_rng(778000 + seed)
+    dtype = [torch.float16, torch.bfloat16][seed % 2]
+    cands = FOUR[rng.integers(4)]
+    cols = int([1024, 2048, 4096, 8192, 11008, 12288, 22016, 24576][rng.integers(8)]) if rng.random() < 0.5 \
+        else 8 * int(rng.integers(128, 3072))
+    n_clip = int([8, 16, 33, 100, 128][rng.integers(5)])
+    lo = LOW_RATIOS[(seed // 2) % 4]
+    clip = mi.clip_ratios(n_clip, lo=lo, hi=float([1.0, 0.9][rng.integers(2)]))
+    order = int(rng.integers(3))
+    if order == 1:
+        clip = clip[::-1].copy()
+    elif order == 2:
+        clip = rng.permutation(clip)
+        clip[int(rng.integers(n_clip))] = clip[0]   # a repeated ratio: the first of the two wins a tie
+    rows = int(rng.integers(1, 7))
+    f16 = bool(rng.integers(2))
+    w = _values(rng, rows, cols, int(rng.integers(5)), dtype)
+    check_tensor(mq, w, list(cands), orc.PER_CHANNEL, np.ascontiguousarray(clip, dtype=np.float32), 0, f16,
+                 label=f"clip-{seed}")
