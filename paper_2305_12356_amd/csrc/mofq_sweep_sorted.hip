@@ -749,16 +749,16 @@ constexpr int kHistMaxTailBins = 2048;  // of INT4's negative elements
 // Count and magnitude sum of the histogram's elements with pattern <= lo + bin, for
 // -1 <= bin (bin = -1: none); bins beyond the last are empty, so bin is clamped to it.
 // hist: counters, two per word; cntp / sump: exclusive prefixes per group of 8 bins;
-// keep[r]: which of a group's eight counters are at or below position r (a table in LDS: one
-// read instead of sixteen compare-and-select instructions).
+// keep[c]: masks of the first c of a group's eight counters (a table in LDS: one read instead of
+// sixteen compare-and-select instructions).
 template <typename In>
 MOFQ_DEV void hist_prefix(const uint32_t* hist, const uint32_t* cntp, const double* sump, const u32x4* keep, int lo,
                           int nbin, int bin, uint32_t& C, double& S) {
-  const bool none = bin < 0;
-  const int bc = none ? 0 : (bin < nbin - 1 ? bin : nbin - 1);
-  const int g = bc >> 3, r = bc & 7;
+  const int bc = bin < nbin - 1 ? bin : nbin - 1;
+  const int g = (bc > 0 ? bc : 0) >> 3;
+  const int r1 = bin < 0 ? 0 : (bc & 7) + 1;   // how many of the group's counters count; none: group 0's prefixes are zero
   const u32x4 w = *reinterpret_cast<const u32x4*>(hist + 4 * g);
-  const u32x4 m = keep[r];   // the group's counters 0..r: 16-bit masks, two per word
+  const u32x4 m = keep[r1];   // 16-bit masks, two per word
   uint32_t cin = 0, win = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -771,8 +771,8 @@ MOFQ_DEV void hist_prefix(const uint32_t* hist, const uint32_t* cntp, const doub
   double s = sump[g];
   s = __builtin_fma(static_cast<double>(v0), static_cast<double>(cin), s);
   s = __builtin_fma(static_cast<double>(ulp), static_cast<double>(win), s);
-  C = none ? 0u : cntp[g] + cin;
-  S = none ? 0.0 : s;
+  C = cntp[g] + cin;
+  S = s;
 }
 
 // Exclusive prefixes of count and magnitude sum per group of 8 bins; the totals in entry ng.
@@ -853,7 +853,7 @@ void sweep_hist_kernel(const SortedArgs a) {
   __shared__ float s_scale[NF][MOFQ_MAX_CLIP];
   __shared__ double s_fast[NF][MOFQ_MAX_CLIP];
   __shared__ float s_wmax[NW];
-  __shared__ double s_wsum[2][NW];
+  __shared__ double s_wsum[1][NW];
   __shared__ uint32_t s_wc[NW];
   __shared__ double s_ws[NW];
   __shared__ double s_thr[NF];
@@ -862,7 +862,7 @@ void sweep_hist_kernel(const SortedArgs a) {
   __shared__ int s_nlist;
   __shared__ double s_p2[NW];
   __shared__ double s_val[MAXL];
-  __shared__ __attribute__((aligned(16))) uint32_t s_keep[8][4];
+  __shared__ __attribute__((aligned(16))) uint32_t s_keep[9][4];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -875,15 +875,15 @@ void sweep_hist_kernel(const SortedArgs a) {
   const typename L::elem* src = static_cast<const typename L::elem*>(T.w) + row * T.ld;
   const int K = a.n_clip;
   const int n = static_cast<int>(a.cols);
-  if (tid < 32) {   // word tid % 4 of the mask for position tid / 4
-    const int r = tid >> 2, i = tid & 3;
-    s_keep[r][i] = (r >= 2 * i + 1) ? 0xFFFFFFFFu : ((r == 2 * i) ? 0x0000FFFFu : 0u);
+  if (tid < 36) {   // word tid % 4 of the mask of the first tid / 4 counters
+    const int c = tid >> 2, i = tid & 3;
+    s_keep[c][i] = (c >= 2 * i + 2) ? 0xFFFFFFFFu : ((c == 2 * i + 1) ? 0x0000FFFFu : 0u);
   }
   const u32x4* const keep = reinterpret_cast<const u32x4*>(&s_keep[0][0]);
 
   // ---- load the row (it stays in registers): absmax, energy; clear the counters ----------------
   u32x4 rawv[CH];
-  float amax = 0.0f, l1f = 0.0f;
+  float amax = 0.0f;
   uint32_t amax2 = 0;   // fp16 rows: running maximum of |x| in both halves of a register
   double en = 0.0;
 #pragma unroll
@@ -912,25 +912,20 @@ void sweep_hist_kernel(const SortedArgs a) {
       const double d0 = static_cast<double>(v0), d1 = static_cast<double>(v1);
       en = __builtin_fma(d0, d0, en);
       en = __builtin_fma(d1, d1, en);
-      l1f += __builtin_fabsf(v0) + __builtin_fabsf(v1);
     }
   }
   if constexpr (std::is_same<In, F16>::value)
     amax = __builtin_fmaxf(bits_to_float<In>(amax2 & 0xFFFFu), bits_to_float<In>(amax2 >> 16));
   amax = wave_max(amax);
   en = wave_sum(en);
-  // sum |x| only enters the rounding bounds below (see the sorting kernel)
-  double l1 = static_cast<double>(wave_sum_f32(l1f)) * (1.0 + 0x1p-17);
-  if (lane == 0) { s_wmax[wave] = amax; s_wsum[0][wave] = en; s_wsum[1][wave] = l1; }
+  if (lane == 0) { s_wmax[wave] = amax; s_wsum[0][wave] = en; }
   __syncthreads();   // also: the counters are clear
   amax = s_wmax[0];
   en = s_wsum[0][0];
-  l1 = s_wsum[1][0];
 #pragma unroll
   for (int w = 1; w < NW; ++w) {
     amax = __builtin_fmaxf(amax, s_wmax[w]);
     en += s_wsum[0][w];
-    l1 += s_wsum[1][w];
   }
   for (int idx = tid; idx < NF * K; idx += THREADS) {
     const int f = idx / K, k = idx - f * K;
@@ -943,22 +938,33 @@ void sweep_hist_kernel(const SortedArgs a) {
   const int hmax = static_cast<int>(pattern_rtz<In>(amax < 3.0e38f ? amax : 3.0e38f));   // exact for a finite amax
   const int lo = (((hmax + 1 - nbin) > 0 ? (hmax + 1 - nbin) : 0) + 7) & ~7;
   const int tlo = (((hmax + 1 - ntbin) > 0 ? (hmax + 1 - ntbin) : 0) + 7) & ~7;
+  {
+    // both halves of a word at once: signed 16-bit differences to the first counted pattern
+    // (patterns are below 2^15), clamped to the last counter
+    const i16x2 lo2 = {static_cast<short>(lo), static_cast<short>(lo)};
+    const i16x2 tlo2 = {static_cast<short>(tlo), static_cast<short>(tlo)};
+    const i16x2 last2 = {static_cast<short>(nbin - 1), static_cast<short>(nbin - 1)};
+    const i16x2 tlast2 = {static_cast<short>(ntbin - 1), static_cast<short>(ntbin - 1)};
+    auto count = [](uint32_t* h, int b) { atomicAdd(&h[b >> 1], 1u << ((b & 1) * 16)); };
 #pragma unroll
-  for (int j = 0; j < CH; ++j) {
+    for (int j = 0; j < CH; ++j) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const uint32_t hs = (rawv[j][i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
-      const int h = static_cast<int>(hs & 0x7FFFu);
-      const int bin = h - lo;
-      if (bin >= 0) {   // padding and whatever lies below every threshold has no counter
-        const int bc = bin < nbin - 1 ? bin : nbin - 1;
-        atomicAdd(&hist[bc >> 1], 1u << ((bc & 1) * 16));
-      }
-      if constexpr (ANY_TAIL) {
-        const int tb = h - tlo;
-        if (tb >= 0 && (hs & 0x8000u)) {
-          const int tc = tb < ntbin - 1 ? tb : ntbin - 1;
-          atomicAdd(&thist[tc >> 1], 1u << ((tc & 1) * 16));
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t w = rawv[j][i];
+        const i16x2 h2 = __builtin_bit_cast(i16x2, w & 0x7FFF7FFFu);
+        const i16x2 b2 = __builtin_elementwise_min(h2 - lo2, last2);
+        // padding (zero) and whatever lies below every threshold has no counter
+        if (b2[0] >= 0) count(hist, b2[0]);
+        if (b2[1] >= 0) count(hist, b2[1]);
+        if constexpr (ANY_TAIL) {
+          const i16x2 t2 = h2 - tlo2;
+          // halves that are negative elements at or above the short histogram's first pattern
+          const uint32_t q2 = sign_fill2(w) & ~sign_fill2(__builtin_bit_cast(uint32_t, t2));
+          if (q2 != 0) {
+            const i16x2 tc2 = __builtin_elementwise_min(t2, tlast2);
+            if (q2 & 0xFFFFu) count(thist, tc2[0]);
+            if (q2 >> 16) count(thist, tc2[1]);
+          }
         }
       }
     }
@@ -970,6 +976,9 @@ void sweep_hist_kernel(const SortedArgs a) {
   if constexpr (ANY_TAIL) hist_group_prefixes<In, THREADS, 1>(thist, tcntp, tsump, tlo, ntg, 1, s_wc, s_ws);
   const uint32_t c_total = cntp[ng];
   const double s_total = sump[ng];
+  // sum |x| enters the rounding bounds only: the counted elements' sum (raised beyond its rounding)
+  // plus, for every other element, the magnitude of the first counted pattern, which exceeds its own
+  const double l1 = s_total * (1.0 + 0x1p-40) + static_cast<double>(n) * static_cast<double>(bits_to_float<In>(static_cast<uint32_t>(lo)));
 
   // ---- level boundaries of every candidate: one lane per candidate, one wave per (format, 64
   // candidates) --------------------------------------------------------------------------------
@@ -986,7 +995,8 @@ void sweep_hist_kernel(const SortedArgs a) {
         // value lies in the gap of a few fp32 steps between that product and the real boundary
         int H = static_cast<int>(pattern_rtz<In>(thr * s));
         H = H > Pattern<In>::MAX_FINITE - 1 ? Pattern<In>::MAX_FINITE - 1 : H;
-        if (!(pass(H) && !pass(H + 1))) {   // (also: no finite pattern fails)
+        const bool at = pass(H), above = pass(H + 1);   // both always: a short circuit costs more than it saves
+        if (!(static_cast<int>(at) & static_cast<int>(!above))) {   // (also: no finite pattern fails)
           int lo_h = 0, hi_h = Pattern<In>::MAX_FINITE;   // pass(lo_h) holds; the answer is in [lo_h, hi_h]
           while (lo_h < hi_h) {
             const int mid = (lo_h + hi_h + 1) >> 1;
@@ -1067,11 +1077,11 @@ void sweep_hist_kernel(const SortedArgs a) {
   }
   if (tid == 0) s_nlist = 0;
   __syncthreads();
-  for (int idx = tid; idx < NF * K; idx += THREADS) {
-    const int f = idx / K, k = idx - f * K;
-    if (s_direct[f] < 0 && !(s_fast[f][k] > s_thr[f]))
-      s_list[atomicAdd(&s_nlist, 1)] = static_cast<uint8_t>(f * MOFQ_MAX_CLIP + k);   // any order
-  }
+#pragma unroll
+  for (int f = 0; f < NF; ++f)
+    if (s_direct[f] < 0)   // uniform
+      for (int k = tid; k < K; k += THREADS)
+        if (!(s_fast[f][k] > s_thr[f])) s_list[atomicAdd(&s_nlist, 1)] = static_cast<uint8_t>(f * MOFQ_MAX_CLIP + k);   // any order
   __syncthreads();
   const int n_list = s_nlist;
 
