@@ -733,6 +733,8 @@ MOFQ_DEV uint32_t dot2(uint32_t a, uint32_t b, uint32_t c) {   // a.lo b.lo + a.
   return __builtin_amdgcn_udot2(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b), c, false);
 }
 
+MOFQ_DEV int med3i(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }   // x clamped to [lo, hi]
+
 // bit pattern of x >= 0 rounded toward zero to the input type; largest finite pattern
 template <typename In> MOFQ_DEV uint32_t pattern_rtz(float x);
 template <> MOFQ_DEV uint32_t pattern_rtz<F16>(float x) {
@@ -743,22 +745,41 @@ template <typename In> struct Pattern;
 template <> struct Pattern<F16> { static constexpr int MAX_FINITE = 0x7BFF; };
 template <> struct Pattern<BF16> { static constexpr int MAX_FINITE = 0x7F7F; };
 
+// Lexicographic minimum of (value, index) over the wave by data-parallel-primitive moves: the
+// smallest value (no NaN among the inputs), then the smallest index among the lanes that hold it.
+template <int CTRL> MOFQ_DEV int dpp_i32(int x) { return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xF, 0xF, true); }
+MOFQ_DEV void wave_argmin_dpp(double& v, int& idx) {
+  double m = v;
+  m = __builtin_fmin(m, dpp_f64<DPP_QUAD_XOR1>(m));
+  m = __builtin_fmin(m, dpp_f64<DPP_QUAD_XOR2>(m));
+  m = __builtin_fmin(m, dpp_f64<DPP_ROW_HALF_MIRROR>(m));
+  m = __builtin_fmin(m, dpp_f64<DPP_ROW_MIRROR>(m));
+  m = __builtin_fmin(__builtin_fmin(readlane_f64(m, 0), readlane_f64(m, 16)), __builtin_fmin(readlane_f64(m, 32), readlane_f64(m, 48)));
+  int c = (v == m) ? idx : 0x7FFFFFFF;
+  c = min(c, dpp_i32<DPP_QUAD_XOR1>(c));
+  c = min(c, dpp_i32<DPP_QUAD_XOR2>(c));
+  c = min(c, dpp_i32<DPP_ROW_HALF_MIRROR>(c));
+  c = min(c, dpp_i32<DPP_ROW_MIRROR>(c));
+  idx = min(min(__builtin_amdgcn_readlane(c, 0), __builtin_amdgcn_readlane(c, 16)),
+            min(__builtin_amdgcn_readlane(c, 32), __builtin_amdgcn_readlane(c, 48)));
+  v = m;
+}
+
 constexpr int kHistMaxBins = 8192;      // patterns with a counter (16 KB)
 constexpr int kHistMaxTailBins = 2048;  // of INT4's negative elements
 
-// Count and magnitude sum of the histogram's elements with pattern <= lo + bin, for
-// -1 <= bin (bin = -1: none); bins beyond the last are empty, so bin is clamped to it.
-// hist: counters, two per word; cntp / sump: exclusive prefixes per group of 8 bins;
+// Count and magnitude sum of the elements in the histogram's first n1 counters, 0 <= n1 <= nbin:
+// the exclusive prefixes of group n1 / 8 plus the first n1 % 8 counters of that group (n1 = nbin
+// reads the 16 bytes after the counters, which are inside the workgroup's LDS, and masks them all).
+// hist: counters, two per word; cntp / sump: exclusive prefixes per group of 8 counters;
 // keep[c]: masks of the first c of a group's eight counters (a table in LDS: one read instead of
 // sixteen compare-and-select instructions).
 template <typename In>
 MOFQ_DEV void hist_prefix(const uint32_t* hist, const uint32_t* cntp, const double* sump, const u32x4* keep, int lo,
-                          int nbin, int bin, uint32_t& C, double& S) {
-  const int bc = bin < nbin - 1 ? bin : nbin - 1;
-  const int g = (bc > 0 ? bc : 0) >> 3;
-  const int r1 = bin < 0 ? 0 : (bc & 7) + 1;   // how many of the group's counters count; none: group 0's prefixes are zero
+                          int n1, uint32_t& C, double& S) {
+  const int g = n1 >> 3;
   const u32x4 w = *reinterpret_cast<const u32x4*>(hist + 4 * g);
-  const u32x4 m = keep[r1];   // 16-bit masks, two per word
+  const u32x4 m = keep[n1 & 7];   // 16-bit masks, two per word
   uint32_t cin = 0, win = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -824,6 +845,50 @@ MOFQ_DEV void hist_group_prefixes(const uint32_t* hist, uint32_t* cntp, double* 
   __syncthreads();
 }
 
+// The same for a short histogram (at most 64 * GPMAX groups) by one wave alone, without barriers:
+// lane l takes the groups [l gp, (l + 1) gp).  The caller's next barrier publishes the result.
+template <typename In, int GPMAX>
+MOFQ_DEV void hist_group_prefixes_wave(const uint32_t* hist, uint32_t* cntp, double* sump, int lo, int ng, int gp) {
+  const int lane = threadIdx.x & 63;
+  uint32_t c8[GPMAX];
+  double s8[GPMAX];
+  uint32_t ct = 0;
+  double st = 0.0;
+#pragma unroll
+  for (int i = 0; i < GPMAX; ++i) {
+    const int g = lane * gp + i;
+    c8[i] = 0;
+    s8[i] = 0.0;
+    if (i < gp && g < ng) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(hist + 4 * g);
+      uint32_t c = 0, wsum = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        c = dot2(w[j], 0x00010001u, c);
+        wsum = dot2(w[j], static_cast<uint32_t>(2 * j) | (static_cast<uint32_t>(2 * j + 1) << 16), wsum);
+      }
+      const float v0 = bits_to_float<In>(static_cast<uint32_t>(lo + 8 * g));
+      const float ulp = bits_to_float<In>(static_cast<uint32_t>(lo + 8 * g + 1)) - v0;
+      c8[i] = c;
+      s8[i] = __builtin_fma(static_cast<double>(ulp), static_cast<double>(wsum), static_cast<double>(v0) * static_cast<double>(c));
+      ct += c;
+      st += s8[i];
+    }
+  }
+  uint32_t wct;
+  double wst;
+  uint32_t cb = wave_excl_scan_u32(ct, wct);
+  double sb = wave_excl_scan_f64(st, wst);
+#pragma unroll
+  for (int i = 0; i < GPMAX; ++i) {
+    const int g = lane * gp + i;
+    if (i < gp && g < ng) { cntp[g] = cb; sump[g] = sb; }
+    cb += c8[i];
+    sb += s8[i];
+  }
+  if (lane == 63) { cntp[ng] = cb; sump[ng] = sb; }
+}
+
 template <typename In, int FA, int FB, int CH>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(CH <= 2 ? 5 : (CH <= 6 ? 4 : 3))))
 void sweep_hist_kernel(const SortedArgs a) {
@@ -837,7 +902,6 @@ void sweep_hist_kernel(const SortedArgs a) {
   constexpr bool TAIL_A = FA == MOFQ_INT4, TAIL_B = (FB >= 0) && FBX == MOFQ_INT4;
   constexpr bool ANY_TAIL = TAIL_A || TAIL_B;
   constexpr int GPMAX = kHistMaxBins / 8 / THREADS;   // groups per thread at most
-  static_assert(kHistMaxTailBins / 8 <= THREADS, "one group of the short histogram per thread");
 
   // dynamic LDS: [sump | tsump | hist | thist | cntp | tcntp]
   extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
@@ -862,7 +926,7 @@ void sweep_hist_kernel(const SortedArgs a) {
   __shared__ int s_nlist;
   __shared__ double s_p2[NW];
   __shared__ double s_val[MAXL];
-  __shared__ __attribute__((aligned(16))) uint32_t s_keep[9][4];
+  __shared__ __attribute__((aligned(16))) uint32_t s_keep[8][4];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -875,7 +939,7 @@ void sweep_hist_kernel(const SortedArgs a) {
   const typename L::elem* src = static_cast<const typename L::elem*>(T.w) + row * T.ld;
   const int K = a.n_clip;
   const int n = static_cast<int>(a.cols);
-  if (tid < 36) {   // word tid % 4 of the mask of the first tid / 4 counters
+  if (tid < 32) {   // word tid % 4 of the mask of the first tid / 4 counters
     const int c = tid >> 2, i = tid & 3;
     s_keep[c][i] = (c >= 2 * i + 2) ? 0xFFFFFFFFu : ((c == 2 * i + 1) ? 0x0000FFFFu : 0u);
   }
@@ -927,11 +991,12 @@ void sweep_hist_kernel(const SortedArgs a) {
     amax = __builtin_fmaxf(amax, s_wmax[w]);
     en += s_wsum[0][w];
   }
-  for (int idx = tid; idx < NF * K; idx += THREADS) {
-    const int f = idx / K, k = idx - f * K;
+  if (tid < 2 * MOFQ_MAX_CLIP) {   // thread f * MOFQ_MAX_CLIP + k
+    const int f = tid / MOFQ_MAX_CLIP, k = tid % MOFQ_MAX_CLIP;
     const float qmax = (f == 0) ? Codec<FA>::QMAX : Codec<FBX>::QMAX;
-    s_scale[f][k] = unit_scale(amax, a.clip[k], qmax, a.scale_f16 != 0);
+    if (f < NF && k < K) s_scale[f][k] = unit_scale(amax, a.clip[k], qmax, a.scale_f16 != 0);
   }
+  static_assert(2 * MOFQ_MAX_CLIP <= THREADS, "one thread per (format, candidate)");
 
   // ---- the histogram covers the nbin patterns up to the largest magnitude's (a non-finite
   // element lands in the last counter: the row's error is non-finite anyway) --------------------
@@ -972,8 +1037,10 @@ void sweep_hist_kernel(const SortedArgs a) {
   __syncthreads();
 
   // ---- group prefixes ----------------------------------------------------------------------------
+  // (the short histogram by the last wave alone, before the barriers of the long one's prefixes)
+  if constexpr (ANY_TAIL)
+    if (wave == NW - 1) hist_group_prefixes_wave<In, kHistMaxTailBins / 8 / 64>(thist, tcntp, tsump, tlo, ntg, (ntg + 63) / 64);
   hist_group_prefixes<In, THREADS, GPMAX>(hist, cntp, sump, lo, ng, (ng + THREADS - 1) / THREADS, s_wc, s_ws);
-  if constexpr (ANY_TAIL) hist_group_prefixes<In, THREADS, 1>(thist, tcntp, tsump, tlo, ntg, 1, s_wc, s_ws);
   const uint32_t c_total = cntp[ng];
   const double s_total = sump[ng];
   // sum |x| enters the rounding bounds only: the counted elements' sum (raised beyond its rounding)
@@ -1009,28 +1076,32 @@ void sweep_hist_kernel(const SortedArgs a) {
       };
       double ca = 0.0;
       int cb4 = 0;       // 4 sum_b (count up to boundary b) (m_b^2 - m_{b+1}^2): an integer below 2^31
-      bool bad = false;  // a threshold below the histogram's range: the candidate goes to the exact pass
+      // counters at or below H, as a number of counters: H - lo + 1 within [0, nbin].  A threshold
+      // more than one pattern below the histogram's range (least < 0) sends the candidate to the
+      // exact pass: uncounted elements might lie above it.
+      int least = 0;
       // one boundary at a time (a rolled loop: unrolled, the eight of them cost some 80 registers)
 #pragma unroll 1
       for (int q = 0; q < 7; ++q) {
-        const int bin = threshold_pattern(a.thr[f][q]) - lo;
-        bad = bad || bin < -1;
+        const int n1 = threshold_pattern(a.thr[f][q]) - lo + 1;
+        least = n1 < least ? n1 : least;
         uint32_t C;
         double S;
-        hist_prefix<In>(hist, cntp, sump, keep, lo, nbin, bin, C, S);
+        hist_prefix<In>(hist, cntp, sump, keep, lo, med3i(n1, 0, nbin), C, S);
         ca = __builtin_fma(S, a.dgd[f][q], ca);
         cb4 = __mul24(static_cast<int>(C), a.dg2q[f][q]) + cb4;
       }
       if constexpr (TAIL) {
         // negative elements with a pattern above H: the short histogram's totals less its prefix
-        const int bin = threshold_pattern(a.thr[f][7]) - tlo;
-        bad = bad || bin < -1;
+        const int n1 = threshold_pattern(a.thr[f][7]) - tlo + 1;
+        least = n1 < least ? n1 : least;
         uint32_t C;
         double S;
-        hist_prefix<In>(thist, tcntp, tsump, keep, tlo, ntbin, bin, C, S);
+        hist_prefix<In>(thist, tcntp, tsump, keep, tlo, med3i(n1, 0, ntbin), C, S);
         ca = __builtin_fma(tsump[ntg] - S, a.dgd[f][7], ca);
         cb4 = __mul24(static_cast<int>(tcntp[ntg] - C), a.dg2q[f][7]) + cb4;
       }
+      const bool bad = least < 0;
       if (k < K) {
         const double gl = static_cast<double>(a.g_last[f]);
         const double A = ca + gl * s_total;
@@ -1060,7 +1131,7 @@ void sweep_hist_kernel(const SortedArgs a) {
       if (v < m) { m = v; km = k; }
       smax = __builtin_fmaxf(smax, s_scale[f][k]);
     }
-    wave_argmin(m, km);
+    wave_argmin_dpp(m, km);
     smax = wave_max(smax);
     const double sm = static_cast<double>(smax), gm = static_cast<double>(a.g_absmax[f]);
     const double nd = static_cast<double>(n);
