@@ -43,15 +43,16 @@ HBM_PEAK_GBPS = 8000.0
 MFMA_PEAK = {"bf16": 2500.0, "int8": 5000.0, "fp8": 5000.0}
 # Work of the EXHAUSTIVE scale search per element, candidate and format: scale (1 multiply),
 # round (1), clamp/saturate (1), residual x - g*s (2), error accumulation d*d + acc (2).  The
-# per-channel search does not execute it (it sorts each row and locates level boundaries),
-# so this prices an equivalent rate, reported under its own key, never as a utilisation.
+# per-channel search does not execute it (it builds a histogram of each row's bit patterns and
+# reads every candidate's level counts and sums from its prefixes), so this prices an
+# equivalent rate, reported under its own key, never as a utilisation.
 FLOPS_PER_ELEM_CAND_FMT = 7
-# Counter-derived facts about sweep_sorted_kernel on 4096-column rows, measured by rocprofv3 runs
+# Counter-derived facts about sweep_hist_kernel on 4096-column rows, measured by rocprofv3 runs
 # of this command (not in the run that prints them): where they come from is printed beside them.
 TAIL_SPREAD = False   # set from --tail-spread
 
-SORTED_KERNEL_COUNTERS = {
-    "from": "profiles/w_only_sorted_kernel_counters.txt, profiles/w_only_7b_k100_hbm_traffic.txt",
+SEARCH_KERNEL_COUNTERS = {
+    "from": "profiles/w_only_hist_kernel_counters.txt, profiles/w_only_7b_k100_hbm_traffic.txt",
     "read_per_input_byte": 373236.0 / (46592 * 4096 * 2 / 1024),     # FETCH_SIZE, scaled by a plain copy
     "write_bytes_per_row": 10192.0 * 1024 / 46592,                   # WRITE_SIZE
 }
@@ -286,7 +287,7 @@ def run_w4(args, shapes, dev, weights, group, model, steps, warmup, ceilings=Non
         "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
         "kernel": (f"sweep_group_kernel<F16, INT4, FP4_E2M1, {GROUP}> on {dom_cols}-column rows" if group else
-                   f"sweep_sorted_kernel<F16, INT4, FP4_E2M1> instance for {dom_cols}-column rows"),
+                   f"sweep_hist_kernel<F16, INT4, FP4_E2M1> instance for {dom_cols}-column rows"),
         "limited_by": "vector instruction issue, not bytes: the search evaluates "
                       f"{n_clip} x {N_FMT} scale candidates per element from LDS and registers",
         "avg_launch_ms": dom_time / len(dom) * 1e3, "launches": len(dom),
@@ -298,14 +299,14 @@ def run_w4(args, shapes, dev, weights, group, model, steps, warmup, ceilings=Non
             "TFLOPs": dom_elems * n_clip * N_FMT * FLOPS_PER_ELEM_CAND_FMT / dom_time / 1e12,
             "flops_per_elem_cand_fmt": FLOPS_PER_ELEM_CAND_FMT,
             "note": "flop of scoring every element x candidate x format one by one (7 each) over the launch "
-                    "time; the kernel reaches the same result with far fewer instructions (sort + boundary "
-                    "search), so this is not a fraction of any peak",
+                    "time; the kernel reaches the same result with far fewer instructions (histogram of the "
+                    "row's bit patterns + prefix look-ups), so this is not a fraction of any peak",
         },
     }
     if ceilings:
         roofline["frac_of_measured_read"] = achieved / ceilings["read_GBps"]
     if not group and model == "7b" and dom_cols == 4096:
-        c = SORTED_KERNEL_COUNTERS
+        c = SEARCH_KERNEL_COUNTERS
         roofline["traffic"] = (alg_bytes_per_launch * c["read_per_input_byte"] +
                                dom_rows / len(dom) * c["write_bytes_per_row"])
         roofline["traffic_from"] = {"file": c["from"], "measured_in_this_run": False,

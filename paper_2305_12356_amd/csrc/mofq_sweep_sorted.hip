@@ -726,8 +726,8 @@ __global__ __launch_bounds__(THREADS, (CH <= 4 ? 4 : 2)) void sweep_sorted_kerne
 // sorting kernel where it would not fit.  INT4's negative elements beyond its extra boundary
 // are counted in a second, short histogram over the top of the range.
 //
-// Filter, shortlist and exact fp64 re-score are those of the sorting kernel; the re-score walks
-// the row in its registers.
+// Filter, shortlist and exact fp64 re-score are those of the sorting kernel; the re-score reads
+// the row again.
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 MOFQ_DEV uint32_t dot2(uint32_t a, uint32_t b, uint32_t c) {   // a.lo b.lo + a.hi b.hi + c
   return __builtin_amdgcn_udot2(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b), c, false);
@@ -945,7 +945,7 @@ void sweep_hist_kernel(const SortedArgs a) {
   }
   const u32x4* const keep = reinterpret_cast<const u32x4*>(&s_keep[0][0]);
 
-  // ---- load the row (it stays in registers): absmax, energy; clear the counters ----------------
+  // ---- load the row (it stays in registers until it is counted): absmax, energy; clear the counters ---
   u32x4 rawv[CH];
   float amax = 0.0f;
   uint32_t amax2 = 0;   // fp16 rows: running maximum of |x| in both halves of a register
@@ -1165,12 +1165,16 @@ void sweep_hist_kernel(const SortedArgs a) {
     const float s = s_scale[f][k], inv = 1.0f / s;
     const double sd = static_cast<double>(s);
     double acc = 0.0;
+    // the row is read again (it left the registers after the counting; this pass is rare)
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
+      const int64_t c0 = (static_cast<int64_t>(j) * THREADS + tid) * 8;
+      u32x4 raw = {0u, 0u, 0u, 0u};   // padding is zero and scores zero
+      if (c0 < a.cols) raw = *reinterpret_cast<const u32x4*>(src + c0);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {   // padding is zero and scores zero
-        const float x0 = bits_to_float<In>(rawv[j][i] & 0xFFFFu);
-        const float x1 = bits_to_float<In>(rawv[j][i] >> 16);
+      for (int i = 0; i < 4; ++i) {
+        const float x0 = bits_to_float<In>(raw[i] & 0xFFFFu);
+        const float x1 = bits_to_float<In>(raw[i] >> 16);
         if (f == 0) rescore2<FA>(acc, x0, x1, inv, sd, carry);
         else rescore2<FBX>(acc, x0, x1, inv, sd, carry);
       }
