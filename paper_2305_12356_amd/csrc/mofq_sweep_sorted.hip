@@ -775,7 +775,7 @@ constexpr int kHistMaxTailBins = 2048;  // of INT4's negative elements
 // keep[c]: masks of the first c of a group's eight counters (a table in LDS: one read instead of
 // sixteen compare-and-select instructions).
 template <typename In>
-MOFQ_DEV void hist_prefix(const uint32_t* hist, const uint32_t* cntp, const double* sump, const u32x4* keep, int lo,
+MOFQ_DEV void hist_prefix(const uint32_t* hist, const uint16_t* cntp, const double* sump, const u32x4* keep, int lo,
                           int n1, uint32_t& C, double& S) {
   const int g = n1 >> 3;
   const u32x4 w = *reinterpret_cast<const u32x4*>(hist + 4 * g);
@@ -799,7 +799,7 @@ MOFQ_DEV void hist_prefix(const uint32_t* hist, const uint32_t* cntp, const doub
 // Exclusive prefixes of count and magnitude sum per group of 8 bins; the totals in entry ng.
 // Thread t takes the groups [t gp, (t + 1) gp), gp <= GPMAX.  Called by all threads.
 template <typename In, int THREADS, int GPMAX>
-MOFQ_DEV void hist_group_prefixes(const uint32_t* hist, uint32_t* cntp, double* sump, int lo, int ng, int gp,
+MOFQ_DEV void hist_group_prefixes(const uint32_t* hist, uint16_t* cntp, double* sump, int lo, int ng, int gp,
                                   uint32_t* s_wc, double* s_ws) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   uint32_t c8[GPMAX];
@@ -837,18 +837,18 @@ MOFQ_DEV void hist_group_prefixes(const uint32_t* hist, uint32_t* cntp, double* 
 #pragma unroll
   for (int i = 0; i < GPMAX; ++i) {
     const int g = tid * gp + i;
-    if (i < gp && g < ng) { cntp[g] = cb; sump[g] = sb; }
+    if (i < gp && g < ng) { cntp[g] = static_cast<uint16_t>(cb); sump[g] = sb; }
     cb += c8[i];
     sb += s8[i];
   }
-  if (tid == THREADS - 1) { cntp[ng] = cb; sump[ng] = sb; }
+  if (tid == THREADS - 1) { cntp[ng] = static_cast<uint16_t>(cb); sump[ng] = sb; }
   __syncthreads();
 }
 
 // The same for a short histogram (at most 64 * GPMAX groups) by one wave alone, without barriers:
 // lane l takes the groups [l gp, (l + 1) gp).  The caller's next barrier publishes the result.
 template <typename In, int GPMAX>
-MOFQ_DEV void hist_group_prefixes_wave(const uint32_t* hist, uint32_t* cntp, double* sump, int lo, int ng, int gp) {
+MOFQ_DEV void hist_group_prefixes_wave(const uint32_t* hist, uint16_t* cntp, double* sump, int lo, int ng, int gp) {
   const int lane = threadIdx.x & 63;
   uint32_t c8[GPMAX];
   double s8[GPMAX];
@@ -882,11 +882,11 @@ MOFQ_DEV void hist_group_prefixes_wave(const uint32_t* hist, uint32_t* cntp, dou
 #pragma unroll
   for (int i = 0; i < GPMAX; ++i) {
     const int g = lane * gp + i;
-    if (i < gp && g < ng) { cntp[g] = cb; sump[g] = sb; }
+    if (i < gp && g < ng) { cntp[g] = static_cast<uint16_t>(cb); sump[g] = sb; }
     cb += c8[i];
     sb += s8[i];
   }
-  if (lane == 63) { cntp[ng] = cb; sump[ng] = sb; }
+  if (lane == 63) { cntp[ng] = static_cast<uint16_t>(cb); sump[ng] = sb; }
 }
 
 template <typename In, int FA, int FB, int CH>
@@ -911,8 +911,8 @@ void sweep_hist_kernel(const SortedArgs a) {
   double* const tsump = sump + (ng + 1);
   uint32_t* const hist = reinterpret_cast<uint32_t*>(s_dyn + (((ng + 1) + (ntg + 1)) * 8 + 15) / 16 * 16);
   uint32_t* const thist = hist + (nbin >> 1);
-  uint32_t* const cntp = thist + (ntbin >> 1);
-  uint32_t* const tcntp = cntp + (ng + 1);
+  uint16_t* const cntp = reinterpret_cast<uint16_t*>(thist + (ntbin >> 1));   // counts stay below 2^16: a row has at most 24576 elements
+  uint16_t* const tcntp = cntp + (ng + 1);
 
   __shared__ float s_scale[NF][MOFQ_MAX_CLIP];
   __shared__ double s_fast[NF][MOFQ_MAX_CLIP];
@@ -925,7 +925,9 @@ void sweep_hist_kernel(const SortedArgs a) {
   __shared__ uint8_t s_list[MAXL];   // format * MOFQ_MAX_CLIP + candidate
   __shared__ int s_nlist;
   __shared__ double s_p2[NW];
-  __shared__ double s_val[MAXL];
+  // re-scored errors of the shortlist: over the sum prefixes, which are no longer needed by then
+  // (the host sizes the dynamic LDS for it)
+  double* const s_val = reinterpret_cast<double*>(s_dyn);
   __shared__ __attribute__((aligned(16))) uint32_t s_keep[8][4];
 
   const int tid = threadIdx.x;
@@ -1264,14 +1266,16 @@ int launch_shape(const SortedArgs& a, int64_t total_rows, hipStream_t st) {
   return MOFQ_ERR_UNSUPPORTED;
 }
 
-// The histogram kernel: dynamic LDS for [sum prefixes | counters | count prefixes] of both histograms.
+// The histogram kernel: dynamic LDS for [sum prefixes | counters | count prefixes (16 bits)] of both
+// histograms; the shortlist's re-scored values lie over its start later.
 template <typename In, int FA, int FB>
 int launch_hist_shape(const SortedArgs& a, int64_t total_rows, hipStream_t st) {
   const dim3 grid(static_cast<unsigned>(total_rows));
   const int64_t chunks = a.cols / 8;
   const int ng = a.nbin / 8, ntg = a.ntbin / 8;
-  const size_t lds = (static_cast<size_t>((ng + 1) + (ntg + 1)) * 8 + 15) / 16 * 16 + 2 * static_cast<size_t>(a.nbin + a.ntbin) +
-                     4 * static_cast<size_t>((ng + 1) + (ntg + 1));
+  const size_t lds = std::max<size_t>((static_cast<size_t>((ng + 1) + (ntg + 1)) * 8 + 15) / 16 * 16 + 2 * static_cast<size_t>(a.nbin + a.ntbin) +
+                                          2 * static_cast<size_t>((ng + 1) + (ntg + 1)),
+                                      2 * MOFQ_MAX_CLIP * sizeof(double));   // at least the shortlist's values
 #define MOFQ_HIST(CH)                                                                         \
   if (chunks <= 256 * (CH)) {                                                                  \
     hipLaunchKernelGGL((sweep_hist_kernel<In, FA, FB, CH>), grid, dim3(256), lds, st, a);       \
