@@ -1064,12 +1064,13 @@ int mofq_select_layers_timed(int32_t n_layers, const mofq_tensor_t* w, const int
   if ((rc = sw.init())) return rc;
   hipStream_t st2 = sw.side;
   auto join = [&](int status) { return sw.join(status); };
-  // Beside the searches the emission has their whole duration to move its bytes: one
-  // workgroup per compute unit leaves the wave slots to the searches (measured on 256 compute
-  // units with the 7B-shaped set: 33.9 ms per pass against 35.1 ms with the device-filling grid;
-  // half and twice as many workgroups are both slower).
+  // Beside the searches the emission has their whole duration to move its bytes: two
+  // workgroups per compute unit leave the wave slots to the searches and still finish in time
+  // (measured on 256 compute units: 7B-shaped set 15.5 ms per pass against 15.7 with one per
+  // compute unit and 18.7 with fewer; 65B-shaped set 123.5 against 140.4 ms, where one per compute
+  // unit no longer keeps up with the searches; three to eight per compute unit are no faster).
   const int cus = compute_units();
-  int emit_cap = sw.two ? cus : 0;
+  int emit_cap = sw.two ? 2 * cus : 0;
 
   auto emit_params = [&](int i, const WOnlyWs& s) {
     EmitParams e{};

@@ -1123,7 +1123,11 @@ void sweep_hist_kernel(const SortedArgs a) {
   }
   __syncthreads();
 
-  // ---- shortlist (bounds as in the sorting kernel: the sums here come from shorter trees) -----
+  // ---- shortlist.  The rounding bound of the filtered error is the sorting kernel's with the depth
+  // of this kernel's summation trees: a group's sum is exact (products and sum of fewer than 2^27
+  // units of one ulp), a group prefix adds at most GPMAX of them in a thread, 6 levels of the wave
+  // scan and the waves before, and a look-up adds two exact products: fewer than D = 16 roundings,
+  // each of at most u sum|x|, whatever the row's length.
   for (int f = wave; f < NF; f += NW) {
     double m = __builtin_inf();
     int km = 0;
@@ -1144,7 +1148,8 @@ void sweep_hist_kernel(const SortedArgs a) {
       const int k = k0 + lane;
       cnt += __builtin_popcountll(__ballot(k < K && !(s_fast[f][k < K ? k : 0] > thr)));
     }
-    const double beta = 0x1p-53 * (40.0 * (2 * E + 32) * 2.0 * sm * l1 + (E + 32) * en + 8.0 * sm * sm * gm * gm * nd);
+    static_assert(GPMAX + 6 + NW + 2 <= 16, "depth of the prefix sums");
+    const double beta = 0x1p-53 * (40.0 * 16 * 2.0 * sm * l1 + (E + 32) * en + 8.0 * sm * sm * gm * gm * nd);
     const bool direct = cnt == 1 && beta <= 0x1p-34 * m;   // false for a zero or non-finite error
     if (lane == 0) { s_thr[f] = thr; s_direct[f] = direct ? km : -1; }
   }
