@@ -53,7 +53,7 @@ TAIL_SPREAD = False   # set from --tail-spread
 
 SEARCH_KERNEL_COUNTERS = {
     "from": "profiles/w_only_hist_kernel_counters.txt, profiles/w_only_7b_k100_hbm_traffic.txt",
-    "read_per_input_byte": 373236.0 / (46592 * 4096 * 2 / 1024),     # FETCH_SIZE, scaled by a plain copy
+    "read_per_input_byte": 373087.0 / (46592 * 4096 * 2 / 1024),     # FETCH_SIZE, scaled by a plain copy
     "write_bytes_per_row": 10192.0 * 1024 / 46592,                   # WRITE_SIZE
 }
 
