@@ -59,3 +59,35 @@ def test_random_clip_tables(mq, seed):  # noqa: F811
     w = _values(rng, rows, cols, int(rng.integers(5)), dtype)
     check_tensor(mq, w, list(cands), orc.PER_CHANNEL, np.ascontiguousarray(clip, dtype=np.float32), 0, f16,
                  label=f"clip-{seed}")
+
+
+def _special_rows(cols, dtype):
+    """Rows that stress the counting and the INT4 asymmetry: zeros, one value, the type's extremes,
+    negative-only and uniform rows (many elements beyond INT4's -7.5 boundary), a lone element."""
+    g = torch.Generator().manual_seed(4242 + cols)
+    big = 65504.0 if dtype == torch.float16 else 3.0e38
+    tiny = 6.0e-8 if dtype == torch.float16 else 1.0e-38
+    rows = []
+    rows.append(torch.zeros(cols))                                          # all zero: degenerate scale
+    rows.append(torch.full((cols,), -0.0))                                  # negative zeros
+    rows.append(torch.full((cols,), 0.37))                                  # one value: one counter holds the row
+    rows.append(torch.full((cols,), -0.37))                                 # the same, all on INT4's negative side
+    r = torch.zeros(cols); r[cols // 3] = -1.0; rows.append(r)              # a lone negative element
+    r = torch.randn(cols, generator=g) * 0.02; r[5] = big; r[6] = -big; rows.append(r)      # the largest finite values
+    r = torch.randn(cols, generator=g) * tiny * 4; rows.append(r)           # subnormals only
+    rows.append(-torch.rand(cols, generator=g))                             # negative only, uniform: a long INT4 tail
+    rows.append(torch.rand(cols, generator=g) * 2 - 1)                      # uniform, both signs
+    rows.append(-torch.rand(cols, generator=g) * 0.5 - 0.5)                 # every element beyond half the maximum
+    r = torch.randn(cols, generator=g); r[r.abs() < 1.0] = 0.0; rows.append(r)              # mostly zeros
+    r = (torch.randint(0, 2, (cols,), generator=g).float() * 2 - 1) * 0.75; rows.append(r)  # two values, +-
+    return torch.stack(rows).to(dtype).to("cuda")
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("cols", [1024, 4096, 5120, 11008])
+@pytest.mark.parametrize("lo", [0.5, 0.02])
+def test_special_rows(mq, dtype, cols, lo):  # noqa: F811
+    w = _special_rows(cols, dtype)
+    for f16 in (False, True):
+        check_tensor(mq, w, [orc.INT4, orc.FP4_E2M1], orc.PER_CHANNEL, mi.clip_ratios(100, lo=lo), 0, f16,
+                     label=f"special-{cols}-{lo}-{f16}")
