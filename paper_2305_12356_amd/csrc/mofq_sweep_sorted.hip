@@ -1,5 +1,8 @@
 // Scale search for one output channel per workgroup without scoring every
-// (element, candidate) pair.
+// (element, candidate) pair.  Two kernels share the formulation below: sweep_sorted_kernel
+// (first in this file) sorts the row and searches it; sweep_hist_kernel (second, with its own
+// description) counts the row's bit patterns instead and is the one that runs wherever the
+// clip ratios let its histogram fit, which includes the usual [0.5, 1].
 //
 // For a fixed scale the magnitude of the quantized value is a non-decreasing step function
 // of the element's magnitude (rounding and the fp32 product are symmetric in the sign), so
@@ -27,7 +30,7 @@
 // shortlist is re-scored element by element in fp64, exactly like the direct kernel, and
 // the first smallest wins.
 //
-// Applies to 16-bit inputs (fp16 / bf16) and the 4-bit formats (16 levels); other
+// Both apply to 16-bit inputs (fp16 / bf16) and the 4-bit formats (16 levels); other
 // cases use the direct kernel in mofq_sweep.hip.
 #include <cmath>
 #include <type_traits>
