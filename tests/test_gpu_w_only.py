@@ -98,7 +98,7 @@ def test_per_channel_other_dtypes(mq, dtype):
 
 def test_repeated_and_dense_clip_ratios(mq):
     """Clip tables whose candidates tie exactly (repeats) or differ by a few ulp: the winner of
-    each row has rivals within any rounding margin, so the sorted search has to settle them
+    each row has rivals within any rounding margin, so the per-channel search has to settle them
     element by element; rows of several tilings, wide (|x| >= 2) and narrow magnitudes."""
     w = mi.llama_like_weight(11, 4096, seed=21, device=DEV)
     w[3] *= 64.0
