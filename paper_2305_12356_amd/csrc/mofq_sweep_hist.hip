@@ -307,7 +307,21 @@ void sweep_hist_kernel(const SortedArgs a) {
     const i16x2 tlo2 = {static_cast<short>(tlo), static_cast<short>(tlo)};
     const i16x2 last2 = {static_cast<short>(nbin - 1), static_cast<short>(nbin - 1)};
     const i16x2 tlast2 = {static_cast<short>(ntbin - 1), static_cast<short>(ntbin - 1)};
-    auto count = [](uint32_t* h, int b) { atomicAdd(&h[b >> 1], 1u << ((b & 1) * 16)); };
+    // Counter b is the low (b even) or high half of word b / 2: add 1 or 65536.  Address and
+    // addend are written out (a shift-add and a mask on the LDS byte address, one 24-bit
+    // multiply-add): left to the compiler the increment costs twice the instructions, and this
+    // loop runs once per element.
+    typedef __attribute__((address_space(3))) uint32_t lds_u32;
+    const uint32_t hist_at = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_u32*)hist));     // LDS byte addresses, multiples of 16
+    const uint32_t thist_at = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_u32*)thist));
+    auto count = [](uint32_t at, uint32_t ub) {
+      uint32_t one_or_65536;
+      asm("v_mad_u32_u24 %0, %1, %2, 1" : "=v"(one_or_65536) : "v"(ub & 1u), "s"(0xFFFFu));
+      lds_u32* const word = (lds_u32*)static_cast<uintptr_t>(((ub << 1) + at) & ~3u);
+      __hip_atomic_fetch_add(word, one_or_65536, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto lo16 = [](i16x2 v) { return static_cast<uint32_t>(__builtin_bit_cast(uint32_t, v) & 0xFFFFu); };
+    auto hi16 = [](i16x2 v) { return static_cast<uint32_t>(__builtin_bit_cast(uint32_t, v) >> 16); };
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
 #pragma unroll
@@ -316,16 +330,16 @@ void sweep_hist_kernel(const SortedArgs a) {
         const i16x2 h2 = __builtin_bit_cast(i16x2, w & 0x7FFF7FFFu);
         const i16x2 b2 = __builtin_elementwise_min(h2 - lo2, last2);
         // padding (zero) and whatever lies below every threshold has no counter
-        if (b2[0] >= 0) count(hist, b2[0]);
-        if (b2[1] >= 0) count(hist, b2[1]);
+        if (b2[0] >= 0) count(hist_at, lo16(b2));   // non-negative: the 16 bits are the counter's number
+        if (b2[1] >= 0) count(hist_at, hi16(b2));
         if constexpr (ANY_TAIL) {
           const i16x2 t2 = h2 - tlo2;
           // halves that are negative elements at or above the short histogram's first pattern
           const uint32_t q2 = sign_fill2(w) & ~sign_fill2(__builtin_bit_cast(uint32_t, t2));
           if (q2 != 0) {
             const i16x2 tc2 = __builtin_elementwise_min(t2, tlast2);
-            if (q2 & 0xFFFFu) count(thist, tc2[0]);
-            if (q2 >> 16) count(thist, tc2[1]);
+            if (q2 & 0xFFFFu) count(thist_at, lo16(tc2));
+            if (q2 >> 16) count(thist_at, hi16(tc2));
           }
         }
       }
