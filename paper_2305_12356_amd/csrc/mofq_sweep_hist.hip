@@ -1,6 +1,8 @@
-// Per-channel scale search from a histogram of the magnitudes' bit patterns (the formulation, the
-// filter and the shortlist are described at the top of mofq_sweep_sorted.hip, whose kernel this one
-// replaces wherever its histogram fits).
+// Per-channel scale search from a histogram of the magnitudes' bit patterns: Algorithm 1's
+// quantize_layer + compute_error with the tensor-error metric (Section 4.1) for per-channel weight
+// scales over a table of clip ratios, INT4 against FP4-E2M1 (Table 1).  The formulation, the filter
+// and the shortlist are described at the top of mofq_sweep_sorted.hip, whose kernel this one replaces
+// wherever its histogram fits.
 //
 // The decision "fl32(|x| * inv) <= threshold" is monotone in the magnitude's bit pattern, so for
 // every (candidate, boundary) there is one largest pattern H that passes, and the elements on

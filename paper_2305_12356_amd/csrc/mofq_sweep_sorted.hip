@@ -1,5 +1,7 @@
 // Scale search for one output channel per workgroup without scoring every
-// (element, candidate) pair.  Two kernels share the formulation below: sweep_sorted_kernel
+// (element, candidate) pair: Algorithm 1's quantize_layer + compute_error with the tensor-error
+// metric (Section 4.1) for per-channel weight scales (Section 3.2, Section 5) over a table of
+// clip ratios, for the 4-bit pair of Section 4.2 (INT4, FP4-E2M1 of Table 1).  Two kernels share the formulation below: sweep_sorted_kernel
 // (this file) sorts the row and searches it; sweep_hist_kernel (mofq_sweep_hist.hip, with its
 // own description) counts the row's bit patterns instead and is the one that runs wherever the
 // clip ratios let its histogram fit, which includes the usual [0.5, 1].  This file also holds
