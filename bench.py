@@ -55,6 +55,7 @@ SEARCH_KERNEL_COUNTERS = {
     "from": "profiles/w_only_hist_kernel_counters.txt, profiles/w_only_7b_k100_hbm_traffic.txt",
     "read_per_input_byte": 373087.0 / (46592 * 4096 * 2 / 1024),     # FETCH_SIZE, scaled by a plain copy
     "write_bytes_per_row": 10192.0 * 1024 / 46592,                   # WRITE_SIZE
+    "valu_instr_per_wave": 1200.0,                                   # SQ_INSTS_VALU / SQ_WAVES, 4096-column instance
 }
 
 
@@ -312,6 +313,14 @@ def run_w4(args, shapes, dev, weights, group, model, steps, warmup, ceilings=Non
         roofline["traffic_from"] = {"file": c["from"], "measured_in_this_run": False,
                                     "how": "rocprofv3 FETCH_SIZE / WRITE_SIZE per row, scaled by a plain copy, "
                                            "times the rows of this run's average launch"}
+        if ceilings:
+            # what binds the kernel: wave instructions issued per second (4 waves per row, the instruction
+            # count per wave from the counters profile) against the rate of the plain FMA loop of this run
+            rate = c["valu_instr_per_wave"] * 4 * dom_rows / dom_time
+            roofline["vector_issue"] = {"wave_instr_per_s": rate, "ceiling_measured": ceilings["valu_wave_instr_per_s"],
+                                        "frac": rate / ceilings["valu_wave_instr_per_s"],
+                                        "instr_per_wave": c["valu_instr_per_wave"],
+                                        "instr_per_wave_from": {"file": c["from"], "measured_in_this_run": False}}
 
     res = mq.read_results(results)
     fp_pct = 100.0 * sum(1 for r in res if r.best == 1) / len(res)
